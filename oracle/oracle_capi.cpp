@@ -1,0 +1,155 @@
+// ORACLE — test infrastructure only (see layout_oracle.hpp).
+// C entry points (prefix oracle_) so that tests can reach the oracle through ctypes.
+#include <cstring>
+#include <string>
+
+#include "layout_oracle.hpp"
+
+using oracle::Layout;
+
+namespace {
+int put_string(const std::string& s, char* buf, size_t cap, size_t* needed) {
+  if (needed) *needed = s.size() + 1;
+  if (buf && cap > 0) {
+    size_t n = s.size() < cap - 1 ? s.size() : cap - 1;
+    std::memcpy(buf, s.data(), n);
+    buf[n] = 0;
+  }
+  return oracle::OK;
+}
+// Coordinates and bare shapes are written as HTuples of non-negative integers, e.g. "((0,1),(1,1))".
+bool parse_htuple(const char* text, oracle::HTuple* out) {
+  struct P {
+    const char* s; size_t pos = 0; bool ok = true;
+    void skip() { while (s[pos] == ' ') ++pos; }
+    oracle::HTuple go() {
+      skip();
+      if (s[pos] == '(') {
+        ++pos;
+        std::vector<oracle::HTuple> items;
+        for (;;) {
+          items.push_back(go());
+          if (!ok) return oracle::HTuple::Int(0);
+          skip();
+          if (s[pos] == ',') { ++pos; continue; }
+          if (s[pos] == ')') { ++pos; break; }
+          ok = false; return oracle::HTuple::Int(0);
+        }
+        return oracle::HTuple::Tup(items);
+      }
+      size_t st = pos;
+      while (s[pos] >= '0' && s[pos] <= '9') ++pos;
+      if (pos == st) { ok = false; return oracle::HTuple::Int(0); }
+      return oracle::HTuple::Int(std::stoll(std::string(s + st, pos - st)));
+    }
+  } p{text};
+  *out = p.go();
+  p.skip();
+  return p.ok && p.s[p.pos] == 0;
+}
+}  // namespace
+
+extern "C" {
+
+int oracle_layout_parse(const char* text, Layout** out) {
+  if (!text || !out) return oracle::ERR_INVALID_ARG;
+  Layout L;
+  oracle::Status st = oracle::parse_layout(text, &L);
+  if (st != oracle::OK) return st;
+  *out = new Layout(L);
+  return oracle::OK;
+}
+void oracle_layout_destroy(Layout* L) { delete L; }
+int oracle_layout_to_string(const Layout* L, char* buf, size_t cap, size_t* needed) {
+  return put_string(oracle::to_string(*L), buf, cap, needed);
+}
+int64_t oracle_layout_size(const Layout* L) { return oracle::size(*L); }
+int64_t oracle_layout_cosize(const Layout* L) { return oracle::cosize(*L); }
+int oracle_layout_rank(const Layout* L) { return oracle::rank(L->shape); }
+int oracle_layout_depth(const Layout* L) { return oracle::depth(L->shape); }
+int64_t oracle_layout_eval(const Layout* L, int64_t i) { return oracle::eval(*L, i); }
+void oracle_layout_eval_range(const Layout* L, int64_t begin, int64_t end, int64_t* out) {
+  for (int64_t i = begin; i < end; ++i) out[i - begin] = oracle::eval(*L, i);
+}
+int oracle_layout_eval_crd(const Layout* L, const char* coord, int64_t* out) {
+  oracle::HTuple c;
+  if (!parse_htuple(coord, &c)) return oracle::ERR_PARSE;
+  if (!oracle::weakly_congruent(c, L->shape)) return oracle::ERR_NOT_CONGRUENT;
+  *out = oracle::eval_crd(*L, c);
+  return oracle::OK;
+}
+int oracle_idx2crd_natural(const Layout* L, int64_t i, char* buf, size_t cap, size_t* needed) {
+  return put_string(oracle::to_string(oracle::idx2crd_natural(i, L->shape)), buf, cap, needed);
+}
+// Coordinate of coordinate-set profile `coarse` (a shape that coarsens L's shape) for integral coordinate i.
+int oracle_idx2crd_in(const char* coarse_shape, int64_t i, char* buf, size_t cap, size_t* needed) {
+  oracle::HTuple s;
+  if (!parse_htuple(coarse_shape, &s)) return oracle::ERR_PARSE;
+  return put_string(oracle::to_string(oracle::idx2crd_natural(i, s)), buf, cap, needed);
+}
+int oracle_crd2idx(const Layout* L, const char* coord, int64_t* out) {
+  oracle::HTuple c;
+  if (!parse_htuple(coord, &c)) return oracle::ERR_PARSE;
+  if (!oracle::weakly_congruent(c, L->shape)) return oracle::ERR_NOT_CONGRUENT;
+  *out = oracle::crd2idx_h(oracle::crd2natural(c, L->shape), L->shape);
+  return oracle::OK;
+}
+int oracle_shape_compatible(const char* p, const char* s) {
+  oracle::HTuple a, b;
+  if (!parse_htuple(p, &a) || !parse_htuple(s, &b)) return -1;
+  return oracle::compatible(a, b) ? 1 : 0;
+}
+int oracle_congruent(const char* p, const char* s) {
+  oracle::HTuple a, b;
+  if (!parse_htuple(p, &a) || !parse_htuple(s, &b)) return -1;
+  return oracle::congruent(a, b) ? 1 : 0;
+}
+int oracle_weakly_congruent(const char* p, const char* s) {
+  oracle::HTuple a, b;
+  if (!parse_htuple(p, &a) || !parse_htuple(s, &b)) return -1;
+  return oracle::weakly_congruent(a, b) ? 1 : 0;
+}
+
+int oracle_coalesce(const Layout* a, Layout** out) { *out = new Layout(oracle::coalesce(*a)); return oracle::OK; }
+int oracle_coalesce_bymode(const Layout* a, Layout** out) { *out = new Layout(oracle::coalesce_bymode(*a)); return oracle::OK; }
+int oracle_right_inverse(const Layout* a, Layout** out) { *out = new Layout(oracle::right_inverse(*a)); return oracle::OK; }
+
+#define ORACLE_BINARY(name)                                             \
+  int oracle_##name(const Layout* a, const Layout* b, Layout** out) {   \
+    Layout r;                                                           \
+    oracle::Status st = oracle::name(*a, *b, &r);                       \
+    if (st != oracle::OK) return st;                                    \
+    *out = new Layout(r);                                               \
+    return oracle::OK;                                                  \
+  }
+ORACLE_BINARY(composition)
+ORACLE_BINARY(composition_bymode)
+ORACLE_BINARY(logical_divide)
+ORACLE_BINARY(logical_divide_bymode)
+ORACLE_BINARY(zipped_divide)
+#undef ORACLE_BINARY
+
+int oracle_complement(const Layout* a, int64_t cotarget, Layout** out) {
+  Layout r;
+  oracle::Status st = oracle::complement(*a, cotarget, &r);
+  if (st != oracle::OK) return st;
+  *out = new Layout(r);
+  return oracle::OK;
+}
+int oracle_max_common_vector_def(const Layout* a, const Layout* b, int64_t* K) {
+  *K = oracle::max_common_vector_def(*a, *b);
+  return oracle::OK;
+}
+int oracle_max_common_vector(const Layout* a, const Layout* b, int64_t* K) {
+  return oracle::max_common_vector_alg(*a, *b, K);
+}
+
+int oracle_copy(const void* src, const Layout* sl, void* dst, const Layout* dl, int elem_bytes) {
+  return oracle::copy(src, *sl, dst, *dl, elem_bytes);
+}
+int oracle_copy_range(const void* src, const Layout* sl, void* dst, const Layout* dl, int elem_bytes,
+                      int64_t begin, int64_t end) {
+  return oracle::copy_range(src, *sl, dst, *dl, elem_bytes, begin, end);
+}
+
+}  // extern "C"

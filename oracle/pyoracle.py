@@ -1,0 +1,237 @@
+"""ORACLE — test infrastructure only.
+
+ctypes access to the CPU oracle (``oracle/layout_oracle.cpp``).  Only tests, the smoke
+check and the benchmark's CPU-baseline leg import this module; the GPU package never does.
+Argument marshalling only: all arithmetic is in the C++ oracle.
+"""
+import ctypes
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_SOURCES = ["layout_oracle.cpp", "oracle_capi.cpp"]
+
+STATUS_NAMES = {
+    0: "OK", 1: "INVALID_ARG", 2: "PARSE", 3: "NOT_CONGRUENT", 4: "BAD_EXTENT", 5: "NEGATIVE_STRIDE",
+    6: "SIZE_MISMATCH", 7: "STRIDE_DIVISIBILITY", 8: "SHAPE_DIVISIBILITY", 9: "NOT_SEGREGATED",
+    10: "NOT_INJECTIVE", 11: "NOT_SURJECTIVE",
+}
+
+
+class OracleError(Exception):
+    def __init__(self, status, what):
+        super().__init__("%s: %s" % (what, STATUS_NAMES.get(status, status)))
+        self.status = status
+        self.status_name = STATUS_NAMES.get(status, str(status))
+
+
+def build(force=False):
+    """Compile the oracle (g++, host only)."""
+    srcs = [os.path.join(_HERE, s) for s in _SOURCES]
+    hdr = os.path.join(_HERE, "layout_oracle.hpp")
+    if not force and os.path.exists(_LIB_PATH):
+        newest = max(os.path.getmtime(p) for p in srcs + [hdr])
+        if os.path.getmtime(_LIB_PATH) >= newest:
+            return _LIB_PATH
+    cmd = ["g++", "-std=c++17", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", "-o", _LIB_PATH] + srcs
+    subprocess.check_call(cmd)
+    return _LIB_PATH
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB_PATH)
+        P = ctypes.c_void_p
+        PP = ctypes.POINTER(ctypes.c_void_p)
+        i64 = ctypes.c_int64
+        L.oracle_layout_parse.argtypes = [ctypes.c_char_p, PP]
+        L.oracle_layout_destroy.argtypes = [P]
+        L.oracle_layout_destroy.restype = None
+        L.oracle_layout_to_string.argtypes = [P, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        for name in ("size", "cosize"):
+            f = getattr(L, "oracle_layout_" + name)
+            f.argtypes = [P]
+            f.restype = i64
+        L.oracle_layout_rank.argtypes = [P]
+        L.oracle_layout_depth.argtypes = [P]
+        L.oracle_layout_eval.argtypes = [P, i64]
+        L.oracle_layout_eval.restype = i64
+        L.oracle_layout_eval_range.argtypes = [P, i64, i64, P]
+        L.oracle_layout_eval_range.restype = None
+        L.oracle_layout_eval_crd.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64)]
+        L.oracle_idx2crd_natural.argtypes = [P, i64, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        L.oracle_idx2crd_in.argtypes = [ctypes.c_char_p, i64, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        L.oracle_crd2idx.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64)]
+        for name in ("shape_compatible", "congruent", "weakly_congruent"):
+            getattr(L, "oracle_" + name).argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+        for name in ("coalesce", "coalesce_bymode", "right_inverse"):
+            getattr(L, "oracle_" + name).argtypes = [P, PP]
+        for name in ("composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide"):
+            getattr(L, "oracle_" + name).argtypes = [P, P, PP]
+        L.oracle_complement.argtypes = [P, i64, PP]
+        L.oracle_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
+        L.oracle_max_common_vector_def.argtypes = [P, P, ctypes.POINTER(i64)]
+        L.oracle_copy.argtypes = [P, P, P, P, ctypes.c_int]
+        L.oracle_copy_range.argtypes = [P, P, P, P, ctypes.c_int, i64, i64]
+        _lib = L
+    return _lib
+
+
+def _check(status, what):
+    if status != 0:
+        raise OracleError(status, what)
+
+
+class Layout:
+    """A layout S:D held by the oracle."""
+
+    def __init__(self, text=None, _handle=None):
+        self._h = ctypes.c_void_p()
+        if _handle is not None:
+            self._h = _handle
+        else:
+            _check(lib().oracle_layout_parse(text.encode(), ctypes.byref(self._h)), "parse %r" % text)
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.oracle_layout_destroy(self._h)
+            self._h = None
+
+    def __str__(self):
+        buf = ctypes.create_string_buffer(4096)
+        lib().oracle_layout_to_string(self._h, buf, 4096, None)
+        return buf.value.decode()
+
+    __repr__ = __str__
+
+    @property
+    def size(self):
+        return lib().oracle_layout_size(self._h)
+
+    @property
+    def cosize(self):
+        return lib().oracle_layout_cosize(self._h)
+
+    @property
+    def rank(self):
+        return lib().oracle_layout_rank(self._h)
+
+    @property
+    def depth(self):
+        return lib().oracle_layout_depth(self._h)
+
+    def __call__(self, c):
+        """L(c): c is an int (integral coordinate, extended domain) or a coordinate string/tuple."""
+        if isinstance(c, int):
+            return lib().oracle_layout_eval(self._h, c)
+        out = ctypes.c_int64()
+        text = c if isinstance(c, str) else _tuple_text(c)
+        _check(lib().oracle_layout_eval_crd(self._h, text.encode(), ctypes.byref(out)), "eval %s" % text)
+        return out.value
+
+    def offsets(self, begin=0, end=None):
+        """numpy int64 array of L(i) for i in [begin, end)."""
+        import numpy as np
+        end = self.size if end is None else end
+        out = np.empty(max(end - begin, 0), dtype=np.int64)
+        lib().oracle_layout_eval_range(self._h, begin, end, out.ctypes.data_as(ctypes.c_void_p))
+        return out
+
+    def natural(self, i):
+        buf = ctypes.create_string_buffer(1024)
+        lib().oracle_idx2crd_natural(self._h, i, buf, 1024, None)
+        return buf.value.decode()
+
+    def crd2idx(self, c):
+        out = ctypes.c_int64()
+        text = c if isinstance(c, str) else _tuple_text(c)
+        _check(lib().oracle_crd2idx(self._h, text.encode(), ctypes.byref(out)), "crd2idx %s" % text)
+        return out.value
+
+
+def _tuple_text(c):
+    if isinstance(c, int):
+        return str(c)
+    return "(" + ",".join(_tuple_text(x) for x in c) + ")"
+
+
+def _as_layout(x):
+    return x if isinstance(x, Layout) else Layout(x)
+
+
+def _unary(name, a):
+    a = _as_layout(a)   # keep the temporary alive across the call
+    h = ctypes.c_void_p()
+    _check(getattr(lib(), "oracle_" + name)(a._h, ctypes.byref(h)), name)
+    return Layout(_handle=h)
+
+
+def _binary(name, a, b):
+    a, b = _as_layout(a), _as_layout(b)
+    h = ctypes.c_void_p()
+    _check(getattr(lib(), "oracle_" + name)(a._h, b._h, ctypes.byref(h)), "%s(%s, %s)" % (name, a, b))
+    return Layout(_handle=h)
+
+
+def coalesce(a): return _unary("coalesce", a)
+def coalesce_bymode(a): return _unary("coalesce_bymode", a)
+def right_inverse(a): return _unary("right_inverse", a)
+def composition(a, b): return _binary("composition", a, b)
+def composition_bymode(a, t): return _binary("composition_bymode", a, t)
+def logical_divide(a, b): return _binary("logical_divide", a, b)
+def logical_divide_bymode(a, t): return _binary("logical_divide_bymode", a, t)
+def zipped_divide(a, t): return _binary("zipped_divide", a, t)
+
+
+def complement(a, cotarget=0):
+    a = _as_layout(a)
+    h = ctypes.c_void_p()
+    _check(lib().oracle_complement(a._h, cotarget, ctypes.byref(h)), "complement(%s, %d)" % (a, cotarget))
+    return Layout(_handle=h)
+
+
+def max_common_vector(a, b):
+    a, b = _as_layout(a), _as_layout(b)
+    k = ctypes.c_int64()
+    _check(lib().oracle_max_common_vector(a._h, b._h, ctypes.byref(k)), "max_common_vector")
+    return k.value
+
+
+def max_common_vector_def(a, b):
+    a, b = _as_layout(a), _as_layout(b)
+    k = ctypes.c_int64()
+    _check(lib().oracle_max_common_vector_def(a._h, b._h, ctypes.byref(k)), "max_common_vector_def")
+    return k.value
+
+
+def idx2crd(shape_text, i):
+    """The i-th coordinate of the coordinate set Z_shape (Fig. coordlists)."""
+    buf = ctypes.create_string_buffer(1024)
+    _check(lib().oracle_idx2crd_in(shape_text.encode(), i, buf, 1024, None), "idx2crd")
+    return buf.value.decode()
+
+
+def shape_compatible(p, s): return lib().oracle_shape_compatible(p.encode(), s.encode()) == 1
+def congruent(p, s): return lib().oracle_congruent(p.encode(), s.encode()) == 1
+def weakly_congruent(p, s): return lib().oracle_weakly_congruent(p.encode(), s.encode()) == 1
+
+
+def copy(src, src_layout, dst, dst_layout, begin=0, end=None):
+    """dst(i) = src(i) over numpy arrays (1-D, same itemsize), element by element, in order."""
+    sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
+    assert src.dtype.itemsize == dst.dtype.itemsize and src.flags.c_contiguous and dst.flags.c_contiguous
+    assert sl.cosize <= src.size and dl.cosize <= dst.size, "buffer smaller than the layout's cosize"
+    if end is None:
+        st = lib().oracle_copy(src.ctypes.data_as(ctypes.c_void_p), sl._h, dst.ctypes.data_as(ctypes.c_void_p), dl._h,
+                               src.dtype.itemsize)
+    else:
+        st = lib().oracle_copy_range(src.ctypes.data_as(ctypes.c_void_p), sl._h, dst.ctypes.data_as(ctypes.c_void_p),
+                                     dl._h, src.dtype.itemsize, begin, end)
+    _check(st, "copy")
+    return dst
