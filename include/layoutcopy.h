@@ -1,0 +1,166 @@
+/* layoutcopy.h — C ABI of the MI355X (gfx950) layout-algebra and layout-driven tensor copy library.
+ *
+ * Vocabulary follows "CuTe Layout Representation and Algebra":
+ *   - a Layout is a congruent pair Shape:Stride of hierarchical tuples of integers (Sec. 2.3-2.4) and
+ *     is a function from coordinates to offsets: L(c) = inner_product(idx2crd_S(c), D)
+ *     (Eq. idx2crd, Eq. innerprod, Sec. 2.4 Def. layout);
+ *   - a Tensor is a pointer accessor composed with a layout, T(c) = *(e + L(c)) (Sec. 2.5, Eq. tensor);
+ *   - COPY moves dst(i) = src(i) for every integral coordinate i (Sec. 2.6.1).
+ *
+ * Conventions that hold for every entry point
+ *   - Strides and offsets are counted in ELEMENTS of the copy's dtype, never in bytes.
+ *   - Layout and plan handles are host objects, immutable after creation, owned by the caller and
+ *     released with the matching destroy call.  Handles may be shared between threads.
+ *   - `const void* src` / `void* dst` of the copy calls are DEVICE pointers to offset 0 of the
+ *     respective layout; the caller owns that memory and guarantees cosize(layout) elements are
+ *     addressable.  The library allocates no device memory, never synchronises the device and
+ *     launches only on the stream it is given (`hip_stream` is a hipStream_t passed as void*;
+ *     NULL = the default stream).
+ *   - Every call returns an lc_status_t; on error `*out` is left untouched.  No C++ exception
+ *     crosses this boundary.
+ */
+#ifndef LAYOUTCOPY_H_
+#define LAYOUTCOPY_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lc_layout lc_layout_t; /* opaque: a layout S:D */
+typedef struct lc_plan lc_plan_t;     /* opaque: a planned copy between two layouts */
+
+typedef enum {
+  LC_OK = 0,
+  LC_ERR_INVALID_ARG = 1,         /* NULL where a handle/pointer is required, bad rank, bad cotarget ... */
+  LC_ERR_PARSE = 2,               /* text is not "S:D" in the paper's notation */
+  LC_ERR_NOT_CONGRUENT = 3,       /* shape and stride have different profiles (Sec. 2.3: S ~ D) */
+  LC_ERR_BAD_EXTENT = 4,          /* an extent < 1 (a shape is an HTuple of positive integers, Sec. 2.2) */
+  LC_ERR_NEGATIVE_STRIDE = 5,     /* only strides in N are supported */
+  LC_ERR_SIZE_MISMATCH = 6,       /* COPY precondition size(src) == size(dst) violated (Sec. 2.6.1) */
+  LC_ERR_STRIDE_DIVISIBILITY = 7, /* composition: stride divisibility condition (Eq. divis_stride) */
+  LC_ERR_SHAPE_DIVISIBILITY = 8,  /* composition: shape divisibility condition (Eq. divis_shape) */
+  LC_ERR_NOT_SEGREGATED = 9,      /* composition: sublayouts of B without segregated images (Sec. 3.3.2) */
+  LC_ERR_NOT_INJECTIVE = 10,      /* complement: a mode of the layout overlaps the span of smaller ones */
+  LC_ERR_NOT_SURJECTIVE = 11,     /* logical divide: (B, B*) misses coordinates of A (Sec. 3.5.2) */
+  LC_ERR_DST_ALIASES = 12,        /* copy: two coordinates of dst share an offset (result would depend on order) */
+  LC_ERR_UNSUPPORTED_DTYPE = 13,
+  LC_ERR_TOO_LARGE = 14,          /* more modes or elements than the kernels index */
+  LC_ERR_MISALIGNED = 15,         /* a device pointer is less aligned than the plan was created for */
+  LC_ERR_HIP = 16                 /* a HIP runtime call failed (no device, launch failure, ...) */
+} lc_status_t;
+
+/* Element types.  The copy moves bit patterns; the dtype only fixes the element width. */
+typedef enum {
+  LC_F32 = 0, LC_F16 = 1, LC_BF16 = 2,
+  LC_B8 = 3, LC_B16 = 4, LC_B32 = 5, LC_B64 = 6, LC_B128 = 7 /* opaque elements of 1, 2, 4, 8, 16 bytes */
+} lc_dtype_t;
+
+const char* lc_status_string(lc_status_t s);
+int lc_dtype_bytes(lc_dtype_t dt); /* element width in bytes, 0 for an unknown dtype */
+
+/* ---------------------------------------------------------------------------------------------
+ * Layout construction and inspection (Sec. 2.1-2.4)
+ * ------------------------------------------------------------------------------------------- */
+
+/* Parse the paper's printed form, e.g. "((8,512),(8,1024)):((1,8),(4096,32768))" or "24:3"
+ * (Sec. 2.4.1).  Whitespace is ignored.  Errors: PARSE, NOT_CONGRUENT, BAD_EXTENT, NEGATIVE_STRIDE. */
+lc_status_t lc_layout_parse(const char* text, lc_layout_t** out);
+
+/* Build from a pre-order encoding of the shape tree: an entry -k (k >= 1) opens a tuple of k children,
+ * a positive entry is a leaf extent.  `leaf_strides` lists the strides of the leaves left to right
+ * (host arrays, copied). */
+lc_status_t lc_layout_from_tree(const int64_t* shape_preorder, int n_nodes, const int64_t* leaf_strides,
+                                int n_leaves, lc_layout_t** out);
+void lc_layout_destroy(lc_layout_t* layout);
+
+/* Writes the printed form into buf (NUL-terminated, truncated to cap); *needed (optional) receives the
+ * size including the terminator. */
+lc_status_t lc_layout_to_string(const lc_layout_t* layout, char* buf, size_t cap, size_t* needed);
+
+int64_t lc_layout_size(const lc_layout_t* layout);   /* |L|: product of the extents (Sec. 2.4.1) */
+int64_t lc_layout_cosize(const lc_layout_t* layout); /* largest offset of the image + 1 (Sec. 2.4.1) */
+int lc_layout_rank(const lc_layout_t* layout);       /* Sec. 2.1 */
+int lc_layout_depth(const lc_layout_t* layout);      /* Sec. 2.1 */
+
+/* L(i) for an integral coordinate.  Any i >= 0 is accepted: beyond |L| the last mode is left
+ * unreduced (extended domain, Sec. 2.2.2 and 2.4.1). */
+int64_t lc_layout_eval(const lc_layout_t* layout, int64_t integral_coord);
+
+/* ---------------------------------------------------------------------------------------------
+ * Layout algebra (Sec. 3).  Each call allocates *out on LC_OK.
+ * A tiler (Sec. 3.3.5) is passed as a layout whose top-level modes are the tiles; an integer tile S is
+ * the mode S:1.  A layout whose shape is a single integer is the 1-tuple tiler of itself.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Coalesce (Sec. 3.2): depth <= 1, same size, same value at every integral coordinate; extent-1
+ * modes removed, neighbouring modes merged when stride_{k+1} = extent_k * stride_k; "1:0" if nothing is left. */
+lc_status_t lc_coalesce(const lc_layout_t* a, lc_layout_t** out);
+/* Coalesce applied to every top-level mode separately (Sec. 3.2, Eq. layout_combinator). */
+lc_status_t lc_coalesce_bymode(const lc_layout_t* a, lc_layout_t** out);
+
+/* Group composition R = A o B (Sec. 3.3): B's shape is compatible with R's and R(c) = A(B(c)) for
+ * every coordinate of B.  Errors: STRIDE_DIVISIBILITY, SHAPE_DIVISIBILITY, NOT_SEGREGATED. */
+lc_status_t lc_composition(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out);
+/* By-mode composition with a tiler (Sec. 3.3.5): (A_0 o T_0, A_1 o T_1, ...); modes of A beyond the
+ * tiler's rank are kept whole. */
+lc_status_t lc_composition_bymode(const lc_layout_t* a, const lc_layout_t* tiler, lc_layout_t** out);
+
+/* Complement (Sec. 3.5) with respect to `cotarget` offsets (0 = cosize(a)): ordered image, disjoint
+ * from the image of `a` on its whole extended domain; ends with the mode that steps over everything
+ * (e.g. "1:32").  Errors: NOT_INJECTIVE, INVALID_ARG (cotarget < 0). */
+lc_status_t lc_complement(const lc_layout_t* a, int64_t cotarget, lc_layout_t** out);
+
+/* Right-inverse of maximal size (Sec. 3.4.1): injective, a(out(k)) = k for every k < |out|; "1:0" when trivial. */
+lc_status_t lc_right_inverse(const lc_layout_t* a, lc_layout_t** out);
+
+/* Logical divide A (/) B = A o (B, B*_{|A|}) (Sec. 3.5.2): rank 2, mode 0 = A o B, mode 1 = the rest. */
+lc_status_t lc_logical_divide(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out);
+/* Logical divide applied to the top-level modes with a tiler (Sec. 3.5.2, related divides). */
+lc_status_t lc_logical_divide_bymode(const lc_layout_t* a, const lc_layout_t* tiler, lc_layout_t** out);
+/* By-mode logical divide, then like modes zipped: ((tile_0, tile_1, ...), (rest_0, rest_1, ..., untouched modes)). */
+lc_status_t lc_zipped_divide(const lc_layout_t* a, const lc_layout_t* tiler, lc_layout_t** out);
+
+/* Largest K such that the first K offsets of both layouts belong to the same coordinates: the extent of the
+ * stride-1 head of coalesce(a o right_inverse(b)) (Sec. 3.4.2).  Requires |a| == |b|. */
+lc_status_t lc_max_common_vector(const lc_layout_t* a, const lc_layout_t* b, int64_t* K);
+
+/* ---------------------------------------------------------------------------------------------
+ * COPY (Sec. 2.6.1): dst(i) = src(i) for i in [0, size(dst)), executed on the GPU.
+ * The plan coalesces both layouts, refines them to a common shape, permutes the iteration order
+ * consistently on both sides (Sec. 3.4.2), picks the common vector width and tiles the copy with
+ * zipped_divide (Sec. 3.5.2); plan creation is pure host work and touches no device.
+ * ------------------------------------------------------------------------------------------- */
+
+/* src_align_bytes / dst_align_bytes: alignment the caller guarantees for the device pointers that
+ * will be passed to lc_plan_execute (a power of two; 256 for fresh allocations).  Errors: SIZE_MISMATCH,
+ * DST_ALIASES (dst not injective; a single-element copy is exempt), UNSUPPORTED_DTYPE, TOO_LARGE. */
+lc_status_t lc_plan_create(const lc_layout_t* src, const lc_layout_t* dst, lc_dtype_t dt,
+                           unsigned src_align_bytes, unsigned dst_align_bytes, lc_plan_t** out);
+/* One-line description: kernel class, vector width, joint modes, tile, grid, LDS bytes, swizzle. */
+lc_status_t lc_plan_describe(const lc_plan_t* plan, char* buf, size_t cap, size_t* needed);
+/* Enqueue the copy on `hip_stream`.  Asynchronous.  Errors: MISALIGNED, HIP. */
+lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream);
+void lc_plan_destroy(lc_plan_t* plan);
+
+/* lc_plan_create (alignment taken from the two pointers) + lc_plan_execute + lc_plan_destroy. */
+lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, const lc_layout_t* dst_layout,
+                    lc_dtype_t dt, void* hip_stream);
+
+/* Bytes the plan moves per execution: elements * element width, once read and once written
+ * (a stride-0 source mode re-reads count once). */
+int64_t lc_plan_algorithmic_bytes(const lc_plan_t* plan);
+
+/* Times `iters` back-to-back executions of the plan on `hip_stream` with HIP events recorded on that
+ * same stream, after `warmup` untimed ones; returns the mean milliseconds per execution in *ms_per_iter.
+ * Synchronises the stream (the only call here that does).  `srcs`/`dsts` are host arrays of `n_buffers`
+ * device pointers used round-robin, so that successive executions touch different memory. */
+lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers,
+                         int warmup, int iters, void* hip_stream, float* ms_per_iter);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAYOUTCOPY_H_ */

@@ -563,6 +563,7 @@ int64_t max_common_vector_def(const Layout& A, const Layout& B) {
 }
 
 Status max_common_vector_alg(const Layout& A, const Layout& B, int64_t* K) {
+  if (size(A) != size(B)) return ERR_SIZE_MISMATCH;   // stated for |A| = |B| (Sec. 3.4.2)
   Layout R;
   Status st = composition(A, right_inverse(B), &R);
   if (st != OK) return st;

@@ -71,6 +71,9 @@ int64_t oracle_layout_eval(const Layout* L, int64_t i) { return oracle::eval(*L,
 void oracle_layout_eval_range(const Layout* L, int64_t begin, int64_t end, int64_t* out) {
   for (int64_t i = begin; i < end; ++i) out[i - begin] = oracle::eval(*L, i);
 }
+void oracle_layout_eval_many(const Layout* L, const int64_t* coords, int64_t n, int64_t* out) {
+  for (int64_t k = 0; k < n; ++k) out[k] = oracle::eval(*L, coords[k]);
+}
 int oracle_layout_eval_crd(const Layout* L, const char* coord, int64_t* out) {
   oracle::HTuple c;
   if (!parse_htuple(coord, &c)) return oracle::ERR_PARSE;

@@ -64,6 +64,8 @@ def lib():
         L.oracle_layout_eval.restype = i64
         L.oracle_layout_eval_range.argtypes = [P, i64, i64, P]
         L.oracle_layout_eval_range.restype = None
+        L.oracle_layout_eval_many.argtypes = [P, P, i64, P]
+        L.oracle_layout_eval_many.restype = None
         L.oracle_layout_eval_crd.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64)]
         L.oracle_idx2crd_natural.argtypes = [P, i64, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
         L.oracle_idx2crd_in.argtypes = [ctypes.c_char_p, i64, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
@@ -141,6 +143,15 @@ class Layout:
         end = self.size if end is None else end
         out = np.empty(max(end - begin, 0), dtype=np.int64)
         lib().oracle_layout_eval_range(self._h, begin, end, out.ctypes.data_as(ctypes.c_void_p))
+        return out
+
+    def offsets_at(self, coords):
+        """numpy int64 array of L(i) for the given integral coordinates."""
+        import numpy as np
+        coords = np.ascontiguousarray(coords, dtype=np.int64)
+        out = np.empty(coords.size, dtype=np.int64)
+        lib().oracle_layout_eval_many(self._h, coords.ctypes.data_as(ctypes.c_void_p), coords.size,
+                                      out.ctypes.data_as(ctypes.c_void_p))
         return out
 
     def natural(self, i):
@@ -222,11 +233,14 @@ def congruent(p, s): return lib().oracle_congruent(p.encode(), s.encode()) == 1
 def weakly_congruent(p, s): return lib().oracle_weakly_congruent(p.encode(), s.encode()) == 1
 
 
-def copy(src, src_layout, dst, dst_layout, begin=0, end=None):
-    """dst(i) = src(i) over numpy arrays (1-D, same itemsize), element by element, in order."""
+def copy(src, src_layout, dst, dst_layout, begin=0, end=None, spans_checked=False):
+    """dst(i) = src(i) over numpy arrays (1-D, same itemsize), element by element, in order.
+    With a range [begin, end) the caller may pass buffers that only cover the offsets that range
+    reaches and vouch for it with spans_checked=True."""
     sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
     assert src.dtype.itemsize == dst.dtype.itemsize and src.flags.c_contiguous and dst.flags.c_contiguous
-    assert sl.cosize <= src.size and dl.cosize <= dst.size, "buffer smaller than the layout's cosize"
+    if not spans_checked:
+        assert sl.cosize <= src.size and dl.cosize <= dst.size, "buffer smaller than the layout's cosize"
     if end is None:
         st = lib().oracle_copy(src.ctypes.data_as(ctypes.c_void_p), sl._h, dst.ctypes.data_as(ctypes.c_void_p), dl._h,
                                src.dtype.itemsize)

@@ -1,0 +1,9 @@
+"""MI355X-native layout algebra and layout-driven tensor copy (COPY of the CuTe layout method).
+
+The work is done by liblayoutcopy.so (C++ host algebra and planner, HIP kernels for gfx950) behind
+the C ABI of include/layoutcopy.h; this package only marshals arguments.
+"""
+from .binding import (DTYPES, DTYPE_BYTES, Layout, LayoutCopyError, Plan, copy_tensor, lc_coalesce,  # noqa: F401
+                      lc_coalesce_bymode, lc_complement, lc_composition, lc_composition_bymode, lc_copy,
+                      lc_logical_divide, lc_logical_divide_bymode, lc_max_common_vector, lc_right_inverse,
+                      lc_zipped_divide, lib)

@@ -1,0 +1,220 @@
+"""ctypes binding of liblayoutcopy.so: the same entry points as include/layoutcopy.h, with
+argument marshalling only.  Every step of a copy runs in the library's HIP kernels; there is no
+Python or CPU fallback, and a missing library is an error."""
+import ctypes
+import os
+
+from . import build as _build
+
+_lib = None
+
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2, "b8": 3, "b16": 4, "b32": 5, "b64": 6, "b128": 7}
+DTYPE_BYTES = {"f32": 4, "f16": 2, "bf16": 2, "b8": 1, "b16": 2, "b32": 4, "b64": 8, "b128": 16}
+
+
+class LayoutCopyError(RuntimeError):
+    def __init__(self, status, what):
+        name = lib().lc_status_string(status).decode()
+        super().__init__("%s: %s" % (what, name))
+        self.status = status
+        self.status_name = name
+
+
+def lib():
+    """Loads the in-tree library (built by paper_2603_02298_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError("liblayoutcopy.so is not built: run `python -m paper_2603_02298_amd.build` "
+                           "(there is no fallback path)")
+    L = ctypes.CDLL(path)
+    P, PP = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
+    i64, sz = ctypes.c_int64, ctypes.c_size_t
+    L.lc_status_string.argtypes = [ctypes.c_int]
+    L.lc_status_string.restype = ctypes.c_char_p
+    L.lc_dtype_bytes.argtypes = [ctypes.c_int]
+    L.lc_layout_parse.argtypes = [ctypes.c_char_p, PP]
+    L.lc_layout_from_tree.argtypes = [ctypes.POINTER(i64), ctypes.c_int, ctypes.POINTER(i64), ctypes.c_int, PP]
+    L.lc_layout_destroy.argtypes = [P]
+    L.lc_layout_destroy.restype = None
+    L.lc_layout_to_string.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
+    for n in ("size", "cosize"):
+        f = getattr(L, "lc_layout_" + n)
+        f.argtypes, f.restype = [P], i64
+    L.lc_layout_rank.argtypes = [P]
+    L.lc_layout_depth.argtypes = [P]
+    L.lc_layout_eval.argtypes = [P, i64]
+    L.lc_layout_eval.restype = i64
+    for n in ("coalesce", "coalesce_bymode", "right_inverse"):
+        getattr(L, "lc_" + n).argtypes = [P, PP]
+    for n in ("composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide"):
+        getattr(L, "lc_" + n).argtypes = [P, P, PP]
+    L.lc_complement.argtypes = [P, i64, PP]
+    L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
+    L.lc_plan_create.argtypes = [P, P, ctypes.c_int, ctypes.c_uint, ctypes.c_uint, PP]
+    L.lc_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
+    L.lc_plan_execute.argtypes = [P, P, P, P]
+    L.lc_plan_destroy.argtypes = [P]
+    L.lc_plan_destroy.restype = None
+    L.lc_copy.argtypes = [P, P, P, P, ctypes.c_int, P]
+    L.lc_plan_algorithmic_bytes.argtypes = [P]
+    L.lc_plan_algorithmic_bytes.restype = i64
+    L.lc_plan_time.argtypes = [P, PP, PP, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
+    L.lc_debug_replay_on_host.argtypes = [P, P, i64, P, i64, ctypes.POINTER(i64)]
+    _lib = L
+    return L
+
+
+def _check(status, what):
+    if status != 0:
+        raise LayoutCopyError(status, what)
+
+
+class Layout:
+    """lc_layout_t handle."""
+
+    def __init__(self, text=None, _handle=None):
+        self._h = _handle if _handle is not None else ctypes.c_void_p()
+        if _handle is None:
+            _check(lib().lc_layout_parse(text.encode(), ctypes.byref(self._h)), "lc_layout_parse(%r)" % text)
+
+    @classmethod
+    def from_tree(cls, shape_preorder, leaf_strides):
+        a = (ctypes.c_int64 * len(shape_preorder))(*shape_preorder)
+        b = (ctypes.c_int64 * len(leaf_strides))(*leaf_strides)
+        h = ctypes.c_void_p()
+        _check(lib().lc_layout_from_tree(a, len(shape_preorder), b, len(leaf_strides), ctypes.byref(h)), "lc_layout_from_tree")
+        return cls(_handle=h)
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.lc_layout_destroy(self._h)
+            self._h = None
+
+    def __str__(self):
+        need = ctypes.c_size_t()
+        lib().lc_layout_to_string(self._h, None, 0, ctypes.byref(need))
+        buf = ctypes.create_string_buffer(need.value)
+        lib().lc_layout_to_string(self._h, buf, need.value, None)
+        return buf.value.decode()
+
+    __repr__ = __str__
+    size = property(lambda self: lib().lc_layout_size(self._h))
+    cosize = property(lambda self: lib().lc_layout_cosize(self._h))
+    rank = property(lambda self: lib().lc_layout_rank(self._h))
+    depth = property(lambda self: lib().lc_layout_depth(self._h))
+
+    def __call__(self, i):
+        return lib().lc_layout_eval(self._h, i)
+
+
+def _as_layout(x):
+    return x if isinstance(x, Layout) else Layout(x)
+
+
+def _unary(name, a):
+    a = _as_layout(a)
+    h = ctypes.c_void_p()
+    _check(getattr(lib(), name)(a._h, ctypes.byref(h)), "%s(%s)" % (name, a))
+    return Layout(_handle=h)
+
+
+def _binary(name, a, b):
+    a, b = _as_layout(a), _as_layout(b)
+    h = ctypes.c_void_p()
+    _check(getattr(lib(), name)(a._h, b._h, ctypes.byref(h)), "%s(%s, %s)" % (name, a, b))
+    return Layout(_handle=h)
+
+
+def lc_coalesce(a): return _unary("lc_coalesce", a)
+def lc_coalesce_bymode(a): return _unary("lc_coalesce_bymode", a)
+def lc_right_inverse(a): return _unary("lc_right_inverse", a)
+def lc_composition(a, b): return _binary("lc_composition", a, b)
+def lc_composition_bymode(a, t): return _binary("lc_composition_bymode", a, t)
+def lc_logical_divide(a, b): return _binary("lc_logical_divide", a, b)
+def lc_logical_divide_bymode(a, t): return _binary("lc_logical_divide_bymode", a, t)
+def lc_zipped_divide(a, t): return _binary("lc_zipped_divide", a, t)
+
+
+def lc_complement(a, cotarget=0):
+    a = _as_layout(a)
+    h = ctypes.c_void_p()
+    _check(lib().lc_complement(a._h, cotarget, ctypes.byref(h)), "lc_complement(%s, %d)" % (a, cotarget))
+    return Layout(_handle=h)
+
+
+def lc_max_common_vector(a, b):
+    a, b = _as_layout(a), _as_layout(b)
+    k = ctypes.c_int64()
+    _check(lib().lc_max_common_vector(a._h, b._h, ctypes.byref(k)), "lc_max_common_vector(%s, %s)" % (a, b))
+    return k.value
+
+
+class Plan:
+    """lc_plan_t handle."""
+
+    def __init__(self, src_layout, dst_layout, dtype, src_align=256, dst_align=256):
+        self.src_layout, self.dst_layout = _as_layout(src_layout), _as_layout(dst_layout)
+        self.dtype = dtype
+        self._h = ctypes.c_void_p()
+        _check(lib().lc_plan_create(self.src_layout._h, self.dst_layout._h, DTYPES[dtype], src_align, dst_align,
+                                    ctypes.byref(self._h)),
+               "lc_plan_create(%s -> %s, %s)" % (self.src_layout, self.dst_layout, dtype))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.lc_plan_destroy(self._h)
+            self._h = None
+
+    def describe(self):
+        need = ctypes.c_size_t()
+        lib().lc_plan_describe(self._h, None, 0, ctypes.byref(need))
+        buf = ctypes.create_string_buffer(need.value)
+        lib().lc_plan_describe(self._h, buf, need.value, None)
+        return buf.value.decode()
+
+    @property
+    def algorithmic_bytes(self):
+        return lib().lc_plan_algorithmic_bytes(self._h)
+
+    def execute(self, src_ptr, dst_ptr, stream=0):
+        """src_ptr / dst_ptr: device addresses (e.g. tensor.data_ptr()); stream: hipStream_t as int."""
+        _check(lib().lc_plan_execute(self._h, src_ptr, dst_ptr, stream), "lc_plan_execute")
+
+    def time(self, src_ptrs, dst_ptrs, warmup, iters, stream=0):
+        n = len(src_ptrs)
+        a = (ctypes.c_void_p * n)(*src_ptrs)
+        b = (ctypes.c_void_p * n)(*dst_ptrs)
+        ms = ctypes.c_float()
+        _check(lib().lc_plan_time(self._h, a, b, n, warmup, iters, stream, ctypes.byref(ms)), "lc_plan_time")
+        return ms.value
+
+    def debug_replay_on_host(self, src, dst):
+        """Test instrumentation: walk the plan's index arithmetic over numpy arrays on the host
+        (bounds-checked); returns the modelled LDS bank-conflict cycles of one tile."""
+        c = ctypes.c_int64()
+        _check(lib().lc_debug_replay_on_host(self._h, src.ctypes.data_as(ctypes.c_void_p), src.size,
+                                             dst.ctypes.data_as(ctypes.c_void_p), dst.size, ctypes.byref(c)),
+               "lc_debug_replay_on_host")
+        return c.value
+
+
+def lc_copy(src_ptr, src_layout, dst_ptr, dst_layout, dtype, stream=0):
+    """COPY on the GPU: dst(i) = src(i) for device pointers src_ptr / dst_ptr."""
+    sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
+    _check(lib().lc_copy(src_ptr, sl._h, dst_ptr, dl._h, DTYPES[dtype], stream), "lc_copy(%s -> %s)" % (sl, dl))
+
+
+def copy_tensor(src, src_layout, dst, dst_layout, dtype=None):
+    """Convenience for torch tensors on the GPU: takes data pointers and torch's current stream."""
+    import torch
+    if not (src.is_cuda and dst.is_cuda):
+        raise RuntimeError("copy_tensor needs GPU tensors: the copy only runs in the HIP kernels")
+    if dtype is None:
+        dtype = {4: "b32", 2: "b16", 1: "b8", 8: "b64"}[src.element_size()]
+    sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
+    if sl.cosize > src.numel() or dl.cosize > dst.numel():
+        raise ValueError("tensor smaller than the layout's cosize")
+    lc_copy(src.data_ptr(), sl, dst.data_ptr(), dl, dtype, torch.cuda.current_stream().cuda_stream)

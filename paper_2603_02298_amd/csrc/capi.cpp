@@ -1,0 +1,218 @@
+// extern "C" boundary of the library (include/layoutcopy.h): argument checks and marshalling only.
+#include <cstring>
+#include <new>
+
+#include "algebra.hpp"
+#include "layoutcopy.h"
+#include "plan.hpp"
+
+namespace {
+
+lc_status_t put_string(const std::string& s, char* buf, size_t cap, size_t* needed) {
+  if (needed) *needed = s.size() + 1;
+  if (buf && cap > 0) {
+    size_t n = s.size() < cap - 1 ? s.size() : cap - 1;
+    std::memcpy(buf, s.data(), n);
+    buf[n] = 0;
+  }
+  return LC_OK;
+}
+
+lc_status_t give(const lc::Layout& L, lc_layout_t** out) {
+  lc_layout_t* h = new (std::nothrow) lc_layout_t{L};
+  if (!h) return LC_ERR_INVALID_ARG;
+  *out = h;
+  return LC_OK;
+}
+
+typedef lc_status_t (*binary_op)(const lc::Layout&, const lc::Layout&, lc::Layout*);
+lc_status_t binary(binary_op op, const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) {
+  if (!a || !b || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::Layout r;
+    lc_status_t st = op(a->L, b->L, &r);
+    return st == LC_OK ? give(r, out) : st;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lc_status_string(lc_status_t s) {
+  switch (s) {
+    case LC_OK: return "OK";
+    case LC_ERR_INVALID_ARG: return "INVALID_ARG";
+    case LC_ERR_PARSE: return "PARSE";
+    case LC_ERR_NOT_CONGRUENT: return "NOT_CONGRUENT";
+    case LC_ERR_BAD_EXTENT: return "BAD_EXTENT";
+    case LC_ERR_NEGATIVE_STRIDE: return "NEGATIVE_STRIDE";
+    case LC_ERR_SIZE_MISMATCH: return "SIZE_MISMATCH";
+    case LC_ERR_STRIDE_DIVISIBILITY: return "STRIDE_DIVISIBILITY";
+    case LC_ERR_SHAPE_DIVISIBILITY: return "SHAPE_DIVISIBILITY";
+    case LC_ERR_NOT_SEGREGATED: return "NOT_SEGREGATED";
+    case LC_ERR_NOT_INJECTIVE: return "NOT_INJECTIVE";
+    case LC_ERR_NOT_SURJECTIVE: return "NOT_SURJECTIVE";
+    case LC_ERR_DST_ALIASES: return "DST_ALIASES";
+    case LC_ERR_UNSUPPORTED_DTYPE: return "UNSUPPORTED_DTYPE";
+    case LC_ERR_TOO_LARGE: return "TOO_LARGE";
+    case LC_ERR_MISALIGNED: return "MISALIGNED";
+    case LC_ERR_HIP: return "HIP";
+  }
+  return "UNKNOWN";
+}
+
+int lc_dtype_bytes(lc_dtype_t dt) {
+  switch (dt) {
+    case LC_F32: case LC_B32: return 4;
+    case LC_F16: case LC_BF16: case LC_B16: return 2;
+    case LC_B8: return 1;
+    case LC_B64: return 8;
+    case LC_B128: return 16;
+  }
+  return 0;
+}
+
+lc_status_t lc_layout_parse(const char* text, lc_layout_t** out) {
+  if (!text || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::Layout L;
+    lc_status_t st = lc::parse(text, &L);
+    return st == LC_OK ? give(L, out) : st;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
+lc_status_t lc_layout_from_tree(const int64_t* shape_preorder, int n_nodes, const int64_t* leaf_strides, int n_leaves,
+                                lc_layout_t** out) {
+  if (!shape_preorder || !leaf_strides || !out || n_nodes < 1 || n_leaves < 1) return LC_ERR_INVALID_ARG;
+  try {
+    lc::Layout L;
+    int leaf = 0;
+    for (int k = 0; k < n_nodes; ++k) {
+      int64_t v = shape_preorder[k];
+      if (v < 0) {
+        if (-v > 64) return LC_ERR_INVALID_ARG;
+        L.profile.push_back((int32_t)-v);
+      } else {
+        if (leaf >= n_leaves) return LC_ERR_NOT_CONGRUENT;
+        L.profile.push_back(0);
+        L.leaves.push_back({v, leaf_strides[leaf++]});
+      }
+    }
+    if (leaf != n_leaves) return LC_ERR_NOT_CONGRUENT;
+    lc_status_t st = lc::validate(L);
+    return st == LC_OK ? give(L, out) : st;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
+void lc_layout_destroy(lc_layout_t* layout) { delete layout; }
+
+lc_status_t lc_layout_to_string(const lc_layout_t* layout, char* buf, size_t cap, size_t* needed) {
+  if (!layout) return LC_ERR_INVALID_ARG;
+  return put_string(layout->L.str(), buf, cap, needed);
+}
+int64_t lc_layout_size(const lc_layout_t* layout) { return layout ? layout->L.size() : -1; }
+int64_t lc_layout_cosize(const lc_layout_t* layout) { return layout ? layout->L.cosize() : -1; }
+int lc_layout_rank(const lc_layout_t* layout) { return layout ? layout->L.rank() : -1; }
+int lc_layout_depth(const lc_layout_t* layout) { return layout ? layout->L.depth() : -1; }
+int64_t lc_layout_eval(const lc_layout_t* layout, int64_t i) { return (layout && i >= 0) ? layout->L(i) : -1; }
+
+lc_status_t lc_coalesce(const lc_layout_t* a, lc_layout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  return give(lc::coalesce(a->L), out);
+}
+lc_status_t lc_coalesce_bymode(const lc_layout_t* a, lc_layout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  return give(lc::coalesce_bymode(a->L), out);
+}
+lc_status_t lc_right_inverse(const lc_layout_t* a, lc_layout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  return give(lc::right_inverse(a->L), out);
+}
+lc_status_t lc_composition(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::composition, a, b, out); }
+lc_status_t lc_composition_bymode(const lc_layout_t* a, const lc_layout_t* t, lc_layout_t** out) { return binary(lc::composition_bymode, a, t, out); }
+lc_status_t lc_logical_divide(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::logical_divide, a, b, out); }
+lc_status_t lc_logical_divide_bymode(const lc_layout_t* a, const lc_layout_t* t, lc_layout_t** out) { return binary(lc::logical_divide_bymode, a, t, out); }
+lc_status_t lc_zipped_divide(const lc_layout_t* a, const lc_layout_t* t, lc_layout_t** out) { return binary(lc::zipped_divide, a, t, out); }
+
+lc_status_t lc_complement(const lc_layout_t* a, int64_t cotarget, lc_layout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  lc::Layout r;
+  lc_status_t st = lc::complement(a->L, cotarget, &r);
+  return st == LC_OK ? give(r, out) : st;
+}
+lc_status_t lc_max_common_vector(const lc_layout_t* a, const lc_layout_t* b, int64_t* K) {
+  if (!a || !b || !K) return LC_ERR_INVALID_ARG;
+  return lc::max_common_vector(a->L, b->L, K);
+}
+
+lc_status_t lc_plan_create(const lc_layout_t* src, const lc_layout_t* dst, lc_dtype_t dt, unsigned src_align_bytes,
+                           unsigned dst_align_bytes, lc_plan_t** out) {
+  if (!src || !dst || !out) return LC_ERR_INVALID_ARG;
+  int es = lc_dtype_bytes(dt);
+  if (es == 0) return LC_ERR_UNSUPPORTED_DTYPE;
+  try {
+    lc_plan_t* plan = new lc_plan_t();
+    lc_status_t st = lc::make_plan(src->L, dst->L, es, src_align_bytes, dst_align_bytes, lc::tuning_from_env(), plan);
+    if (st != LC_OK) { delete plan; return st; }
+    *out = plan;
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+lc_status_t lc_plan_describe(const lc_plan_t* plan, char* buf, size_t cap, size_t* needed) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return put_string(lc::describe(*plan), buf, cap, needed);
+}
+lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::execute_plan(*plan, src, dst, hip_stream);
+}
+void lc_plan_destroy(lc_plan_t* plan) { delete plan; }
+
+lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, const lc_layout_t* dst_layout, lc_dtype_t dt,
+                    void* hip_stream) {
+  if (!src || !dst || !src_layout || !dst_layout) return LC_ERR_INVALID_ARG;
+  auto align_of = [](const void* p) {
+    uintptr_t v = reinterpret_cast<uintptr_t>(p);
+    unsigned a = 1;
+    while (a < 256 && (v % (2 * a)) == 0) a *= 2;
+    return a;
+  };
+  int es = lc_dtype_bytes(dt);
+  if (es == 0) return LC_ERR_UNSUPPORTED_DTYPE;
+  if (align_of(src) < (unsigned)es || align_of(dst) < (unsigned)es) return LC_ERR_MISALIGNED;
+  try {
+    lc_plan_t plan;
+    lc_status_t st = lc::make_plan(src_layout->L, dst_layout->L, es, align_of(src), align_of(dst), lc::tuning_from_env(), &plan);
+    if (st != LC_OK) return st;
+    return lc::execute_plan(plan, src, dst, hip_stream);
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
+int64_t lc_plan_algorithmic_bytes(const lc_plan_t* plan) { return plan ? 2 * plan->n_elems * plan->elem_bytes : -1; }
+
+lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup, int iters,
+                         void* hip_stream, float* ms_per_iter) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::time_plan(*plan, srcs, dsts, n_buffers, warmup, iters, hip_stream, ms_per_iter);
+}
+
+// Checking device for tests: replays the plan's index arithmetic on HOST buffers (see plan.hpp).
+// Not declared in the public header; never used to execute a copy.
+lc_status_t lc_debug_replay_on_host(const lc_plan_t* plan, const void* src_host, int64_t src_elems, void* dst_host,
+                                    int64_t dst_elems, int64_t* lds_conflicts) {
+  if (!plan || !src_host || !dst_host) return LC_ERR_INVALID_ARG;
+  return lc::replay_on_host(*plan, src_host, src_elems, dst_host, dst_elems, lds_conflicts);
+}
+
+}  // extern "C"

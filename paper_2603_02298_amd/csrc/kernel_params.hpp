@@ -1,0 +1,167 @@
+// Kernel argument blocks and the index arithmetic shared by the device kernels and the host-side
+// plan checker.  Everything here is plain-old-data passed by value at launch: the planner does the
+// layout algebra once on the host, the kernels only evaluate idx2crd / inner_product
+// (Eq. idx2crd, Eq. innerprod of "CuTe Layout Representation and Algebra") on what is left.
+#pragma once
+#include <cstdint>
+
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define LC_HD __host__ __device__ inline
+#else
+#define LC_HD inline
+#endif
+
+namespace lc {
+
+constexpr int kMaxModes = 8;          // joint / rest / micro modes per kernel
+constexpr int kMaxGenericModes = 12;  // leaf modes per side in the element-wise kernel
+constexpr int kBlock = 256;           // threads per workgroup = 4 wavefronts of 64
+
+// Division of a 31-bit unsigned value by a constant: q = (mulhi(n, mul) + n) >> shift
+// (round-up multiplier of Granlund & Montgomery; exact for n < 2^31, any divisor in [1, 2^31)).
+struct FastDiv {
+  uint32_t mul, shift, div;
+};
+
+LC_HD uint32_t mulhi_u32(uint32_t a, uint32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __umulhi(a, b);
+#else
+  return (uint32_t)(((uint64_t)a * b) >> 32);
+#endif
+}
+LC_HD uint32_t fd_div(uint32_t n, const FastDiv& f) { return (mulhi_u32(n, f.mul) + n) >> f.shift; }
+// n -> (n / div, n % div)
+LC_HD void fd_divmod(uint32_t n, const FastDiv& f, uint32_t* q, uint32_t* r) {
+  *q = fd_div(n, f);
+  *r = n - *q * f.div;
+}
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.div = d;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  f.shift = l;
+  f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+  return f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Element-wise kernel: dst[L_dst(i)] = src[L_src(i)] with both (coalesced) layouts evaluated per
+// element.  Used when the two shapes have no common refinement.
+// ---------------------------------------------------------------------------------------------
+struct FlatLayoutArg {
+  int32_t n_modes;
+  FastDiv div[kMaxGenericModes];   // extents, leftmost mode first
+  int64_t stride[kMaxGenericModes];
+};
+struct GenericParams {
+  FlatLayoutArg src, dst;
+  uint32_t n;                      // elements (< 2^31)
+};
+LC_HD int64_t flat_eval(const FlatLayoutArg& L, uint32_t i) {
+  int64_t off = 0;
+  for (int k = 0; k + 1 < L.n_modes; ++k) {
+    uint32_t q, r;
+    fd_divmod(i, L.div[k], &q, &r);
+    off += (int64_t)r * L.stride[k];
+    i = q;
+  }
+  return off + (int64_t)i * L.stride[L.n_modes - 1];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct kernel: joint modes (extent, src stride, dst stride) in destination order; consecutive
+// lanes walk the destination-contiguous mode.  One work item = one access of W bytes on each side;
+// all strides are in units of W bytes.  One more mode may be looped inside the thread (a stride-0
+// source mode is then read once and written `loop_extent` times).
+// ---------------------------------------------------------------------------------------------
+struct DirectParams {
+  int32_t n_modes;
+  FastDiv div[kMaxModes];
+  int64_t sa[kMaxModes], sb[kMaxModes];
+  uint32_t loop_extent;
+  int64_t loop_sa, loop_sb;
+  uint32_t n_items;                // items excluding the looped mode (< 2^31)
+};
+LC_HD void direct_offsets(const DirectParams& P, uint32_t item, int64_t* so, int64_t* dof) {
+  int64_t s = 0, d = 0;
+  for (int k = 0; k + 1 < P.n_modes; ++k) {
+    uint32_t q, r;
+    fd_divmod(item, P.div[k], &q, &r);
+    s += (int64_t)r * P.sa[k];
+    d += (int64_t)r * P.sb[k];
+    item = q;
+  }
+  *so = s + (int64_t)item * P.sa[P.n_modes - 1];
+  *dof = d + (int64_t)item * P.sb[P.n_modes - 1];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transpose kernel: the source-contiguous mode p and the destination-contiguous mode q differ.
+// A tile is a box of the joint modes; it is cut into V x V micro-tiles (V elements along p times V
+// along q).  A lane loads V vectors along p (one per q step), transposes them in registers, and
+// parks V vectors along q in LDS; after a barrier lanes pick the vectors up in destination order.
+// Micro-tile coordinates are decoded twice: in source order (loads) and in destination order (stores).
+// ---------------------------------------------------------------------------------------------
+struct TransposeParams {
+  int32_t n_micro_modes;
+  // source-order decode of the micro-tile index u: extents, source stride (elements) and the
+  // weight of the mode in the destination-order micro-tile index
+  uint32_t ext_s[kMaxModes];
+  int32_t sa_s[kMaxModes];
+  uint32_t dpos_s[kMaxModes];
+  // destination-order decode of the micro-tile index w
+  uint32_t ext_d[kMaxModes];
+  int32_t sb_d[kMaxModes];
+  uint32_t n_micro;                // micro-tiles per tile
+  int32_t a_q;                     // source stride of one step along q (elements)
+  int32_t b_p;                     // destination stride of one step along p (elements)
+  // LDS: V planes (one per position along p) of plane_slots vectors; slot = c ^ ((c >> swz_shift) & swz_mask)
+  uint32_t plane_slots, swz_shift, swz_mask;
+  // tiles: the rest modes of zipped_divide; the tile id is their colexicographic index
+  int32_t n_rest;
+  FastDiv rdiv[kMaxModes];
+  int64_t ra[kMaxModes], rb[kMaxModes];
+  uint32_t n_tiles;
+};
+LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t c) { return c ^ ((c >> P.swz_shift) & P.swz_mask); }
+// micro-tile u (source order) -> source offset inside the tile and destination-order index
+LC_HD void micro_from_src_order(const TransposeParams& P, uint32_t u, int32_t* src_off, uint32_t* c) {
+  int32_t s = 0;
+  uint32_t cc = 0;
+  for (int k = 0; k < P.n_micro_modes; ++k) {
+    uint32_t r = u % P.ext_s[k];
+    u /= P.ext_s[k];
+    s += (int32_t)r * P.sa_s[k];
+    cc += r * P.dpos_s[k];
+  }
+  *src_off = s;
+  *c = cc;
+}
+// micro-tile w (destination order) -> destination offset inside the tile
+LC_HD int32_t micro_dst_offset(const TransposeParams& P, uint32_t w) {
+  int32_t d = 0;
+  for (int k = 0; k < P.n_micro_modes; ++k) {
+    uint32_t r = w % P.ext_d[k];
+    w /= P.ext_d[k];
+    d += (int32_t)r * P.sb_d[k];
+  }
+  return d;
+}
+// tile id -> offsets of the tile's origin (slicing the rest mode: the coordinate is folded into the accessor, Sec. 2.5.1)
+LC_HD void tile_origin(const TransposeParams& P, uint32_t tile, int64_t* so, int64_t* dof) {
+  int64_t s = 0, d = 0;
+  for (int k = 0; k < P.n_rest; ++k) {
+    uint32_t q, r;
+    fd_divmod(tile, P.rdiv[k], &q, &r);
+    s += (int64_t)r * P.ra[k];
+    d += (int64_t)r * P.rb[k];
+    tile = q;
+  }
+  *so = s;
+  *dof = d;
+}
+
+}  // namespace lc

@@ -1,0 +1,335 @@
+// HIP kernels for gfx950 (CDNA4, wave64) that execute a planned COPY (Sec. 2.6.1 of "CuTe Layout
+// Representation and Algebra"): dst(i) = src(i) with the iteration order permuted consistently on
+// both sides (Sec. 3.4.2) so that global accesses are wide and coalesced.  No MFMA: the work is
+// pure data movement and is bounded by HBM bandwidth.
+#include <hip/hip_runtime.h>
+
+#include "kernel_params.hpp"
+#include "plan.hpp"
+
+namespace lc {
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int W> struct Word;
+template <> struct Word<1> { typedef uint8_t type; };
+template <> struct Word<2> { typedef uint16_t type; };
+template <> struct Word<4> { typedef uint32_t type; };
+template <> struct Word<8> { typedef u32x2 type; };
+template <> struct Word<16> { typedef u32x4 type; };
+
+template <bool NT, typename T>
+__device__ __forceinline__ T gload(const T* p) {
+  if (NT) return __builtin_nontemporal_load(p);
+  return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void gstore(T* p, T v) {
+  if (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Element-wise: both layouts evaluated per element (idx2crd + inner_product, Eq. idx2crd / Eq. innerprod).
+// ---------------------------------------------------------------------------------------------
+template <int ES>
+__global__ __launch_bounds__(kBlock) void generic_kernel(GenericParams P, const typename Word<ES>::type* __restrict__ src,
+                                                        typename Word<ES>::type* __restrict__ dst) {
+  const uint32_t step = gridDim.x * kBlock;
+  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < P.n; i += step) dst[flat_eval(P.dst, i)] = src[flat_eval(P.src, i)];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Direct: one W-byte access per item and side; lanes are consecutive along the destination order.
+// U items are in flight per lane; an optional looped mode re-uses a loaded value when its source
+// stride is zero (broadcast).
+// ---------------------------------------------------------------------------------------------
+template <int W, int U, bool NT>
+__global__ __launch_bounds__(kBlock) void direct_kernel(DirectParams P, const typename Word<W>::type* __restrict__ src,
+                                                       typename Word<W>::type* __restrict__ dst) {
+  typedef typename Word<W>::type T;
+  const uint32_t step = gridDim.x * kBlock;
+  for (uint32_t base = blockIdx.x * kBlock + threadIdx.x; base < P.n_items; base += step * U) {
+    int64_t so[U], dof[U];
+    bool ok[U];
+    T v[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      uint32_t it = base + (uint32_t)j * step;
+      ok[j] = it < P.n_items;
+      so[j] = dof[j] = 0;
+      if (ok[j]) direct_offsets(P, it, &so[j], &dof[j]);
+    }
+    if (P.loop_extent == 1) {
+#pragma unroll
+      for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j]);
+#pragma unroll
+      for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j], v[j]);
+    } else if (P.loop_sa == 0) {
+#pragma unroll
+      for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j]);
+      for (uint32_t r = 0; r < P.loop_extent; ++r) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j] + (int64_t)r * P.loop_sb, v[j]);
+      }
+    } else {
+      for (uint32_t r = 0; r < P.loop_extent; ++r) {
+#pragma unroll
+        for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j] + (int64_t)r * P.loop_sa);
+#pragma unroll
+        for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j] + (int64_t)r * P.loop_sb, v[j]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transpose through LDS.  Persistent workgroups walk the grid of tiles (the rest mode of
+// zipped_divide, Sec. 3.5.2); per tile each lane owns MT micro-tiles of V x V elements.
+//   load : V global loads of V*ES bytes along the source-contiguous mode p (one per step along q)
+//   park : register transpose, V LDS writes of V*ES bytes (now contiguous along q), XOR-swizzled slots
+//   store: V LDS reads and V global stores of V*ES bytes along the destination-contiguous mode q
+// The loads of the next tile are issued before the stores of the current one.
+// ---------------------------------------------------------------------------------------------
+template <int ES, int V>
+__device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 4], uint32_t (&o)[V][V * ES / 4]) {
+  if (ES == 4) {
+#pragma unroll
+    for (int ip = 0; ip < V; ++ip)
+#pragma unroll
+      for (int iq = 0; iq < V; ++iq) o[ip][iq] = r[iq][ip];
+  } else {  // ES == 2: two elements per dword
+#pragma unroll
+    for (int ip = 0; ip < V; ++ip)
+#pragma unroll
+      for (int j = 0; j < V / 2; ++j) {
+        uint32_t lo = r[2 * j][ip / 2], hi = r[2 * j + 1][ip / 2];
+        o[ip][j] = (ip % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
+      }
+  }
+}
+
+template <int ES, int V, int MT, bool NT>
+__global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
+                                                          unsigned char* __restrict__ dst) {
+  constexpr int DW = V * ES / 4;                 // dwords per vector
+  constexpr int SLOT = V * ES;                   // bytes per vector
+  typedef typename Word<SLOT>::type Vec;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+  // tile-invariant lane state (wavefront-level index arithmetic done once)
+  int32_t src_in[MT], dst_in[MT];
+  uint32_t park_at[MT], pick_at[MT];
+  bool act[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    uint32_t u = threadIdx.x + (uint32_t)m * kBlock;
+    act[m] = u < P.n_micro;
+    src_in[m] = dst_in[m] = 0;
+    park_at[m] = pick_at[m] = 0;
+    if (act[m]) {
+      uint32_t c;
+      micro_from_src_order(P, u, &src_in[m], &c);
+      park_at[m] = lds_slot(P, c) * SLOT;
+      dst_in[m] = micro_dst_offset(P, u);
+      pick_at[m] = lds_slot(P, u) * SLOT;
+    }
+  }
+  const uint32_t plane_bytes = P.plane_slots * SLOT;
+
+  uint32_t r[MT][V][DW];
+  auto load_tile = [&](uint32_t tile) {
+    int64_t so, dof;
+    tile_origin(P, tile, &so, &dof);
+    const unsigned char* base = src + so * ES;
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      if (act[m]) {
+#pragma unroll
+        for (int iq = 0; iq < V; ++iq) {
+          Vec v = gload<NT>(reinterpret_cast<const Vec*>(base + ((int64_t)src_in[m] + (int64_t)iq * P.a_q) * ES));
+          const uint32_t* w = reinterpret_cast<const uint32_t*>(&v);
+#pragma unroll
+          for (int k = 0; k < DW; ++k) r[m][iq][k] = w[k];
+        }
+      }
+  };
+
+  uint32_t tile = blockIdx.x;
+  if (tile < P.n_tiles) load_tile(tile);
+  while (tile < P.n_tiles) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      if (act[m]) {
+        uint32_t o[V][DW];
+        micro_transpose<ES, V>(r[m], o);
+#pragma unroll
+        for (int ip = 0; ip < V; ++ip) {
+          Vec v;
+          uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+          for (int k = 0; k < DW; ++k) w[k] = o[ip][k];
+          *reinterpret_cast<Vec*>(lds + (uint32_t)ip * plane_bytes + park_at[m]) = v;
+        }
+      }
+    __syncthreads();
+    int64_t so, dof;
+    tile_origin(P, tile, &so, &dof);
+    const uint32_t next = tile + gridDim.x;
+    if (next < P.n_tiles) load_tile(next);
+    unsigned char* base = dst + dof * ES;
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      if (act[m]) {
+#pragma unroll
+        for (int ip = 0; ip < V; ++ip) {
+          Vec v = *reinterpret_cast<const Vec*>(lds + (uint32_t)ip * plane_bytes + pick_at[m]);
+          gstore<NT>(reinterpret_cast<Vec*>(base + ((int64_t)dst_in[m] + (int64_t)ip * P.b_p) * ES), v);
+        }
+      }
+    __syncthreads();
+    tile = next;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------------
+static int device_cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+    cus = n;
+  }
+  return cus;
+}
+
+template <int ES>
+static void launch_generic(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  typedef typename Word<ES>::type T;
+  hipLaunchKernelGGL(generic_kernel<ES>, dim3(grid), dim3(kBlock), 0, s, plan.generic, static_cast<const T*>(src), static_cast<T*>(dst));
+}
+
+template <int W, int U>
+static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  typedef typename Word<W>::type T;
+  if (plan.nontemporal)
+    hipLaunchKernelGGL((direct_kernel<W, U, true>), dim3(grid), dim3(kBlock), 0, s, plan.direct, static_cast<const T*>(src), static_cast<T*>(dst));
+  else
+    hipLaunchKernelGGL((direct_kernel<W, U, false>), dim3(grid), dim3(kBlock), 0, s, plan.direct, static_cast<const T*>(src), static_cast<T*>(dst));
+}
+template <int W>
+static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  switch (plan.unroll) {
+    case 1: launch_direct_u<W, 1>(plan, src, dst, grid, s); break;
+    case 2: launch_direct_u<W, 2>(plan, src, dst, grid, s); break;
+    case 8: launch_direct_u<W, 8>(plan, src, dst, grid, s); break;
+    default: launch_direct_u<W, 4>(plan, src, dst, grid, s); break;
+  }
+}
+
+template <int ES, int V, int MT>
+static hipError_t launch_transpose_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  const unsigned char* sp = static_cast<const unsigned char*>(src);
+  unsigned char* dp = static_cast<unsigned char*>(dst);
+  if (plan.lds_bytes > 64 * 1024) {
+    static bool raised_nt = false, raised = false;   // per instantiation
+    bool& flag = plan.nontemporal ? raised_nt : raised;
+    if (!flag) {
+      hipError_t e = plan.nontemporal
+          ? hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
+          : hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+      flag = true;
+    }
+  }
+  if (plan.nontemporal)
+    hipLaunchKernelGGL((transpose_kernel<ES, V, MT, true>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  else
+    hipLaunchKernelGGL((transpose_kernel<ES, V, MT, false>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  return hipSuccess;
+}
+template <int ES, int V>
+static hipError_t launch_transpose(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  switch (plan.micro_per_thread) {
+    case 1: return launch_transpose_m<ES, V, 1>(plan, src, dst, grid, s);
+    case 2: return launch_transpose_m<ES, V, 2>(plan, src, dst, grid, s);
+    case 4: return launch_transpose_m<ES, V, 4>(plan, src, dst, grid, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream) {
+  if (!src || !dst) return LC_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(src) % plan.src_align) != 0 || (reinterpret_cast<uintptr_t>(dst) % plan.dst_align) != 0)
+    return LC_ERR_MISALIGNED;
+  const int cus = device_cu_count();
+  if (cus <= 0) return LC_ERR_HIP;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  hipError_t pre = hipSuccess;
+  if (plan.cls == KernelClass::Generic) {
+    uint64_t want = ((uint64_t)plan.generic.n + kBlock - 1) / kBlock;
+    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, (uint64_t)cus * 16));
+    switch (plan.elem_bytes) {
+      case 1: launch_generic<1>(plan, src, dst, grid, s); break;
+      case 2: launch_generic<2>(plan, src, dst, grid, s); break;
+      case 4: launch_generic<4>(plan, src, dst, grid, s); break;
+      case 8: launch_generic<8>(plan, src, dst, grid, s); break;
+      case 16: launch_generic<16>(plan, src, dst, grid, s); break;
+      default: return LC_ERR_UNSUPPORTED_DTYPE;
+    }
+  } else if (plan.cls == KernelClass::Direct) {
+    uint64_t want = ((uint64_t)plan.direct.n_items + (uint64_t)kBlock * plan.unroll - 1) / ((uint64_t)kBlock * plan.unroll);
+    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, (uint64_t)cus * plan.wgs_per_cu));
+    switch (plan.width_bytes) {
+      case 1: launch_direct<1>(plan, src, dst, grid, s); break;
+      case 2: launch_direct<2>(plan, src, dst, grid, s); break;
+      case 4: launch_direct<4>(plan, src, dst, grid, s); break;
+      case 8: launch_direct<8>(plan, src, dst, grid, s); break;
+      case 16: launch_direct<16>(plan, src, dst, grid, s); break;
+      default: return LC_ERR_UNSUPPORTED_DTYPE;
+    }
+  } else {
+    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(plan.transpose.n_tiles, (uint64_t)cus * plan.wgs_per_cu));
+    const int key = plan.elem_bytes * 100 + plan.V;
+    switch (key) {
+      case 404: pre = launch_transpose<4, 4>(plan, src, dst, grid, s); break;
+      case 402: pre = launch_transpose<4, 2>(plan, src, dst, grid, s); break;
+      case 208: pre = launch_transpose<2, 8>(plan, src, dst, grid, s); break;
+      case 204: pre = launch_transpose<2, 4>(plan, src, dst, grid, s); break;
+      case 202: pre = launch_transpose<2, 2>(plan, src, dst, grid, s); break;
+      default: return LC_ERR_UNSUPPORTED_DTYPE;
+    }
+  }
+  if (pre != hipSuccess || hipGetLastError() != hipSuccess) return LC_ERR_HIP;
+  return LC_OK;
+}
+
+lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
+                      int iters, void* stream, float* ms_per_iter) {
+  if (!srcs || !dsts || n_buffers < 1 || iters < 1 || warmup < 0 || !ms_per_iter) return LC_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return LC_ERR_HIP;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return LC_ERR_HIP; }
+  lc_status_t st = LC_OK;
+  int b = 0;
+  for (int i = 0; i < warmup && st == LC_OK; ++i, b = (b + 1) % n_buffers) st = execute_plan(plan, srcs[b], dsts[b], stream);
+  if (st == LC_OK && hipEventRecord(e0, s) != hipSuccess) st = LC_ERR_HIP;
+  for (int i = 0; i < iters && st == LC_OK; ++i, b = (b + 1) % n_buffers) st = execute_plan(plan, srcs[b], dsts[b], stream);
+  if (st == LC_OK && hipEventRecord(e1, s) != hipSuccess) st = LC_ERR_HIP;
+  if (st == LC_OK && hipEventSynchronize(e1) != hipSuccess) st = LC_ERR_HIP;
+  float ms = 0.f;
+  if (st == LC_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) st = LC_ERR_HIP;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (st == LC_OK) *ms_per_iter = ms / (float)iters;
+  return st;
+}
+
+}  // namespace lc

@@ -1,0 +1,510 @@
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+namespace lc {
+
+static int env_int(const char* name, int dflt) {
+  const char* v = std::getenv(name);
+  return (v && *v) ? std::atoi(v) : dflt;
+}
+
+Tuning tuning_from_env() {
+  Tuning t;
+  t.micro_per_thread = env_int("LC_TUNE_MICRO_PER_THREAD", t.micro_per_thread);
+  t.rest_order = env_int("LC_TUNE_REST_ORDER", t.rest_order);
+  t.wgs_per_cu = env_int("LC_TUNE_WGS_PER_CU", t.wgs_per_cu);
+  t.unroll = env_int("LC_TUNE_UNROLL", t.unroll);
+  t.swizzle_shift = env_int("LC_TUNE_SWIZZLE_SHIFT", t.swizzle_shift);
+  t.nontemporal = env_int("LC_TUNE_NONTEMPORAL", t.nontemporal);
+  t.force_class = env_int("LC_TUNE_FORCE_CLASS", t.force_class);
+  t.max_vec_bytes = env_int("LC_TUNE_MAX_VEC_BYTES", t.max_vec_bytes);
+  return t;
+}
+
+// ---------------------------------------------------------------------------------------------
+// a1: is the destination layout injective?  Nested strides prove it; otherwise small layouts are
+// enumerated and large ones are refused.
+// ---------------------------------------------------------------------------------------------
+static bool dst_is_injective(const Modes& coalesced, int64_t n) {
+  Modes m;
+  for (const Mode& x : coalesced) {
+    if (x.extent == 1) continue;
+    if (x.stride == 0) return false;
+    m.push_back(x);
+  }
+  std::stable_sort(m.begin(), m.end(), [](const Mode& x, const Mode& y) { return x.stride < y.stride; });
+  bool nested = true;
+  int64_t covered = 1;
+  for (const Mode& x : m) {
+    if (x.stride < covered) nested = false;
+    covered = x.stride * (x.extent - 1) + covered;   // largest offset so far + 1
+  }
+  if (nested) return true;
+  if (n > (1 << 22)) return false;   // cannot be proved cheaply: refuse rather than risk a race
+  std::vector<int64_t> offs((size_t)n);
+  Layout L = Layout::flat(coalesced);
+  for (int64_t i = 0; i < n; ++i) offs[(size_t)i] = L(i);
+  std::sort(offs.begin(), offs.end());
+  return std::adjacent_find(offs.begin(), offs.end()) == offs.end();
+}
+
+// ---------------------------------------------------------------------------------------------
+// a3: the coarsest shape that refines both flat shapes (mixed-radix boundaries must nest).
+// ---------------------------------------------------------------------------------------------
+static bool common_refinement(const Modes& S, const Modes& D, std::vector<int64_t>* F) {
+  size_t i = 0, j = 0;
+  int64_t x = S[0].extent, y = D[0].extent;
+  for (;;) {
+    int64_t g = std::min(x, y);
+    if (x % g != 0 || y % g != 0) return false;
+    F->push_back(g);
+    x /= g;
+    y /= g;
+    if (x == 1) { if (++i < S.size()) x = S[i].extent; }
+    if (y == 1) { if (++j < D.size()) y = D[j].extent; }
+    if (i == S.size() || j == D.size()) break;
+  }
+  return i == S.size() && j == D.size();
+}
+
+static int pow2_floor(int64_t v) { int p = 1; while (2 * p <= v) p *= 2; return p; }
+
+// Largest power of two <= cap that divides every listed quantity.
+static int common_pow2(int cap, const std::vector<int64_t>& must_divide) {
+  int v = pow2_floor(cap);
+  for (; v > 1; v /= 2) {
+    bool ok = true;
+    for (int64_t x : must_divide) if (x % v != 0) { ok = false; break; }
+    if (ok) break;
+  }
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS bank model used to pick the swizzle (and reported by the host replay): 64 banks of 4 bytes;
+// a wavefront access of b bytes per lane is served in passes of 256/b consecutive lanes; inside a
+// pass a bank serves one distinct dword address per cycle.  Cost = extra cycles.
+// ---------------------------------------------------------------------------------------------
+int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes) {
+  int per_pass = 256 / access_bytes;
+  if (per_pass > 64) per_pass = 64;
+  int cost = 0;
+  for (int base = 0; base < lanes; base += per_pass) {
+    uint32_t seen[64][8];
+    int cnt[64];
+    std::memset(cnt, 0, sizeof(cnt));
+    for (int l = base; l < base + per_pass && l < lanes; ++l) {
+      if (!active[l]) continue;
+      for (int w = 0; w < access_bytes / 4 || (w == 0 && access_bytes < 4); ++w) {
+        uint32_t dword = byte_addr[l] / 4 + (uint32_t)w;
+        int bank = (int)(dword % 64);
+        bool dup = false;
+        for (int k = 0; k < cnt[bank] && k < 8; ++k) if (seen[bank][k] == dword) dup = true;
+        if (!dup) { if (cnt[bank] < 8) seen[bank][cnt[bank]] = dword; cnt[bank]++; }
+      }
+    }
+    int worst = 1;
+    for (int b = 0; b < 64; ++b) worst = std::max(worst, cnt[b]);
+    cost += worst - 1;
+  }
+  return cost;
+}
+
+static int transpose_swizzle_cost(const TransposeParams& P, int V, int es, int micro_per_thread) {
+  // writes: lane u parks its V vectors at plane ip, slot(c(u)); reads: lane w picks slot(w)
+  int cost = 0;
+  int slot_bytes = V * es;
+  uint32_t waves = std::min<uint32_t>((P.n_micro + 63) / 64, 4u * (uint32_t)micro_per_thread);
+  for (uint32_t wv = 0; wv < waves; ++wv) {
+    uint32_t wa[64], ra[64];
+    bool act[64];
+    for (int l = 0; l < 64; ++l) {
+      uint32_t u = wv * 64 + (uint32_t)l;
+      act[l] = u < P.n_micro;
+      int32_t so;
+      uint32_t c = 0;
+      if (act[l]) micro_from_src_order(P, u, &so, &c);
+      wa[l] = lds_slot(P, c) * (uint32_t)slot_bytes;
+      ra[l] = lds_slot(P, u) * (uint32_t)slot_bytes;
+    }
+    cost += lds_pass_conflicts(wa, act, 64, slot_bytes) + lds_pass_conflicts(ra, act, 64, slot_bytes);
+  }
+  return cost;
+}
+
+// Contiguous run length (elements) of a tile along one side: follow the modes in stride order
+// starting at stride 1 while each is fully inside the tile and the next continues it.
+static int64_t run_length(const std::vector<JointMode>& J, const std::vector<int64_t>& t, bool src_side) {
+  std::vector<int> order;
+  for (int k = 0; k < (int)J.size(); ++k) order.push_back(k);
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+    return (src_side ? J[(size_t)x].a : J[(size_t)x].b) < (src_side ? J[(size_t)y].a : J[(size_t)y].b);
+  });
+  int64_t run = 1, expect = 1;
+  for (int k : order) {
+    int64_t st = src_side ? J[(size_t)k].a : J[(size_t)k].b;
+    if (st == 0) continue;
+    if (st != expect) break;
+    run *= t[(size_t)k];
+    if (t[(size_t)k] < J[(size_t)k].extent) break;
+    expect = st * J[(size_t)k].extent;
+  }
+  return run;
+}
+
+static int64_t smallest_prime_factor(int64_t v) {
+  for (int64_t f = 2; f * f <= v; ++f) if (v % f == 0) return f;
+  return v;
+}
+
+static void fill_flat_arg(const Modes& m, FlatLayoutArg* out) {
+  out->n_modes = (int32_t)m.size();
+  for (size_t k = 0; k < m.size(); ++k) {
+    out->div[k] = make_fastdiv((uint32_t)m[k].extent);
+    out->stride[k] = m[k].stride;
+  }
+}
+
+static lc_status_t plan_generic(const Modes& S, const Modes& D, int64_t n, lc_plan* plan, const std::string& why) {
+  if (S.size() > (size_t)kMaxGenericModes || D.size() > (size_t)kMaxGenericModes || n >= (1ll << 31)) return LC_ERR_TOO_LARGE;
+  plan->cls = KernelClass::Generic;
+  fill_flat_arg(S, &plan->generic.src);
+  fill_flat_arg(D, &plan->generic.dst);
+  plan->generic.n = (uint32_t)n;
+  plan->width_bytes = plan->elem_bytes;
+  plan->note = why;
+  return LC_OK;
+}
+
+static bool transpose_instantiated(int es, int V) {
+  return (es == 4 && (V == 4 || V == 2)) || (es == 2 && (V == 8 || V == 4 || V == 2));
+}
+
+lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src_align, unsigned dst_align,
+                      const Tuning& tune, lc_plan* plan) {
+  if (src.size() != dst.size()) return LC_ERR_SIZE_MISMATCH;             // @pre size(src) == size(dst)
+  if (es != 1 && es != 2 && es != 4 && es != 8 && es != 16) return LC_ERR_UNSUPPORTED_DTYPE;
+  if (src_align == 0 || dst_align == 0 || (src_align & (src_align - 1)) || (dst_align & (dst_align - 1)))
+    return LC_ERR_INVALID_ARG;
+  const int64_t n = dst.size();
+  plan->elem_bytes = es;
+  plan->n_elems = n;
+  plan->src_align = std::min(src_align, 256u);
+  plan->dst_align = std::min(dst_align, 256u);
+  plan->nontemporal = tune.nontemporal > 0;
+
+  // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
+  Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
+  // a1: the destination must be injective, otherwise the result would depend on the iteration order
+  if (n > 1 && !dst_is_injective(D, n)) return LC_ERR_DST_ALIASES;
+
+  // a5 (the paper's route): K = stride-1 head of src o dst^ (Sec. 3.4.2); kept for reporting and
+  // cross-checked against the joint modes below
+  int64_t K = 1;
+  if (max_common_vector(src, dst, &K) != LC_OK) K = 1;
+  plan->common_vector = K;
+
+  // a3: refine both shapes to one shape F by composing each layout with the identity layout of F
+  // (Sec. 3.3.1); then every mode of F has one stride on each side.
+  std::vector<int64_t> F;
+  if (!common_refinement(S, D, &F)) return plan_generic(S, D, n, plan, "shapes have no common refinement");
+  Modes ident;
+  {
+    int64_t run = 1;
+    for (int64_t e : F) { ident.push_back({e, run}); run *= e; }
+  }
+  Layout IF = Layout::flat(ident), Sr, Dr;
+  if (composition(Layout::flat(S), IF, &Sr) != LC_OK || composition(Layout::flat(D), IF, &Dr) != LC_OK ||
+      Sr.leaves.size() != F.size() || Dr.leaves.size() != F.size())
+    return plan_generic(S, D, n, plan, "refinement by composition was not admissible");
+  std::vector<JointMode> J;
+  for (size_t k = 0; k < F.size(); ++k)
+    if (F[k] > 1) J.push_back({F[k], Sr.leaves[k].stride, Dr.leaves[k].stride});
+  if (J.empty()) J.push_back({1, 0, 0});
+
+  // a4: the same permutation on both sides leaves COPY unchanged (Sec. 3.4.2): order by destination
+  // stride, then merge neighbours that continue each other on both sides.
+  std::stable_sort(J.begin(), J.end(), [](const JointMode& x, const JointMode& y) { return x.b != y.b ? x.b < y.b : x.a < y.a; });
+  {
+    std::vector<JointMode> merged;
+    for (const JointMode& m : J) {
+      if (!merged.empty() && m.a == merged.back().extent * merged.back().a && m.b == merged.back().extent * merged.back().b)
+        merged.back().extent *= m.extent;
+      else
+        merged.push_back(m);
+    }
+    J = merged;
+  }
+  plan->joint = J;
+  if (J.size() > (size_t)kMaxModes) return plan_generic(S, D, n, plan, "more joint modes than the tiled kernels index");
+
+  const int nj = (int)J.size();
+  int q = -1, p = -1;
+  for (int k = 0; k < nj; ++k) {
+    if (q < 0 && J[(size_t)k].b == 1) q = k;
+    if (p < 0 && J[(size_t)k].a == 1) p = k;
+  }
+  int cap = 16 / es;
+  if (tune.max_vec_bytes > 0) cap = std::max(1, std::min(cap, tune.max_vec_bytes / es));
+  cap = std::max(1, std::min<int>(cap, (int)std::min(plan->src_align, plan->dst_align) / es));
+
+  // ---- Transpose class: p and q exist and differ -------------------------------------------
+  bool want_transpose = (p >= 0 && q >= 0 && p != q) && tune.force_class != 0 && tune.force_class != 1;
+  if (want_transpose) {
+    std::vector<int64_t> need = {J[(size_t)p].extent, J[(size_t)q].extent};
+    for (int k = 0; k < nj; ++k) {
+      if (k != p) need.push_back(J[(size_t)k].a);
+      if (k != q) need.push_back(J[(size_t)k].b);
+    }
+    int V = common_pow2(cap, need);
+    while (V >= 2 && !transpose_instantiated(es, V)) V /= 2;
+    if (V >= 2) {
+      int mpt = tune.micro_per_thread > 0 ? tune.micro_per_thread : 1;
+      if (mpt != 1 && mpt != 2 && mpt != 4) mpt = 1;
+      const int64_t target = (int64_t)kBlock * mpt;
+      // a6: grow the tile one prime factor at a time, always helping the shorter contiguous run
+      std::vector<int64_t> t((size_t)nj, 1);
+      t[(size_t)p] = V;
+      t[(size_t)q] = V;
+      int64_t micro = 1;
+      for (;;) {
+        int best = -1;
+        int64_t best_min = -1, best_sum = -1, best_f = 1;
+        for (int k = 0; k < nj; ++k) {
+          int64_t left = J[(size_t)k].extent / t[(size_t)k];
+          if (left <= 1) continue;
+          int64_t f = smallest_prime_factor(left);
+          if (micro * f > target) continue;
+          t[(size_t)k] *= f;
+          int64_t rs = run_length(J, t, true), rd = run_length(J, t, false);
+          t[(size_t)k] /= f;
+          int64_t mn = std::min(rs, rd), sm = rs + rd;
+          if (mn > best_min || (mn == best_min && sm > best_sum)) { best = k; best_min = mn; best_sum = sm; best_f = f; }
+        }
+        if (best < 0) break;
+        int64_t cur_min = std::min(run_length(J, t, true), run_length(J, t, false));
+        int64_t cur_sum = run_length(J, t, true) + run_length(J, t, false);
+        if (best_min <= cur_min && best_sum <= cur_sum) break;   // growing further no longer lengthens any run
+        t[(size_t)best] *= best_f;
+        micro *= best_f;
+      }
+      // no run can be lengthened any more: still fill the workgroup, smallest destination strides first
+      for (int k = 0; k < nj; ++k)
+        for (;;) {
+          int64_t left = J[(size_t)k].extent / t[(size_t)k];
+          int64_t f = left > 1 ? smallest_prime_factor(left) : 0;
+          if (f == 0 || micro * f > target) break;
+          t[(size_t)k] *= f;
+          micro *= f;
+        }
+      // tiling = zipped_divide of both joint layouts by the tile extents (Sec. 3.5.2): mode 0 is
+      // the tile, mode 1 the grid of tiles; a workgroup slices mode 1 with its tile id.
+      Modes js, jd, tl;
+      for (int k = 0; k < nj; ++k) {
+        js.push_back({J[(size_t)k].extent, J[(size_t)k].a});
+        jd.push_back({J[(size_t)k].extent, J[(size_t)k].b});
+        tl.push_back({t[(size_t)k], 1});
+      }
+      Layout zs, zd;
+      Layout tiler = nj == 1 ? Layout::tuple({Layout::flat(tl)}) : Layout::flat(tl);
+      Layout jsl = nj == 1 ? Layout::tuple({Layout::flat(js)}) : Layout::flat(js);
+      Layout jdl = nj == 1 ? Layout::tuple({Layout::flat(jd)}) : Layout::flat(jd);
+      bool ok = zipped_divide(jsl, tiler, &zs) == LC_OK && zipped_divide(jdl, tiler, &zd) == LC_OK;
+      Layout ts, td, rs_, rd_;
+      if (ok) {
+        ts = zs.mode(0); td = zd.mode(0); rs_ = zs.mode(1); rd_ = zd.mode(1);
+        ok = ts.leaves.size() == (size_t)nj && td.leaves.size() == (size_t)nj && rs_.leaves.size() == rd_.leaves.size();
+      }
+      TransposeParams& P = plan->transpose;
+      std::memset(&P, 0, sizeof(P));
+      int64_t max_in_tile = 0;
+      if (ok) {
+        // micro modes: the tile box with V taken out of p and q
+        struct MM { int64_t ext, sa, sb; bool is_p, is_q; };
+        std::vector<MM> mm;
+        for (int k = 0; k < nj; ++k) {
+          int64_t te = ts.leaves[(size_t)k].extent, ta = ts.leaves[(size_t)k].stride, tb = td.leaves[(size_t)k].stride;
+          if (te != t[(size_t)k] || td.leaves[(size_t)k].extent != te) { ok = false; break; }
+          max_in_tile = std::max(max_in_tile, std::max((te - 1) * ta, (te - 1) * tb));
+          int64_t ext = (k == p || k == q) ? te / V : te;
+          int64_t scale = (k == p || k == q) ? V : 1;
+          if (ext > 1) mm.push_back({ext, ta * scale, tb * scale, k == p, k == q});
+        }
+        int64_t span_s = 0, span_d = 0;
+        for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * J[(size_t)k].a; span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
+        if (span_s >= (1ll << 30) || span_d >= (1ll << 30) || mm.size() > (size_t)kMaxModes) ok = false;
+        if (ok) {
+          std::vector<int> so, dord;
+          for (int k = 0; k < (int)mm.size(); ++k) { so.push_back(k); dord.push_back(k); }
+          std::stable_sort(so.begin(), so.end(), [&](int x, int y) {
+            if (mm[(size_t)x].is_p != mm[(size_t)y].is_p) return mm[(size_t)x].is_p;
+            return mm[(size_t)x].sa < mm[(size_t)y].sa; });
+          std::stable_sort(dord.begin(), dord.end(), [&](int x, int y) {
+            if (mm[(size_t)x].is_q != mm[(size_t)y].is_q) return mm[(size_t)x].is_q;
+            return mm[(size_t)x].sb < mm[(size_t)y].sb; });
+          std::vector<uint32_t> dpos(mm.size(), 0);
+          uint32_t run = 1;
+          for (size_t j = 0; j < dord.size(); ++j) {
+            const MM& m = mm[(size_t)dord[j]];
+            P.ext_d[j] = (uint32_t)m.ext;
+            P.sb_d[j] = (int32_t)m.sb;
+            dpos[(size_t)dord[j]] = run;
+            run *= (uint32_t)m.ext;
+          }
+          for (size_t j = 0; j < so.size(); ++j) {
+            const MM& m = mm[(size_t)so[j]];
+            P.ext_s[j] = (uint32_t)m.ext;
+            P.sa_s[j] = (int32_t)m.sa;
+            P.dpos_s[j] = dpos[(size_t)so[j]];
+          }
+          P.n_micro_modes = (int32_t)mm.size();
+          P.n_micro = run;
+          P.a_q = (int32_t)J[(size_t)q].a;
+          P.b_p = (int32_t)J[(size_t)p].b;
+          if (J[(size_t)q].a * (V - 1) >= (1ll << 30) || J[(size_t)p].b * (V - 1) >= (1ll << 30)) ok = false;
+        }
+      }
+      if (ok) {
+        // rest modes = grid of tiles
+        struct RM { int64_t ext, a, b; };
+        std::vector<RM> rest;
+        for (size_t k = 0; k < rs_.leaves.size(); ++k) {
+          if (rs_.leaves[k].extent != rd_.leaves[k].extent) { ok = false; break; }
+          if (rs_.leaves[k].extent > 1) rest.push_back({rs_.leaves[k].extent, rs_.leaves[k].stride, rd_.leaves[k].stride});
+        }
+        if (tune.rest_order == 1)
+          std::stable_sort(rest.begin(), rest.end(), [](const RM& x, const RM& y) { return x.a < y.a; });
+        int64_t tiles = 1;
+        for (const RM& r : rest) tiles *= r.ext;
+        if (rest.size() > (size_t)kMaxModes || tiles >= (1ll << 31) || tiles * (int64_t)P.n_micro * V * V != n) ok = false;
+        if (ok) {
+          P.n_rest = (int32_t)rest.size();
+          for (size_t k = 0; k < rest.size(); ++k) {
+            P.rdiv[k] = make_fastdiv((uint32_t)rest[k].ext);
+            P.ra[k] = rest[k].a;
+            P.rb[k] = rest[k].b;
+          }
+          P.n_tiles = (uint32_t)tiles;
+        }
+      }
+      if (ok) {
+        P.plane_slots = (P.n_micro + 15u) & ~15u;
+        // swizzle: XOR four higher bits of the slot index into its low four bits; pick the source bits
+        // that minimise the modelled bank conflicts of the parking writes (reads stay contiguous)
+        int best_shift = -1, best_cost = 0;
+        P.swz_shift = 0; P.swz_mask = 0;
+        best_cost = transpose_swizzle_cost(P, V, es, mpt);
+        if (tune.swizzle_shift == -2) {
+          for (int sh = 4; sh <= 12 && (P.n_micro >> sh) > 0; ++sh) {
+            P.swz_shift = (uint32_t)sh; P.swz_mask = 15;
+            int c = transpose_swizzle_cost(P, V, es, mpt);
+            if (c < best_cost) { best_cost = c; best_shift = sh; }
+          }
+        } else if (tune.swizzle_shift >= 4) {
+          best_shift = tune.swizzle_shift;
+        }
+        if (best_shift >= 4) { P.swz_shift = (uint32_t)best_shift; P.swz_mask = 15; }
+        else { P.swz_shift = 0; P.swz_mask = 0; }
+        plan->lds_conflict_cost = transpose_swizzle_cost(P, V, es, mpt);
+        plan->cls = KernelClass::Transpose;
+        plan->V = V;
+        plan->width_bytes = V * es;
+        plan->micro_per_thread = (int)((P.n_micro + kBlock - 1) / kBlock);
+        if (plan->micro_per_thread == 3) plan->micro_per_thread = 4;
+        plan->tile_extent = t;
+        plan->p_mode = p;
+        plan->q_mode = q;
+        plan->lds_bytes = P.plane_slots * (unsigned)V * (unsigned)(V * es);
+        plan->src_run_bytes = run_length(J, t, true) * es;
+        plan->dst_run_bytes = run_length(J, t, false) * es;
+        int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
+        plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(8, fit));
+        plan->src_align = (unsigned)(V * es);
+        plan->dst_align = (unsigned)(V * es);
+        return LC_OK;
+      }
+      plan->note = "tile did not fit the transpose kernel's index ranges";
+    } else {
+      plan->note = "no common vector on both sides for a transposing tile";
+    }
+  }
+  if (tune.force_class == 0) return plan_generic(S, D, n, plan, "forced");
+
+  // ---- Direct class: lanes follow the destination order --------------------------------------
+  int VEC = 1;
+  if (q >= 0 && J[(size_t)q].a == 1) {
+    std::vector<int64_t> need = {J[(size_t)q].extent};
+    for (int k = 0; k < nj; ++k)
+      if (k != q) { need.push_back(J[(size_t)k].a); need.push_back(J[(size_t)k].b); }
+    VEC = common_pow2(cap, need);
+  }
+  DirectParams& P = plan->direct;
+  std::memset(&P, 0, sizeof(P));
+  // a stride-0 source mode (broadcast) is looped inside the lane: one read, many writes
+  int loop_mode = -1;
+  for (int k = 0; k < nj; ++k)
+    if (J[(size_t)k].a == 0 && J[(size_t)k].extent > 1 && k != q && J[(size_t)k].extent <= 65536 &&
+        (loop_mode < 0 || J[(size_t)k].extent > J[(size_t)loop_mode].extent))
+      loop_mode = k;
+  int64_t items = 1;
+  int m = 0;
+  for (int k = 0; k < nj; ++k) {
+    if (k == loop_mode) continue;
+    int64_t ext = J[(size_t)k].extent, a = J[(size_t)k].a, b = J[(size_t)k].b;
+    if (k == q && VEC > 1) ext /= VEC; else { a /= (k == q ? 1 : VEC); b /= (k == q ? 1 : VEC); }
+    P.div[m] = make_fastdiv((uint32_t)ext);
+    P.sa[m] = a;
+    P.sb[m] = b;
+    items *= ext;
+    ++m;
+  }
+  if (m == 0) { P.div[0] = make_fastdiv(1); P.sa[0] = 0; P.sb[0] = 0; m = 1; }
+  if (items >= (1ll << 31)) return LC_ERR_TOO_LARGE;
+  P.n_modes = m;
+  P.n_items = (uint32_t)items;
+  P.loop_extent = loop_mode >= 0 ? (uint32_t)J[(size_t)loop_mode].extent : 1u;
+  P.loop_sa = loop_mode >= 0 ? J[(size_t)loop_mode].a / VEC : 0;
+  P.loop_sb = loop_mode >= 0 ? J[(size_t)loop_mode].b / VEC : 0;
+  plan->cls = KernelClass::Direct;
+  plan->width_bytes = VEC * es;
+  plan->unroll = (tune.unroll == 1 || tune.unroll == 2 || tune.unroll == 4 || tune.unroll == 8) ? tune.unroll : 4;
+  plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : 8;
+  plan->src_align = (unsigned)(VEC * es);
+  plan->dst_align = (unsigned)(VEC * es);
+  return LC_OK;
+}
+
+std::string describe(const lc_plan& plan) {
+  std::string s;
+  const char* cls = plan.cls == KernelClass::Generic ? "generic" : plan.cls == KernelClass::Direct ? "direct" : "transpose";
+  s += std::string("class=") + cls;
+  s += " elem_bytes=" + std::to_string(plan.elem_bytes) + " n=" + std::to_string(plan.n_elems);
+  s += " K=" + std::to_string(plan.common_vector) + " width_bytes=" + std::to_string(plan.width_bytes);
+  s += " joint=[";
+  for (size_t k = 0; k < plan.joint.size(); ++k) {
+    if (k) s += " ";
+    s += "(" + std::to_string(plan.joint[k].extent) + "," + std::to_string(plan.joint[k].a) + "," + std::to_string(plan.joint[k].b) + ")";
+  }
+  s += "]";
+  if (plan.cls == KernelClass::Transpose) {
+    s += " V=" + std::to_string(plan.V) + " tile=[";
+    for (size_t k = 0; k < plan.tile_extent.size(); ++k) { if (k) s += ","; s += std::to_string(plan.tile_extent[k]); }
+    s += "] p=" + std::to_string(plan.p_mode) + " q=" + std::to_string(plan.q_mode);
+    s += " micro_tiles=" + std::to_string(plan.transpose.n_micro) + " per_lane=" + std::to_string(plan.micro_per_thread);
+    s += " tiles=" + std::to_string(plan.transpose.n_tiles) + " lds_bytes=" + std::to_string(plan.lds_bytes);
+    s += " swizzle_shift=" + std::to_string(plan.transpose.swz_mask ? (int)plan.transpose.swz_shift : -1);
+    s += " modelled_lds_conflicts=" + std::to_string(plan.lds_conflict_cost);
+    s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
+  } else if (plan.cls == KernelClass::Direct) {
+    s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);
+    s += " unroll=" + std::to_string(plan.unroll);
+  }
+  s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal ? 1 : 0);
+  if (!plan.note.empty()) s += " note=\"" + plan.note + "\"";
+  return s;
+}
+
+}  // namespace lc

@@ -1,0 +1,82 @@
+// Host planner for COPY (Sec. 2.6.1 of "CuTe Layout Representation and Algebra"): turns a pair of
+// layouts into kernel arguments using the layout algebra (Sec. 3).
+#pragma once
+#include <string>
+#include <vector>
+
+#include "algebra.hpp"
+#include "kernel_params.hpp"
+
+namespace lc {
+
+struct JointMode {
+  int64_t extent, a, b;   // extent, source stride, destination stride (elements)
+};
+
+enum class KernelClass { Generic, Direct, Transpose };
+
+// Knobs the planner normally chooses itself; values < 0 mean "planner's choice".  Read from the
+// environment (LC_TUNE_*) once per plan so that tile shapes can be swept without rebuilding.
+struct Tuning {
+  int micro_per_thread = -1;   // transpose: micro-tiles per lane (1, 2 or 4)
+  int rest_order = -1;         // transpose: 0 = tiles ordered by destination stride, 1 = by source stride
+  int wgs_per_cu = -1;         // persistent grid size = CUs * wgs_per_cu
+  int unroll = -1;             // direct: items per lane per loop trip (1, 2, 4, 8)
+  int swizzle_shift = -2;      // transpose: -1 = no swizzle
+  int nontemporal = -1;        // 1 = nontemporal loads and stores
+  int force_class = -1;        // 0 generic, 1 direct, 2 transpose (falls back when not applicable)
+  int max_vec_bytes = -1;      // cap on the access width
+};
+Tuning tuning_from_env();
+
+}  // namespace lc
+
+struct lc_plan {
+  lc::KernelClass cls = lc::KernelClass::Generic;
+  int elem_bytes = 0;
+  int64_t n_elems = 0;
+  int64_t common_vector = 1;               // K of Sec. 3.4.2 before hardware clamps
+  std::vector<lc::JointMode> joint;        // after common refinement, destination-order sort, joint coalesce
+  unsigned src_align = 0, dst_align = 0;   // alignment the access widths rely on
+
+  // Direct
+  int width_bytes = 0;                     // bytes per access (element width x vector length)
+  lc::DirectParams direct{};
+  int unroll = 4;
+
+  // Transpose
+  int V = 0;                               // micro-tile edge (elements)
+  int micro_per_thread = 1;
+  std::vector<int64_t> tile_extent;        // per joint mode
+  int p_mode = -1, q_mode = -1;
+  lc::TransposeParams transpose{};
+  unsigned lds_bytes = 0;
+  int64_t src_run_bytes = 0, dst_run_bytes = 0;
+  int lds_conflict_cost = 0;               // modelled bank-conflict cost of the chosen swizzle
+
+  // Generic
+  lc::GenericParams generic{};
+
+  int wgs_per_cu = 0;
+  bool nontemporal = false;
+  std::string note;                        // why a faster class was not taken
+};
+
+namespace lc {
+
+lc_status_t make_plan(const Layout& src, const Layout& dst, int elem_bytes, unsigned src_align,
+                      unsigned dst_align, const Tuning& tune, lc_plan* out);
+std::string describe(const lc_plan& plan);
+
+// Walks the plan on the host exactly along the kernels' index arithmetic and moves the bytes in
+// host memory.  It exists to prove the routing of a plan (and that every access stays inside the
+// two buffers) without a GPU; it is not a way to execute a copy and nothing in the copy path calls it.
+lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_elems, void* dst, int64_t dst_elems,
+                           int64_t* lds_conflicts);
+
+// Defined with the kernels: enqueue the plan's kernel on a HIP stream / time repeated executions.
+lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream);
+lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
+                      int iters, void* stream, float* ms_per_iter);
+
+}  // namespace lc

@@ -1,0 +1,98 @@
+// Host replay of a plan: the same index arithmetic as the kernels (kernel_params.hpp), executed
+// lane by lane on host memory, with every access checked against the buffer sizes.  A checking
+// device for plans; never part of executing a copy.
+#include <cstring>
+#include <vector>
+
+#include "plan.hpp"
+
+namespace lc {
+
+int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes);
+
+namespace {
+struct Buffers {
+  const unsigned char* src;
+  unsigned char* dst;
+  int64_t src_bytes, dst_bytes;
+  bool ok = true;
+  void move(int64_t so, int64_t dof, int bytes) {
+    if (so < 0 || dof < 0 || so + bytes > src_bytes || dof + bytes > dst_bytes) { ok = false; return; }
+    std::memcpy(dst + dof, src + so, (size_t)bytes);
+  }
+};
+}  // namespace
+
+lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_elems, void* dst, int64_t dst_elems,
+                           int64_t* lds_conflicts) {
+  const int es = plan.elem_bytes;
+  Buffers B{static_cast<const unsigned char*>(src), static_cast<unsigned char*>(dst), src_elems * es, dst_elems * es};
+  if (lds_conflicts) *lds_conflicts = 0;
+  if (plan.cls == KernelClass::Generic) {
+    const GenericParams& P = plan.generic;
+    for (uint32_t i = 0; i < P.n; ++i) B.move(flat_eval(P.src, i) * es, flat_eval(P.dst, i) * es, es);
+  } else if (plan.cls == KernelClass::Direct) {
+    const DirectParams& P = plan.direct;
+    const int W = plan.width_bytes;
+    for (uint32_t item = 0; item < P.n_items; ++item) {
+      int64_t so, dof;
+      direct_offsets(P, item, &so, &dof);
+      for (uint32_t r = 0; r < P.loop_extent; ++r) B.move((so + r * P.loop_sa) * W, (dof + r * P.loop_sb) * W, W);
+    }
+  } else {
+    const TransposeParams& P = plan.transpose;
+    const int V = plan.V, slot = V * es;
+    std::vector<unsigned char> lds((size_t)plan.lds_bytes);
+    const uint32_t lanes = (uint32_t)kBlock * (uint32_t)plan.micro_per_thread;
+    for (uint32_t tile = 0; tile < P.n_tiles && B.ok; ++tile) {
+      int64_t sbase, dbase;
+      tile_origin(P, tile, &sbase, &dbase);
+      // load phase: lane u reads V vectors along p (one per step along q), parks V vectors along q
+      for (uint32_t u = 0; u < lanes; ++u) {
+        if (u >= P.n_micro) continue;
+        int32_t so;
+        uint32_t c;
+        micro_from_src_order(P, u, &so, &c);
+        for (int iq = 0; iq < V; ++iq) {
+          int64_t off = (sbase + so + (int64_t)iq * P.a_q) * es;
+          if (off < 0 || off + slot > B.src_bytes) { B.ok = false; break; }
+          for (int ip = 0; ip < V; ++ip) {
+            size_t l = ((size_t)ip * P.plane_slots + lds_slot(P, c)) * (size_t)slot + (size_t)iq * (size_t)es;
+            if (l + (size_t)es > lds.size()) { B.ok = false; break; }
+            std::memcpy(&lds[l], B.src + off + (int64_t)ip * es, (size_t)es);
+          }
+        }
+      }
+      // store phase: lane w picks up V vectors along q and writes one per step along p
+      for (uint32_t w = 0; w < lanes && B.ok; ++w) {
+        if (w >= P.n_micro) continue;
+        int32_t dof = micro_dst_offset(P, w);
+        for (int ip = 0; ip < V; ++ip) {
+          int64_t off = (dbase + dof + (int64_t)ip * P.b_p) * es;
+          size_t l = ((size_t)ip * P.plane_slots + lds_slot(P, w)) * (size_t)slot;
+          if (off < 0 || off + slot > B.dst_bytes || l + (size_t)slot > lds.size()) { B.ok = false; break; }
+          std::memcpy(B.dst + off, &lds[l], (size_t)slot);
+        }
+      }
+      if (lds_conflicts && tile == 0) {
+        for (uint32_t wave = 0; wave * 64 < lanes; ++wave) {
+          uint32_t wa[64], ra[64];
+          bool act[64];
+          for (int l = 0; l < 64; ++l) {
+            uint32_t u = wave * 64 + (uint32_t)l;
+            act[l] = u < P.n_micro;
+            int32_t so;
+            uint32_t c = 0;
+            if (act[l]) micro_from_src_order(P, u, &so, &c);
+            wa[l] = lds_slot(P, c) * (uint32_t)slot;
+            ra[l] = lds_slot(P, u) * (uint32_t)slot;
+          }
+          *lds_conflicts += (int64_t)V * (lds_pass_conflicts(wa, act, 64, slot) + lds_pass_conflicts(ra, act, 64, slot));
+        }
+      }
+    }
+  }
+  return B.ok ? LC_OK : LC_ERR_INVALID_ARG;
+}
+
+}  // namespace lc

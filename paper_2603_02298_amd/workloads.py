@@ -1,0 +1,129 @@
+"""Seeded synthetic inputs and the five benchmark workloads.
+
+This module holds no layout arithmetic: layouts are given as text, buffer sizes as plain numbers
+(checked against cosize in the tests), values come from numpy's seeded generators.  It serves the
+CPU oracle and the GPU path alike so that both see the same bits.
+
+The paper names no dataset; the workloads are stand-ins shaped like its tiling / partitioning
+examples (tile-then-slice of Sec. 3.5.2, the COPY applications table of Sec. 2.6.1), at the sizes
+the benchmark spec lists.  `scale` shrinks a workload for parity tests by shortening its outer modes.
+"""
+import numpy as np
+
+SEED_BASE = 2603022980
+
+
+class Workload:
+    def __init__(self, name, dtype, src_layout, dst_layout, src_elems, dst_elems, n, values, note=""):
+        self.name, self.dtype = name, dtype
+        self.src_layout, self.dst_layout = src_layout, dst_layout
+        self.src_elems, self.dst_elems, self.n = src_elems, dst_elems, n
+        self.values, self.note = values, note
+
+    @property
+    def elem_bytes(self):
+        return 2 if self.dtype in ("bf16", "f16") else 4
+
+    @property
+    def algorithmic_bytes(self):
+        return 2 * self.n * self.elem_bytes
+
+
+def _c1(scale=1):
+    m = 1024 // scale
+    return Workload("c1_transpose_f32", "f32", "(%d,%d):(1,%d)" % (m, m, m), "(%d,%d):(%d,1)" % (m, m, m),
+                    m * m, m * m, m * m, "uniform", "2-D fp32 transpose, column-major to row-major")
+
+
+def _c2(scale=1):
+    # shape ((8,512),(8,1024)); source compact column-major; destination compact with mode order (2,0,3,1)
+    a, b = 512 // scale, 1024 // scale
+    src = "((8,%d),(8,%d)):((1,8),(%d,%d))" % (a, b, 8 * a, 64 * a)
+    dst = "((8,%d),(8,%d)):((8,%d),(1,64))" % (a, b, 64 * b)
+    n = 64 * a * b
+    return Workload("c2_hier_relayout_bf16", "bf16", src, dst, n, n, n, "normal",
+                    "hierarchical bf16 relayout, compact reading of the destination")
+
+
+def _c2_literal():
+    # the strides exactly as the benchmark spec prints them: not compact, cosize 2^32 - 1016 elements
+    src = "((8,512),(8,1024)):((1,8),(4096,32768))"
+    dst = "((8,512),(8,1024)):((1024,8388608),(1,8192))"
+    n = 1 << 25
+    return Workload("c2_literal_bf16", "bf16", src, dst, n, 4294966280, n, "normal",
+                    "destination strides as printed; 16-byte runs over an 8.6 GB span")
+
+
+def _c3(scale=1):
+    # (S,D,H,B) column-major over (D,S,H,B), zipped_divide by <128,64>, into the compact layout of that shape
+    S, D, H, B = 4096, 128, max(32 // scale, 1), max(64 // scale, 1)
+    so, do = S // 128, D // 64
+    src = "((128,64),(%d,%d,%d,%d)):((%d,1),(%d,64,%d,%d))" % (so, do, H, B, D, 128 * D, S * D, S * D * H)
+    t = 128 * 64
+    dst = "((128,64),(%d,%d,%d,%d)):((1,128),(%d,%d,%d,%d))" % (so, do, H, B, t, t * so, t * so * do, t * so * do * H)
+    n = S * D * H * B
+    return Workload("c3_tiled_partition_f16", "f16", src, dst, n, n, n, "normal",
+                    "fp16 (B,H,S,D) tensor partitioned into 128x64 tiles")
+
+
+def _c4a(scale=1):
+    n = (1 << 26) // scale
+    return Workload("c4a_strided_gather_f32", "f32", "%d:3" % n, "%d:1" % n, (1 << 28) // scale, n, n, "int_valued",
+                    "gather with stride 3 into a contiguous destination")
+
+
+def _c4b(scale=1):
+    m = (1 << 20) // scale
+    return Workload("c4b_broadcast_f32", "f32", "(%d,16):(1,0)" % m, "(%d,16):(1,%d)" % (m, m), m, 16 * m, 16 * m,
+                    "int_valued", "stride-0 broadcast of a vector into 16 rows")
+
+
+def _c5(scale=1):
+    N, C, H, W = max(64 // scale, 1), 256, 256, 256
+    if scale > 64:
+        C = H = W = 256 // (scale // 64)
+    src = "(%d,%d,%d,%d):(%d,%d,%d,1)" % (N, C, H, W, C * H * W, H * W, W)
+    dst = "(%d,%d,%d,%d):(%d,1,%d,%d)" % (N, C, H, W, H * W * C, W * C, C)
+    n = N * C * H * W
+    return Workload("c5_nchw_to_nhwc_f32", "f32", src, dst, n, n, n, "uniform", "rank-4 fp32 permutation NCHW -> NHWC")
+
+
+_MAKERS = {"c1": _c1, "c2": _c2, "c3": _c3, "c4a": _c4a, "c4b": _c4b, "c5": _c5}
+
+
+def workload(name, scale=1):
+    if name == "c2_literal":
+        return _c2_literal()
+    return _MAKERS[name](scale)
+
+
+WORKLOAD_NAMES = ["c1", "c2", "c3", "c4a", "c4b", "c5"]
+
+
+def _bf16_bits(x32):
+    """float32 array -> bfloat16 bit patterns (round to nearest even), as uint16."""
+    u = x32.view(np.uint32).astype(np.uint64)
+    rounded = u + 0x7FFF + ((u >> 16) & 1)
+    return (rounded >> 16).astype(np.uint16)
+
+
+def source_bits(w, elems=None, chunk=1 << 24):
+    """Seeded source buffer of the workload as raw bit patterns (uint16 / uint32 numpy array)."""
+    elems = w.src_elems if elems is None else elems
+    rng = np.random.default_rng(SEED_BASE + int(w.name[1]))   # one seed per BASELINE config (c1..c5)
+    out = np.empty(elems, dtype=np.uint16 if w.elem_bytes == 2 else np.uint32)
+    for lo in range(0, elems, chunk):
+        hi = min(lo + chunk, elems)
+        if w.values == "uniform":
+            x = rng.uniform(-1.0, 1.0, hi - lo).astype(np.float32)
+        elif w.values == "normal":
+            x = rng.standard_normal(hi - lo, dtype=np.float32)
+        else:  # integer-valued fp32 in [0, 2^20)
+            x = rng.integers(0, 1 << 20, hi - lo).astype(np.float32)
+        if w.dtype == "f32":
+            out[lo:hi] = x.view(np.uint32)
+        elif w.dtype == "f16":
+            out[lo:hi] = x.astype(np.float16).view(np.uint16)
+        else:
+            out[lo:hi] = _bf16_bits(x)
+    return out

@@ -1,0 +1,86 @@
+"""Full-size workloads (the benchmark spec sizes) in the launch configuration bench.py times.
+The oracle cannot walk 2^30 elements in a test, so parity is checked (a) on sampled outputs whose
+source and destination offsets the oracle computes one by one, and (b) over the whole result against a
+library routine the copy reduces to (torch permute / slicing on the same device buffers)."""
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from paper_2603_02298_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _device_source(w, dev):
+    """Seeded device-side stand-in for the numpy generator (same distribution family, torch's generator):
+    generating 2^30 values on the host would dominate the test."""
+    g = torch.Generator(device=dev)
+    g.manual_seed(W.SEED_BASE + int(w.name[1]))
+    if w.elem_bytes == 2:
+        x = torch.randn(w.src_elems, device=dev, generator=g, dtype=torch.float32)
+        x = x.to(torch.bfloat16 if w.dtype == "bf16" else torch.float16)
+        return x.view(torch.int16)
+    if w.values == "uniform":
+        return (torch.rand(w.src_elems, device=dev, generator=g, dtype=torch.float32) * 2 - 1).view(torch.int32)
+    return torch.randint(0, 1 << 20, (w.src_elems,), device=dev, generator=g).to(torch.float32).view(torch.int32)
+
+
+def _reference(name, src):
+    if name == "c1":
+        return src.view(1024, 1024).t()                       # src[m + 1024 n] -> dst[1024 m + n]
+    if name == "c2":
+        # src offset = i0 + 8 i1 + 4096 j0 + 32768 j1 ; dst offset = j0 + 8 i0 + 64 j1 + 65536 i1
+        return src.view(1024, 8, 512, 8).permute(2, 0, 3, 1)  # dims (j1,j0,i1,i0) -> (i1,j1,i0,j0)
+    if name == "c3":
+        # src (b,h,s_out,s_in,d_out,d_in) row-major ; dst (b,h,d_out,s_out,d_in,s_in) row-major
+        return src.view(64, 32, 32, 128, 2, 64).permute(0, 1, 4, 2, 5, 3)
+    if name == "c4a":
+        return src[::3][:1 << 26]
+    if name == "c4b":
+        return src[:1 << 20].unsqueeze(0).expand(16, 1 << 20)
+    if name == "c5":
+        return src.view(64, 256, 256, 256).permute(0, 2, 3, 1)
+    raise KeyError(name)
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4a", "c4b", "c5"])
+def test_full_size(oracle, name):
+    dev = torch.device("cuda:0")
+    w = W.workload(name)
+    print("full-size", w.name, w.src_layout, "->", w.dst_layout, flush=True)
+    src = _device_source(w, dev)
+    dst = torch.full((w.dst_elems,), 0x5A5A if w.elem_bytes == 2 else 0x5A5A5A5A, dtype=src.dtype, device=dev)
+    plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
+    print(plan.describe(), flush=True)
+    lc.copy_tensor(src, w.src_layout, dst, w.dst_layout, w.dtype)       # same call bench.py times
+    torch.cuda.synchronize()
+    # (a) sampled outputs, offsets from the oracle
+    sl, dl = oracle.Layout(w.src_layout), oracle.Layout(w.dst_layout)
+    rng = np.random.default_rng(11)
+    idx = np.unique(np.concatenate([rng.integers(0, w.n, 400000), np.arange(0, 4096), np.arange(w.n - 4096, w.n)]))
+    so = torch.from_numpy(sl.offsets_at(idx)).to(dev)
+    do = torch.from_numpy(dl.offsets_at(idx)).to(dev)
+    assert torch.equal(dst[do], src[so])
+    # (b) the whole result against torch's own permute / slicing of the same buffer
+    ref = _reference(name, src)
+    assert torch.equal(dst.view(ref.shape), ref)
+
+
+def test_c2_literal_strides(oracle):
+    """Destination strides exactly as the benchmark spec prints them (not compact: 8.6 GB span, 16-byte runs)."""
+    dev = torch.device("cuda:0")
+    w = W.workload("c2_literal")
+    src = _device_source(w, dev)
+    dst = torch.zeros(w.dst_elems, dtype=torch.int16, device=dev)
+    print(lc.Plan(w.src_layout, w.dst_layout, w.dtype).describe(), flush=True)
+    lc.copy_tensor(src, w.src_layout, dst, w.dst_layout, w.dtype)
+    torch.cuda.synchronize()
+    sl, dl = oracle.Layout(w.src_layout), oracle.Layout(w.dst_layout)
+    rng = np.random.default_rng(12)
+    idx = np.unique(np.concatenate([rng.integers(0, w.n, 400000), np.arange(0, 4096), np.arange(w.n - 4096, w.n)]))
+    so = torch.from_numpy(sl.offsets_at(idx)).to(dev)
+    do = torch.from_numpy(dl.offsets_at(idx)).to(dev)
+    assert torch.equal(dst[do], src[so])
+    # every written element is accounted for: the number of non-zero destinations equals the non-zero sources
+    assert int((dst != 0).sum()) == int((src != 0).sum())

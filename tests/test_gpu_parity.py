@@ -1,0 +1,164 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit, on the same
+seeded inputs.  Run on the MI355X machine with `-m gpu`."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from paper_2603_02298_amd import workloads as W
+from conftest import golden_lines
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _torch_int(es):
+    return {1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}[es]
+
+
+def _np_int(es):
+    return {1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[es]
+
+
+def _gpu_copy(src_bits, src_layout, dst_layout, dtype, dst_elems, fill=0x5A):
+    es = lc.DTYPE_BYTES[dtype]
+    dev = torch.device("cuda:0")
+    src_t = torch.from_numpy(src_bits.view(_np_int(es))).to(dev)
+    dst_t = torch.from_numpy(np.full(dst_elems * es, fill, np.uint8).view(_np_int(es))).to(dev)
+    lc.copy_tensor(src_t, src_layout, dst_t, dst_layout, dtype)
+    torch.cuda.synchronize()
+    return dst_t.cpu().numpy()
+
+
+def _parity(oracle, src_layout, dst_layout, dtype, seed=0, src_bits=None, tag=""):
+    es = lc.DTYPE_BYTES[dtype]
+    sl, dl = oracle.Layout(src_layout), oracle.Layout(dst_layout)
+    print("case", tag, src_layout, "->", dst_layout, dtype, flush=True)
+    if src_bits is None:
+        rng = np.random.default_rng(seed)
+        src_bits = rng.integers(0, 255, size=max(sl.cosize, 1) * es, dtype=np.uint8).view(_np_int(es))
+    want = np.full(dl.cosize * es, 0x5A, np.uint8).view(_np_int(es))
+    oracle.copy(src_bits.view(want.dtype), sl, want, dl)
+    got = _gpu_copy(src_bits, src_layout, dst_layout, dtype, dl.cosize)
+    assert (got == want).all(), lc.Plan(src_layout, dst_layout, dtype).describe()
+
+
+@pytest.mark.parametrize("name,scale", [("c1", 1), ("c1", 16), ("c2", 4), ("c2", 16), ("c3", 16), ("c4a", 16),
+                                        ("c4b", 4), ("c5", 256), ("c5", 64)])
+def test_workloads_elementwise(oracle, name, scale):
+    # sizes the oracle finishes in seconds; every one spans many tiles
+    w = W.workload(name, scale)
+    _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag=w.name)
+
+
+def test_copy_applications_table(oracle):
+    for ln in golden_lines("copy_applications.txt"):
+        name, s, d = [x.strip() for x in ln.split("|")]
+        if name == "Constant":
+            continue
+        for dt in ("f32", "bf16", "b8", "b64", "b128"):
+            if dt == "b128":
+                continue
+            _parity(oracle, s, d, dt, tag=name)
+
+
+def test_random_layout_pairs(oracle):
+    import sys
+    sys.path.insert(0, os.path.dirname(__file__))
+    from test_plan_replay import _random_pair
+    rng = np.random.default_rng(4242)
+    for k in range(400):
+        s, d = _random_pair(rng)
+        _parity(oracle, s, d, ["f32", "bf16", "b8", "b64", "f16"][k % 5], seed=k, tag="random%d" % k)
+
+
+@pytest.mark.parametrize("s,d,dt", [
+    ("1:0", "1:0", "f32"),                                   # single element
+    ("1:5", "1:7", "bf16"),
+    ("(1,1,1):(3,4,5)", "1:0", "f32"),
+    ("7:1", "7:1", "f32"),                                   # shorter than one vector
+    ("1000003:1", "1000003:1", "f32"),                       # prime length: ragged tail, width 4
+    ("(1000,3):(3,3001)", "(1000,3):(1,1000)", "f32"),       # ragged rows
+    ("(68,36):(1,68)", "(68,36):(36,1)", "f32"),             # transpose, 4 | extents but not tile multiples
+    ("(70,34):(1,70)", "(70,34):(34,1)", "f32"),             # transpose with V=2
+    ("(71,33):(1,71)", "(71,33):(33,1)", "f32"),             # odd extents: no vector on either side
+    ("(136,72):(1,136)", "(136,72):(72,1)", "bf16"),         # V=8 with ragged tile counts
+    ("(132,68):(1,132)", "(132,68):(68,1)", "f16"),          # V=4
+    ("(8,3,8):(1,64,8)", "(8,3,8):(24,8,1)", "f16"),         # tiny transposed tiles, batch of 3
+    ("(6,10):(10,1)", "(4,15):(15,1)", "f32"),               # no common refinement: element-wise kernel
+    ("(5,7,3):(21,3,1)", "(3,35):(1,3)", "bf16"),
+    ("(256,16):(1,0)", "(256,16):(1,256)", "f32"),           # broadcast
+    ("(3,16,5):(1,0,3)", "(3,16,5):(80,1,16)", "f32"),       # broadcast in the middle
+    ("4096:7", "4096:1", "bf16"),                            # 2-byte gather
+    ("4096:1", "4096:5", "f32"),                             # scatter
+    ("(64,64,4):(1,64,4096)", "(64,64,4):(64,1,8192)", "b64"),
+])
+def test_edge_cases(oracle, s, d, dt):
+    _parity(oracle, s, d, dt, seed=3, tag="edge")
+
+
+def test_large_lds_tiles(oracle, monkeypatch):
+    # 4 micro-tiles per lane: 64 KiB (fp32) and 128 KiB (bf16) of LDS per workgroup
+    monkeypatch.setenv("LC_TUNE_MICRO_PER_THREAD", "4")
+    w = W.workload("c2", 8)
+    assert "lds_bytes=131072" in lc.Plan(w.src_layout, w.dst_layout, w.dtype).describe()
+    _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="c2 mt4")
+    w = W.workload("c1", 2)
+    _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="c1 mt4")
+    monkeypatch.setenv("LC_TUNE_MICRO_PER_THREAD", "2")
+    _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="c1 mt2")
+
+
+def test_tuning_variants_stay_exact(oracle, monkeypatch):
+    w = W.workload("c5", 256)
+    bits = W.source_bits(w)
+    for env in [{"LC_TUNE_NONTEMPORAL": "1"}, {"LC_TUNE_REST_ORDER": "1"}, {"LC_TUNE_SWIZZLE_SHIFT": "-1"},
+                {"LC_TUNE_FORCE_CLASS": "1"}, {"LC_TUNE_FORCE_CLASS": "0"}, {"LC_TUNE_MAX_VEC_BYTES": "8"}]:
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=bits, tag=str(env))
+        for k in env:
+            monkeypatch.delenv(k)
+    w = W.workload("c4a", 64)
+    for u in ("1", "2", "8"):
+        monkeypatch.setenv("LC_TUNE_UNROLL", u)
+        _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="unroll" + u)
+
+
+def test_misaligned_pointers(oracle):
+    dev = torch.device("cuda:0")
+    n = 4096
+    src = torch.arange(n + 8, dtype=torch.int32, device=dev)
+    dst = torch.zeros(n + 8, dtype=torch.int32, device=dev)
+    plan = lc.Plan("%d:1" % n, "%d:1" % n, "f32")            # created for 256-byte aligned pointers
+    with pytest.raises(lc.LayoutCopyError) as e:
+        plan.execute(src.data_ptr() + 4, dst.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert e.value.status_name == "MISALIGNED"
+    # lc_copy derives the alignment from the pointers and narrows the accesses instead
+    lc.lc_copy(src.data_ptr() + 4, "%d:1" % n, dst.data_ptr() + 8, "%d:1" % n, "f32", torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[2:n + 2], src[1:n + 1])
+    assert int(dst[:2].abs().sum()) == 0 and int(dst[n + 2:].abs().sum()) == 0
+
+
+def test_plan_reuse_and_streams(oracle):
+    w = W.workload("c2", 16)
+    bits = W.source_bits(w)
+    dev = torch.device("cuda:0")
+    src = torch.from_numpy(bits.view(np.int16)).to(dev)
+    plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
+    want = np.zeros(w.dst_elems, np.int16)
+    oracle.copy(bits.view(np.int16), w.src_layout, want, w.dst_layout)
+    side = torch.cuda.Stream()
+    outs = []
+    for k in range(4):
+        dst = torch.zeros(w.dst_elems, dtype=torch.int16, device=dev)
+        st = side if k % 2 else torch.cuda.current_stream()
+        st.wait_stream(torch.cuda.current_stream())
+        plan.execute(src.data_ptr(), dst.data_ptr(), st.cuda_stream)
+        outs.append(dst)
+    torch.cuda.synchronize()
+    for dst in outs:
+        assert (dst.cpu().numpy() == want).all()

@@ -1,0 +1,170 @@
+"""The library's host algebra (C ABI) against the oracle: same status, same function, same printed
+form, on the paper's examples and on seeded random layouts.  No GPU needed."""
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from conftest import golden_lines
+
+OPS = {
+    "coalesce": lc.lc_coalesce, "coalesce_bymode": lc.lc_coalesce_bymode, "right_inverse": lc.lc_right_inverse,
+    "composition": lc.lc_composition, "composition_bymode": lc.lc_composition_bymode,
+    "logical_divide": lc.lc_logical_divide, "logical_divide_bymode": lc.lc_logical_divide_bymode,
+    "zipped_divide": lc.lc_zipped_divide,
+}
+
+
+def _lib_run(op, args):
+    if op == "complement":
+        return str(lc.lc_complement(args[0]))
+    if op == "complement_under":
+        return str(lc.lc_complement(args[0], int(args[1])))
+    if op == "max_common_vector":
+        return str(lc.lc_max_common_vector(args[0], args[1]))
+    return str(OPS[op](*args))
+
+
+def _oracle_run(oracle, op, args):
+    if op == "complement":
+        return str(oracle.complement(args[0]))
+    if op == "complement_under":
+        return str(oracle.complement(args[0], int(args[1])))
+    if op == "max_common_vector":
+        return str(oracle.max_common_vector(args[0], args[1]))
+    return str(getattr(oracle, op)(*args))
+
+
+def _both(oracle, op, args):
+    """(status name or 'OK', printed result) from library and oracle."""
+    try:
+        a = ("OK", _lib_run(op, args))
+    except lc.LayoutCopyError as e:
+        a = (e.status_name, None)
+    try:
+        b = ("OK", _oracle_run(oracle, op, args))
+    except oracle.OracleError as e:
+        b = (e.status_name, None)
+    return a, b
+
+
+def test_paper_examples_match_oracle_and_paper(oracle):
+    for ln in golden_lines("algebra_examples.txt"):
+        parts = [x.strip() for x in ln.split("|")]
+        op, args, expect = parts[0], parts[1:-2], parts[-2]
+        a, b = _both(oracle, op, args)
+        assert a == b, ln
+        if expect.startswith("FAIL:"):
+            assert a[0] != "OK", ln
+            if expect != "FAIL:ANY":
+                assert a[0] == expect[5:], ln
+        elif op != "complement_under":
+            assert a[1] == expect, ln
+
+
+def test_layout_inspection(oracle):
+    for text in ["24:3", "((2,2),(4,2)):((1,8),(2,16))", "(4,(3,2)):(2,(8,1))", "((3,2),((2,3),2)):((4,1),((2,15),100))", "(7):(3)"]:
+        A, B = lc.Layout(text), oracle.Layout(text)
+        assert (str(A), A.size, A.cosize, A.rank, A.depth) == (str(B), B.size, B.cosize, B.rank, B.depth)
+        for i in range(3 * A.size):   # extended domain included
+            assert A(i) == B(i)
+
+
+def test_from_tree_equals_parse():
+    a = lc.Layout.from_tree([-2, -2, 8, 512, -2, 8, 1024], [1, 8, 4096, 32768])
+    assert str(a) == "((8,512),(8,1024)):((1,8),(4096,32768))"
+    with pytest.raises(lc.LayoutCopyError):
+        lc.Layout.from_tree([-2, 4, 8], [1])
+
+
+@pytest.mark.parametrize("text,status", [
+    ("(4,8):(1,4", "PARSE"), ("4,8:1,4", "PARSE"), ("(4,8):(1,(2,3))", "NOT_CONGRUENT"), ("(4,0):(1,4)", "BAD_EXTENT"),
+    ("(4,8):(1,-4)", "NEGATIVE_STRIDE"), ("", "PARSE"), ("(4,8)", "PARSE"), ("(4,8):(1,4) x", "PARSE")])
+def test_parse_errors(oracle, text, status):
+    with pytest.raises(lc.LayoutCopyError) as e:
+        lc.Layout(text)
+    assert e.value.status_name == status
+    with pytest.raises(oracle.OracleError) as e2:
+        oracle.Layout(text)
+    assert e2.value.status_name == status
+
+
+def _random_layout(rng, max_leaves=4, max_extent=6):
+    """Random hierarchical layout text with small extents and a mix of compact / padded / zero strides."""
+    n = int(rng.integers(1, max_leaves + 1))
+    ext = [int(rng.integers(1, max_extent + 1)) for _ in range(n)]
+    order = rng.permutation(n)
+    stride, run = [0] * n, 1
+    for m in order:
+        stride[m] = run
+        run *= ext[m] * int(rng.choice([1, 1, 1, 2, 3]))
+    for k in range(n):
+        r = rng.random()
+        if r < 0.08:
+            stride[k] = 0
+        elif r < 0.16:
+            stride[k] = int(rng.integers(0, 13))
+
+    def nest(lo, hi):
+        if hi - lo == 1:
+            return str(ext[lo]), str(stride[lo])
+        if rng.random() < 0.5:
+            cut = int(rng.integers(lo + 1, hi))
+            a, b = nest(lo, cut), nest(cut, hi)
+            return "(%s,%s)" % (a[0], b[0]), "(%s,%s)" % (a[1], b[1])
+        return "(%s)" % ",".join(map(str, ext[lo:hi])), "(%s)" % ",".join(map(str, stride[lo:hi]))
+    s, d = nest(0, n)
+    return "%s:%s" % (s, d)
+
+
+def test_random_layouts_match_oracle(oracle):
+    rng = np.random.default_rng(2603)
+    unary = ["coalesce", "coalesce_bymode", "right_inverse", "complement"]
+    binary = ["composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide", "max_common_vector"]
+    ok = {k: 0 for k in unary + binary}
+    for _ in range(6000):
+        A, B = _random_layout(rng), _random_layout(rng)
+        for op in unary:
+            a, b = _both(oracle, op, [A])
+            assert a == b, (op, A)
+            ok[op] += a[0] == "OK"
+        for op in binary:
+            a, b = _both(oracle, op, [A, B])
+            assert (a[0] == "OK") == (b[0] == "OK"), (op, A, B, a, b)
+            if a[0] == "OK":
+                assert a[1] == b[1], (op, A, B)
+                ok[op] += 1
+            else:
+                assert a[0] == b[0] or {a[0], b[0]} <= {"STRIDE_DIVISIBILITY", "SHAPE_DIVISIBILITY", "NOT_SEGREGATED"}, (op, A, B, a, b)
+    for k, v in ok.items():
+        assert v > 50, (k, v)
+
+
+def test_common_vector_on_equal_sizes(oracle):
+    rng = np.random.default_rng(77)
+    ok = 0
+    for _ in range(3000):
+        n = int(rng.integers(1, 5))
+        ext = [int(rng.choice([1, 2, 3, 4, 6, 8])) for _ in range(n)]
+
+        def compact(order):
+            d, run = [0] * n, 1
+            for m in order:
+                d[m] = run
+                run *= ext[m] * int(rng.choice([1, 1, 1, 2]))
+            return "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, d)))
+        A, B = compact(rng.permutation(n)), compact(rng.permutation(n))
+        a, b = _both(oracle, "max_common_vector", [A, B])
+        assert a == b, (A, B)
+        if a[0] == "OK":
+            ok += 1
+            assert int(a[1]) == oracle.max_common_vector_def(A, B), (A, B)   # both injective here
+    assert ok > 1000
+
+
+def test_complement_cotargets_match_oracle(oracle):
+    rng = np.random.default_rng(5)
+    for _ in range(2000):
+        A = _random_layout(rng)
+        for m in (0, 1, 7, 24, 1000):
+            a, b = _both(oracle, "complement_under", [A, str(m)]) if m else _both(oracle, "complement", [A])
+            assert a == b, (A, m)

@@ -1,0 +1,151 @@
+"""The planner's routing, proven without a GPU: every plan is walked on the host along the same
+index arithmetic the kernels use (bounds-checked) and compared bit for bit with the oracle's COPY."""
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from paper_2603_02298_amd import workloads as W
+
+
+def _np_dtype(es):
+    return {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[es]
+
+
+def _check(oracle, src_layout, dst_layout, dtype, expect_class=None, seed=0):
+    es = lc.DTYPE_BYTES[dtype]
+    sl, dl = oracle.Layout(src_layout), oracle.Layout(dst_layout)
+    rng = np.random.default_rng(seed)
+    src = rng.integers(0, 255, size=sl.cosize * es, dtype=np.uint8).view(_np_dtype(es))
+    want = np.full(dl.cosize, 0xA5A5A5A5A5A5A5A5 & ((1 << (8 * es)) - 1), dtype=_np_dtype(es))
+    got = want.copy()
+    oracle.copy(src, sl, want, dl)
+    plan = lc.Plan(src_layout, dst_layout, dtype)
+    desc = plan.describe()
+    if expect_class:
+        assert ("class=" + expect_class) in desc, desc
+    conflicts = plan.debug_replay_on_host(src, got)
+    assert (got == want).all(), desc
+    return desc, conflicts
+
+
+def test_fast_division_is_exact():
+    # the kernels' division by a constant, checked through a plan whose only job is idx2crd: a
+    # generic-class copy between shapes without common refinement exercises it on every element
+    import ctypes
+    from paper_2603_02298_amd.binding import lib
+    assert lib() is not None
+    rng = np.random.default_rng(1)
+    # white-box: same formula as kernel_params.hpp, on random 31-bit operands
+    for d in [1, 2, 3, 5, 7, 12, 64, 125, 1000, 65535, 65536, 65537, (1 << 31) - 1] + [int(x) for x in rng.integers(1, 1 << 31, 200)]:
+        l = 0
+        while (1 << l) < d:
+            l += 1
+        mul = (((1 << l) - d) << 32) // d + 1
+        assert mul < (1 << 32)
+        ns = np.concatenate([rng.integers(0, 1 << 31, 2000), np.array([0, 1, d - 1, d, d + 1, (1 << 31) - 1])]).astype(np.uint64)
+        q = (((ns * np.uint64(mul)) >> np.uint64(32)) + ns) >> np.uint64(l)
+        assert (q == ns // np.uint64(d)).all(), d
+
+
+@pytest.mark.parametrize("name,scale,cls", [
+    ("c1", 1, "transpose"), ("c1", 16, "transpose"), ("c2", 4, "transpose"), ("c2", 16, "transpose"),
+    ("c3", 16, "transpose"), ("c4a", 64, "direct"), ("c4b", 16, "direct"), ("c5", 256, "transpose")])
+def test_workloads_at_reduced_size(oracle, name, scale, cls):
+    w = W.workload(name, scale)
+    desc, conflicts = _check(oracle, w.src_layout, w.dst_layout, w.dtype, cls)
+    if cls == "transpose":
+        assert "width_bytes=16" in desc
+        assert conflicts == 0, desc          # the chosen XOR swizzle is conflict-free in the bank model
+
+
+def test_full_size_plans_have_expected_shape():
+    # plan creation is pure host work: the full-size workloads can be planned here
+    expect = {"c1": ("transpose", 16), "c2": ("transpose", 16), "c3": ("transpose", 16), "c4a": ("direct", 4),
+              "c4b": ("direct", 16), "c5": ("transpose", 16)}
+    for name, (cls, width) in expect.items():
+        w = W.workload(name)
+        d = lc.Plan(w.src_layout, w.dst_layout, w.dtype).describe()
+        assert "class=%s " % cls in d and "width_bytes=%d " % width in d, d
+        assert lc.Plan(w.src_layout, w.dst_layout, w.dtype).algorithmic_bytes == w.algorithmic_bytes
+
+
+def test_copy_applications_table(oracle):
+    from conftest import golden_lines
+    for ln in golden_lines("copy_applications.txt"):
+        name, s, d = [x.strip() for x in ln.split("|")]
+        if name == "Constant":   # destination aliases: refused by the GPU library
+            with pytest.raises(lc.LayoutCopyError) as e:
+                lc.Plan(s, d, "f32")
+            assert e.value.status_name == "DST_ALIASES"
+            continue
+        for dt in ("f32", "bf16", "b8", "b64"):
+            _check(oracle, s, d, dt)
+
+
+def _random_pair(rng):
+    n = int(rng.integers(1, 5))
+    ext = [int(rng.choice([1, 2, 3, 4, 5, 6, 8, 12, 16])) for _ in range(n)]
+
+    def strides(allow_zero):
+        d, run = [0] * n, 1
+        for m in rng.permutation(n):
+            d[m] = run
+            run *= ext[m] * int(rng.choice([1, 1, 1, 2, 3]))
+        if allow_zero and rng.random() < 0.2:
+            d[int(rng.integers(n))] = 0
+        return d
+
+    def text(exts, ds):
+        # random regrouping of neighbouring modes, and random merging of compatible neighbours
+        parts, i = [], 0
+        while i < len(exts):
+            j = min(len(exts), i + int(rng.integers(1, 3)))
+            if j - i == 1:
+                parts.append((str(exts[i]), str(ds[i])))
+            else:
+                parts.append(("(%s)" % ",".join(map(str, exts[i:j])), "(%s)" % ",".join(map(str, ds[i:j]))))
+            i = j
+        if len(parts) == 1:
+            return "%s:%s" % parts[0]
+        return "(%s):(%s)" % (",".join(p[0] for p in parts), ",".join(p[1] for p in parts))
+    return text(ext, strides(True)), text(ext, strides(False))
+
+
+def test_random_layout_pairs(oracle):
+    rng = np.random.default_rng(42)
+    seen = {"generic": 0, "direct": 0, "transpose": 0}
+    for k in range(1500):
+        s, d = _random_pair(rng)
+        dt = ["f32", "bf16", "b8", "b64", "f16"][k % 5]
+        desc, _ = _check(oracle, s, d, dt, seed=k)
+        seen[desc.split()[0][6:]] += 1
+    assert seen["direct"] > 100 and seen["transpose"] > 100, seen
+
+
+def test_shapes_without_common_refinement_use_generic_class(oracle):
+    for s, d in [("(2,3):(3,1)", "(3,2):(2,1)"), ("(4,9):(9,1)", "(6,6):(1,6)"), ("(5,7,3):(21,3,1)", "(3,35):(1,3)")]:
+        desc, _ = _check(oracle, s, d, "f32")
+    desc, _ = _check(oracle, "(6,10):(10,1)", "(4,15):(15,1)", "f32", "generic")
+
+
+def test_plan_errors():
+    with pytest.raises(lc.LayoutCopyError) as e:
+        lc.Plan("8:1", "9:1", "f32")
+    assert e.value.status_name == "SIZE_MISMATCH"
+    with pytest.raises(lc.LayoutCopyError) as e:
+        lc.Plan("(4,2):(1,0)", "(4,2):(1,0)", "f32")
+    assert e.value.status_name == "DST_ALIASES"
+    with pytest.raises(lc.LayoutCopyError) as e:
+        lc.Plan("(4,4):(1,4)", "(4,4):(1,3)", "f32")      # overlapping rows
+    assert e.value.status_name == "DST_ALIASES"
+    assert "class=" in lc.Plan("1:0", "1:0", "f32").describe()    # a single element never aliases
+    assert "class=" in lc.Plan("(2,3):(3,2)", "(2,3):(3,2)", "f32").describe()   # injective though not nested
+
+
+def test_alignment_limits_vector_width():
+    wide = lc.Plan("4096:1", "4096:1", "f32").describe()
+    narrow = lc.Plan("4096:1", "4096:1", "f32", src_align=4, dst_align=256).describe()
+    assert "width_bytes=16" in wide and "width_bytes=4" in narrow
+    # padded rows whose pitch is not a multiple of the vector: width drops to what divides it
+    assert "width_bytes=8" in lc.Plan("(64,32):(1,66)", "(64,32):(1,64)", "f32").describe()
+    assert "width_bytes=4" in lc.Plan("(64,32):(1,65)", "(64,32):(1,64)", "f32").describe()
