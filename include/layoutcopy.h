@@ -59,6 +59,9 @@ typedef enum {
 } lc_dtype_t;
 
 const char* lc_status_string(lc_status_t s);
+/* Text of the HIP error behind the calling thread's most recent LC_ERR_HIP ("" if there was none).
+ * The pointer stays valid until the thread's next failing call. */
+const char* lc_last_hip_error(void);
 int lc_dtype_bytes(lc_dtype_t dt); /* element width in bytes, 0 for an unknown dtype */
 
 /* ---------------------------------------------------------------------------------------------

@@ -15,7 +15,8 @@ DTYPE_BYTES = {"f32": 4, "f16": 2, "bf16": 2, "b8": 1, "b16": 2, "b32": 4, "b64"
 class LayoutCopyError(RuntimeError):
     def __init__(self, status, what):
         name = lib().lc_status_string(status).decode()
-        super().__init__("%s: %s" % (what, name))
+        detail = lib().lc_last_hip_error().decode() if name == "HIP" else ""
+        super().__init__("%s: %s%s" % (what, name, " [" + detail + "]" if detail else ""))
         self.status = status
         self.status_name = name
 
@@ -29,11 +30,20 @@ def lib():
     if not os.path.exists(path):
         raise RuntimeError("liblayoutcopy.so is not built: run `python -m paper_2603_02298_amd.build` "
                            "(there is no fallback path)")
+    # Streams and device pointers handed to the library come from PyTorch, so both must talk to the
+    # same HIP runtime: PyTorch's wheel carries its own libamdhip64 and the loader keeps whichever
+    # copy it sees first.  Importing torch first makes that copy the one this library binds to.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(path)
     P, PP = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
     i64, sz = ctypes.c_int64, ctypes.c_size_t
     L.lc_status_string.argtypes = [ctypes.c_int]
     L.lc_status_string.restype = ctypes.c_char_p
+    L.lc_last_hip_error.argtypes = []
+    L.lc_last_hip_error.restype = ctypes.c_char_p
     L.lc_dtype_bytes.argtypes = [ctypes.c_int]
     L.lc_layout_parse.argtypes = [ctypes.c_char_p, PP]
     L.lc_layout_from_tree.argtypes = [ctypes.POINTER(i64), ctypes.c_int, ctypes.POINTER(i64), ctypes.c_int, PP]

@@ -64,6 +64,8 @@ const char* lc_status_string(lc_status_t s) {
   return "UNKNOWN";
 }
 
+const char* lc_last_hip_error(void) { return lc::last_hip_error(); }
+
 int lc_dtype_bytes(lc_dtype_t dt) {
   switch (dt) {
     case LC_F32: case LC_B32: return 4;

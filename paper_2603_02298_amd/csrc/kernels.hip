@@ -4,6 +4,9 @@
 // pure data movement and is bounded by HBM bandwidth.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <string>
+
 #include "kernel_params.hpp"
 #include "plan.hpp"
 
@@ -196,13 +199,21 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
 // ---------------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------------
+static thread_local std::string g_last_hip_error;
+const char* last_hip_error() { return g_last_hip_error.c_str(); }
+static bool hip_failed(hipError_t e, const char* what) {
+  if (e == hipSuccess) return false;
+  g_last_hip_error = std::string(what) + ": " + hipGetErrorName(e) + " (" + hipGetErrorString(e) + ")";
+  return true;
+}
+
 static int device_cu_count() {
   static int cus = 0;
   if (cus == 0) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    if (hip_failed(hipGetDevice(&dev), "hipGetDevice")) return -1;
     int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return -1;
+    if (hip_failed(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute") || n <= 0) return -1;
     cus = n;
   }
   return cus;
@@ -306,7 +317,7 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
       default: return LC_ERR_UNSUPPORTED_DTYPE;
     }
   }
-  if (pre != hipSuccess || hipGetLastError() != hipSuccess) return LC_ERR_HIP;
+  if (hip_failed(pre, "hipFuncSetAttribute") || hip_failed(hipGetLastError(), "kernel launch")) return LC_ERR_HIP;
   return LC_OK;
 }
 
@@ -315,17 +326,17 @@ lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const*
   if (!srcs || !dsts || n_buffers < 1 || iters < 1 || warmup < 0 || !ms_per_iter) return LC_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipEvent_t e0, e1;
-  if (hipEventCreate(&e0) != hipSuccess) return LC_ERR_HIP;
-  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return LC_ERR_HIP; }
+  if (hip_failed(hipEventCreate(&e0), "hipEventCreate")) return LC_ERR_HIP;
+  if (hip_failed(hipEventCreate(&e1), "hipEventCreate")) { (void)hipEventDestroy(e0); return LC_ERR_HIP; }
   lc_status_t st = LC_OK;
   int b = 0;
   for (int i = 0; i < warmup && st == LC_OK; ++i, b = (b + 1) % n_buffers) st = execute_plan(plan, srcs[b], dsts[b], stream);
-  if (st == LC_OK && hipEventRecord(e0, s) != hipSuccess) st = LC_ERR_HIP;
+  if (st == LC_OK && hip_failed(hipEventRecord(e0, s), "hipEventRecord")) st = LC_ERR_HIP;
   for (int i = 0; i < iters && st == LC_OK; ++i, b = (b + 1) % n_buffers) st = execute_plan(plan, srcs[b], dsts[b], stream);
-  if (st == LC_OK && hipEventRecord(e1, s) != hipSuccess) st = LC_ERR_HIP;
-  if (st == LC_OK && hipEventSynchronize(e1) != hipSuccess) st = LC_ERR_HIP;
+  if (st == LC_OK && hip_failed(hipEventRecord(e1, s), "hipEventRecord")) st = LC_ERR_HIP;
+  if (st == LC_OK && hip_failed(hipEventSynchronize(e1), "hipEventSynchronize")) st = LC_ERR_HIP;
   float ms = 0.f;
-  if (st == LC_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) st = LC_ERR_HIP;
+  if (st == LC_OK && hip_failed(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime")) st = LC_ERR_HIP;
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   if (st == LC_OK) *ms_per_iter = ms / (float)iters;

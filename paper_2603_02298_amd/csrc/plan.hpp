@@ -75,6 +75,7 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
                            int64_t* lds_conflicts);
 
 // Defined with the kernels: enqueue the plan's kernel on a HIP stream / time repeated executions.
+const char* last_hip_error();
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream);
 lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
                       int iters, void* stream, float* ms_per_iter);
