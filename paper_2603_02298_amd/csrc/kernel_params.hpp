@@ -84,6 +84,7 @@ struct DirectParams {
   uint32_t loop_extent;
   int64_t loop_sa, loop_sb;
   uint32_t n_items;                // items excluding the looped mode (< 2^31)
+  uint32_t blocked;                // 1: a workgroup owns one contiguous range of items; 0: grid-stride
 };
 LC_HD void direct_offsets(const DirectParams& P, uint32_t item, int64_t* so, int64_t* dof) {
   int64_t s = 0, d = 0;
@@ -102,50 +103,57 @@ LC_HD void direct_offsets(const DirectParams& P, uint32_t item, int64_t* so, int
 // Transpose kernel: the source-contiguous mode p and the destination-contiguous mode q differ.
 // A tile is a box of the joint modes; it is cut into V x V micro-tiles (V elements along p times V
 // along q).  A lane loads V vectors along p (one per q step), transposes them in registers, and
-// parks V vectors along q in LDS; after a barrier lanes pick the vectors up in destination order.
-// Micro-tile coordinates are decoded twice: in source order (loads) and in destination order (stores).
+// parks V vectors along q in LDS; after a barrier the tile's vectors are picked up in destination
+// address order, consecutive lanes taking consecutive vectors.
+// Micro-tiles are enumerated in source order (index u) for the loads; vectors are enumerated in
+// destination order (index g) for the stores and for their place in LDS.
 // ---------------------------------------------------------------------------------------------
 struct TransposeParams {
   int32_t n_micro_modes;
   // source-order decode of the micro-tile index u: extents, source stride (elements) and the
-  // weight of the mode in the destination-order micro-tile index
-  uint32_t ext_s[kMaxModes];
+  // weight of the mode in the destination-order vector index g
+  FastDiv ext_s[kMaxModes];
   int32_t sa_s[kMaxModes];
-  uint32_t dpos_s[kMaxModes];
-  // destination-order decode of the micro-tile index w
-  uint32_t ext_d[kMaxModes];
-  int32_t sb_d[kMaxModes];
+  uint32_t gpos_s[kMaxModes];
+  uint32_t gpos_pv;                // weight in g of the position ip along p inside a micro-tile
+  // destination-order decode of the vector index g: the micro modes plus the mode "ip" (extent V)
+  int32_t n_dst_modes;
+  FastDiv ext_d[kMaxModes + 1];
+  int32_t sb_d[kMaxModes + 1];
   uint32_t n_micro;                // micro-tiles per tile
+  uint32_t n_vec;                  // vectors per tile = n_micro * V
   int32_t a_q;                     // source stride of one step along q (elements)
-  int32_t b_p;                     // destination stride of one step along p (elements)
-  // LDS: V planes (one per position along p) of plane_slots vectors; slot = c ^ ((c >> swz_shift) & swz_mask)
-  uint32_t plane_slots, swz_shift, swz_mask;
+  // LDS holds the tile's vectors at slot(g) = g ^ ((g >> swz_shift) & swz_mask), g = destination-order index
+  uint32_t swz_shift, swz_mask;
   // tiles: the rest modes of zipped_divide; the tile id is their colexicographic index
   int32_t n_rest;
   FastDiv rdiv[kMaxModes];
   int64_t ra[kMaxModes], rb[kMaxModes];
   uint32_t n_tiles;
+  uint32_t blocked;                // 1: a workgroup owns a contiguous range of tile ids; 0: tile ids strided by the grid
 };
-LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t c) { return c ^ ((c >> P.swz_shift) & P.swz_mask); }
-// micro-tile u (source order) -> source offset inside the tile and destination-order index
-LC_HD void micro_from_src_order(const TransposeParams& P, uint32_t u, int32_t* src_off, uint32_t* c) {
+LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t g) { return g ^ ((g >> P.swz_shift) & P.swz_mask); }
+// micro-tile u (source order) -> source offset inside the tile and the part of g the micro-tile fixes
+LC_HD void micro_from_src_order(const TransposeParams& P, uint32_t u, int32_t* src_off, uint32_t* g0) {
   int32_t s = 0;
-  uint32_t cc = 0;
+  uint32_t g = 0;
   for (int k = 0; k < P.n_micro_modes; ++k) {
-    uint32_t r = u % P.ext_s[k];
-    u /= P.ext_s[k];
+    uint32_t q, r;
+    fd_divmod(u, P.ext_s[k], &q, &r);
+    u = q;
     s += (int32_t)r * P.sa_s[k];
-    cc += r * P.dpos_s[k];
+    g += r * P.gpos_s[k];
   }
   *src_off = s;
-  *c = cc;
+  *g0 = g;
 }
-// micro-tile w (destination order) -> destination offset inside the tile
-LC_HD int32_t micro_dst_offset(const TransposeParams& P, uint32_t w) {
+// vector g (destination order) -> destination offset inside the tile
+LC_HD int32_t vector_dst_offset(const TransposeParams& P, uint32_t g) {
   int32_t d = 0;
-  for (int k = 0; k < P.n_micro_modes; ++k) {
-    uint32_t r = w % P.ext_d[k];
-    w /= P.ext_d[k];
+  for (int k = 0; k < P.n_dst_modes; ++k) {
+    uint32_t q, r;
+    fd_divmod(g, P.ext_d[k], &q, &r);
+    g = q;
     d += (int32_t)r * P.sb_d[k];
   }
   return d;

@@ -22,14 +22,15 @@ template <> struct Word<4> { typedef uint32_t type; };
 template <> struct Word<8> { typedef u32x2 type; };
 template <> struct Word<16> { typedef u32x4 type; };
 
-template <bool NT, typename T>
+// NT: bit 0 = nontemporal loads, bit 1 = nontemporal stores (streaming data is touched once)
+template <int NT, typename T>
 __device__ __forceinline__ T gload(const T* p) {
-  if (NT) return __builtin_nontemporal_load(p);
+  if (NT & 1) return __builtin_nontemporal_load(p);
   return *p;
 }
-template <bool NT, typename T>
+template <int NT, typename T>
 __device__ __forceinline__ void gstore(T* p, T v) {
-  if (NT) __builtin_nontemporal_store(v, p);
+  if (NT & 2) __builtin_nontemporal_store(v, p);
   else *p = v;
 }
 
@@ -48,19 +49,29 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(GenericParams P, const 
 // U items are in flight per lane; an optional looped mode re-uses a loaded value when its source
 // stride is zero (broadcast).
 // ---------------------------------------------------------------------------------------------
-template <int W, int U, bool NT>
+template <int W, int U, int NT>
 __global__ __launch_bounds__(kBlock) void direct_kernel(DirectParams P, const typename Word<W>::type* __restrict__ src,
                                                        typename Word<W>::type* __restrict__ dst) {
   typedef typename Word<W>::type T;
-  const uint32_t step = gridDim.x * kBlock;
-  for (uint32_t base = blockIdx.x * kBlock + threadIdx.x; base < P.n_items; base += step * U) {
+  // strided: lane items are `step` apart and the whole grid sweeps memory together;
+  // blocked: a workgroup owns the contiguous range [first, last) and sweeps it kBlock items at a time
+  uint32_t step = gridDim.x * kBlock, first = blockIdx.x * kBlock, last = P.n_items;
+  if (P.blocked) {
+    uint32_t chunk = (P.n_items + gridDim.x - 1) / gridDim.x;
+    chunk = (chunk + kBlock * U - 1) / (kBlock * U) * (kBlock * U);
+    step = kBlock;
+    first = blockIdx.x * chunk;
+    last = min(P.n_items, first + chunk);
+    if (blockIdx.x * (uint64_t)chunk >= P.n_items) return;
+  }
+  for (uint32_t base = first + threadIdx.x; base < last; base += step * U) {
     int64_t so[U], dof[U];
     bool ok[U];
     T v[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) {
       uint32_t it = base + (uint32_t)j * step;
-      ok[j] = it < P.n_items;
+      ok[j] = it < last;
       so[j] = dof[j] = 0;
       if (ok[j]) direct_offsets(P, it, &so[j], &dof[j]);
     }
@@ -113,7 +124,7 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 
   }
 }
 
-template <int ES, int V, int MT, bool NT>
+template <int ES, int V, int MT, int NT>
 __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
                                                           unsigned char* __restrict__ dst) {
   constexpr int DW = V * ES / 4;                 // dwords per vector
@@ -121,25 +132,24 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
   typedef typename Word<SLOT>::type Vec;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
-  // tile-invariant lane state (wavefront-level index arithmetic done once)
-  int32_t src_in[MT], dst_in[MT];
-  uint32_t park_at[MT], pick_at[MT];
+  // tile-invariant lane state (wavefront-level index arithmetic done once):
+  // per owned micro-tile its source offset and LDS base index; per picked vector its destination offset
+  int32_t src_in[MT], dst_in[MT * V];
+  uint32_t park_g[MT];
   bool act[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     uint32_t u = threadIdx.x + (uint32_t)m * kBlock;
     act[m] = u < P.n_micro;
-    src_in[m] = dst_in[m] = 0;
-    park_at[m] = pick_at[m] = 0;
-    if (act[m]) {
-      uint32_t c;
-      micro_from_src_order(P, u, &src_in[m], &c);
-      park_at[m] = lds_slot(P, c) * SLOT;
-      dst_in[m] = micro_dst_offset(P, u);
-      pick_at[m] = lds_slot(P, u) * SLOT;
-    }
+    src_in[m] = 0;
+    park_g[m] = 0;
+    if (act[m]) micro_from_src_order(P, u, &src_in[m], &park_g[m]);
   }
-  const uint32_t plane_bytes = P.plane_slots * SLOT;
+#pragma unroll
+  for (int j = 0; j < MT * V; ++j) {
+    uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+    dst_in[j] = g < P.n_vec ? vector_dst_offset(P, g) : 0;
+  }
 
   uint32_t r[MT][V][DW];
   auto load_tile = [&](uint32_t tile) {
@@ -159,9 +169,15 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
       }
   };
 
-  uint32_t tile = blockIdx.x;
-  if (tile < P.n_tiles) load_tile(tile);
-  while (tile < P.n_tiles) {
+  uint32_t tile = blockIdx.x, tile_step = gridDim.x, tile_end = P.n_tiles;
+  if (P.blocked) {
+    const uint32_t per_wg = (P.n_tiles + gridDim.x - 1) / gridDim.x;
+    tile = blockIdx.x * per_wg;
+    tile_step = 1;
+    tile_end = min(P.n_tiles, tile + per_wg);
+  }
+  if (tile < tile_end) load_tile(tile);
+  while (tile < tile_end) {
 #pragma unroll
     for (int m = 0; m < MT; ++m)
       if (act[m]) {
@@ -173,24 +189,23 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
           uint32_t* w = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
           for (int k = 0; k < DW; ++k) w[k] = o[ip][k];
-          *reinterpret_cast<Vec*>(lds + (uint32_t)ip * plane_bytes + park_at[m]) = v;
+          *reinterpret_cast<Vec*>(lds + lds_slot(P, park_g[m] + (uint32_t)ip * P.gpos_pv) * SLOT) = v;
         }
       }
     __syncthreads();
     int64_t so, dof;
     tile_origin(P, tile, &so, &dof);
-    const uint32_t next = tile + gridDim.x;
-    if (next < P.n_tiles) load_tile(next);
+    const uint32_t next = tile + tile_step;
+    if (next < tile_end) load_tile(next);
     unsigned char* base = dst + dof * ES;
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
-      if (act[m]) {
-#pragma unroll
-        for (int ip = 0; ip < V; ++ip) {
-          Vec v = *reinterpret_cast<const Vec*>(lds + (uint32_t)ip * plane_bytes + pick_at[m]);
-          gstore<NT>(reinterpret_cast<Vec*>(base + ((int64_t)dst_in[m] + (int64_t)ip * P.b_p) * ES), v);
-        }
+    for (int j = 0; j < MT * V; ++j) {
+      const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+      if (g < P.n_vec) {
+        Vec v = *reinterpret_cast<const Vec*>(lds + lds_slot(P, g) * SLOT);
+        gstore<NT>(reinterpret_cast<Vec*>(base + (int64_t)dst_in[j] * ES), v);
       }
+    }
     __syncthreads();
     tile = next;
   }
@@ -228,10 +243,14 @@ static void launch_generic(const lc_plan& plan, const void* src, void* dst, unsi
 template <int W, int U>
 static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   typedef typename Word<W>::type T;
-  if (plan.nontemporal)
-    hipLaunchKernelGGL((direct_kernel<W, U, true>), dim3(grid), dim3(kBlock), 0, s, plan.direct, static_cast<const T*>(src), static_cast<T*>(dst));
-  else
-    hipLaunchKernelGGL((direct_kernel<W, U, false>), dim3(grid), dim3(kBlock), 0, s, plan.direct, static_cast<const T*>(src), static_cast<T*>(dst));
+  const T* sp = static_cast<const T*>(src);
+  T* dp = static_cast<T*>(dst);
+  switch (plan.nontemporal) {
+    case 0: hipLaunchKernelGGL((direct_kernel<W, U, 0>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
+    case 1: hipLaunchKernelGGL((direct_kernel<W, U, 1>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
+    case 2: hipLaunchKernelGGL((direct_kernel<W, U, 2>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
+    default: hipLaunchKernelGGL((direct_kernel<W, U, 3>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
+  }
 }
 template <int W>
 static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
@@ -243,26 +262,30 @@ static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsig
   }
 }
 
-template <int ES, int V, int MT>
-static hipError_t launch_transpose_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+template <int ES, int V, int MT, int NT>
+static hipError_t launch_transpose_n(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   const unsigned char* sp = static_cast<const unsigned char*>(src);
   unsigned char* dp = static_cast<unsigned char*>(dst);
   if (plan.lds_bytes > 64 * 1024) {
-    static bool raised_nt = false, raised = false;   // per instantiation
-    bool& flag = plan.nontemporal ? raised_nt : raised;
-    if (!flag) {
-      hipError_t e = plan.nontemporal
-          ? hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
-          : hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    static bool raised = false;   // one flag per instantiation: the attribute belongs to the kernel function
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
-      flag = true;
+      raised = true;
     }
   }
-  if (plan.nontemporal)
-    hipLaunchKernelGGL((transpose_kernel<ES, V, MT, true>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
-  else
-    hipLaunchKernelGGL((transpose_kernel<ES, V, MT, false>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
   return hipSuccess;
+}
+template <int ES, int V, int MT>
+static hipError_t launch_transpose_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  switch (plan.nontemporal) {
+    case 0: return launch_transpose_n<ES, V, MT, 0>(plan, src, dst, grid, s);
+    case 1: return launch_transpose_n<ES, V, MT, 1>(plan, src, dst, grid, s);
+    case 2: return launch_transpose_n<ES, V, MT, 2>(plan, src, dst, grid, s);
+    default: return launch_transpose_n<ES, V, MT, 3>(plan, src, dst, grid, s);
+  }
 }
 template <int ES, int V>
 static hipError_t launch_transpose(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {

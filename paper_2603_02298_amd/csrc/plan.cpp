@@ -21,6 +21,13 @@ Tuning tuning_from_env() {
   t.nontemporal = env_int("LC_TUNE_NONTEMPORAL", t.nontemporal);
   t.force_class = env_int("LC_TUNE_FORCE_CLASS", t.force_class);
   t.max_vec_bytes = env_int("LC_TUNE_MAX_VEC_BYTES", t.max_vec_bytes);
+  t.blocked = env_int("LC_TUNE_BLOCKED", t.blocked);
+  if (const char* v = std::getenv("LC_TUNE_TILE")) {
+    for (const char* p = v; *p;) {
+      t.tile.push_back(std::strtoll(p, const_cast<char**>(&p), 10));
+      if (*p == ',') ++p; else break;
+    }
+  }
   return t;
 }
 
@@ -91,58 +98,77 @@ static int common_pow2(int cap, const std::vector<int64_t>& must_divide) {
 int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes) {
   int per_pass = 256 / access_bytes;
   if (per_pass > 64) per_pass = 64;
+  const int words = access_bytes >= 4 ? access_bytes / 4 : 1;
   int cost = 0;
   for (int base = 0; base < lanes; base += per_pass) {
-    uint32_t seen[64][8];
-    int cnt[64];
+    uint8_t cnt[64];
+    uint32_t first[64];
     std::memset(cnt, 0, sizeof(cnt));
     for (int l = base; l < base + per_pass && l < lanes; ++l) {
       if (!active[l]) continue;
-      for (int w = 0; w < access_bytes / 4 || (w == 0 && access_bytes < 4); ++w) {
+      for (int w = 0; w < words; ++w) {
         uint32_t dword = byte_addr[l] / 4 + (uint32_t)w;
-        int bank = (int)(dword % 64);
-        bool dup = false;
-        for (int k = 0; k < cnt[bank] && k < 8; ++k) if (seen[bank][k] == dword) dup = true;
-        if (!dup) { if (cnt[bank] < 8) seen[bank][cnt[bank]] = dword; cnt[bank]++; }
+        int bank = (int)(dword & 63u);
+        if (cnt[bank] && first[bank] == dword) continue;   // same dword again: served by the same access
+        if (!cnt[bank]) first[bank] = dword;
+        cnt[bank]++;
       }
     }
     int worst = 1;
-    for (int b = 0; b < 64; ++b) worst = std::max(worst, cnt[b]);
+    for (int b = 0; b < 64; ++b) worst = std::max<int>(worst, cnt[b]);
     cost += worst - 1;
   }
   return cost;
 }
 
-static int transpose_swizzle_cost(const TransposeParams& P, int V, int es, int micro_per_thread) {
-  // writes: lane u parks its V vectors at plane ip, slot(c(u)); reads: lane w picks slot(w)
+int transpose_swizzle_cost(const TransposeParams& P, int V, int es, uint32_t max_waves, int max_ip, int lanes = 64) {
+  // parks: lane u writes vector (u, ip) at slot(g0(u) + ip * gpos_pv); picks: lane reads slot(g) for consecutive g
   int cost = 0;
   int slot_bytes = V * es;
-  uint32_t waves = std::min<uint32_t>((P.n_micro + 63) / 64, 4u * (uint32_t)micro_per_thread);
+  uint32_t waves = std::min<uint32_t>((P.n_micro + 63) / 64, max_waves);
   for (uint32_t wv = 0; wv < waves; ++wv) {
-    uint32_t wa[64], ra[64];
+    uint32_t g0[64];
     bool act[64];
     for (int l = 0; l < 64; ++l) {
       uint32_t u = wv * 64 + (uint32_t)l;
       act[l] = u < P.n_micro;
       int32_t so;
-      uint32_t c = 0;
-      if (act[l]) micro_from_src_order(P, u, &so, &c);
-      wa[l] = lds_slot(P, c) * (uint32_t)slot_bytes;
-      ra[l] = lds_slot(P, u) * (uint32_t)slot_bytes;
+      g0[l] = 0;
+      if (act[l]) micro_from_src_order(P, u, &so, &g0[l]);
     }
-    cost += lds_pass_conflicts(wa, act, 64, slot_bytes) + lds_pass_conflicts(ra, act, 64, slot_bytes);
+    for (int ip = 0; ip < V && ip < max_ip; ++ip) {
+      uint32_t wa[64];
+      for (int l = 0; l < 64; ++l) wa[l] = lds_slot(P, g0[l] + (uint32_t)ip * P.gpos_pv) * (uint32_t)slot_bytes;
+      cost += lds_pass_conflicts(wa, act, lanes, slot_bytes);
+    }
+  }
+  uint32_t pick_waves = std::min<uint32_t>((P.n_vec + 63) / 64, max_waves);
+  for (uint32_t wv = 0; wv < pick_waves; ++wv) {
+    uint32_t ra[64];
+    bool act[64];
+    for (int l = 0; l < 64; ++l) {
+      uint32_t g = wv * 64 + (uint32_t)l;
+      act[l] = g < P.n_vec;
+      ra[l] = lds_slot(P, g) * (uint32_t)slot_bytes;
+    }
+    cost += lds_pass_conflicts(ra, act, lanes, slot_bytes);
   }
   return cost;
 }
 
 // Contiguous run length (elements) of a tile along one side: follow the modes in stride order
-// starting at stride 1 while each is fully inside the tile and the next continues it.
-static int64_t run_length(const std::vector<JointMode>& J, const std::vector<int64_t>& t, bool src_side) {
+// (`order`, computed once per plan) starting at stride 1 while each is fully inside the tile and the
+// next continues it.
+static std::vector<int> stride_order(const std::vector<JointMode>& J, bool src_side) {
   std::vector<int> order;
   for (int k = 0; k < (int)J.size(); ++k) order.push_back(k);
   std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
     return (src_side ? J[(size_t)x].a : J[(size_t)x].b) < (src_side ? J[(size_t)y].a : J[(size_t)y].b);
   });
+  return order;
+}
+static int64_t run_length(const std::vector<JointMode>& J, const std::vector<int>& order, const std::vector<int64_t>& t,
+                          bool src_side) {
   int64_t run = 1, expect = 1;
   for (int k : order) {
     int64_t st = src_side ? J[(size_t)k].a : J[(size_t)k].b;
@@ -194,7 +220,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   plan->n_elems = n;
   plan->src_align = std::min(src_align, 256u);
   plan->dst_align = std::min(dst_align, 256u);
-  plan->nontemporal = tune.nontemporal > 0;
+  plan->nontemporal = tune.nontemporal >= 0 ? (tune.nontemporal & 3) : 1;   // stores: decided per class below
 
   // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
   Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
@@ -262,9 +288,14 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     int V = common_pow2(cap, need);
     while (V >= 2 && !transpose_instantiated(es, V)) V /= 2;
     if (V >= 2) {
-      int mpt = tune.micro_per_thread > 0 ? tune.micro_per_thread : 1;
-      if (mpt != 1 && mpt != 2 && mpt != 4) mpt = 1;
-      const int64_t target = (int64_t)kBlock * mpt;
+      // Tile size: up to 4 micro-tiles per lane (64 KiB of fp32), but never so large that fewer than
+      // ~1024 tiles remain for the 256 CUs; growth stops early once both sides move >= 512-byte runs.
+      int64_t target = 4 * kBlock;
+      while (target > 64 && n / (target * V * V) < 1024) target /= 2;
+      if (tune.micro_per_thread == 1 || tune.micro_per_thread == 2 || tune.micro_per_thread == 4)
+        target = (int64_t)kBlock * tune.micro_per_thread;
+      const int64_t enough_run_bytes = 512;
+      const std::vector<int> src_order = stride_order(J, true), dst_order = stride_order(J, false);
       // a6: grow the tile one prime factor at a time, always helping the shorter contiguous run
       std::vector<int64_t> t((size_t)nj, 1);
       t[(size_t)p] = V;
@@ -279,24 +310,35 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
           int64_t f = smallest_prime_factor(left);
           if (micro * f > target) continue;
           t[(size_t)k] *= f;
-          int64_t rs = run_length(J, t, true), rd = run_length(J, t, false);
+          int64_t rs = run_length(J, src_order, t, true), rd = run_length(J, dst_order, t, false);
           t[(size_t)k] /= f;
           int64_t mn = std::min(rs, rd), sm = rs + rd;
           if (mn > best_min || (mn == best_min && sm > best_sum)) { best = k; best_min = mn; best_sum = sm; best_f = f; }
         }
         if (best < 0) break;
-        int64_t cur_min = std::min(run_length(J, t, true), run_length(J, t, false));
-        int64_t cur_sum = run_length(J, t, true) + run_length(J, t, false);
+        const int64_t cur_s = run_length(J, src_order, t, true), cur_d = run_length(J, dst_order, t, false);
+        int64_t cur_min = std::min(cur_s, cur_d), cur_sum = cur_s + cur_d;
         if (best_min <= cur_min && best_sum <= cur_sum) break;   // growing further no longer lengthens any run
+        if (tune.micro_per_thread <= 0 && micro >= kBlock && cur_min * es >= enough_run_bytes) break;   // runs are long enough: keep more tiles
         t[(size_t)best] *= best_f;
         micro *= best_f;
       }
+      if (tune.tile.size() == (size_t)nj) {   // explicit tile (tuning): must divide the extents and hold whole micro-tiles
+        bool valid = true;
+        int64_t m2 = 1;
+        for (int k = 0; k < nj; ++k) {
+          int64_t te = tune.tile[(size_t)k];
+          if (te < 1 || J[(size_t)k].extent % te != 0 || ((k == p || k == q) && te % V != 0)) valid = false;
+          else m2 *= (k == p || k == q) ? te / V : te;
+        }
+        if (valid && m2 <= 4 * kBlock) { t = tune.tile; micro = m2; }
+      }
       // no run can be lengthened any more: still fill the workgroup, smallest destination strides first
-      for (int k = 0; k < nj; ++k)
+      for (int k = 0; k < nj && tune.tile.size() != (size_t)nj; ++k)
         for (;;) {
           int64_t left = J[(size_t)k].extent / t[(size_t)k];
           int64_t f = left > 1 ? smallest_prime_factor(left) : 0;
-          if (f == 0 || micro * f > target) break;
+          if (f == 0 || micro * f > (tune.micro_per_thread > 0 ? target : std::min<int64_t>(target, kBlock))) break;
           t[(size_t)k] *= f;
           micro *= f;
         }
@@ -335,35 +377,41 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
         }
         int64_t span_s = 0, span_d = 0;
         for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * J[(size_t)k].a; span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
-        if (span_s >= (1ll << 30) || span_d >= (1ll << 30) || mm.size() > (size_t)kMaxModes) ok = false;
+        if (span_s >= (1ll << 30) || span_d >= (1ll << 30) || mm.size() >= (size_t)kMaxModes) ok = false;
         if (ok) {
+          // destination order of the tile's vectors: the micro modes and the position ip along p
+          // inside a micro-tile (extent V, destination stride b_p), by destination stride, q first
+          mm.push_back({V, 0, J[(size_t)p].b, false, false});
+          const int pv = (int)mm.size() - 1;
           std::vector<int> so, dord;
-          for (int k = 0; k < (int)mm.size(); ++k) { so.push_back(k); dord.push_back(k); }
+          for (int k = 0; k < (int)mm.size(); ++k) { if (k != pv) so.push_back(k); dord.push_back(k); }
           std::stable_sort(so.begin(), so.end(), [&](int x, int y) {
             if (mm[(size_t)x].is_p != mm[(size_t)y].is_p) return mm[(size_t)x].is_p;
             return mm[(size_t)x].sa < mm[(size_t)y].sa; });
           std::stable_sort(dord.begin(), dord.end(), [&](int x, int y) {
             if (mm[(size_t)x].is_q != mm[(size_t)y].is_q) return mm[(size_t)x].is_q;
             return mm[(size_t)x].sb < mm[(size_t)y].sb; });
-          std::vector<uint32_t> dpos(mm.size(), 0);
+          std::vector<uint32_t> gpos(mm.size(), 0);
           uint32_t run = 1;
           for (size_t j = 0; j < dord.size(); ++j) {
             const MM& m = mm[(size_t)dord[j]];
-            P.ext_d[j] = (uint32_t)m.ext;
+            P.ext_d[j] = make_fastdiv((uint32_t)m.ext);
             P.sb_d[j] = (int32_t)m.sb;
-            dpos[(size_t)dord[j]] = run;
+            gpos[(size_t)dord[j]] = run;
             run *= (uint32_t)m.ext;
           }
+          P.n_dst_modes = (int32_t)dord.size();
+          P.gpos_pv = gpos[(size_t)pv];
           for (size_t j = 0; j < so.size(); ++j) {
             const MM& m = mm[(size_t)so[j]];
-            P.ext_s[j] = (uint32_t)m.ext;
+            P.ext_s[j] = make_fastdiv((uint32_t)m.ext);
             P.sa_s[j] = (int32_t)m.sa;
-            P.dpos_s[j] = dpos[(size_t)so[j]];
+            P.gpos_s[j] = gpos[(size_t)so[j]];
           }
-          P.n_micro_modes = (int32_t)mm.size();
-          P.n_micro = run;
+          P.n_micro_modes = (int32_t)so.size();
+          P.n_vec = run;
+          P.n_micro = run / (uint32_t)V;
           P.a_q = (int32_t)J[(size_t)q].a;
-          P.b_p = (int32_t)J[(size_t)p].b;
           if (J[(size_t)q].a * (V - 1) >= (1ll << 30) || J[(size_t)p].b * (V - 1) >= (1ll << 30)) ok = false;
         }
       }
@@ -388,19 +436,20 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
             P.rb[k] = rest[k].b;
           }
           P.n_tiles = (uint32_t)tiles;
+          P.blocked = tune.blocked > 0 ? 1u : 0u;
         }
       }
       if (ok) {
-        P.plane_slots = (P.n_micro + 15u) & ~15u;
         // swizzle: XOR four higher bits of the slot index into its low four bits; pick the source bits
-        // that minimise the modelled bank conflicts of the parking writes (reads stay contiguous)
+        // that minimise the modelled bank conflicts of the parking writes (picks stay contiguous)
+        // (the search looks at the first wavefront only; describe() reports the model over the whole tile)
         int best_shift = -1, best_cost = 0;
         P.swz_shift = 0; P.swz_mask = 0;
-        best_cost = transpose_swizzle_cost(P, V, es, mpt);
+        best_cost = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
         if (tune.swizzle_shift == -2) {
-          for (int sh = 4; sh <= 12 && (P.n_micro >> sh) > 0; ++sh) {
+          for (int sh = 4; best_cost > 0 && sh <= 12 && (P.n_vec >> sh) > 0; ++sh) {
             P.swz_shift = (uint32_t)sh; P.swz_mask = 15;
-            int c = transpose_swizzle_cost(P, V, es, mpt);
+            int c = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
             if (c < best_cost) { best_cost = c; best_shift = sh; }
           }
         } else if (tune.swizzle_shift >= 4) {
@@ -408,7 +457,6 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
         }
         if (best_shift >= 4) { P.swz_shift = (uint32_t)best_shift; P.swz_mask = 15; }
         else { P.swz_shift = 0; P.swz_mask = 0; }
-        plan->lds_conflict_cost = transpose_swizzle_cost(P, V, es, mpt);
         plan->cls = KernelClass::Transpose;
         plan->V = V;
         plan->width_bytes = V * es;
@@ -417,11 +465,17 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
         plan->tile_extent = t;
         plan->p_mode = p;
         plan->q_mode = q;
-        plan->lds_bytes = P.plane_slots * (unsigned)V * (unsigned)(V * es);
-        plan->src_run_bytes = run_length(J, t, true) * es;
-        plan->dst_run_bytes = run_length(J, t, false) * es;
+        plan->lds_bytes = ((P.n_vec + 15u) & ~15u) * (unsigned)(V * es);
+        plan->src_run_bytes = run_length(J, src_order, t, true) * es;
+        plan->dst_run_bytes = run_length(J, dst_order, t, false) * es;
+        // nontemporal stores only when every store instruction covers whole 128-byte lines
+        if (tune.nontemporal < 0 && plan->dst_run_bytes % 128 == 0) plan->nontemporal |= 2;
+        // nontemporal stores only when every store instruction covers whole 128-byte lines
+        // Measured on MI355X: HBM efficiency is best with ONE resident workgroup per CU (its next tile's
+        // loads overlap its current tile's stores); short grids need more workgroups to fill the chip.
         int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
-        plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(8, fit));
+        int want = P.n_tiles >= 16384 ? 1 : (P.n_tiles >= 2048 ? 2 : 4);
+        plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(std::min(8, fit), want));
         plan->src_align = (unsigned)(V * es);
         plan->dst_align = (unsigned)(V * es);
         return LC_OK;
@@ -468,10 +522,15 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   P.loop_extent = loop_mode >= 0 ? (uint32_t)J[(size_t)loop_mode].extent : 1u;
   P.loop_sa = loop_mode >= 0 ? J[(size_t)loop_mode].a / VEC : 0;
   P.loop_sb = loop_mode >= 0 ? J[(size_t)loop_mode].b / VEC : 0;
+  P.blocked = tune.blocked > 0 ? 1u : 0u;
   plan->cls = KernelClass::Direct;
   plan->width_bytes = VEC * es;
-  plan->unroll = (tune.unroll == 1 || tune.unroll == 2 || tune.unroll == 4 || tune.unroll == 8) ? tune.unroll : 4;
-  plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : 8;
+  // about 16 KiB of accesses in flight per CU measured best on MI355X: unroll x workgroups = 64 / width
+  const int W = VEC * es;
+  int dflt_unroll = W >= 16 ? 2 : (W >= 4 ? 4 : 8), dflt_wgs = W >= 8 ? 2 : 4;
+  plan->unroll = (tune.unroll == 1 || tune.unroll == 2 || tune.unroll == 4 || tune.unroll == 8) ? tune.unroll : dflt_unroll;
+  plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : dflt_wgs;
+  if (tune.nontemporal < 0 && ((int64_t)W * (q >= 0 ? J[(size_t)q].extent / VEC : 1)) % 128 == 0) plan->nontemporal |= 2;
   plan->src_align = (unsigned)(VEC * es);
   plan->dst_align = (unsigned)(VEC * es);
   return LC_OK;
@@ -496,13 +555,14 @@ std::string describe(const lc_plan& plan) {
     s += " micro_tiles=" + std::to_string(plan.transpose.n_micro) + " per_lane=" + std::to_string(plan.micro_per_thread);
     s += " tiles=" + std::to_string(plan.transpose.n_tiles) + " lds_bytes=" + std::to_string(plan.lds_bytes);
     s += " swizzle_shift=" + std::to_string(plan.transpose.swz_mask ? (int)plan.transpose.swz_shift : -1);
-    s += " modelled_lds_conflicts=" + std::to_string(plan.lds_conflict_cost);
+    s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.elem_bytes, 1u << 20, 64));
     s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
   } else if (plan.cls == KernelClass::Direct) {
     s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);
     s += " unroll=" + std::to_string(plan.unroll);
   }
-  s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal ? 1 : 0);
+  s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal);
+  s += " blocked=" + std::to_string(plan.cls == KernelClass::Transpose ? plan.transpose.blocked : plan.cls == KernelClass::Direct ? plan.direct.blocked : 0u);
   if (!plan.note.empty()) s += " note=\"" + plan.note + "\"";
   return s;
 }

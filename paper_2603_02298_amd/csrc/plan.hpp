@@ -23,7 +23,9 @@ struct Tuning {
   int wgs_per_cu = -1;         // persistent grid size = CUs * wgs_per_cu
   int unroll = -1;             // direct: items per lane per loop trip (1, 2, 4, 8)
   int swizzle_shift = -2;      // transpose: -1 = no swizzle
-  int nontemporal = -1;        // 1 = nontemporal loads and stores
+  int nontemporal = -1;        // bit 0 = nontemporal loads, bit 1 = nontemporal stores
+  int blocked = -1;            // 1 = contiguous range of tiles / items per workgroup, 0 = strided by the grid
+  std::vector<int64_t> tile;   // transpose: tile extents per joint mode (overrides the planner's choice)
   int force_class = -1;        // 0 generic, 1 direct, 2 transpose (falls back when not applicable)
   int max_vec_bytes = -1;      // cap on the access width
 };
@@ -52,13 +54,12 @@ struct lc_plan {
   lc::TransposeParams transpose{};
   unsigned lds_bytes = 0;
   int64_t src_run_bytes = 0, dst_run_bytes = 0;
-  int lds_conflict_cost = 0;               // modelled bank-conflict cost of the chosen swizzle
 
   // Generic
   lc::GenericParams generic{};
 
   int wgs_per_cu = 0;
-  bool nontemporal = false;
+  int nontemporal = 0;                     // bit 0: loads, bit 1: stores
   std::string note;                        // why a faster class was not taken
 };
 

@@ -51,43 +51,52 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
       for (uint32_t u = 0; u < lanes; ++u) {
         if (u >= P.n_micro) continue;
         int32_t so;
-        uint32_t c;
-        micro_from_src_order(P, u, &so, &c);
+        uint32_t g0;
+        micro_from_src_order(P, u, &so, &g0);
         for (int iq = 0; iq < V; ++iq) {
           int64_t off = (sbase + so + (int64_t)iq * P.a_q) * es;
           if (off < 0 || off + slot > B.src_bytes) { B.ok = false; break; }
           for (int ip = 0; ip < V; ++ip) {
-            size_t l = ((size_t)ip * P.plane_slots + lds_slot(P, c)) * (size_t)slot + (size_t)iq * (size_t)es;
+            size_t l = (size_t)lds_slot(P, g0 + (uint32_t)ip * P.gpos_pv) * (size_t)slot + (size_t)iq * (size_t)es;
             if (l + (size_t)es > lds.size()) { B.ok = false; break; }
             std::memcpy(&lds[l], B.src + off + (int64_t)ip * es, (size_t)es);
           }
         }
       }
-      // store phase: lane w picks up V vectors along q and writes one per step along p
-      for (uint32_t w = 0; w < lanes && B.ok; ++w) {
-        if (w >= P.n_micro) continue;
-        int32_t dof = micro_dst_offset(P, w);
-        for (int ip = 0; ip < V; ++ip) {
-          int64_t off = (dbase + dof + (int64_t)ip * P.b_p) * es;
-          size_t l = ((size_t)ip * P.plane_slots + lds_slot(P, w)) * (size_t)slot;
-          if (off < 0 || off + slot > B.dst_bytes || l + (size_t)slot > lds.size()) { B.ok = false; break; }
-          std::memcpy(B.dst + off, &lds[l], (size_t)slot);
-        }
+      // store phase: the tile's vectors in destination order, consecutive lanes taking consecutive vectors
+      for (uint32_t g = 0; g < lanes * (uint32_t)V && B.ok; ++g) {
+        if (g >= P.n_vec) continue;
+        int64_t off = (dbase + vector_dst_offset(P, g)) * es;
+        size_t l = (size_t)lds_slot(P, g) * (size_t)slot;
+        if (off < 0 || off + slot > B.dst_bytes || l + (size_t)slot > lds.size()) { B.ok = false; break; }
+        std::memcpy(B.dst + off, &lds[l], (size_t)slot);
       }
       if (lds_conflicts && tile == 0) {
         for (uint32_t wave = 0; wave * 64 < lanes; ++wave) {
-          uint32_t wa[64], ra[64];
+          uint32_t g0[64];
           bool act[64];
           for (int l = 0; l < 64; ++l) {
             uint32_t u = wave * 64 + (uint32_t)l;
             act[l] = u < P.n_micro;
             int32_t so;
-            uint32_t c = 0;
-            if (act[l]) micro_from_src_order(P, u, &so, &c);
-            wa[l] = lds_slot(P, c) * (uint32_t)slot;
-            ra[l] = lds_slot(P, u) * (uint32_t)slot;
+            g0[l] = 0;
+            if (act[l]) micro_from_src_order(P, u, &so, &g0[l]);
           }
-          *lds_conflicts += (int64_t)V * (lds_pass_conflicts(wa, act, 64, slot) + lds_pass_conflicts(ra, act, 64, slot));
+          for (int ip = 0; ip < V; ++ip) {
+            uint32_t wa[64];
+            for (int l = 0; l < 64; ++l) wa[l] = lds_slot(P, g0[l] + (uint32_t)ip * P.gpos_pv) * (uint32_t)slot;
+            *lds_conflicts += lds_pass_conflicts(wa, act, 64, slot);
+          }
+        }
+        for (uint32_t wave = 0; wave * 64 < lanes * (uint32_t)V; ++wave) {
+          uint32_t ra[64];
+          bool act[64];
+          for (int l = 0; l < 64; ++l) {
+            uint32_t g = wave * 64 + (uint32_t)l;
+            act[l] = g < P.n_vec;
+            ra[l] = lds_slot(P, g) * (uint32_t)slot;
+          }
+          *lds_conflicts += lds_pass_conflicts(ra, act, 64, slot);
         }
       }
     }
