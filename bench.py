@@ -5,7 +5,7 @@ A step is one pass of the whole hot path — validate, coalesce, refine, sort, v
 (all host), launch, kernel — through the C ABI call lc_copy, over one synthetic batch that is
 already resident in HBM.  Buffers rotate so that a step never finds its data in the last-level cache.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4a|c4b|c5] [--all]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4a|c4b|c5|copy] [--no-all]
 
 Prints ONE JSON line (see the keys below).  `roofline` is measured live with HIP events on the
 launch stream; `cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
@@ -123,7 +123,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2")
-    ap.add_argument("--all", action="store_true", help="also time the other workloads (reported under all_workloads)")
+    ap.add_argument("--no-all", action="store_true", help="skip timing the other workloads (reported under all_workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -165,9 +165,9 @@ def main():
                      "kernel_ms": round(ms_kernel, 5), "dram_minimum_bytes": dram_min,
                      "frac_dram_minimum": round(dram_min / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
     }
-    if args.all:
+    if not args.no_all:
         allw = {}
-        for name in W.WORKLOAD_NAMES:
+        for name in W.WORKLOAD_NAMES + ["copy"]:
             if name == args.workload:
                 continue
             wk = W.workload(name)

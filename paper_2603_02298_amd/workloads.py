@@ -88,7 +88,14 @@ def _c5(scale=1):
     return Workload("c5_nchw_to_nhwc_f32", "f32", src, dst, n, n, n, "uniform", "rank-4 fp32 permutation NCHW -> NHWC")
 
 
-_MAKERS = {"c1": _c1, "c2": _c2, "c3": _c3, "c4a": _c4a, "c4b": _c4b, "c5": _c5}
+def _copy(scale=1):
+    # not one of the BASELINE configs: a plain contiguous copy, used to calibrate the profiler's byte
+    # counters and as the practical ceiling of any copy on this chip
+    n = (1 << 28) // scale
+    return Workload("c0_plain_copy_f32", "f32", "%d:1" % n, "%d:1" % n, n, n, n, "uniform", "contiguous copy (calibration)")
+
+
+_MAKERS = {"c1": _c1, "c2": _c2, "c3": _c3, "c4a": _c4a, "c4b": _c4b, "c5": _c5, "copy": _copy}
 
 
 def workload(name, scale=1):
