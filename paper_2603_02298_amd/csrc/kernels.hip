@@ -320,13 +320,17 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
   } else if (plan.cls == KernelClass::Direct) {
     uint64_t want = ((uint64_t)plan.direct.n_items + (uint64_t)kBlock * plan.unroll - 1) / ((uint64_t)kBlock * plan.unroll);
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, (uint64_t)cus * plan.wgs_per_cu));
-    switch (plan.width_bytes) {
-      case 1: launch_direct<1>(plan, src, dst, grid, s); break;
-      case 2: launch_direct<2>(plan, src, dst, grid, s); break;
-      case 4: launch_direct<4>(plan, src, dst, grid, s); break;
-      case 8: launch_direct<8>(plan, src, dst, grid, s); break;
-      case 16: launch_direct<16>(plan, src, dst, grid, s); break;
-      default: return LC_ERR_UNSUPPORTED_DTYPE;
+    for (int64_t j = 0; j < plan.n_launches; ++j) {
+      const void* sj = static_cast<const unsigned char*>(src) + j * plan.launch_src_step * plan.elem_bytes;
+      void* dj = static_cast<unsigned char*>(dst) + j * plan.launch_dst_step * plan.elem_bytes;
+      switch (plan.width_bytes) {
+        case 1: launch_direct<1>(plan, sj, dj, grid, s); break;
+        case 2: launch_direct<2>(plan, sj, dj, grid, s); break;
+        case 4: launch_direct<4>(plan, sj, dj, grid, s); break;
+        case 8: launch_direct<8>(plan, sj, dj, grid, s); break;
+        case 16: launch_direct<16>(plan, sj, dj, grid, s); break;
+        default: return LC_ERR_UNSUPPORTED_DTYPE;
+      }
     }
   } else {
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(plan.transpose.n_tiles, (uint64_t)cus * plan.wgs_per_cu));

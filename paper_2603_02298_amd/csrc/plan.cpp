@@ -22,6 +22,7 @@ Tuning tuning_from_env() {
   t.force_class = env_int("LC_TUNE_FORCE_CLASS", t.force_class);
   t.max_vec_bytes = env_int("LC_TUNE_MAX_VEC_BYTES", t.max_vec_bytes);
   t.blocked = env_int("LC_TUNE_BLOCKED", t.blocked);
+  t.max_items = env_int("LC_TUNE_MAX_ITEMS", (int)t.max_items);
   if (const char* v = std::getenv("LC_TUNE_TILE")) {
     for (const char* p = v; *p;) {
       t.tile.push_back(std::strtoll(p, const_cast<char**>(&p), 10));
@@ -301,6 +302,12 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
       t[(size_t)p] = V;
       t[(size_t)q] = V;
       int64_t micro = 1;
+      // offsets inside a tile are 32-bit in the kernel: a growth step must keep both spans below 2^30 elements
+      auto spans_fit = [&](const std::vector<int64_t>& tt) {
+        int64_t ss = 0, sd = 0;
+        for (int k = 0; k < nj; ++k) { ss += (tt[(size_t)k] - 1) * J[(size_t)k].a; sd += (tt[(size_t)k] - 1) * J[(size_t)k].b; }
+        return ss < (1ll << 30) && sd < (1ll << 30);
+      };
       for (;;) {
         int best = -1;
         int64_t best_min = -1, best_sum = -1, best_f = 1;
@@ -310,8 +317,10 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
           int64_t f = smallest_prime_factor(left);
           if (micro * f > target) continue;
           t[(size_t)k] *= f;
+          const bool fits = spans_fit(t);
           int64_t rs = run_length(J, src_order, t, true), rd = run_length(J, dst_order, t, false);
           t[(size_t)k] /= f;
+          if (!fits) continue;
           int64_t mn = std::min(rs, rd), sm = rs + rd;
           if (mn > best_min || (mn == best_min && sm > best_sum)) { best = k; best_min = mn; best_sum = sm; best_f = f; }
         }
@@ -340,6 +349,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
           int64_t f = left > 1 ? smallest_prime_factor(left) : 0;
           if (f == 0 || micro * f > (tune.micro_per_thread > 0 ? target : std::min<int64_t>(target, kBlock))) break;
           t[(size_t)k] *= f;
+          if (!spans_fit(t)) { t[(size_t)k] /= f; break; }
           micro *= f;
         }
       // tiling = zipped_divide of both joint layouts by the tile extents (Sec. 3.5.2): mode 0 is
@@ -503,11 +513,35 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     if (J[(size_t)k].a == 0 && J[(size_t)k].extent > 1 && k != q && J[(size_t)k].extent <= 65536 &&
         (loop_mode < 0 || J[(size_t)k].extent > J[(size_t)loop_mode].extent))
       loop_mode = k;
+  // Work items are indexed with 31 bits.  A larger copy is cut along its outermost joint mode into
+  // equal slices, one launch per slice (a slice is a pointer offset, Sec. 2.5.1).
+  std::vector<JointMode> Jd = J;
+  {
+    int64_t total = 1;
+    int outer = -1;
+    for (int k = 0; k < nj; ++k) {
+      if (k == loop_mode) continue;
+      total *= (k == q) ? Jd[(size_t)k].extent / VEC : Jd[(size_t)k].extent;
+      outer = k;
+    }
+    const int64_t limit = tune.max_items > 0 ? tune.max_items : (1ll << 31) - 1;
+    if (total > limit && outer >= 0) {
+      int64_t ext = (outer == q) ? Jd[(size_t)outer].extent / VEC : Jd[(size_t)outer].extent;
+      int64_t need = (total + limit - 1) / limit, cuts = 0;
+      for (int64_t c = need; c <= ext && c < need + (1 << 20); ++c)
+        if (ext % c == 0) { cuts = c; break; }
+      if (cuts == 0) return LC_ERR_TOO_LARGE;
+      Jd[(size_t)outer].extent /= cuts;
+      plan->n_launches = cuts;
+      plan->launch_src_step = Jd[(size_t)outer].extent * Jd[(size_t)outer].a;
+      plan->launch_dst_step = Jd[(size_t)outer].extent * Jd[(size_t)outer].b;
+    }
+  }
   int64_t items = 1;
   int m = 0;
   for (int k = 0; k < nj; ++k) {
     if (k == loop_mode) continue;
-    int64_t ext = J[(size_t)k].extent, a = J[(size_t)k].a, b = J[(size_t)k].b;
+    int64_t ext = Jd[(size_t)k].extent, a = Jd[(size_t)k].a, b = Jd[(size_t)k].b;
     if (k == q && VEC > 1) ext /= VEC; else { a /= (k == q ? 1 : VEC); b /= (k == q ? 1 : VEC); }
     P.div[m] = make_fastdiv((uint32_t)ext);
     P.sa[m] = a;
@@ -559,6 +593,7 @@ std::string describe(const lc_plan& plan) {
     s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
   } else if (plan.cls == KernelClass::Direct) {
     s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);
+    s += " launches=" + std::to_string(plan.n_launches);
     s += " unroll=" + std::to_string(plan.unroll);
   }
   s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal);

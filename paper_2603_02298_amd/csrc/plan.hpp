@@ -25,6 +25,7 @@ struct Tuning {
   int swizzle_shift = -2;      // transpose: -1 = no swizzle
   int nontemporal = -1;        // bit 0 = nontemporal loads, bit 1 = nontemporal stores
   int blocked = -1;            // 1 = contiguous range of tiles / items per workgroup, 0 = strided by the grid
+  int64_t max_items = -1;      // direct: work items per launch before the copy is sliced (default 2^31 - 1; lowered in tests)
   std::vector<int64_t> tile;   // transpose: tile extents per joint mode (overrides the planner's choice)
   int force_class = -1;        // 0 generic, 1 direct, 2 transpose (falls back when not applicable)
   int max_vec_bytes = -1;      // cap on the access width
@@ -45,6 +46,8 @@ struct lc_plan {
   int width_bytes = 0;                     // bytes per access (element width x vector length)
   lc::DirectParams direct{};
   int unroll = 4;
+  int64_t n_launches = 1;                  // slices along the outermost mode, one launch each
+  int64_t launch_src_step = 0, launch_dst_step = 0;   // elements between consecutive slices
 
   // Transpose
   int V = 0;                               // micro-tile edge (elements)

@@ -34,11 +34,13 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
   } else if (plan.cls == KernelClass::Direct) {
     const DirectParams& P = plan.direct;
     const int W = plan.width_bytes;
-    for (uint32_t item = 0; item < P.n_items; ++item) {
-      int64_t so, dof;
-      direct_offsets(P, item, &so, &dof);
-      for (uint32_t r = 0; r < P.loop_extent; ++r) B.move((so + r * P.loop_sa) * W, (dof + r * P.loop_sb) * W, W);
-    }
+    for (int64_t j = 0; j < plan.n_launches; ++j)
+      for (uint32_t item = 0; item < P.n_items; ++item) {
+        int64_t so, dof;
+        direct_offsets(P, item, &so, &dof);
+        for (uint32_t r = 0; r < P.loop_extent; ++r)
+          B.move((so + r * P.loop_sa) * W + j * plan.launch_src_step * es, (dof + r * P.loop_sb) * W + j * plan.launch_dst_step * es, W);
+      }
   } else {
     const TransposeParams& P = plan.transpose;
     const int V = plan.V, slot = V * es;

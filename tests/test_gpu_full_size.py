@@ -84,3 +84,27 @@ def test_c2_literal_strides(oracle):
     assert torch.equal(dst[do], src[so])
     # every written element is accounted for: the number of non-zero destinations equals the non-zero sources
     assert int((dst != 0).sum()) == int((src != 0).sum())
+
+
+def test_more_than_2_31_work_items(oracle):
+    """A 2^32-element gather: the work items no longer fit 31 bits, so the copy runs as four launches over
+    slices of the outermost mode (24 GiB source span, 8 GiB destination)."""
+    dev = torch.device("cuda:0")
+    n = 1 << 32
+    src_layout, dst_layout = "%d:3" % n, "%d:1" % n
+    plan = lc.Plan(src_layout, dst_layout, "bf16")
+    print(plan.describe(), flush=True)
+    assert "launches=4 " in plan.describe()
+    g = torch.Generator(device=dev)
+    g.manual_seed(W.SEED_BASE)
+    src = torch.randint(-32768, 32767, (3 * n,), device=dev, generator=g, dtype=torch.int16)
+    dst = torch.zeros(n, dtype=torch.int16, device=dev)
+    lc.copy_tensor(src, src_layout, dst, dst_layout, "bf16")
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src[::3])
+    sl, dl = oracle.Layout(src_layout), oracle.Layout(dst_layout)
+    idx = np.concatenate([np.arange(0, 1024), np.arange(n - 1024, n), np.arange((1 << 31) - 512, (1 << 31) + 512),
+                          np.random.default_rng(5).integers(0, n, 100000)])
+    so = torch.from_numpy(sl.offsets_at(idx)).to(dev)
+    do = torch.from_numpy(dl.offsets_at(idx)).to(dev)
+    assert torch.equal(dst[do], src[so])

@@ -127,6 +127,24 @@ def test_tuning_variants_stay_exact(oracle, monkeypatch):
         _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="unroll" + u)
 
 
+def test_sliced_launches(oracle, monkeypatch):
+    # the slicing used beyond 2^31 work items, forced at a small size
+    monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
+    for s, d, dt in [("4096:3", "4096:1", "f32"), ("(64,240):(1,64)", "(64,240):(1,100)", "bf16"),
+                     ("(30,7,11):(1,30,210)", "(30,7,11):(77,11,1)", "f32"), ("(256,64):(1,0)", "(256,64):(1,256)", "f32")]:
+        assert "launches=1 " not in lc.Plan(s, d, dt).describe()
+        _parity(oracle, s, d, dt, seed=9, tag="sliced")
+
+
+def test_literal_strides_pattern_small(oracle):
+    # the shape of BASELINE config 2 with its printed (non-compact) destination strides, scaled down:
+    # 16-byte destination runs at a large pitch, transposing class
+    s = "((8,16),(8,32)):((1,8),(128,1024))"
+    d = "((8,16),(8,32)):((32,8192),(1,256))"
+    assert "class=transpose" in lc.Plan(s, d, "bf16").describe()
+    _parity(oracle, s, d, "bf16", seed=4, tag="literal-small")
+
+
 def test_misaligned_pointers(oracle):
     dev = torch.device("cuda:0")
     n = 4096

@@ -128,6 +128,18 @@ def test_shapes_without_common_refinement_use_generic_class(oracle):
     desc, _ = _check(oracle, "(6,10):(10,1)", "(4,15):(15,1)", "f32", "generic")
 
 
+def test_large_copies_are_sliced_into_launches(oracle, monkeypatch):
+    # work items are indexed with 31 bits; beyond that the outermost joint mode is cut into equal slices.
+    # The limit is lowered here so that the slicing logic runs on sizes the host can check.
+    assert "launches=4 " in lc.Plan("%d:3" % (1 << 32), "%d:1" % (1 << 32), "bf16").describe()
+    assert "launches=16 " in lc.Plan("%d:1" % (1 << 36), "%d:1" % (1 << 36), "f32").describe()
+    monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
+    for s, d, dt, launches in [("4096:3", "4096:1", "f32", 8), ("(64,240):(1,64)", "(64,240):(1,100)", "bf16", 4),
+                               ("(30,7,11):(1,30,210)", "(30,7,11):(77,11,1)", "f32", 3), ("4099:1", "4099:1", "b8", 4099)]:
+        desc, _ = _check(oracle, s, d, dt, "direct")
+        assert "launches=%d " % launches in desc, desc
+
+
 def test_plan_errors():
     with pytest.raises(lc.LayoutCopyError) as e:
         lc.Plan("8:1", "9:1", "f32")
