@@ -131,7 +131,7 @@ def test_sliced_launches(oracle, monkeypatch):
     # the slicing used beyond 2^31 work items, forced at a small size
     monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
     for s, d, dt in [("4096:3", "4096:1", "f32"), ("(64,240):(1,64)", "(64,240):(1,100)", "bf16"),
-                     ("(30,7,11):(1,30,210)", "(30,7,11):(77,11,1)", "f32"), ("(256,64):(1,0)", "(256,64):(1,256)", "f32")]:
+                     ("(30,7,11):(1,30,210)", "(30,7,11):(77,11,1)", "f32"), ("(8192,16):(1,0)", "(8192,16):(1,8192)", "f32")]:
         assert "launches=1 " not in lc.Plan(s, d, dt).describe()
         _parity(oracle, s, d, dt, seed=9, tag="sliced")
 
