@@ -119,6 +119,19 @@ lc_status_t lc_complement(const lc_layout_t* a, int64_t cotarget, lc_layout_t** 
 /* Right-inverse of maximal size (Sec. 3.4.1): injective, a(out(k)) = k for every k < |out|; "1:0" when trivial. */
 lc_status_t lc_right_inverse(const lc_layout_t* a, lc_layout_t** out);
 
+/* Left-inverse (Sec. 3.4.3): a(out(a(k))) = a(k) for every k < |a|, and out(a(k)) = k when `a` is
+ * injective.  Stride-0 modes of `a` are not inverted.  Errors: NOT_INJECTIVE (moving modes overlap),
+ * STRIDE_DIVISIBILITY (a stride does not divide the next larger one: no layout inverts that). */
+lc_status_t lc_left_inverse(const lc_layout_t* a, lc_layout_t** out);
+
+/* Logical product A (x) B = (A, A* o B) (Sec. 3.5.1): mode 0 is the tile A, mode 1 repeats it over the
+ * grid B.  Errors of lc_complement and lc_composition. */
+lc_status_t lc_logical_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out);
+/* The logical product with like modes paired (Sec. 3.5.1, related products); needs rank(a) == rank(b).
+ * blocked: ((A_0,B'_0),(A_1,B'_1),...); raked: ((B'_0,A_0),(B'_1,A_1),...) with B' = A* o B. */
+lc_status_t lc_blocked_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out);
+lc_status_t lc_raked_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out);
+
 /* Logical divide A (/) B = A o (B, B*_{|A|}) (Sec. 3.5.2): rank 2, mode 0 = A o B, mode 1 = the rest. */
 lc_status_t lc_logical_divide(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out);
 /* Logical divide applied to the top-level modes with a tiler (Sec. 3.5.2, related divides). */

@@ -189,6 +189,18 @@ void check_unary(const Layout& A) {
       if (m == kstar) tm.ok++;
     }
   }
+  {  // left inverse, Sec. 3.4.3: L(L+(L(k))) = L(k) for every k (L+ evaluated on its extended domain)
+    Tally& t = tally("left_inverse");
+    t.cases++;
+    Layout Li;
+    if (left_inverse(A, &Li) == OK) {
+      bool good = depth(Li.shape) <= 1;
+      for (int64_t k = 0; good && k < n; ++k) good = eval(A, eval(Li, img[(size_t)k])) == img[(size_t)k];
+      // injective L: the canonical form L+(L(k)) = k
+      if (good && inj) for (int64_t k = 0; good && k < n; ++k) good = eval(Li, img[(size_t)k]) == k;
+      if (good) t.ok++; else t.failed("left_inverse " + name + " -> " + to_string(Li));
+    }
+  }
   {  // complement, Sec. 3.5: ordered image, disjoint images on the extended domain of L*
     for (int variant = 0; variant < 3; ++variant) {
       int64_t co = cosize(A);
@@ -271,6 +283,52 @@ void check_pair(const Layout& A, const Layout& B) {
       if (good && K < size(Bi)) { int64_t c = eval(Bi, K); if (eval(A, c) == K) good = false; }
       if (good && is_injective(A) && is_injective(B) && K != max_common_vector_def(A, B)) good = false;
       if (good) t.ok++; else t.failed("max_common_vector " + name + " -> " + std::to_string(K));
+    }
+  }
+  {  // logical product, Sec. 3.5.1: R = (A, A* o B): mode 0 is A, mode 1 is compatible with B,
+     // R(a, b) = A(a) + A*(B(b)); tiles are disjoint when A and B are injective and A's modes nest
+    Tally& t = tally("logical_product");
+    t.cases++;
+    Layout R;
+    if (logical_product(A, B, &R) == OK) {
+      Layout Astar;
+      bool good = complement(A, 0, &Astar) == OK && rank(R.shape) == 2 && to_string(sublayout(R, 0)) == to_string(A) &&
+                  compatible(B.shape, sublayout(R, 1).shape);
+      const int64_t na = size(A), nb = size(B);
+      for (int64_t b = 0; good && b < nb; ++b)
+        for (int64_t a = 0; good && a < na; ++a) good = eval(R, a + na * b) == eval(A, a) + eval(Astar, eval(B, b));
+      if (good && is_injective(A) && is_injective(B)) {
+        // the complement is disjoint from A on its whole extended domain, so distinct grid points give disjoint tiles
+        std::vector<int64_t> all = image_of(R, na * nb);
+        std::sort(all.begin(), all.end());
+        // holds when the complement itself is injective over what B asks of it (A's modes nest exactly)
+        std::vector<int64_t> as = leaves(A.shape), ad = leaves(A.stride);
+        std::vector<std::pair<int64_t, int64_t>> md;
+        for (size_t k = 0; k < as.size(); ++k) if (as[k] > 1 && ad[k] > 0) md.push_back({ad[k], as[k]});
+        std::sort(md.begin(), md.end());
+        bool nested = true;
+        int64_t cur = 1;
+        for (auto& p : md) { if (p.first % cur != 0) nested = false; cur = p.first * p.second; }
+        if (nested && std::adjacent_find(all.begin(), all.end()) != all.end()) good = false;
+      }
+      if (good) t.ok++; else t.failed("logical_product " + name + " -> " + to_string(R));
+    }
+    if (rank(A.shape) == rank(B.shape) && !A.shape.is_int) {
+      Tally& tb = tally("blocked_raked_product");
+      tb.cases++;
+      Layout P, Bp, Rp;
+      if (logical_product(A, B, &P) == OK && blocked_product(A, B, &Bp) == OK && raked_product(A, B, &Rp) == OK) {
+        // both are rearrangements of the logical product: coordinate ((a_0,b_0),(a_1,b_1),...) resp. ((b_0,a_0),...)
+        bool good2 = rank(Bp.shape) == rank(A.shape) && rank(Rp.shape) == rank(A.shape) && size(Bp) == size(P) && size(Rp) == size(P);
+        std::vector<int64_t> x = image_of(P, size(P)), y = image_of(Bp, size(Bp)), z = image_of(Rp, size(Rp));
+        std::sort(x.begin(), x.end()); std::sort(y.begin(), y.end()); std::sort(z.begin(), z.end());
+        if (good2 && (x != y || x != z)) good2 = false;
+        for (int i = 0; good2 && i < rank(A.shape); ++i) {
+          good2 = to_string(sublayout(sublayout(Bp, i), 0)) == to_string(sublayout(A, i)) &&
+                  to_string(sublayout(sublayout(Rp, i), 1)) == to_string(sublayout(A, i));
+        }
+        if (good2) tb.ok++; else tb.failed("blocked/raked product " + name);
+      }
     }
   }
   {  // logical divide, Sec. 3.5.2: R = A o (B, B*_{|A|}); (B, B*) reaches every coordinate of A; mode 0 is A o B
@@ -381,7 +439,8 @@ int main(int argc, char** argv) {
   rng_state = seed;
   for (const char* n : {"coalesce", "coalesce_bymode", "right_inverse", "right_inverse_size_bound",
                         "right_inverse_maximal_when_injective", "complement", "composition", "composition_refused",
-                        "max_common_vector", "logical_divide", "zipped_divide"})
+                        "max_common_vector", "logical_divide", "zipped_divide", "left_inverse", "logical_product",
+                        "blocked_raked_product"})
     tally(n);
 
   typedef std::pair<std::vector<int64_t>, std::vector<int64_t>> Flat;

@@ -465,6 +465,75 @@ Layout right_inverse(const Layout& A) {
 }
 
 // ===========================================================================
+// Left-inverse (Sec. 3.4.3).  Reading: take the coalesced modes that move (stride > 0) in
+// stride order; an offset o splits as o = sum_k c_k d_k with c_k = floor(o / d_k) mod (d_{k+1}/d_k),
+// so the inverse has, per mode, extent d_{k+1}/d_k (the last keeps its own extent) and stride
+// "position of that mode in A".  Offsets below the first stride map to coordinate 0 (a leading
+// stride-0 mode; Table linv notes that any stride would do there).  Needs every stride to divide
+// the next and the moving modes not to overlap (stride-0 modes are simply not inverted).
+// ===========================================================================
+Status left_inverse(const Layout& A, Layout* R) {
+  FlatModes f = coalesce_flat(A, false);
+  struct M { int64_t s, d, pos; };
+  std::vector<M> modes;
+  int64_t pos = 1;
+  for (size_t k = 0; k < f.s.size(); ++k) {
+    if (f.d[k] != 0 && f.s[k] > 1) modes.push_back({f.s[k], f.d[k], pos});
+    pos *= f.s[k];
+  }
+  std::stable_sort(modes.begin(), modes.end(), [](const M& a, const M& b) { return a.d < b.d; });
+  std::vector<int64_t> rs, rd;
+  if (modes.empty()) { *R = make_layout({1}, {0}); return OK; }
+  if (modes[0].d > 1) { rs.push_back(modes[0].d); rd.push_back(0); }
+  for (size_t k = 0; k < modes.size(); ++k) {
+    if (k + 1 < modes.size()) {
+      if (modes[k].s * modes[k].d > modes[k + 1].d) return ERR_NOT_INJECTIVE;   // modes overlap: no layout inverts them
+      if (modes[k + 1].d % modes[k].d != 0) return ERR_STRIDE_DIVISIBILITY;
+      rs.push_back(modes[k + 1].d / modes[k].d);
+    } else {
+      rs.push_back(modes[k].s);
+    }
+    rd.push_back(modes[k].pos);
+  }
+  *R = coalesce(make_layout(rs, rd));
+  return OK;
+}
+
+// ===========================================================================
+// Logical product and its rearrangements (Sec. 3.5.1)
+// ===========================================================================
+Status logical_product(const Layout& A, const Layout& B, Layout* R) {
+  Layout Astar;
+  Status st = complement(A, 0, &Astar);
+  if (st != OK) return st;
+  Layout grid;
+  st = composition(Astar, B, &grid);            // B orders and shapes the complement
+  if (st != OK) return st;
+  *R = concat({A, grid});
+  return OK;
+}
+
+static Status zipped_product(const Layout& A, const Layout& B, bool tile_first, Layout* R) {
+  int ra = A.shape.is_int ? 1 : rank(A.shape), rb = B.shape.is_int ? 1 : rank(B.shape);
+  if (ra != rb) return ERR_INVALID_ARG;         // requires rank(A) == rank(B)
+  Layout P;
+  Status st = logical_product(A, B, &P);
+  if (st != OK) return st;
+  Layout tile = sublayout(P, 0), grid = sublayout(P, 1);
+  std::vector<Layout> modes;
+  for (int i = 0; i < ra; ++i) {
+    Layout t = tile.shape.is_int ? tile : sublayout(tile, i);
+    Layout g = grid.shape.is_int || B.shape.is_int ? grid : sublayout(grid, i);
+    modes.push_back(tile_first ? concat({t, g}) : concat({g, t}));
+  }
+  *R = modes.size() == 1 ? modes[0] : concat(modes);
+  return OK;
+}
+
+Status blocked_product(const Layout& A, const Layout& B, Layout* R) { return zipped_product(A, B, true, R); }
+Status raked_product(const Layout& A, const Layout& B, Layout* R) { return zipped_product(A, B, false, R); }
+
+// ===========================================================================
 // Logical divide and zipped divide (Sec. 3.5.2)
 // ===========================================================================
 // Removes extent-1 leaves from a "rest" layout; nothing left -> 1:0; one mode left -> unwrapped.

@@ -94,6 +94,10 @@ Status composition(const Layout& A, const Layout& B, Layout* R);        // Sec. 
 Status composition_bymode(const Layout& A, const Layout& tiler, Layout* R); // Sec. 3.3.5
 Status complement(const Layout& A, int64_t cotarget, Layout* R);        // Sec. 3.5; cotarget 0 = cosize(A)
 Layout right_inverse(const Layout& A);                      // Sec. 3.4.1
+Status left_inverse(const Layout& A, Layout* R);            // Sec. 3.4.3: A(R(A(k))) = A(k)
+Status logical_product(const Layout& A, const Layout& B, Layout* R);    // Sec. 3.5.1: (A, A* o B)
+Status blocked_product(const Layout& A, const Layout& B, Layout* R);    // Sec. 3.5.1 "Related products": ((A_0,B'_0),(A_1,B'_1),...)
+Status raked_product(const Layout& A, const Layout& B, Layout* R);      // Sec. 3.5.1 "Related products": ((B'_0,A_0),(B'_1,A_1),...)
 Status logical_divide(const Layout& A, const Layout& B, Layout* R);     // Sec. 3.5.2: A o (B, B*_{|A|})
 Status logical_divide_bymode(const Layout& A, const Layout& tiler, Layout* R); // Sec. 3.5.2 "Related divides"
 Status zipped_divide(const Layout& A, const Layout& tiler, Layout* R);  // Sec. 3.5.2 "Related divides"

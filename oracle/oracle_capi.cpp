@@ -125,6 +125,9 @@ int oracle_right_inverse(const Layout* a, Layout** out) { *out = new Layout(orac
     *out = new Layout(r);                                               \
     return oracle::OK;                                                  \
   }
+ORACLE_BINARY(logical_product)
+ORACLE_BINARY(blocked_product)
+ORACLE_BINARY(raked_product)
 ORACLE_BINARY(composition)
 ORACLE_BINARY(composition_bymode)
 ORACLE_BINARY(logical_divide)
@@ -132,6 +135,13 @@ ORACLE_BINARY(logical_divide_bymode)
 ORACLE_BINARY(zipped_divide)
 #undef ORACLE_BINARY
 
+int oracle_left_inverse(const Layout* a, Layout** out) {
+  Layout r;
+  oracle::Status st = oracle::left_inverse(*a, &r);
+  if (st != oracle::OK) return st;
+  *out = new Layout(r);
+  return oracle::OK;
+}
 int oracle_complement(const Layout* a, int64_t cotarget, Layout** out) {
   Layout r;
   oracle::Status st = oracle::complement(*a, cotarget, &r);

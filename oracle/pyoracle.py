@@ -72,9 +72,10 @@ def lib():
         L.oracle_crd2idx.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64)]
         for name in ("shape_compatible", "congruent", "weakly_congruent"):
             getattr(L, "oracle_" + name).argtypes = [ctypes.c_char_p, ctypes.c_char_p]
-        for name in ("coalesce", "coalesce_bymode", "right_inverse"):
+        for name in ("coalesce", "coalesce_bymode", "right_inverse", "left_inverse"):
             getattr(L, "oracle_" + name).argtypes = [P, PP]
-        for name in ("composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide"):
+        for name in ("composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide",
+                     "logical_product", "blocked_product", "raked_product"):
             getattr(L, "oracle_" + name).argtypes = [P, P, PP]
         L.oracle_complement.argtypes = [P, i64, PP]
         L.oracle_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
@@ -193,6 +194,10 @@ def _binary(name, a, b):
 def coalesce(a): return _unary("coalesce", a)
 def coalesce_bymode(a): return _unary("coalesce_bymode", a)
 def right_inverse(a): return _unary("right_inverse", a)
+def left_inverse(a): return _unary("left_inverse", a)
+def logical_product(a, b): return _binary("logical_product", a, b)
+def blocked_product(a, b): return _binary("blocked_product", a, b)
+def raked_product(a, b): return _binary("raked_product", a, b)
 def composition(a, b): return _binary("composition", a, b)
 def composition_bymode(a, t): return _binary("composition_bymode", a, t)
 def logical_divide(a, b): return _binary("logical_divide", a, b)

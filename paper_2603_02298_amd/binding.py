@@ -57,9 +57,10 @@ def lib():
     L.lc_layout_depth.argtypes = [P]
     L.lc_layout_eval.argtypes = [P, i64]
     L.lc_layout_eval.restype = i64
-    for n in ("coalesce", "coalesce_bymode", "right_inverse"):
+    for n in ("coalesce", "coalesce_bymode", "right_inverse", "left_inverse"):
         getattr(L, "lc_" + n).argtypes = [P, PP]
-    for n in ("composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide"):
+    for n in ("composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide",
+              "logical_product", "blocked_product", "raked_product"):
         getattr(L, "lc_" + n).argtypes = [P, P, PP]
     L.lc_complement.argtypes = [P, i64, PP]
     L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
@@ -141,6 +142,10 @@ def _binary(name, a, b):
 def lc_coalesce(a): return _unary("lc_coalesce", a)
 def lc_coalesce_bymode(a): return _unary("lc_coalesce_bymode", a)
 def lc_right_inverse(a): return _unary("lc_right_inverse", a)
+def lc_left_inverse(a): return _unary("lc_left_inverse", a)
+def lc_logical_product(a, b): return _binary("lc_logical_product", a, b)
+def lc_blocked_product(a, b): return _binary("lc_blocked_product", a, b)
+def lc_raked_product(a, b): return _binary("lc_raked_product", a, b)
 def lc_composition(a, b): return _binary("lc_composition", a, b)
 def lc_composition_bymode(a, t): return _binary("lc_composition_bymode", a, t)
 def lc_logical_divide(a, b): return _binary("lc_logical_divide", a, b)

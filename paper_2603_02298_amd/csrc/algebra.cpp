@@ -199,6 +199,66 @@ Layout right_inverse(const Layout& a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Left-inverse (Sec. 3.4.3): offsets are decomposed digit by digit in the mixed radix given by the
+// ratios of consecutive strides; digit k is sent to the position of the mode that produced it.
+// ---------------------------------------------------------------------------------------------
+lc_status_t left_inverse(const Layout& a, Layout* out) {
+  Modes c = coalesce_modes(a.leaves);
+  struct Link { int64_t extent, stride, position; };
+  std::vector<Link> links;
+  int64_t position = 1;
+  for (const Mode& m : c) {
+    if (m.stride > 0 && m.extent > 1) links.push_back({m.extent, m.stride, position});
+    position *= m.extent;
+  }
+  std::stable_sort(links.begin(), links.end(), [](const Link& x, const Link& y) { return x.stride < y.stride; });
+  if (links.empty()) { *out = Layout::leaf(1, 0); return LC_OK; }
+  Modes inv;
+  if (links.front().stride > 1) inv.push_back({links.front().stride, 0});   // offsets below the first stride
+  for (size_t k = 0; k < links.size(); ++k) {
+    int64_t radix = links[k].extent;
+    if (k + 1 < links.size()) {
+      if (links[k].extent * links[k].stride > links[k + 1].stride) return LC_ERR_NOT_INJECTIVE;
+      if (links[k + 1].stride % links[k].stride != 0) return LC_ERR_STRIDE_DIVISIBILITY;
+      radix = links[k + 1].stride / links[k].stride;
+    }
+    inv.push_back({radix, links[k].position});
+  }
+  *out = Layout::flat(coalesce_modes(inv));
+  return LC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Products (Sec. 3.5.1): A (x) B = (A, A* o B); the blocked / raked products pair up like modes.
+// ---------------------------------------------------------------------------------------------
+lc_status_t logical_product(const Layout& a, const Layout& b, Layout* out) {
+  Layout astar, grid;
+  lc_status_t st = complement(a, 0, &astar);
+  if (st != LC_OK) return st;
+  st = composition(astar, b, &grid);
+  if (st != LC_OK) return st;
+  *out = Layout::tuple({a, grid});
+  return LC_OK;
+}
+
+static lc_status_t paired_product(const Layout& a, const Layout& b, bool tile_first, Layout* out) {
+  if (a.rank() != b.rank()) return LC_ERR_INVALID_ARG;
+  Layout p;
+  lc_status_t st = logical_product(a, b, &p);
+  if (st != LC_OK) return st;
+  const Layout tile = p.mode(0), grid = p.mode(1);
+  std::vector<Layout> pairs;
+  for (int i = 0; i < a.rank(); ++i) {
+    Layout t = tile.mode(i), g = b.is_leaf() ? grid : grid.mode(i);
+    pairs.push_back(tile_first ? Layout::tuple({t, g}) : Layout::tuple({g, t}));
+  }
+  *out = pairs.size() == 1 ? pairs[0] : Layout::tuple(pairs);
+  return LC_OK;
+}
+lc_status_t blocked_product(const Layout& a, const Layout& b, Layout* out) { return paired_product(a, b, true, out); }
+lc_status_t raked_product(const Layout& a, const Layout& b, Layout* out) { return paired_product(a, b, false, out); }
+
+// ---------------------------------------------------------------------------------------------
 // Divides (Sec. 3.5.2)
 // ---------------------------------------------------------------------------------------------
 static Layout without_unit_modes(const Layout& L) {

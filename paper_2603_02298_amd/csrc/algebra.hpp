@@ -15,6 +15,10 @@ lc_status_t composition(const Layout& a, const Layout& b, Layout* out);         
 lc_status_t composition_bymode(const Layout& a, const Layout& tiler, Layout* out);      // Sec. 3.3.5
 lc_status_t complement(const Layout& a, int64_t cotarget, Layout* out);                 // Sec. 3.5
 Layout right_inverse(const Layout& a);                                                  // Sec. 3.4.1
+lc_status_t left_inverse(const Layout& a, Layout* out);                                 // Sec. 3.4.3
+lc_status_t logical_product(const Layout& a, const Layout& b, Layout* out);             // Sec. 3.5.1
+lc_status_t blocked_product(const Layout& a, const Layout& b, Layout* out);             // Sec. 3.5.1
+lc_status_t raked_product(const Layout& a, const Layout& b, Layout* out);               // Sec. 3.5.1
 lc_status_t logical_divide(const Layout& a, const Layout& b, Layout* out);              // Sec. 3.5.2
 lc_status_t logical_divide_bymode(const Layout& a, const Layout& tiler, Layout* out);   // Sec. 3.5.2
 lc_status_t zipped_divide(const Layout& a, const Layout& tiler, Layout* out);           // Sec. 3.5.2

@@ -137,6 +137,15 @@ lc_status_t lc_right_inverse(const lc_layout_t* a, lc_layout_t** out) {
   if (!a || !out) return LC_ERR_INVALID_ARG;
   return give(lc::right_inverse(a->L), out);
 }
+lc_status_t lc_left_inverse(const lc_layout_t* a, lc_layout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  lc::Layout r;
+  lc_status_t st = lc::left_inverse(a->L, &r);
+  return st == LC_OK ? give(r, out) : st;
+}
+lc_status_t lc_logical_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::logical_product, a, b, out); }
+lc_status_t lc_blocked_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::blocked_product, a, b, out); }
+lc_status_t lc_raked_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::raked_product, a, b, out); }
 lc_status_t lc_composition(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::composition, a, b, out); }
 lc_status_t lc_composition_bymode(const lc_layout_t* a, const lc_layout_t* t, lc_layout_t** out) { return binary(lc::composition_bymode, a, t, out); }
 lc_status_t lc_logical_divide(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::logical_divide, a, b, out); }

@@ -10,7 +10,8 @@ OPS = {
     "coalesce": lc.lc_coalesce, "coalesce_bymode": lc.lc_coalesce_bymode, "right_inverse": lc.lc_right_inverse,
     "composition": lc.lc_composition, "composition_bymode": lc.lc_composition_bymode,
     "logical_divide": lc.lc_logical_divide, "logical_divide_bymode": lc.lc_logical_divide_bymode,
-    "zipped_divide": lc.lc_zipped_divide,
+    "zipped_divide": lc.lc_zipped_divide, "left_inverse": lc.lc_left_inverse, "logical_product": lc.lc_logical_product,
+    "blocked_product": lc.lc_blocked_product, "raked_product": lc.lc_raked_product,
 }
 
 
@@ -118,8 +119,9 @@ def _random_layout(rng, max_leaves=4, max_extent=6):
 
 def test_random_layouts_match_oracle(oracle):
     rng = np.random.default_rng(2603)
-    unary = ["coalesce", "coalesce_bymode", "right_inverse", "complement"]
-    binary = ["composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide", "max_common_vector"]
+    unary = ["coalesce", "coalesce_bymode", "right_inverse", "left_inverse", "complement"]
+    binary = ["composition", "composition_bymode", "logical_divide", "logical_divide_bymode", "zipped_divide", "max_common_vector",
+              "logical_product", "blocked_product", "raked_product"]
     ok = {k: 0 for k in unary + binary}
     for _ in range(6000):
         A, B = _random_layout(rng), _random_layout(rng)
@@ -136,7 +138,7 @@ def test_random_layouts_match_oracle(oracle):
             else:
                 assert a[0] == b[0] or {a[0], b[0]} <= {"STRIDE_DIVISIBILITY", "SHAPE_DIVISIBILITY", "NOT_SEGREGATED"}, (op, A, B, a, b)
     for k, v in ok.items():
-        assert v > 50, (k, v)
+        assert v > 40, (k, v)
 
 
 def test_common_vector_on_equal_sizes(oracle):

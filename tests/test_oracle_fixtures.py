@@ -123,7 +123,7 @@ def test_algebra_examples(oracle):
             else:
                 assert got == expect, ln
         n += 1
-    assert n == 53
+    assert n == 65
 
 
 def test_associativity_counterexample(oracle):
