@@ -433,7 +433,10 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
           if (rs_.leaves[k].extent != rd_.leaves[k].extent) { ok = false; break; }
           if (rs_.leaves[k].extent > 1) rest.push_back({rs_.leaves[k].extent, rs_.leaves[k].stride, rd_.leaves[k].stride});
         }
-        if (tune.rest_order == 1)
+        // Tile ids run fastest along the smallest SOURCE stride: resident workgroups then read one
+        // contiguous region together (measured 1-3 % better than destination order; writes are combined
+        // by the caches anyway).
+        if (tune.rest_order != 0)
           std::stable_sort(rest.begin(), rest.end(), [](const RM& x, const RM& y) { return x.a < y.a; });
         int64_t tiles = 1;
         for (const RM& r : rest) tiles *= r.ext;
@@ -484,7 +487,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
         // Measured on MI355X: HBM efficiency is best with ONE resident workgroup per CU (its next tile's
         // loads overlap its current tile's stores); short grids need more workgroups to fill the chip.
         int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
-        int want = P.n_tiles >= 16384 ? 1 : (P.n_tiles >= 2048 ? 2 : 4);
+        int want = P.n_tiles >= 16384 ? 1 : (P.n_tiles >= 2048 ? 3 : 4);
         plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(std::min(8, fit), want));
         plan->src_align = (unsigned)(V * es);
         plan->dst_align = (unsigned)(V * es);
@@ -561,7 +564,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   plan->width_bytes = VEC * es;
   // about 16 KiB of accesses in flight per CU measured best on MI355X: unroll x workgroups = 64 / width
   const int W = VEC * es;
-  int dflt_unroll = W >= 16 ? 2 : (W >= 4 ? 4 : 8), dflt_wgs = W >= 8 ? 2 : 4;
+  int dflt_unroll = W >= 16 ? 2 : (W >= 4 ? 4 : 8), dflt_wgs = W >= 8 ? 3 : 4;   // 3 x 256 CUs: a grid that is not a power of two
   plan->unroll = (tune.unroll == 1 || tune.unroll == 2 || tune.unroll == 4 || tune.unroll == 8) ? tune.unroll : dflt_unroll;
   plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : dflt_wgs;
   if (tune.nontemporal < 0 && ((int64_t)W * (q >= 0 ? J[(size_t)q].extent / VEC : 1)) % 128 == 0) plan->nontemporal |= 2;

@@ -19,7 +19,7 @@ enum class KernelClass { Generic, Direct, Transpose };
 // environment (LC_TUNE_*) once per plan so that tile shapes can be swept without rebuilding.
 struct Tuning {
   int micro_per_thread = -1;   // transpose: micro-tiles per lane (1, 2 or 4)
-  int rest_order = -1;         // transpose: 0 = tiles ordered by destination stride, 1 = by source stride
+  int rest_order = -1;         // transpose: 0 = tiles ordered by destination stride, 1 = by source stride (default)
   int wgs_per_cu = -1;         // persistent grid size = CUs * wgs_per_cu
   int unroll = -1;             // direct: items per lane per loop trip (1, 2, 4, 8)
   int swizzle_shift = -2;      // transpose: -1 = no swizzle
