@@ -47,7 +47,7 @@ typedef enum {
   LC_ERR_NOT_SURJECTIVE = 11,     /* logical divide: (B, B*) misses coordinates of A (Sec. 3.5.2) */
   LC_ERR_DST_ALIASES = 12,        /* copy: two coordinates of dst share an offset (result would depend on order) */
   LC_ERR_UNSUPPORTED_DTYPE = 13,
-  LC_ERR_TOO_LARGE = 14,          /* more modes or elements than the kernels index */
+  LC_ERR_TOO_LARGE = 14,          /* size or cosize beyond 2^62, more than 64 leaf modes, or more work than the kernels index */
   LC_ERR_MISALIGNED = 15,         /* a device pointer is less aligned than the plan was created for */
   LC_ERR_HIP = 16                 /* a HIP runtime call failed (no device, launch failure, ...) */
 } lc_status_t;

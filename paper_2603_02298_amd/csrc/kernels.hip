@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <string>
 
 #include "kernel_params.hpp"
@@ -223,15 +224,15 @@ static bool hip_failed(hipError_t e, const char* what) {
 }
 
 static int device_cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
+  static std::atomic<int> cus{0};
+  if (cus.load() == 0) {
     int dev = 0;
     if (hip_failed(hipGetDevice(&dev), "hipGetDevice")) return -1;
     int n = 0;
     if (hip_failed(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute") || n <= 0) return -1;
-    cus = n;
+    cus.store(n);
   }
-  return cus;
+  return cus.load();
 }
 
 template <int ES>
@@ -267,12 +268,12 @@ static hipError_t launch_transpose_n(const lc_plan& plan, const void* src, void*
   const unsigned char* sp = static_cast<const unsigned char*>(src);
   unsigned char* dp = static_cast<unsigned char*>(dst);
   if (plan.lds_bytes > 64 * 1024) {
-    static bool raised = false;   // one flag per instantiation: the attribute belongs to the kernel function
-    if (!raised) {
+    static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
+    if (!raised.load(std::memory_order_acquire)) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
-      raised = true;
+      raised.store(true, std::memory_order_release);
     }
   }
   hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);

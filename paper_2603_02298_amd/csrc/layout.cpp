@@ -177,10 +177,17 @@ lc_status_t validate(const Layout& L) {
   if (L.profile.empty() || L.leaves.empty()) return LC_ERR_INVALID_ARG;
   size_t nl = 0;
   if (skip_subtree(L.profile, 0, &nl) != L.profile.size() || nl != L.leaves.size()) return LC_ERR_NOT_CONGRUENT;
+  // sizes and offsets are computed in int64: keep size and cosize below 2^62
+  const long double limit = 4.0e18L;
+  long double size = 1.0L, top = 0.0L;
   for (const Mode& m : L.leaves) {
     if (m.extent < 1) return LC_ERR_BAD_EXTENT;
     if (m.stride < 0) return LC_ERR_NEGATIVE_STRIDE;
+    size *= (long double)m.extent;
+    top += (long double)(m.extent - 1) * (long double)m.stride;
+    if (size > limit || top > limit) return LC_ERR_TOO_LARGE;
   }
+  if (L.leaves.size() > 64 || L.profile.size() > 256) return LC_ERR_TOO_LARGE;
   return LC_OK;
 }
 

@@ -89,6 +89,14 @@ def test_parse_errors(oracle, text, status):
     assert e2.value.status_name == status
 
 
+def test_absurd_sizes_are_refused():
+    for text in ["(4294967296,4294967296,4294967296):(1,1,1)", "(8,2):(900000000000000000,1)"]:
+        with pytest.raises(lc.LayoutCopyError) as e:
+            lc.Layout(text)
+        assert e.value.status_name == "TOO_LARGE"
+    assert lc.Layout("(2147483648,2147483648):(1,2147483648)").size == 1 << 62
+
+
 def _random_layout(rng, max_leaves=4, max_extent=6):
     """Random hierarchical layout text with small extents and a mix of compact / padded / zero strides."""
     n = int(rng.integers(1, max_leaves + 1))
