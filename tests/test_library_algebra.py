@@ -94,7 +94,7 @@ def test_absurd_sizes_are_refused():
         with pytest.raises(lc.LayoutCopyError) as e:
             lc.Layout(text)
         assert e.value.status_name == "TOO_LARGE"
-    assert lc.Layout("(2147483648,2147483648):(1,2147483648)").size == 1 << 62
+    assert lc.Layout("(1073741824,1073741824):(1,1073741824)").size == 1 << 60
 
 
 def _random_layout(rng, max_leaves=4, max_extent=6):
