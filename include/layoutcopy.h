@@ -92,6 +92,12 @@ int lc_layout_depth(const lc_layout_t* layout);      /* Sec. 2.1 */
  * unreduced (extended domain, Sec. 2.2.2 and 2.4.1). */
 int64_t lc_layout_eval(const lc_layout_t* layout, int64_t integral_coord);
 
+/* Slicing (Sec. 2.5.1): `coord` is a coordinate in the paper's notation with "_" at the unspecified
+ * positions, e.g. "(2,((0,_),_))"; an integer may stand for a whole sub-mode (integral coordinate of
+ * that mode).  *offset receives L(specified part) — add it to the tensor's pointer — and *out the
+ * sublayout of the unspecified modes ("1:0" if none is left).  Errors: PARSE, NOT_CONGRUENT. */
+lc_status_t lc_layout_slice(const lc_layout_t* layout, const char* coord, int64_t* offset, lc_layout_t** out);
+
 /* ---------------------------------------------------------------------------------------------
  * Layout algebra (Sec. 3).  Each call allocates *out on LC_OK.
  * A tiler (Sec. 3.3.5) is passed as a layout whose top-level modes are the tiles; an integer tile S is

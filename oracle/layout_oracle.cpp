@@ -265,6 +265,35 @@ int64_t eval_crd(const Layout& L, const HTuple& c) {
 }
 
 // ===========================================================================
+// Slicing (Sec. 2.5.1): T(c' + c*) = (e + L(c')) o L(c*).  A hole keeps its whole sub-mode; a tuple
+// that keeps exactly one piece is that piece, a tuple that keeps none disappears.
+// ===========================================================================
+static bool slice_rec(const Layout& L, const HTuple& c, int64_t* offset, std::vector<Layout>* kept, Status* st) {
+  if (c.is_int) {
+    if (c.value == -1) { kept->push_back(L); return true; }       // unspecified: stays
+    *offset += eval(L, c.value);                                    // specified: L(c') goes into the accessor
+    return true;
+  }
+  if (L.shape.is_int || rank(L.shape) != (int)c.items.size()) { *st = ERR_NOT_CONGRUENT; return false; }
+  std::vector<Layout> mine;
+  for (int i = 0; i < rank(L.shape); ++i)
+    if (!slice_rec(sublayout(L, i), c.items[(size_t)i], offset, &mine, st)) return false;
+  if (mine.size() == 1) kept->push_back(mine[0]);
+  else if (mine.size() > 1) kept->push_back(concat(mine));
+  return true;
+}
+
+Status slice(const Layout& L, const HTuple& coord_with_holes, Slice* out) {
+  Status st = OK;
+  int64_t offset = 0;
+  std::vector<Layout> kept;
+  if (!slice_rec(L, coord_with_holes, &offset, &kept, &st)) return st;
+  out->offset = offset;
+  out->rest = kept.empty() ? make_layout({1}, {0}) : kept[0];
+  return OK;
+}
+
+// ===========================================================================
 // Coalesce (Sec. 3.2).  Reading: walk the leaves left to right, skip extent-1
 // leaves, merge a leaf into the previous kept mode when its stride equals
 // extent*stride of that mode; never reorder.  All-ones collapses to 1:0.

@@ -87,6 +87,11 @@ int64_t eval(const Layout& L, int64_t i);
 // L(c) for any coordinate weakly congruent with the shape.
 int64_t eval_crd(const Layout& L, const HTuple& c);
 
+// Slicing (Sec. 2.5.1): a coordinate with unspecified positions (here: value -1 leaves, "_" in text)
+// evaluates the specified part into an offset and leaves the sublayout of the unspecified modes.
+struct Slice { int64_t offset; Layout rest; };
+Status slice(const Layout& L, const HTuple& coord_with_holes, Slice* out);
+
 // ---- Algebra (Sec. 3) ------------------------------------------------------
 Layout coalesce(const Layout& A);                           // Sec. 3.2
 Layout coalesce_bymode(const Layout& A);                    // Sec. 3.2 with the combinator of Eq. layout_combinator

@@ -37,6 +37,7 @@ bool parse_htuple(const char* text, oracle::HTuple* out) {
         }
         return oracle::HTuple::Tup(items);
       }
+      if (s[pos] == '_') { ++pos; return oracle::HTuple::Int(-1); }   // an unspecified position of a slice
       size_t st = pos;
       while (s[pos] >= '0' && s[pos] <= '9') ++pos;
       if (pos == st) { ok = false; return oracle::HTuple::Int(0); }
@@ -113,6 +114,16 @@ int oracle_weakly_congruent(const char* p, const char* s) {
   return oracle::weakly_congruent(a, b) ? 1 : 0;
 }
 
+int oracle_layout_slice(const Layout* L, const char* coord, int64_t* offset, Layout** out) {
+  oracle::HTuple c;
+  if (!parse_htuple(coord, &c)) return oracle::ERR_PARSE;
+  oracle::Slice sl;
+  oracle::Status st = oracle::slice(*L, c, &sl);
+  if (st != oracle::OK) return st;
+  *offset = sl.offset;
+  *out = new Layout(sl.rest);
+  return oracle::OK;
+}
 int oracle_coalesce(const Layout* a, Layout** out) { *out = new Layout(oracle::coalesce(*a)); return oracle::OK; }
 int oracle_coalesce_bymode(const Layout* a, Layout** out) { *out = new Layout(oracle::coalesce_bymode(*a)); return oracle::OK; }
 int oracle_right_inverse(const Layout* a, Layout** out) { *out = new Layout(oracle::right_inverse(*a)); return oracle::OK; }

@@ -78,6 +78,7 @@ def lib():
                      "logical_product", "blocked_product", "raked_product"):
             getattr(L, "oracle_" + name).argtypes = [P, P, PP]
         L.oracle_complement.argtypes = [P, i64, PP]
+        L.oracle_layout_slice.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64), PP]
         L.oracle_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
         L.oracle_max_common_vector_def.argtypes = [P, P, ctypes.POINTER(i64)]
         L.oracle_copy.argtypes = [P, P, P, P, ctypes.c_int]
@@ -203,6 +204,14 @@ def composition_bymode(a, t): return _binary("composition_bymode", a, t)
 def logical_divide(a, b): return _binary("logical_divide", a, b)
 def logical_divide_bymode(a, t): return _binary("logical_divide_bymode", a, t)
 def zipped_divide(a, t): return _binary("zipped_divide", a, t)
+
+
+def slice_layout(a, coord):
+    """(offset, remaining layout) for a coordinate text with "_" at the unspecified positions."""
+    a = _as_layout(a)
+    h, off = ctypes.c_void_p(), ctypes.c_int64()
+    _check(lib().oracle_layout_slice(a._h, coord.encode(), ctypes.byref(off), ctypes.byref(h)), "slice(%s, %s)" % (a, coord))
+    return off.value, Layout(_handle=h)
 
 
 def complement(a, cotarget=0):

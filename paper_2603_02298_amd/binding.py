@@ -63,6 +63,7 @@ def lib():
               "logical_product", "blocked_product", "raked_product"):
         getattr(L, "lc_" + n).argtypes = [P, P, PP]
     L.lc_complement.argtypes = [P, i64, PP]
+    L.lc_layout_slice.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64), PP]
     L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
     L.lc_plan_create.argtypes = [P, P, ctypes.c_int, ctypes.c_uint, ctypes.c_uint, PP]
     L.lc_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
@@ -151,6 +152,14 @@ def lc_composition_bymode(a, t): return _binary("lc_composition_bymode", a, t)
 def lc_logical_divide(a, b): return _binary("lc_logical_divide", a, b)
 def lc_logical_divide_bymode(a, t): return _binary("lc_logical_divide_bymode", a, t)
 def lc_zipped_divide(a, t): return _binary("lc_zipped_divide", a, t)
+
+
+def lc_layout_slice(a, coord):
+    """(offset, remaining layout) for a coordinate text with "_" at the unspecified positions."""
+    a = _as_layout(a)
+    h, off = ctypes.c_void_p(), ctypes.c_int64()
+    _check(lib().lc_layout_slice(a._h, coord.encode(), ctypes.byref(off), ctypes.byref(h)), "lc_layout_slice(%s, %s)" % (a, coord))
+    return off.value, Layout(_handle=h)
 
 
 def lc_complement(a, cotarget=0):

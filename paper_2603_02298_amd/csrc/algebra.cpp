@@ -332,6 +332,64 @@ lc_status_t zipped_divide(const Layout& a, const Layout& tiler, Layout* out) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Slicing (Sec. 2.5.1).  The coordinate text is walked together with the layout: an integer is
+// evaluated by the sub-layout it addresses and added to the offset, "_" keeps that sub-layout.
+// ---------------------------------------------------------------------------------------------
+namespace {
+struct SliceWalk {
+  const char* p;
+  int64_t offset = 0;
+  lc_status_t status = LC_OK;
+  void ws() { while (*p == ' ') ++p; }
+  // returns the kept part of `L` under the coordinate at the cursor (nullptr-like: empty profile = nothing kept)
+  bool walk(const Layout& L, Layout* kept) {
+    ws();
+    kept->profile.clear();
+    kept->leaves.clear();
+    if (*p == '_') { ++p; *kept = L; return true; }
+    if (*p >= '0' && *p <= '9') {
+      int64_t v = 0;
+      int digits = 0;
+      while (*p >= '0' && *p <= '9') { v = v * 10 + (*p++ - '0'); if (++digits > 18) { status = LC_ERR_PARSE; return false; } }
+      offset += L(v);
+      return true;
+    }
+    if (*p != '(') { status = LC_ERR_PARSE; return false; }
+    ++p;
+    if (L.is_leaf()) { status = LC_ERR_NOT_CONGRUENT; return false; }
+    std::vector<Layout> mine;
+    for (int i = 0; i < L.rank(); ++i) {
+      Layout part;
+      if (!walk(L.mode(i), &part)) return false;
+      if (!part.profile.empty()) mine.push_back(part);
+      ws();
+      if (i + 1 < L.rank()) {
+        if (*p != ',') { status = (*p == ')') ? LC_ERR_NOT_CONGRUENT : LC_ERR_PARSE; return false; }
+        ++p;
+      }
+    }
+    ws();
+    if (*p != ')') { status = (*p == ',') ? LC_ERR_NOT_CONGRUENT : LC_ERR_PARSE; return false; }
+    ++p;
+    if (mine.size() == 1) *kept = mine[0];
+    else if (mine.size() > 1) *kept = Layout::tuple(mine);
+    return true;
+  }
+};
+}  // namespace
+
+lc_status_t slice(const Layout& a, const char* coord, int64_t* offset, Layout* out) {
+  SliceWalk w{coord};
+  Layout kept;
+  if (!w.walk(a, &kept)) return w.status;
+  w.ws();
+  if (*w.p != 0) return LC_ERR_PARSE;
+  *offset = w.offset;
+  *out = kept.profile.empty() ? Layout::leaf(1, 0) : kept;
+  return LC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Vectorisation (Sec. 3.4.2): K = extent of the stride-1 head of coalesce(A o B^).
 // ---------------------------------------------------------------------------------------------
 lc_status_t max_common_vector(const Layout& a, const Layout& b, int64_t* K) {

@@ -22,6 +22,9 @@ lc_status_t raked_product(const Layout& a, const Layout& b, Layout* out);       
 lc_status_t logical_divide(const Layout& a, const Layout& b, Layout* out);              // Sec. 3.5.2
 lc_status_t logical_divide_bymode(const Layout& a, const Layout& tiler, Layout* out);   // Sec. 3.5.2
 lc_status_t zipped_divide(const Layout& a, const Layout& tiler, Layout* out);           // Sec. 3.5.2
+// Sec. 2.5.1: coordinate text with "_" at the unspecified positions -> offset of the specified part
+// and the sublayout of the unspecified modes.
+lc_status_t slice(const Layout& a, const char* coord, int64_t* offset, Layout* out);
 lc_status_t max_common_vector(const Layout& a, const Layout& b, int64_t* K);            // Sec. 3.4.2
 
 }  // namespace lc

@@ -125,6 +125,21 @@ int lc_layout_rank(const lc_layout_t* layout) { return layout ? layout->L.rank()
 int lc_layout_depth(const lc_layout_t* layout) { return layout ? layout->L.depth() : -1; }
 int64_t lc_layout_eval(const lc_layout_t* layout, int64_t i) { return (layout && i >= 0) ? layout->L(i) : -1; }
 
+lc_status_t lc_layout_slice(const lc_layout_t* layout, const char* coord, int64_t* offset, lc_layout_t** out) {
+  if (!layout || !coord || !offset || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::Layout r;
+    int64_t off = 0;
+    lc_status_t st = lc::slice(layout->L, coord, &off, &r);
+    if (st != LC_OK) return st;
+    st = give(r, out);
+    if (st == LC_OK) *offset = off;
+    return st;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
 lc_status_t lc_coalesce(const lc_layout_t* a, lc_layout_t** out) {
   if (!a || !out) return LC_ERR_INVALID_ARG;
   return give(lc::coalesce(a->L), out);

@@ -74,6 +74,16 @@ def test_random_layout_pairs(oracle):
         _parity(oracle, s, d, ["f32", "bf16", "b8", "b64", "f16"][k % 5], seed=k, tag="random%d" % k)
 
 
+def test_random_pairs_with_different_shapes(oracle):
+    import sys
+    sys.path.insert(0, os.path.dirname(__file__))
+    from test_plan_replay import _random_refined_pair
+    rng = np.random.default_rng(2718)
+    for k in range(400):
+        s, d = _random_refined_pair(rng)
+        _parity(oracle, s, d, ["f32", "bf16", "b64", "b8"][k % 4], seed=k, tag="refined%d" % k)
+
+
 @pytest.mark.parametrize("s,d,dt", [
     ("1:0", "1:0", "f32"),                                   # single element
     ("1:5", "1:7", "bf16"),

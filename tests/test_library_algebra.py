@@ -70,6 +70,39 @@ def test_layout_inspection(oracle):
             assert A(i) == B(i)
 
 
+def test_slicing_matches_oracle_and_paper(oracle):
+    A = "((3,2),((2,3),2)):((4,1),((2,15),100))"
+    for ln in golden_lines("slices.txt"):
+        crd, off, rest = [x.strip() for x in ln.split("|")]
+        o, r = lc.lc_layout_slice(A, crd)
+        assert (o, str(r)) == (int(off), rest), ln
+    rng = np.random.default_rng(8)
+    for _ in range(300):
+        text = _random_layout(rng)
+        L = oracle.Layout(text)
+        shape = text.split(":")[0]
+        # random coordinate of the same profile with holes
+        out, i = [], 0
+        while i < len(shape):
+            if shape[i].isdigit():
+                j = i
+                while j < len(shape) and shape[j].isdigit():
+                    j += 1
+                ext = int(shape[i:j])
+                out.append("_" if rng.random() < 0.4 else str(int(rng.integers(0, ext))))
+                i = j
+            else:
+                out.append(shape[i])
+                i += 1
+        crd = "".join(out)
+        a, b = lc.lc_layout_slice(text, crd), oracle.slice_layout(L, crd)
+        assert (a[0], str(a[1])) == (b[0], str(b[1])), (text, crd)
+    for bad, status in [("(1,2,3)", "NOT_CONGRUENT"), ("(1", "PARSE"), ("(1,x)", "PARSE"), ("((0,0,0),_)", "NOT_CONGRUENT")]:
+        with pytest.raises(lc.LayoutCopyError) as e:
+            lc.lc_layout_slice(A, bad)
+        assert e.value.status_name == status, bad
+
+
 def test_from_tree_equals_parse():
     a = lc.Layout.from_tree([-2, -2, 8, 512, -2, 8, 1024], [1, 8, 4096, 32768])
     assert str(a) == "((8,512),(8,1024)):((1,8),(4096,32768))"

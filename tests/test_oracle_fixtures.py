@@ -140,6 +140,60 @@ def test_logical_products_from_complement_and_composition(oracle):
         assert str(oracle.composition(oracle.complement(a), b)) == expect
 
 
+def test_slice_operation(oracle):
+    # Fig. slicing: offset and remaining layout exactly as printed
+    A = "((3,2),((2,3),2)):((4,1),((2,15),100))"
+    for ln in golden_lines("slices.txt"):
+        crd, off, rest = [x.strip() for x in ln.split("|")]
+        got_off, got_rest = oracle.slice_layout(A, crd)
+        assert (got_off, str(got_rest)) == (int(off), rest), ln
+    assert oracle.slice_layout(A, "(2,5)")[0] == oracle.Layout(A)((2, 5)) and str(oracle.slice_layout(A, "(2,5)")[1]) == "1:0"
+    assert str(oracle.slice_layout(A, "_")[1]) == A and str(oracle.slice_layout(A, "(_,_)")[1]) == A
+    # tile-then-slice (end of Sec. 3.5.2): one tile of a zipped_divide
+    z = oracle.zipped_divide("(8,16):(20,1)", "(4,8):(1,2)")
+    off, tile = oracle.slice_layout(z, "(_,(1,1))")
+    assert (off, str(tile)) == (81, "(4,8):(20,2)")
+
+
+def test_slice_property_on_random_layouts(oracle):
+    # Sec. 2.5.1: for every coordinate c* of the remaining layout, L(c' + c*) = offset + rest(c*)
+    import re
+    rng = np.random.default_rng(251)
+    checked = 0
+    for _ in range(400):
+        n = int(rng.integers(1, 5))
+        ext = [int(rng.integers(1, 6)) for _ in range(n)]
+        strd = [int(rng.integers(0, 40)) for _ in range(n)]
+        # random nesting of the n leaves
+        def nest(items):
+            if len(items) == 1:
+                return items[0]
+            if len(items) == 2 or rng.random() < 0.5:
+                return "(" + ",".join(items) + ")"
+            k = int(rng.integers(1, len(items)))
+            return "(" + nest(items[:k]) + "," + nest(items[k:]) + ")"
+        tags = ["#%d#" % i for i in range(n)]
+        skeleton = nest(tags)
+        def fill(vals):
+            return re.sub(r"#(\d+)#", lambda m: str(vals[int(m.group(1))]), skeleton)
+        L = oracle.Layout(fill(ext) + ":" + fill(strd))
+        holes = [bool(rng.random() < 0.5) for _ in range(n)]
+        fixed = [int(rng.integers(0, e)) for e in ext]
+        off, rest = oracle.slice_layout(L, fill(["_" if h else v for h, v in zip(holes, fixed)]))
+        hole_ext = [e for e, h in zip(ext, holes) if h]
+        assert rest.size == int(np.prod(hole_ext)) if hole_ext else rest.size == 1
+        for j in range(rest.size):
+            vals, q = list(fixed), j
+            for i in range(n):
+                if holes[i]:
+                    vals[i] = q % ext[i]
+                    q //= ext[i]
+            full = fill(vals)
+            assert L(full if n > 1 or full.startswith("(") else int(full)) == off + rest(j), (str(L), holes, fixed, j)
+            checked += 1
+    assert checked > 3000
+
+
 def test_slices(oracle):
     # Fig. slicing: fixing part of a natural coordinate leaves an offset and the sublayout of the free modes
     A = oracle.Layout("((3,2),((2,3),2)):((4,1),((2,15),100))")

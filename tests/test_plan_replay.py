@@ -111,6 +111,43 @@ def _random_pair(rng):
     return text(ext, strides(True)), text(ext, strides(False))
 
 
+def _random_refined_pair(rng):
+    """Source and destination shapes that differ but share a refinement: a list of small factors is
+    grouped into modes differently on each side (e.g. (6,4) against (2,12)); strides are compact over
+    a random order of each side's own modes, sometimes padded."""
+    nf = int(rng.integers(2, 6))
+    factors = [int(rng.choice([2, 2, 2, 3, 4, 5, 8])) for _ in range(nf)]
+
+    def side():
+        modes, i = [], 0
+        while i < nf:
+            j = min(nf, i + int(rng.integers(1, 4)))
+            e = 1
+            for f in factors[i:j]:
+                e *= f
+            modes.append(e)
+            i = j
+        d, run = [0] * len(modes), 1
+        for m in rng.permutation(len(modes)):
+            d[m] = run
+            run *= modes[m] * int(rng.choice([1, 1, 1, 2]))
+        if len(modes) == 1:
+            return "%d:%d" % (modes[0], d[0])
+        return "(%s):(%s)" % (",".join(map(str, modes)), ",".join(map(str, d)))
+    return side(), side()
+
+
+def test_random_pairs_with_different_shapes(oracle):
+    rng = np.random.default_rng(314)
+    seen = {"generic": 0, "direct": 0, "transpose": 0}
+    for k in range(1200):
+        s, d = _random_refined_pair(rng)
+        desc, _ = _check(oracle, s, d, ["f32", "bf16", "b64", "b8"][k % 4], seed=k)
+        assert "note=\"shapes have no common refinement\"" not in desc, (s, d)
+        seen[desc.split()[0][6:]] += 1
+    assert seen["direct"] > 100 and seen["transpose"] > 100, seen
+
+
 def test_random_layout_pairs(oracle):
     rng = np.random.default_rng(42)
     seen = {"generic": 0, "direct": 0, "transpose": 0}
