@@ -17,6 +17,8 @@ namespace lc {
 constexpr int kMaxModes = 8;          // joint / rest / micro modes per kernel
 constexpr int kMaxGenericModes = 12;  // leaf modes per side in the element-wise kernel
 constexpr int kBlock = 256;           // threads per workgroup = 4 wavefronts of 64
+constexpr int kMaxMicroPerLane = 4;   // micro-tiles a lane owns per tile
+constexpr int kMaxPicksPerLane = 32;  // vectors a lane stores per tile (micro-tiles per lane x longest vector)
 
 // Division of a 31-bit unsigned value by a constant: q = (mulhi(n, mul) + n) >> shift
 // (round-up multiplier of Granlund & Montgomery; exact for n < 2^31, any divisor in [1, 2^31)).
@@ -120,6 +122,16 @@ struct TransposeParams {
   int32_t n_dst_modes;
   FastDiv ext_d[kMaxModes + 1];
   int32_t sb_d[kMaxModes + 1];
+  // When extents and kBlock nest (the leading modes of the source-order / destination-order decode
+  // multiply up to a divisor of kBlock, and what is left of kBlock divides the next extent), the
+  // index lane + i * kBlock decodes without a carry between its two terms: the lane reaches into
+  // the first src_split (dst_split) modes only, and the offset is the lane's plus the trip's.  The
+  // planner tabulates the trips' parts (the same for every lane), so a lane decodes once, over few
+  // modes.  0 = no such nesting: every index is decoded in full.
+  int32_t src_split, dst_split;
+  int32_t src_trip_off[kMaxMicroPerLane];      // source offset contributed by trip i (micro-tile lane + i * kBlock)
+  uint32_t src_trip_g[kMaxMicroPerLane];       // ... and its part of g
+  int32_t dst_trip_off[kMaxPicksPerLane];      // destination offset contributed by trip i (vector lane + i * kBlock)
   uint32_t n_micro;                // micro-tiles per tile
   uint32_t n_vec;                  // vectors per tile = n_micro * V
   int32_t a_q;                     // source stride of one step along q (elements)
@@ -133,6 +145,11 @@ struct TransposeParams {
   uint32_t blocked;                // 1: a workgroup owns a contiguous range of tile ids; 0: tile ids strided by the grid
 };
 LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t g) { return g ^ ((g >> P.swz_shift) & P.swz_mask); }
+// A loop over modes with a run-time trip count reads its parameters with one dependent scalar load
+// per trip, and every index decode costs three quarter-rate integer multiplies per mode and lane;
+// a chain of those ahead of the first global load costs microseconds per launch.  Hence the lane /
+// trip split below and the loops that run to a compile-time bound with the live count as a guard
+// (their parameters sit at constant offsets and arrive in a few wide scalar loads).
 // micro-tile u (source order) -> source offset inside the tile and the part of g the micro-tile fixes
 LC_HD void micro_from_src_order(const TransposeParams& P, uint32_t u, int32_t* src_off, uint32_t* g0) {
   int32_t s = 0;
@@ -143,6 +160,23 @@ LC_HD void micro_from_src_order(const TransposeParams& P, uint32_t u, int32_t* s
     u = q;
     s += (int32_t)r * P.sa_s[k];
     g += r * P.gpos_s[k];
+  }
+  *src_off = s;
+  *g0 = g;
+}
+// the lane's digits only (P.src_split > 0): micro-tile lane + i * kBlock adds src_trip_off[i] / src_trip_g[i]
+LC_HD void micro_lane_part(const TransposeParams& P, uint32_t lane, int32_t* src_off, uint32_t* g0) {
+  int32_t s = 0;
+  uint32_t g = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxModes; ++k) {
+    if (k < P.src_split) {
+      uint32_t q, r;
+      fd_divmod(lane, P.ext_s[k], &q, &r);
+      lane = q;
+      s += (int32_t)r * P.sa_s[k];
+      g += r * P.gpos_s[k];
+    }
   }
   *src_off = s;
   *g0 = g;
@@ -158,10 +192,35 @@ LC_HD int32_t vector_dst_offset(const TransposeParams& P, uint32_t g) {
   }
   return d;
 }
+// the lane's digits only (P.dst_split > 0): vector lane + i * kBlock adds dst_trip_off[i]
+LC_HD int32_t vector_lane_part(const TransposeParams& P, uint32_t lane) {
+  int32_t d = 0;
+#pragma unroll
+  for (int k = 0; k < kMaxModes + 1; ++k) {
+    if (k < P.dst_split) {
+      uint32_t q, r;
+      fd_divmod(lane, P.ext_d[k], &q, &r);
+      lane = q;
+      d += (int32_t)r * P.sb_d[k];
+    }
+  }
+  return d;
+}
 // tile id -> offsets of the tile's origin (slicing the rest mode: the coordinate is folded into the accessor, Sec. 2.5.1)
 LC_HD void tile_origin(const TransposeParams& P, uint32_t tile, int64_t* so, int64_t* dof) {
   int64_t s = 0, d = 0;
-  for (int k = 0; k < P.n_rest; ++k) {
+  constexpr int kInline = 4;   // the first modes at constant offsets of the argument block, the others in a loop
+#pragma unroll
+  for (int k = 0; k < kInline; ++k) {
+    if (k < P.n_rest) {
+      uint32_t q, r;
+      fd_divmod(tile, P.rdiv[k], &q, &r);
+      s += (int64_t)r * P.ra[k];
+      d += (int64_t)r * P.rb[k];
+      tile = q;
+    }
+  }
+  for (int k = kInline; k < P.n_rest; ++k) {
     uint32_t q, r;
     fd_divmod(tile, P.rdiv[k], &q, &r);
     s += (int64_t)r * P.ra[k];

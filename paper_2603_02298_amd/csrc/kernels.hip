@@ -35,12 +35,30 @@ __device__ __forceinline__ void gstore(T* p, T v) {
   else *p = v;
 }
 
+// Reads one dword of every 64-byte line of the kernel-argument block, all at once.  The blocks here
+// span up to a dozen lines and their fields are needed one group after the other; without this
+// each group's first use pays its own scalar-cache miss, in series, before the first global load.
+template <int BYTES>
+__device__ __forceinline__ void touch_kernel_arguments() {
+  typedef const uint32_t __attribute__((address_space(4))) * KernargPtr;
+  KernargPtr ka = (KernargPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  constexpr int LINES = (BYTES + 63) / 64;
+  static_assert(LINES <= 16, "one scalar register per line");
+  uint32_t t[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t[i] = ka[(i < LINES ? i : 0) * 16];
+  // a use the compiler cannot move or split: all loads are issued together, and waited for, here
+  asm volatile("" ::"s"(t[0]), "s"(t[1]), "s"(t[2]), "s"(t[3]), "s"(t[4]), "s"(t[5]), "s"(t[6]), "s"(t[7]), "s"(t[8]), "s"(t[9]),
+               "s"(t[10]), "s"(t[11]), "s"(t[12]), "s"(t[13]), "s"(t[14]), "s"(t[15]));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Element-wise: both layouts evaluated per element (idx2crd + inner_product, Eq. idx2crd / Eq. innerprod).
 // ---------------------------------------------------------------------------------------------
 template <int ES>
 __global__ __launch_bounds__(kBlock) void generic_kernel(GenericParams P, const typename Word<ES>::type* __restrict__ src,
                                                         typename Word<ES>::type* __restrict__ dst) {
+  touch_kernel_arguments<(int)sizeof(GenericParams)>();
   const uint32_t step = gridDim.x * kBlock;
   for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < P.n; i += step) dst[flat_eval(P.dst, i)] = src[flat_eval(P.src, i)];
 }
@@ -54,6 +72,7 @@ template <int W, int U, int NT>
 __global__ __launch_bounds__(kBlock) void direct_kernel(DirectParams P, const typename Word<W>::type* __restrict__ src,
                                                        typename Word<W>::type* __restrict__ dst) {
   typedef typename Word<W>::type T;
+  touch_kernel_arguments<(int)sizeof(DirectParams)>();
   // strided: lane items are `step` apart and the whole grid sweeps memory together;
   // blocked: a workgroup owns the contiguous range [first, last) and sweeps it kBlock items at a time
   uint32_t step = gridDim.x * kBlock, first = blockIdx.x * kBlock, last = P.n_items;
@@ -125,13 +144,18 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 
   }
 }
 
-template <int ES, int V, int MT, int NT>
+// FULL: every lane owns MT micro-tiles and MT*V picks (n_micro == MT * kBlock), so the tile loop has
+// no per-lane predicates.  Its body is straight-line code on purpose: the loads of the next tile are
+// issued before the stores of the current one, and with no branch between them the wait before
+// parking can count the stores out (memory operations retire in issue order) instead of draining them.
+template <int ES, int V, int MT, int NT, bool FULL>
 __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
                                                           unsigned char* __restrict__ dst) {
   constexpr int DW = V * ES / 4;                 // dwords per vector
   constexpr int SLOT = V * ES;                   // bytes per vector
   typedef typename Word<SLOT>::type Vec;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  touch_kernel_arguments<(int)sizeof(TransposeParams)>();
 
   // tile-invariant lane state (wavefront-level index arithmetic done once):
   // per owned micro-tile its source offset and LDS base index; per picked vector its destination offset
@@ -141,25 +165,43 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     uint32_t u = threadIdx.x + (uint32_t)m * kBlock;
-    act[m] = u < P.n_micro;
+    act[m] = FULL || u < P.n_micro;
     src_in[m] = 0;
     park_g[m] = 0;
-    if (act[m]) micro_from_src_order(P, u, &src_in[m], &park_g[m]);
   }
+  if (P.src_split > 0) {
+    int32_t s0;
+    uint32_t g0;
+    micro_lane_part(P, threadIdx.x, &s0, &g0);
 #pragma unroll
-  for (int j = 0; j < MT * V; ++j) {
-    uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
-    dst_in[j] = g < P.n_vec ? vector_dst_offset(P, g) : 0;
+    for (int m = 0; m < MT; ++m) {
+      src_in[m] = s0 + P.src_trip_off[m];
+      park_g[m] = g0 + P.src_trip_g[m];
+    }
+  } else {
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      if (act[m]) micro_from_src_order(P, threadIdx.x + (uint32_t)m * kBlock, &src_in[m], &park_g[m]);
+  }
+  if (P.dst_split > 0) {
+    const int32_t d0 = vector_lane_part(P, threadIdx.x);
+#pragma unroll
+    for (int j = 0; j < MT * V; ++j) dst_in[j] = d0 + P.dst_trip_off[j];
+  } else {
+#pragma unroll
+    for (int j = 0; j < MT * V; ++j) {
+      const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+      dst_in[j] = (FULL || g < P.n_vec) ? vector_dst_offset(P, g) : 0;
+    }
   }
 
   uint32_t r[MT][V][DW];
-  auto load_tile = [&](uint32_t tile) {
-    int64_t so, dof;
-    tile_origin(P, tile, &so, &dof);
+  // global -> registers: V vectors along p per micro-tile, one per step along q
+  auto load_tile = [&](int64_t so) {
     const unsigned char* base = src + so * ES;
 #pragma unroll
     for (int m = 0; m < MT; ++m)
-      if (act[m]) {
+      if (FULL || act[m]) {
 #pragma unroll
         for (int iq = 0; iq < V; ++iq) {
           Vec v = gload<NT>(reinterpret_cast<const Vec*>(base + ((int64_t)src_in[m] + (int64_t)iq * P.a_q) * ES));
@@ -169,19 +211,11 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
         }
       }
   };
-
-  uint32_t tile = blockIdx.x, tile_step = gridDim.x, tile_end = P.n_tiles;
-  if (P.blocked) {
-    const uint32_t per_wg = (P.n_tiles + gridDim.x - 1) / gridDim.x;
-    tile = blockIdx.x * per_wg;
-    tile_step = 1;
-    tile_end = min(P.n_tiles, tile + per_wg);
-  }
-  if (tile < tile_end) load_tile(tile);
-  while (tile < tile_end) {
+  // registers -> LDS: transposed micro-tiles, V vectors along q each
+  auto park_tile = [&]() {
 #pragma unroll
     for (int m = 0; m < MT; ++m)
-      if (act[m]) {
+      if (FULL || act[m]) {
         uint32_t o[V][DW];
         micro_transpose<ES, V>(r[m], o);
 #pragma unroll
@@ -193,22 +227,54 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
           *reinterpret_cast<Vec*>(lds + lds_slot(P, park_g[m] + (uint32_t)ip * P.gpos_pv) * SLOT) = v;
         }
       }
-    __syncthreads();
-    int64_t so, dof;
-    tile_origin(P, tile, &so, &dof);
-    const uint32_t next = tile + tile_step;
-    if (next < tile_end) load_tile(next);
+  };
+  // LDS -> global: the tile's vectors in destination address order, consecutive lanes on consecutive vectors
+  auto store_tile = [&](int64_t dof) {
     unsigned char* base = dst + dof * ES;
+    Vec v[MT * V];
 #pragma unroll
     for (int j = 0; j < MT * V; ++j) {
       const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
-      if (g < P.n_vec) {
-        Vec v = *reinterpret_cast<const Vec*>(lds + lds_slot(P, g) * SLOT);
-        gstore<NT>(reinterpret_cast<Vec*>(base + (int64_t)dst_in[j] * ES), v);
-      }
+      if (FULL || g < P.n_vec) v[j] = *reinterpret_cast<const Vec*>(lds + lds_slot(P, g) * SLOT);
     }
+#pragma unroll
+    for (int j = 0; j < MT * V; ++j) {
+      const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+      if (FULL || g < P.n_vec) gstore<NT>(reinterpret_cast<Vec*>(base + (int64_t)dst_in[j] * ES), v[j]);
+    }
+  };
+
+  uint32_t tile = blockIdx.x, tile_step = gridDim.x, tile_end = P.n_tiles;
+  if (P.blocked) {
+    const uint32_t per_wg = (P.n_tiles + gridDim.x - 1) / gridDim.x;
+    tile = blockIdx.x * per_wg;
+    tile_step = 1;
+    tile_end = min(P.n_tiles, tile + per_wg);
+  }
+  if (tile >= tile_end) return;
+  int64_t so, dof;
+  tile_origin(P, tile, &so, &dof);
+  load_tile(so);
+  park_tile();
+  __syncthreads();
+  // invariant at the top: the current tile is parked in LDS, no load is in flight
+  for (;;) {
+    const uint32_t next = tile + tile_step;
+    if (next >= tile_end) {
+      store_tile(dof);
+      break;
+    }
+    int64_t dof_next;
+    tile_origin(P, next, &so, &dof_next);
+    load_tile(so);
+    __builtin_amdgcn_sched_barrier(0);   // keep every load ahead of every store in program order
+    store_tile(dof);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();   // every pick is done: LDS may be overwritten
+    park_tile();
     __syncthreads();
     tile = next;
+    dof = dof_next;
   }
 }
 
@@ -263,21 +329,26 @@ static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsig
   }
 }
 
-template <int ES, int V, int MT, int NT>
-static hipError_t launch_transpose_n(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+template <int ES, int V, int MT, int NT, bool FULL>
+static hipError_t launch_transpose_f(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   const unsigned char* sp = static_cast<const unsigned char*>(src);
   unsigned char* dp = static_cast<unsigned char*>(dst);
   if (plan.lds_bytes > 64 * 1024) {
     static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
     if (!raised.load(std::memory_order_acquire)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT, FULL>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
       raised.store(true, std::memory_order_release);
     }
   }
-  hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
   return hipSuccess;
+}
+template <int ES, int V, int MT, int NT>
+static hipError_t launch_transpose_n(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  if (plan.transpose.n_micro == (uint32_t)MT * kBlock) return launch_transpose_f<ES, V, MT, NT, true>(plan, src, dst, grid, s);
+  return launch_transpose_f<ES, V, MT, NT, false>(plan, src, dst, grid, s);
 }
 template <int ES, int V, int MT>
 static hipError_t launch_transpose_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {

@@ -419,6 +419,36 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
             P.gpos_s[j] = gpos[(size_t)so[j]];
           }
           P.n_micro_modes = (int32_t)so.size();
+          // lane / trip split of the two decodes (see TransposeParams)
+          P.src_split = P.dst_split = 0;
+          {
+            // number of leading modes the lane index reaches into, when lane + i * kBlock decodes without
+            // a carry between the two terms: the modes below the last are covered by the lane alone, and
+            // in the last one the lane's digit stays below a divisor c of the extent while i moves it in
+            // steps of c.  0 when extents and kBlock do not nest that way.
+            auto split_of = [](const FastDiv* ext, int n_modes) -> int {
+              uint64_t prod = 1;
+              for (int k = 0; k < n_modes; ++k) {
+                const uint64_t c = (uint64_t)kBlock / prod;
+                if (c == 1) return k;
+                if (ext[k].div % c == 0) return k + 1;
+                if (c % ext[k].div != 0) return 0;
+                prod *= ext[k].div;
+              }
+              return 0;
+            };
+            P.src_split = split_of(P.ext_s, P.n_micro_modes);
+            P.dst_split = split_of(P.ext_d, P.n_dst_modes);
+            // the trips' parts: decode i * kBlock in full (its lane digits are zero)
+            for (int i = 0; i < kMaxMicroPerLane; ++i) {
+              P.src_trip_off[i] = 0;
+              P.src_trip_g[i] = 0;
+              if (P.src_split > 0 && (uint64_t)i * kBlock < run / (uint32_t)V)
+                micro_from_src_order(P, (uint32_t)i * kBlock, &P.src_trip_off[i], &P.src_trip_g[i]);
+            }
+            for (int i = 0; i < kMaxPicksPerLane; ++i)
+              P.dst_trip_off[i] = (P.dst_split > 0 && (uint64_t)i * kBlock < run) ? vector_dst_offset(P, (uint32_t)i * kBlock) : 0;
+          }
           P.n_vec = run;
           P.n_micro = run / (uint32_t)V;
           P.a_q = (int32_t)J[(size_t)q].a;
@@ -593,6 +623,7 @@ std::string describe(const lc_plan& plan) {
     s += " tiles=" + std::to_string(plan.transpose.n_tiles) + " lds_bytes=" + std::to_string(plan.lds_bytes);
     s += " swizzle_shift=" + std::to_string(plan.transpose.swz_mask ? (int)plan.transpose.swz_shift : -1);
     s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.elem_bytes, 1u << 20, 64));
+    s += " lane_split=" + std::to_string(plan.transpose.src_split) + "/" + std::to_string(plan.transpose.dst_split);
     s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
   } else if (plan.cls == KernelClass::Direct) {
     s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);

@@ -54,7 +54,14 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
         if (u >= P.n_micro) continue;
         int32_t so;
         uint32_t g0;
-        micro_from_src_order(P, u, &so, &g0);
+        // the same choice of decode as the kernel's lanes make
+        if (P.src_split > 0) {
+          micro_lane_part(P, u % (uint32_t)kBlock, &so, &g0);
+          so += P.src_trip_off[u / (uint32_t)kBlock];
+          g0 += P.src_trip_g[u / (uint32_t)kBlock];
+        } else {
+          micro_from_src_order(P, u, &so, &g0);
+        }
         for (int iq = 0; iq < V; ++iq) {
           int64_t off = (sbase + so + (int64_t)iq * P.a_q) * es;
           if (off < 0 || off + slot > B.src_bytes) { B.ok = false; break; }
@@ -68,7 +75,8 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
       // store phase: the tile's vectors in destination order, consecutive lanes taking consecutive vectors
       for (uint32_t g = 0; g < lanes * (uint32_t)V && B.ok; ++g) {
         if (g >= P.n_vec) continue;
-        int64_t off = (dbase + vector_dst_offset(P, g)) * es;
+        const int32_t din = P.dst_split > 0 ? vector_lane_part(P, g % (uint32_t)kBlock) + P.dst_trip_off[g / (uint32_t)kBlock] : vector_dst_offset(P, g);
+        int64_t off = (dbase + din) * es;
         size_t l = (size_t)lds_slot(P, g) * (size_t)slot;
         if (off < 0 || off + slot > B.dst_bytes || l + (size_t)slot > lds.size()) { B.ok = false; break; }
         std::memcpy(B.dst + off, &lds[l], (size_t)slot);
