@@ -183,18 +183,6 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     for (int m = 0; m < MT; ++m)
       if (act[m]) micro_from_src_order(P, threadIdx.x + (uint32_t)m * kBlock, &src_in[m], &park_g[m]);
   }
-  if (P.dst_split > 0) {
-    const int32_t d0 = vector_lane_part(P, threadIdx.x);
-#pragma unroll
-    for (int j = 0; j < MT * V; ++j) dst_in[j] = d0 + P.dst_trip_off[j];
-  } else {
-#pragma unroll
-    for (int j = 0; j < MT * V; ++j) {
-      const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
-      dst_in[j] = (FULL || g < P.n_vec) ? vector_dst_offset(P, g) : 0;
-    }
-  }
-
   uint32_t r[MT][V][DW];
   // global -> registers: V vectors along p per micro-tile, one per step along q
   auto load_tile = [&](int64_t so) {
@@ -255,6 +243,20 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
   int64_t so, dof;
   tile_origin(P, tile, &so, &dof);
   load_tile(so);
+  // The destination side of the lane state is worked out while the first loads are in flight.  The
+  // empty statement below counts as a possible store, so the compiler cannot sink the loads past it.
+  asm volatile("" ::: "memory");
+  if (P.dst_split > 0) {
+    const int32_t d0 = vector_lane_part(P, threadIdx.x);
+#pragma unroll
+    for (int j = 0; j < MT * V; ++j) dst_in[j] = d0 + P.dst_trip_off[j];
+  } else {
+#pragma unroll
+    for (int j = 0; j < MT * V; ++j) {
+      const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+      dst_in[j] = (FULL || g < P.n_vec) ? vector_dst_offset(P, g) : 0;
+    }
+  }
   park_tile();
   __syncthreads();
   // invariant at the top: the current tile is parked in LDS, no load is in flight
