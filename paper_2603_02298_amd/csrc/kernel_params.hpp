@@ -17,7 +17,7 @@ namespace lc {
 constexpr int kMaxModes = 8;          // joint / rest / micro modes per kernel
 constexpr int kMaxGenericModes = 12;  // leaf modes per side in the element-wise kernel
 constexpr int kBlock = 256;           // threads per workgroup = 4 wavefronts of 64
-constexpr int kMaxMicroPerLane = 4;   // micro-tiles a lane owns per tile
+constexpr int kMaxMicroPerLane = 8;   // micro-tiles a lane owns per tile
 constexpr int kMaxPicksPerLane = 32;  // vectors a lane stores per tile (micro-tiles per lane x longest vector)
 
 // Division of a 31-bit unsigned value by a constant: q = (mulhi(n, mul) + n) >> shift

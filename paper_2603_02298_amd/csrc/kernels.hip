@@ -128,7 +128,10 @@ __global__ __launch_bounds__(kBlock) void direct_kernel(DirectParams P, const ty
 // ---------------------------------------------------------------------------------------------
 template <int ES, int V>
 __device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 4], uint32_t (&o)[V][V * ES / 4]) {
-  if (ES == 4) {
+  if constexpr (V == 1) {  // a single element (a 16-byte word): nothing to transpose
+#pragma unroll
+    for (int k = 0; k < V * ES / 4; ++k) o[0][k] = r[0][k];
+  } else if constexpr (ES == 4) {
 #pragma unroll
     for (int ip = 0; ip < V; ++ip)
 #pragma unroll
@@ -367,6 +370,9 @@ static hipError_t launch_transpose(const lc_plan& plan, const void* src, void* d
     case 1: return launch_transpose_m<ES, V, 1>(plan, src, dst, grid, s);
     case 2: return launch_transpose_m<ES, V, 2>(plan, src, dst, grid, s);
     case 4: return launch_transpose_m<ES, V, 4>(plan, src, dst, grid, s);
+    case 8:
+      if constexpr (V == 1) return launch_transpose_m<ES, V, 8>(plan, src, dst, grid, s);
+      break;
   }
   return hipErrorInvalidValue;
 }
@@ -408,8 +414,9 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
     }
   } else {
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(plan.transpose.n_tiles, (uint64_t)cus * plan.wgs_per_cu));
-    const int key = plan.elem_bytes * 100 + plan.V;
+    const int key = plan.tile_elem_bytes * 100 + plan.V;
     switch (key) {
+      case 1601: pre = launch_transpose<16, 1>(plan, src, dst, grid, s); break;
       case 404: pre = launch_transpose<4, 4>(plan, src, dst, grid, s); break;
       case 402: pre = launch_transpose<4, 2>(plan, src, dst, grid, s); break;
       case 208: pre = launch_transpose<2, 8>(plan, src, dst, grid, s); break;

@@ -207,7 +207,254 @@ static lc_status_t plan_generic(const Modes& S, const Modes& D, int64_t n, lc_pl
 }
 
 static bool transpose_instantiated(int es, int V) {
-  return (es == 4 && (V == 4 || V == 2)) || (es == 2 && (V == 8 || V == 4 || V == 2));
+  return (es == 4 && (V == 4 || V == 2)) || (es == 2 && (V == 8 || V == 4 || V == 2)) || (es == 16 && V == 1);
+}
+
+// Tiles a copy over joint modes J (extents and strides in units of `es` bytes) for the transposing
+// kernel with V x V micro-tiles; p / q are the modes the micro-tile extends along on the source /
+// destination side.  Fills the plan and returns true, or leaves the class undecided.
+static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, int q, int64_t n, const Tuning& tune, lc_plan* plan) {
+  const int nj = (int)J.size();
+  // Tile size: up to 4 micro-tiles per lane (64 KiB of fp32), but never so large that fewer than
+  // ~1024 tiles remain for the 256 CUs; growth stops early once both sides move >= 512-byte runs.
+  const int max_per_lane = V == 1 ? 8 : 4;   // 32 KiB of 16-byte words, 64 KiB of 4 x 4 fp32 micro-tiles
+  int64_t target = (int64_t)max_per_lane * kBlock;
+  while (target > 64 && n / (target * V * V) < 1024) target /= 2;
+  if (tune.micro_per_thread == 1 || tune.micro_per_thread == 2 || tune.micro_per_thread == 4 || (tune.micro_per_thread == 8 && V == 1))
+    target = (int64_t)kBlock * tune.micro_per_thread;
+  const int64_t enough_run_bytes = 512;
+  // a lane should have about eight 16-byte loads in flight: one V = 8 micro-tile, or eight single words
+  const int64_t full_wg = (int64_t)kBlock * (V == 1 ? 8 : 1);
+  const std::vector<int> src_order = stride_order(J, true), dst_order = stride_order(J, false);
+  // a6: grow the tile one prime factor at a time, always helping the shorter contiguous run
+  std::vector<int64_t> t((size_t)nj, 1);
+  t[(size_t)p] = V;
+  t[(size_t)q] = V;
+  int64_t micro = 1;
+  // offsets inside a tile are 32-bit in the kernel: a growth step must keep both spans below 2^30 elements
+  auto spans_fit = [&](const std::vector<int64_t>& tt) {
+    int64_t ss = 0, sd = 0;
+    for (int k = 0; k < nj; ++k) { ss += (tt[(size_t)k] - 1) * J[(size_t)k].a; sd += (tt[(size_t)k] - 1) * J[(size_t)k].b; }
+    return ss < (1ll << 30) && sd < (1ll << 30);
+  };
+  for (;;) {
+    int best = -1;
+    int64_t best_min = -1, best_sum = -1, best_f = 1;
+    for (int k = 0; k < nj; ++k) {
+      int64_t left = J[(size_t)k].extent / t[(size_t)k];
+      if (left <= 1) continue;
+      int64_t f = smallest_prime_factor(left);
+      if (micro * f > target) continue;
+      t[(size_t)k] *= f;
+      const bool fits = spans_fit(t);
+      int64_t rs = run_length(J, src_order, t, true), rd = run_length(J, dst_order, t, false);
+      t[(size_t)k] /= f;
+      if (!fits) continue;
+      int64_t mn = std::min(rs, rd), sm = rs + rd;
+      if (mn > best_min || (mn == best_min && sm > best_sum)) { best = k; best_min = mn; best_sum = sm; best_f = f; }
+    }
+    if (best < 0) break;
+    const int64_t cur_s = run_length(J, src_order, t, true), cur_d = run_length(J, dst_order, t, false);
+    int64_t cur_min = std::min(cur_s, cur_d), cur_sum = cur_s + cur_d;
+    if (best_min <= cur_min && best_sum <= cur_sum) break;   // growing further no longer lengthens any run
+    if (tune.micro_per_thread <= 0 && micro >= full_wg && cur_min * es >= enough_run_bytes) break;   // runs are long enough: keep more tiles
+    t[(size_t)best] *= best_f;
+    micro *= best_f;
+  }
+  if (tune.tile.size() == (size_t)nj) {   // explicit tile (tuning): must divide the extents and hold whole micro-tiles
+    bool valid = true;
+    int64_t m2 = 1;
+    for (int k = 0; k < nj; ++k) {
+      int64_t te = tune.tile[(size_t)k];
+      if (te < 1 || J[(size_t)k].extent % te != 0 || ((k == p || k == q) && te % V != 0)) valid = false;
+      else m2 *= (k == p || k == q) ? te / V : te;
+    }
+    if (valid && m2 <= (int64_t)max_per_lane * kBlock) { t = tune.tile; micro = m2; }
+  }
+  // no run can be lengthened any more: still fill the workgroup, smallest destination strides first
+  for (int k = 0; k < nj && tune.tile.size() != (size_t)nj; ++k)
+    for (;;) {
+      int64_t left = J[(size_t)k].extent / t[(size_t)k];
+      int64_t f = left > 1 ? smallest_prime_factor(left) : 0;
+      if (f == 0 || micro * f > (tune.micro_per_thread > 0 ? target : std::min<int64_t>(target, full_wg))) break;
+      t[(size_t)k] *= f;
+      if (!spans_fit(t)) { t[(size_t)k] /= f; break; }
+      micro *= f;
+    }
+  // tiling = zipped_divide of both joint layouts by the tile extents (Sec. 3.5.2): mode 0 is
+  // the tile, mode 1 the grid of tiles; a workgroup slices mode 1 with its tile id.
+  Modes js, jd, tl;
+  for (int k = 0; k < nj; ++k) {
+    js.push_back({J[(size_t)k].extent, J[(size_t)k].a});
+    jd.push_back({J[(size_t)k].extent, J[(size_t)k].b});
+    tl.push_back({t[(size_t)k], 1});
+  }
+  Layout zs, zd;
+  Layout tiler = nj == 1 ? Layout::tuple({Layout::flat(tl)}) : Layout::flat(tl);
+  Layout jsl = nj == 1 ? Layout::tuple({Layout::flat(js)}) : Layout::flat(js);
+  Layout jdl = nj == 1 ? Layout::tuple({Layout::flat(jd)}) : Layout::flat(jd);
+  bool ok = zipped_divide(jsl, tiler, &zs) == LC_OK && zipped_divide(jdl, tiler, &zd) == LC_OK;
+  Layout ts, td, rs_, rd_;
+  if (ok) {
+    ts = zs.mode(0); td = zd.mode(0); rs_ = zs.mode(1); rd_ = zd.mode(1);
+    ok = ts.leaves.size() == (size_t)nj && td.leaves.size() == (size_t)nj && rs_.leaves.size() == rd_.leaves.size();
+  }
+  TransposeParams& P = plan->transpose;
+  std::memset(&P, 0, sizeof(P));
+  int64_t max_in_tile = 0;
+  if (ok) {
+    // micro modes: the tile box with V taken out of p and q
+    struct MM { int64_t ext, sa, sb; bool is_p, is_q; };
+    std::vector<MM> mm;
+    for (int k = 0; k < nj; ++k) {
+      int64_t te = ts.leaves[(size_t)k].extent, ta = ts.leaves[(size_t)k].stride, tb = td.leaves[(size_t)k].stride;
+      if (te != t[(size_t)k] || td.leaves[(size_t)k].extent != te) { ok = false; break; }
+      max_in_tile = std::max(max_in_tile, std::max((te - 1) * ta, (te - 1) * tb));
+      int64_t ext = (k == p || k == q) ? te / V : te;
+      int64_t scale = (k == p || k == q) ? V : 1;
+      if (ext > 1) mm.push_back({ext, ta * scale, tb * scale, k == p, k == q});
+    }
+    int64_t span_s = 0, span_d = 0;
+    for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * J[(size_t)k].a; span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
+    if (span_s >= (1ll << 30) || span_d >= (1ll << 30) || mm.size() >= (size_t)kMaxModes) ok = false;
+    if (ok) {
+      // destination order of the tile's vectors: the micro modes and the position ip along p
+      // inside a micro-tile (extent V, destination stride b_p), by destination stride, q first
+      mm.push_back({V, 0, J[(size_t)p].b, false, false});
+      const int pv = (int)mm.size() - 1;
+      std::vector<int> so, dord;
+      for (int k = 0; k < (int)mm.size(); ++k) { if (k != pv) so.push_back(k); dord.push_back(k); }
+      std::stable_sort(so.begin(), so.end(), [&](int x, int y) {
+        if (mm[(size_t)x].is_p != mm[(size_t)y].is_p) return mm[(size_t)x].is_p;
+        return mm[(size_t)x].sa < mm[(size_t)y].sa; });
+      std::stable_sort(dord.begin(), dord.end(), [&](int x, int y) {
+        if (mm[(size_t)x].is_q != mm[(size_t)y].is_q) return mm[(size_t)x].is_q;
+        return mm[(size_t)x].sb < mm[(size_t)y].sb; });
+      std::vector<uint32_t> gpos(mm.size(), 0);
+      uint32_t run = 1;
+      for (size_t j = 0; j < dord.size(); ++j) {
+        const MM& m = mm[(size_t)dord[j]];
+        P.ext_d[j] = make_fastdiv((uint32_t)m.ext);
+        P.sb_d[j] = (int32_t)m.sb;
+        gpos[(size_t)dord[j]] = run;
+        run *= (uint32_t)m.ext;
+      }
+      P.n_dst_modes = (int32_t)dord.size();
+      P.gpos_pv = gpos[(size_t)pv];
+      for (size_t j = 0; j < so.size(); ++j) {
+        const MM& m = mm[(size_t)so[j]];
+        P.ext_s[j] = make_fastdiv((uint32_t)m.ext);
+        P.sa_s[j] = (int32_t)m.sa;
+        P.gpos_s[j] = gpos[(size_t)so[j]];
+      }
+      P.n_micro_modes = (int32_t)so.size();
+      // lane / trip split of the two decodes (see TransposeParams)
+      P.src_split = P.dst_split = 0;
+      {
+        // number of leading modes the lane index reaches into, when lane + i * kBlock decodes without
+        // a carry between the two terms: the modes below the last are covered by the lane alone, and
+        // in the last one the lane's digit stays below a divisor c of the extent while i moves it in
+        // steps of c.  0 when extents and kBlock do not nest that way.
+        auto split_of = [](const FastDiv* ext, int n_modes) -> int {
+          uint64_t prod = 1;
+          for (int k = 0; k < n_modes; ++k) {
+            const uint64_t c = (uint64_t)kBlock / prod;
+            if (c == 1) return k;
+            if (ext[k].div % c == 0) return k + 1;
+            if (c % ext[k].div != 0) return 0;
+            prod *= ext[k].div;
+          }
+          return 0;
+        };
+        P.src_split = split_of(P.ext_s, P.n_micro_modes);
+        P.dst_split = split_of(P.ext_d, P.n_dst_modes);
+        // the trips' parts: decode i * kBlock in full (its lane digits are zero)
+        for (int i = 0; i < kMaxMicroPerLane; ++i) {
+          P.src_trip_off[i] = 0;
+          P.src_trip_g[i] = 0;
+          if (P.src_split > 0 && (uint64_t)i * kBlock < run / (uint32_t)V)
+            micro_from_src_order(P, (uint32_t)i * kBlock, &P.src_trip_off[i], &P.src_trip_g[i]);
+        }
+        for (int i = 0; i < kMaxPicksPerLane; ++i)
+          P.dst_trip_off[i] = (P.dst_split > 0 && (uint64_t)i * kBlock < run) ? vector_dst_offset(P, (uint32_t)i * kBlock) : 0;
+      }
+      P.n_vec = run;
+      P.n_micro = run / (uint32_t)V;
+      P.a_q = (int32_t)J[(size_t)q].a;
+      if (J[(size_t)q].a * (V - 1) >= (1ll << 30) || J[(size_t)p].b * (V - 1) >= (1ll << 30)) ok = false;
+    }
+  }
+  if (ok) {
+    // rest modes = grid of tiles
+    struct RM { int64_t ext, a, b; };
+    std::vector<RM> rest;
+    for (size_t k = 0; k < rs_.leaves.size(); ++k) {
+      if (rs_.leaves[k].extent != rd_.leaves[k].extent) { ok = false; break; }
+      if (rs_.leaves[k].extent > 1) rest.push_back({rs_.leaves[k].extent, rs_.leaves[k].stride, rd_.leaves[k].stride});
+    }
+    // Tile ids run fastest along the smallest SOURCE stride: resident workgroups then read one
+    // contiguous region together (measured 1-3 % better than destination order; writes are combined
+    // by the caches anyway).
+    if (tune.rest_order != 0)
+      std::stable_sort(rest.begin(), rest.end(), [](const RM& x, const RM& y) { return x.a < y.a; });
+    int64_t tiles = 1;
+    for (const RM& r : rest) tiles *= r.ext;
+    if (rest.size() > (size_t)kMaxModes || tiles >= (1ll << 31) || tiles * (int64_t)P.n_micro * V * V != n) ok = false;
+    if (ok) {
+      P.n_rest = (int32_t)rest.size();
+      for (size_t k = 0; k < rest.size(); ++k) {
+        P.rdiv[k] = make_fastdiv((uint32_t)rest[k].ext);
+        P.ra[k] = rest[k].a;
+        P.rb[k] = rest[k].b;
+      }
+      P.n_tiles = (uint32_t)tiles;
+      P.blocked = tune.blocked > 0 ? 1u : 0u;
+    }
+  }
+  if (ok) {
+    // swizzle: XOR four higher bits of the slot index into its low four bits; pick the source bits
+    // that minimise the modelled bank conflicts of the parking writes (picks stay contiguous)
+    // (the search looks at the first wavefront only; describe() reports the model over the whole tile)
+    int best_shift = -1, best_cost = 0;
+    P.swz_shift = 0; P.swz_mask = 0;
+    best_cost = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
+    if (tune.swizzle_shift == -2) {
+      for (int sh = 4; best_cost > 0 && sh <= 12 && (P.n_vec >> sh) > 0; ++sh) {
+        P.swz_shift = (uint32_t)sh; P.swz_mask = 15;
+        int c = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
+        if (c < best_cost) { best_cost = c; best_shift = sh; }
+      }
+    } else if (tune.swizzle_shift >= 4) {
+      best_shift = tune.swizzle_shift;
+    }
+    if (best_shift >= 4) { P.swz_shift = (uint32_t)best_shift; P.swz_mask = 15; }
+    else { P.swz_shift = 0; P.swz_mask = 0; }
+    plan->cls = KernelClass::Transpose;
+    plan->V = V;
+    plan->width_bytes = V * es;
+    plan->micro_per_thread = (int)((P.n_micro + kBlock - 1) / kBlock);
+    if (plan->micro_per_thread == 3) plan->micro_per_thread = 4;
+    if (plan->micro_per_thread > 4) plan->micro_per_thread = 8;
+    plan->tile_elem_bytes = es;
+    plan->tile_extent = t;
+    plan->p_mode = p;
+    plan->q_mode = q;
+    plan->lds_bytes = ((P.n_vec + 15u) & ~15u) * (unsigned)(V * es);
+    plan->src_run_bytes = run_length(J, src_order, t, true) * es;
+    plan->dst_run_bytes = run_length(J, dst_order, t, false) * es;
+    // nontemporal stores only when every store instruction covers whole 128-byte lines
+    if (tune.nontemporal < 0 && plan->dst_run_bytes % 128 == 0) plan->nontemporal |= 2;
+    // nontemporal stores only when every store instruction covers whole 128-byte lines
+    // Measured on MI355X: HBM efficiency is best with ONE resident workgroup per CU (its next tile's
+    // loads overlap its current tile's stores); short grids need more workgroups to fill the chip.
+    int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
+    int want = P.n_tiles >= 16384 ? 1 : (P.n_tiles >= 4096 ? 2 : (P.n_tiles >= 2048 ? 3 : 4));
+    plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(std::min(8, fit), want));
+    plan->src_align = (unsigned)(V * es);
+    plan->dst_align = (unsigned)(V * es);
+    return true;
+  }
+  return false;
 }
 
 lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src_align, unsigned dst_align,
@@ -289,240 +536,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     int V = common_pow2(cap, need);
     while (V >= 2 && !transpose_instantiated(es, V)) V /= 2;
     if (V >= 2) {
-      // Tile size: up to 4 micro-tiles per lane (64 KiB of fp32), but never so large that fewer than
-      // ~1024 tiles remain for the 256 CUs; growth stops early once both sides move >= 512-byte runs.
-      int64_t target = 4 * kBlock;
-      while (target > 64 && n / (target * V * V) < 1024) target /= 2;
-      if (tune.micro_per_thread == 1 || tune.micro_per_thread == 2 || tune.micro_per_thread == 4)
-        target = (int64_t)kBlock * tune.micro_per_thread;
-      const int64_t enough_run_bytes = 512;
-      const std::vector<int> src_order = stride_order(J, true), dst_order = stride_order(J, false);
-      // a6: grow the tile one prime factor at a time, always helping the shorter contiguous run
-      std::vector<int64_t> t((size_t)nj, 1);
-      t[(size_t)p] = V;
-      t[(size_t)q] = V;
-      int64_t micro = 1;
-      // offsets inside a tile are 32-bit in the kernel: a growth step must keep both spans below 2^30 elements
-      auto spans_fit = [&](const std::vector<int64_t>& tt) {
-        int64_t ss = 0, sd = 0;
-        for (int k = 0; k < nj; ++k) { ss += (tt[(size_t)k] - 1) * J[(size_t)k].a; sd += (tt[(size_t)k] - 1) * J[(size_t)k].b; }
-        return ss < (1ll << 30) && sd < (1ll << 30);
-      };
-      for (;;) {
-        int best = -1;
-        int64_t best_min = -1, best_sum = -1, best_f = 1;
-        for (int k = 0; k < nj; ++k) {
-          int64_t left = J[(size_t)k].extent / t[(size_t)k];
-          if (left <= 1) continue;
-          int64_t f = smallest_prime_factor(left);
-          if (micro * f > target) continue;
-          t[(size_t)k] *= f;
-          const bool fits = spans_fit(t);
-          int64_t rs = run_length(J, src_order, t, true), rd = run_length(J, dst_order, t, false);
-          t[(size_t)k] /= f;
-          if (!fits) continue;
-          int64_t mn = std::min(rs, rd), sm = rs + rd;
-          if (mn > best_min || (mn == best_min && sm > best_sum)) { best = k; best_min = mn; best_sum = sm; best_f = f; }
-        }
-        if (best < 0) break;
-        const int64_t cur_s = run_length(J, src_order, t, true), cur_d = run_length(J, dst_order, t, false);
-        int64_t cur_min = std::min(cur_s, cur_d), cur_sum = cur_s + cur_d;
-        if (best_min <= cur_min && best_sum <= cur_sum) break;   // growing further no longer lengthens any run
-        if (tune.micro_per_thread <= 0 && micro >= kBlock && cur_min * es >= enough_run_bytes) break;   // runs are long enough: keep more tiles
-        t[(size_t)best] *= best_f;
-        micro *= best_f;
-      }
-      if (tune.tile.size() == (size_t)nj) {   // explicit tile (tuning): must divide the extents and hold whole micro-tiles
-        bool valid = true;
-        int64_t m2 = 1;
-        for (int k = 0; k < nj; ++k) {
-          int64_t te = tune.tile[(size_t)k];
-          if (te < 1 || J[(size_t)k].extent % te != 0 || ((k == p || k == q) && te % V != 0)) valid = false;
-          else m2 *= (k == p || k == q) ? te / V : te;
-        }
-        if (valid && m2 <= 4 * kBlock) { t = tune.tile; micro = m2; }
-      }
-      // no run can be lengthened any more: still fill the workgroup, smallest destination strides first
-      for (int k = 0; k < nj && tune.tile.size() != (size_t)nj; ++k)
-        for (;;) {
-          int64_t left = J[(size_t)k].extent / t[(size_t)k];
-          int64_t f = left > 1 ? smallest_prime_factor(left) : 0;
-          if (f == 0 || micro * f > (tune.micro_per_thread > 0 ? target : std::min<int64_t>(target, kBlock))) break;
-          t[(size_t)k] *= f;
-          if (!spans_fit(t)) { t[(size_t)k] /= f; break; }
-          micro *= f;
-        }
-      // tiling = zipped_divide of both joint layouts by the tile extents (Sec. 3.5.2): mode 0 is
-      // the tile, mode 1 the grid of tiles; a workgroup slices mode 1 with its tile id.
-      Modes js, jd, tl;
-      for (int k = 0; k < nj; ++k) {
-        js.push_back({J[(size_t)k].extent, J[(size_t)k].a});
-        jd.push_back({J[(size_t)k].extent, J[(size_t)k].b});
-        tl.push_back({t[(size_t)k], 1});
-      }
-      Layout zs, zd;
-      Layout tiler = nj == 1 ? Layout::tuple({Layout::flat(tl)}) : Layout::flat(tl);
-      Layout jsl = nj == 1 ? Layout::tuple({Layout::flat(js)}) : Layout::flat(js);
-      Layout jdl = nj == 1 ? Layout::tuple({Layout::flat(jd)}) : Layout::flat(jd);
-      bool ok = zipped_divide(jsl, tiler, &zs) == LC_OK && zipped_divide(jdl, tiler, &zd) == LC_OK;
-      Layout ts, td, rs_, rd_;
-      if (ok) {
-        ts = zs.mode(0); td = zd.mode(0); rs_ = zs.mode(1); rd_ = zd.mode(1);
-        ok = ts.leaves.size() == (size_t)nj && td.leaves.size() == (size_t)nj && rs_.leaves.size() == rd_.leaves.size();
-      }
-      TransposeParams& P = plan->transpose;
-      std::memset(&P, 0, sizeof(P));
-      int64_t max_in_tile = 0;
-      if (ok) {
-        // micro modes: the tile box with V taken out of p and q
-        struct MM { int64_t ext, sa, sb; bool is_p, is_q; };
-        std::vector<MM> mm;
-        for (int k = 0; k < nj; ++k) {
-          int64_t te = ts.leaves[(size_t)k].extent, ta = ts.leaves[(size_t)k].stride, tb = td.leaves[(size_t)k].stride;
-          if (te != t[(size_t)k] || td.leaves[(size_t)k].extent != te) { ok = false; break; }
-          max_in_tile = std::max(max_in_tile, std::max((te - 1) * ta, (te - 1) * tb));
-          int64_t ext = (k == p || k == q) ? te / V : te;
-          int64_t scale = (k == p || k == q) ? V : 1;
-          if (ext > 1) mm.push_back({ext, ta * scale, tb * scale, k == p, k == q});
-        }
-        int64_t span_s = 0, span_d = 0;
-        for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * J[(size_t)k].a; span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
-        if (span_s >= (1ll << 30) || span_d >= (1ll << 30) || mm.size() >= (size_t)kMaxModes) ok = false;
-        if (ok) {
-          // destination order of the tile's vectors: the micro modes and the position ip along p
-          // inside a micro-tile (extent V, destination stride b_p), by destination stride, q first
-          mm.push_back({V, 0, J[(size_t)p].b, false, false});
-          const int pv = (int)mm.size() - 1;
-          std::vector<int> so, dord;
-          for (int k = 0; k < (int)mm.size(); ++k) { if (k != pv) so.push_back(k); dord.push_back(k); }
-          std::stable_sort(so.begin(), so.end(), [&](int x, int y) {
-            if (mm[(size_t)x].is_p != mm[(size_t)y].is_p) return mm[(size_t)x].is_p;
-            return mm[(size_t)x].sa < mm[(size_t)y].sa; });
-          std::stable_sort(dord.begin(), dord.end(), [&](int x, int y) {
-            if (mm[(size_t)x].is_q != mm[(size_t)y].is_q) return mm[(size_t)x].is_q;
-            return mm[(size_t)x].sb < mm[(size_t)y].sb; });
-          std::vector<uint32_t> gpos(mm.size(), 0);
-          uint32_t run = 1;
-          for (size_t j = 0; j < dord.size(); ++j) {
-            const MM& m = mm[(size_t)dord[j]];
-            P.ext_d[j] = make_fastdiv((uint32_t)m.ext);
-            P.sb_d[j] = (int32_t)m.sb;
-            gpos[(size_t)dord[j]] = run;
-            run *= (uint32_t)m.ext;
-          }
-          P.n_dst_modes = (int32_t)dord.size();
-          P.gpos_pv = gpos[(size_t)pv];
-          for (size_t j = 0; j < so.size(); ++j) {
-            const MM& m = mm[(size_t)so[j]];
-            P.ext_s[j] = make_fastdiv((uint32_t)m.ext);
-            P.sa_s[j] = (int32_t)m.sa;
-            P.gpos_s[j] = gpos[(size_t)so[j]];
-          }
-          P.n_micro_modes = (int32_t)so.size();
-          // lane / trip split of the two decodes (see TransposeParams)
-          P.src_split = P.dst_split = 0;
-          {
-            // number of leading modes the lane index reaches into, when lane + i * kBlock decodes without
-            // a carry between the two terms: the modes below the last are covered by the lane alone, and
-            // in the last one the lane's digit stays below a divisor c of the extent while i moves it in
-            // steps of c.  0 when extents and kBlock do not nest that way.
-            auto split_of = [](const FastDiv* ext, int n_modes) -> int {
-              uint64_t prod = 1;
-              for (int k = 0; k < n_modes; ++k) {
-                const uint64_t c = (uint64_t)kBlock / prod;
-                if (c == 1) return k;
-                if (ext[k].div % c == 0) return k + 1;
-                if (c % ext[k].div != 0) return 0;
-                prod *= ext[k].div;
-              }
-              return 0;
-            };
-            P.src_split = split_of(P.ext_s, P.n_micro_modes);
-            P.dst_split = split_of(P.ext_d, P.n_dst_modes);
-            // the trips' parts: decode i * kBlock in full (its lane digits are zero)
-            for (int i = 0; i < kMaxMicroPerLane; ++i) {
-              P.src_trip_off[i] = 0;
-              P.src_trip_g[i] = 0;
-              if (P.src_split > 0 && (uint64_t)i * kBlock < run / (uint32_t)V)
-                micro_from_src_order(P, (uint32_t)i * kBlock, &P.src_trip_off[i], &P.src_trip_g[i]);
-            }
-            for (int i = 0; i < kMaxPicksPerLane; ++i)
-              P.dst_trip_off[i] = (P.dst_split > 0 && (uint64_t)i * kBlock < run) ? vector_dst_offset(P, (uint32_t)i * kBlock) : 0;
-          }
-          P.n_vec = run;
-          P.n_micro = run / (uint32_t)V;
-          P.a_q = (int32_t)J[(size_t)q].a;
-          if (J[(size_t)q].a * (V - 1) >= (1ll << 30) || J[(size_t)p].b * (V - 1) >= (1ll << 30)) ok = false;
-        }
-      }
-      if (ok) {
-        // rest modes = grid of tiles
-        struct RM { int64_t ext, a, b; };
-        std::vector<RM> rest;
-        for (size_t k = 0; k < rs_.leaves.size(); ++k) {
-          if (rs_.leaves[k].extent != rd_.leaves[k].extent) { ok = false; break; }
-          if (rs_.leaves[k].extent > 1) rest.push_back({rs_.leaves[k].extent, rs_.leaves[k].stride, rd_.leaves[k].stride});
-        }
-        // Tile ids run fastest along the smallest SOURCE stride: resident workgroups then read one
-        // contiguous region together (measured 1-3 % better than destination order; writes are combined
-        // by the caches anyway).
-        if (tune.rest_order != 0)
-          std::stable_sort(rest.begin(), rest.end(), [](const RM& x, const RM& y) { return x.a < y.a; });
-        int64_t tiles = 1;
-        for (const RM& r : rest) tiles *= r.ext;
-        if (rest.size() > (size_t)kMaxModes || tiles >= (1ll << 31) || tiles * (int64_t)P.n_micro * V * V != n) ok = false;
-        if (ok) {
-          P.n_rest = (int32_t)rest.size();
-          for (size_t k = 0; k < rest.size(); ++k) {
-            P.rdiv[k] = make_fastdiv((uint32_t)rest[k].ext);
-            P.ra[k] = rest[k].a;
-            P.rb[k] = rest[k].b;
-          }
-          P.n_tiles = (uint32_t)tiles;
-          P.blocked = tune.blocked > 0 ? 1u : 0u;
-        }
-      }
-      if (ok) {
-        // swizzle: XOR four higher bits of the slot index into its low four bits; pick the source bits
-        // that minimise the modelled bank conflicts of the parking writes (picks stay contiguous)
-        // (the search looks at the first wavefront only; describe() reports the model over the whole tile)
-        int best_shift = -1, best_cost = 0;
-        P.swz_shift = 0; P.swz_mask = 0;
-        best_cost = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
-        if (tune.swizzle_shift == -2) {
-          for (int sh = 4; best_cost > 0 && sh <= 12 && (P.n_vec >> sh) > 0; ++sh) {
-            P.swz_shift = (uint32_t)sh; P.swz_mask = 15;
-            int c = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
-            if (c < best_cost) { best_cost = c; best_shift = sh; }
-          }
-        } else if (tune.swizzle_shift >= 4) {
-          best_shift = tune.swizzle_shift;
-        }
-        if (best_shift >= 4) { P.swz_shift = (uint32_t)best_shift; P.swz_mask = 15; }
-        else { P.swz_shift = 0; P.swz_mask = 0; }
-        plan->cls = KernelClass::Transpose;
-        plan->V = V;
-        plan->width_bytes = V * es;
-        plan->micro_per_thread = (int)((P.n_micro + kBlock - 1) / kBlock);
-        if (plan->micro_per_thread == 3) plan->micro_per_thread = 4;
-        plan->tile_extent = t;
-        plan->p_mode = p;
-        plan->q_mode = q;
-        plan->lds_bytes = ((P.n_vec + 15u) & ~15u) * (unsigned)(V * es);
-        plan->src_run_bytes = run_length(J, src_order, t, true) * es;
-        plan->dst_run_bytes = run_length(J, dst_order, t, false) * es;
-        // nontemporal stores only when every store instruction covers whole 128-byte lines
-        if (tune.nontemporal < 0 && plan->dst_run_bytes % 128 == 0) plan->nontemporal |= 2;
-        // nontemporal stores only when every store instruction covers whole 128-byte lines
-        // Measured on MI355X: HBM efficiency is best with ONE resident workgroup per CU (its next tile's
-        // loads overlap its current tile's stores); short grids need more workgroups to fill the chip.
-        int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
-        int want = P.n_tiles >= 16384 ? 1 : (P.n_tiles >= 2048 ? 3 : 4);
-        plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(std::min(8, fit), want));
-        plan->src_align = (unsigned)(V * es);
-        plan->dst_align = (unsigned)(V * es);
-        return LC_OK;
-      }
+      if (plan_tiled(J, es, V, p, q, n, tune, plan)) return LC_OK;
       plan->note = "tile did not fit the transpose kernel's index ranges";
     } else {
       plan->note = "no common vector on both sides for a transposing tile";
@@ -537,6 +551,40 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     for (int k = 0; k < nj; ++k)
       if (k != q) { need.push_back(J[(size_t)k].a); need.push_back(J[(size_t)k].b); }
     VEC = common_pow2(cap, need);
+  }
+
+  // ---- Transpose class on 16-byte words ---------------------------------------------------------
+  // The common vector keeps whole 16-byte words together on both sides (p = q), but it is short: in
+  // destination order the source would be read in pieces of K elements.  With the word as the
+  // element the copy is a permutation of words, and a tile through LDS (V = 1: nothing to transpose
+  // inside a word) reads and writes runs of many words.  Measured on MI355X (2^25..2^27 bf16 elements):
+  // 128-byte pieces 59 % of the HBM peak in destination order, 71 % through tiles; 256-byte pieces
+  // run at 72-73 % either way and stay with the direct class.
+  {
+    const int64_t direct_run_bytes = q >= 0 ? J[(size_t)q].extent * es : es;
+    bool stage = VEC * es == 16 && q >= 0 && p == q && nj >= 3 && direct_run_bytes < 256 && tune.force_class != 1;
+    for (int k = 0; k < nj && stage; ++k)
+      if (J[(size_t)k].a == 0) stage = false;   // broadcasts are looped inside a lane by the direct class
+    if (stage) {
+      std::vector<JointMode> W;
+      for (int k = 0; k < nj; ++k) {
+        JointMode m = J[(size_t)k];
+        if (k == q) m.extent /= VEC; else { m.a /= VEC; m.b /= VEC; }
+        if (m.extent > 1) W.push_back(m);
+      }
+      int pw = 0, qw = 0;   // modes of the smallest source / destination stride
+      for (int k = 1; k < (int)W.size(); ++k) {
+        if (W[(size_t)k].a < W[(size_t)pw].a) pw = k;
+        if (W[(size_t)k].b < W[(size_t)qw].b) qw = k;
+      }
+      lc_plan staged = *plan;
+      if (W.size() >= 2 && plan_tiled(W, 16, 1, pw, qw, n / VEC, tune, &staged) &&
+          (tune.force_class == 2 || (staged.src_run_bytes >= 4 * direct_run_bytes && staged.dst_run_bytes >= 4 * direct_run_bytes &&
+                                     staged.transpose.n_tiles >= 256))) {
+        *plan = staged;
+        return LC_OK;
+      }
+    }
   }
   DirectParams& P = plan->direct;
   std::memset(&P, 0, sizeof(P));
@@ -616,13 +664,13 @@ std::string describe(const lc_plan& plan) {
   }
   s += "]";
   if (plan.cls == KernelClass::Transpose) {
-    s += " V=" + std::to_string(plan.V) + " tile=[";
+    s += " V=" + std::to_string(plan.V) + " tile_elem_bytes=" + std::to_string(plan.tile_elem_bytes) + " tile=[";
     for (size_t k = 0; k < plan.tile_extent.size(); ++k) { if (k) s += ","; s += std::to_string(plan.tile_extent[k]); }
     s += "] p=" + std::to_string(plan.p_mode) + " q=" + std::to_string(plan.q_mode);
     s += " micro_tiles=" + std::to_string(plan.transpose.n_micro) + " per_lane=" + std::to_string(plan.micro_per_thread);
     s += " tiles=" + std::to_string(plan.transpose.n_tiles) + " lds_bytes=" + std::to_string(plan.lds_bytes);
     s += " swizzle_shift=" + std::to_string(plan.transpose.swz_mask ? (int)plan.transpose.swz_shift : -1);
-    s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.elem_bytes, 1u << 20, 64));
+    s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.tile_elem_bytes, 1u << 20, 64));
     s += " lane_split=" + std::to_string(plan.transpose.src_split) + "/" + std::to_string(plan.transpose.dst_split);
     s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
   } else if (plan.cls == KernelClass::Direct) {

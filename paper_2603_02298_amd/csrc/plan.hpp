@@ -18,7 +18,7 @@ enum class KernelClass { Generic, Direct, Transpose };
 // Knobs the planner normally chooses itself; values < 0 mean "planner's choice".  Read from the
 // environment (LC_TUNE_*) once per plan so that tile shapes can be swept without rebuilding.
 struct Tuning {
-  int micro_per_thread = -1;   // transpose: micro-tiles per lane (1, 2 or 4)
+  int micro_per_thread = -1;   // transpose: micro-tiles per lane (1, 2, 4; 8 with V = 1)
   int rest_order = -1;         // transpose: 0 = tiles ordered by destination stride, 1 = by source stride (default)
   int wgs_per_cu = -1;         // persistent grid size = CUs * wgs_per_cu
   int unroll = -1;             // direct: items per lane per loop trip (1, 2, 4, 8)
@@ -50,7 +50,9 @@ struct lc_plan {
   int64_t launch_src_step = 0, launch_dst_step = 0;   // elements between consecutive slices
 
   // Transpose
-  int V = 0;                               // micro-tile edge (elements)
+  int tile_elem_bytes = 0;                 // width of what the tiled kernel treats as an element: elem_bytes, or 16 when whole
+                                           // 16-byte words keep together on both sides and are only re-ordered (V = 1)
+  int V = 0;                               // micro-tile edge (elements of tile_elem_bytes)
   int micro_per_thread = 1;
   std::vector<int64_t> tile_extent;        // per joint mode
   int p_mode = -1, q_mode = -1;

@@ -67,6 +67,32 @@ def test_full_size(oracle, name):
     assert torch.equal(dst.view(ref.shape), ref)
 
 
+def test_head_permute_through_word_tiles(oracle):
+    """(B,S,H,D) -> (B,H,S,D) with 128-byte heads, 2^26 bf16 elements: the common vector is 8 words
+    long, so the planner re-orders 16-byte words through LDS tiles instead of reading 128-byte pieces."""
+    dev = torch.device("cuda:0")
+    D, H, S, B = 64, 32, 4096, 8
+    n = D * H * S * B
+    src_layout = "(%d,%d,%d,%d):(1,%d,%d,%d)" % (D, H, S, B, D, D * H, D * H * S)
+    dst_layout = "(%d,%d,%d,%d):(1,%d,%d,%d)" % (D, H, S, B, D * S, D, D * H * S)
+    desc = lc.Plan(src_layout, dst_layout, "bf16").describe()
+    print(desc, flush=True)
+    assert "class=transpose" in desc and "V=1 tile_elem_bytes=16" in desc, desc
+    g = torch.Generator(device=dev)
+    g.manual_seed(W.SEED_BASE + 7)
+    src = torch.randint(-32768, 32767, (n,), device=dev, generator=g, dtype=torch.int16)
+    dst = torch.full((n,), 0x5A5A, dtype=torch.int16, device=dev)
+    lc.copy_tensor(src, src_layout, dst, dst_layout, "bf16")
+    torch.cuda.synchronize()
+    sl, dl = oracle.Layout(src_layout), oracle.Layout(dst_layout)
+    rng = np.random.default_rng(13)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 400000), np.arange(0, 4096), np.arange(n - 4096, n)]))
+    so = torch.from_numpy(sl.offsets_at(idx)).to(dev)
+    do = torch.from_numpy(dl.offsets_at(idx)).to(dev)
+    assert torch.equal(dst[do], src[so])
+    assert torch.equal(dst.view(B, H, S, D), src.view(B, S, H, D).permute(0, 2, 1, 3))
+
+
 def test_c2_literal_strides(oracle):
     """Destination strides exactly as the benchmark spec prints them (not compact: 8.6 GB span, 16-byte runs)."""
     dev = torch.device("cuda:0")

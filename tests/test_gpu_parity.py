@@ -42,7 +42,9 @@ def _parity(oracle, src_layout, dst_layout, dtype, seed=0, src_bits=None, tag=""
     want = np.full(dl.cosize * es, 0x5A, np.uint8).view(_np_int(es))
     oracle.copy(src_bits.view(want.dtype), sl, want, dl)
     got = _gpu_copy(src_bits, src_layout, dst_layout, dtype, dl.cosize)
-    assert (got == want).all(), lc.Plan(src_layout, dst_layout, dtype).describe()
+    desc = lc.Plan(src_layout, dst_layout, dtype).describe()
+    assert (got == want).all(), desc
+    return desc
 
 
 @pytest.mark.parametrize("name,scale", [("c1", 1), ("c1", 16), ("c2", 4), ("c2", 16), ("c3", 16), ("c4a", 16),

@@ -159,6 +159,54 @@ def test_random_layout_pairs(oracle):
     assert seen["direct"] > 100 and seen["transpose"] > 100, seen
 
 
+def _inner_kept_permutation(rng, es):
+    """Permutation of 3-5 modes that keeps a short innermost mode in place: the common vector is a few
+    16-byte words long and the copy re-orders those words (p = q)."""
+    words = int(rng.choice([1, 2, 4, 8, 16]))
+    inner = words * 16 // es
+    n_outer = int(rng.integers(2, 5))
+    ext = [inner] + [int(rng.choice([2, 3, 4, 6, 8, 12, 16, 24, 32])) for _ in range(n_outer)]
+    def compact(order):
+        st, run = [0] * len(ext), 1
+        for m in order:
+            st[m] = run
+            run *= ext[m]
+        return st
+    so = [0] + [int(x) + 1 for x in rng.permutation(n_outer)]
+    do = [0] + [int(x) + 1 for x in rng.permutation(n_outer)]
+    shape = "(" + ",".join(map(str, ext)) + ")"
+    return shape + ":(" + ",".join(map(str, compact(so))) + ")", shape + ":(" + ",".join(map(str, compact(do))) + ")"
+
+
+def test_word_level_tiles(oracle, monkeypatch):
+    # permutations that keep a short innermost mode: tiles of 16-byte words through LDS (V = 1);
+    # the planner takes that route by itself from 256 tiles on (checked in the full-size plans), here it is forced
+    monkeypatch.setenv("LC_TUNE_FORCE_CLASS", "2")
+    desc, _ = _check(oracle, "(64,32,32,4):(1,64,2048,65536)", "(64,32,32,4):(1,2048,64,65536)", "bf16", "transpose")
+    assert "V=1 tile_elem_bytes=16" in desc, desc
+    desc, _ = _check(oracle, "(32,64,16,6):(1,32,2048,32768)", "(32,64,16,6):(1,512,32,32768)", "f32", "transpose")
+    assert "V=1 tile_elem_bytes=16" in desc, desc
+    for per_lane in (2, 4, 8):     # the tile sizes of the full-size plans
+        monkeypatch.setenv("LC_TUNE_MICRO_PER_THREAD", str(per_lane))
+        desc, _ = _check(oracle, "(64,32,32,4):(1,64,2048,65536)", "(64,32,32,4):(1,2048,64,65536)", "bf16", "transpose")
+        assert "V=1 tile_elem_bytes=16" in desc and ("per_lane=%d" % per_lane) in desc, desc
+    monkeypatch.delenv("LC_TUNE_MICRO_PER_THREAD")
+    rng = np.random.default_rng(77)
+    staged = 0
+    for i in range(300):
+        dt = ["bf16", "f32", "b8", "b64"][i % 4]
+        s, d = _inner_kept_permutation(rng, lc.DTYPE_BYTES[dt])
+        desc, _ = _check(oracle, s, d, dt, seed=i)
+        staged += "tile_elem_bytes=16" in desc
+    assert staged > 40, staged
+    monkeypatch.delenv("LC_TUNE_FORCE_CLASS")
+    # by itself: an attention-head permute (B,S,H,D) -> (B,H,S,D) with 128-byte heads; longer common vectors stay direct
+    desc = lc.Plan("(64,32,4096,8):(1,64,2048,8388608)", "(64,32,4096,8):(1,262144,64,8388608)", "bf16").describe()
+    assert "class=transpose" in desc and "V=1 tile_elem_bytes=16" in desc and "src_run_bytes=2048" in desc, desc
+    desc = lc.Plan("(128,32,4096,8):(1,128,4096,16777216)", "(128,32,4096,8):(1,524288,128,16777216)", "bf16").describe()
+    assert "class=direct" in desc, desc
+
+
 def test_shapes_without_common_refinement_use_generic_class(oracle):
     for s, d in [("(2,3):(3,1)", "(3,2):(2,1)"), ("(4,9):(9,1)", "(6,6):(1,6)"), ("(5,7,3):(21,3,1)", "(3,35):(1,3)")]:
         desc, _ = _check(oracle, s, d, "f32")
