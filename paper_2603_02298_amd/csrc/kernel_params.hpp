@@ -143,6 +143,17 @@ struct TransposeParams {
   int64_t ra[kMaxModes], rb[kMaxModes];
   uint32_t n_tiles;
   uint32_t blocked;                // 1: a workgroup owns a contiguous range of tile ids; 0: tile ids strided by the grid
+  // Ragged tiles: up to two joint modes whose extent the tile does not divide.  The grid then has
+  // ceil(extent / tile) tiles along such a mode and the last of them hangs over the edge; an access
+  // is made only if its coordinate along the mode is inside (the role the paper gives to coordinate
+  // tensors, Sec. 2.3.2 / Fig. layouts2: a layout with strides e_i yields the coordinate to compare
+  // with the shape).  Coordinates of the two modes travel packed, 16 bits each.
+  int32_t n_ragged;                // 0: every tile is whole
+  uint32_t rag_extent[2];          // extent of the mode (elements)
+  uint32_t rag_tile[2];            // tile extent along it (elements, < 2^15)
+  int32_t rag_rest[2];             // which rest mode counts the tiles along it (-1: the mode has a single tile)
+  uint32_t cw_s[kMaxModes];        // coordinate step (packed) of one step of source-order micro mode k
+  uint32_t cw_d[kMaxModes + 1];    // the same for the destination-order modes
 };
 LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t g) { return g ^ ((g >> P.swz_shift) & P.swz_mask); }
 // A loop over modes with a run-time trip count reads its parameters with one dependent scalar load
@@ -180,6 +191,55 @@ LC_HD void micro_lane_part(const TransposeParams& P, uint32_t lane, int32_t* src
   }
   *src_off = s;
   *g0 = g;
+}
+// the same with the micro-tile's packed coordinates along the ragged modes
+LC_HD void micro_from_src_order_ragged(const TransposeParams& P, uint32_t u, int32_t* src_off, uint32_t* g0, uint32_t* crd) {
+  int32_t s = 0;
+  uint32_t g = 0, c = 0;
+  for (int k = 0; k < P.n_micro_modes; ++k) {
+    uint32_t q, r;
+    fd_divmod(u, P.ext_s[k], &q, &r);
+    u = q;
+    s += (int32_t)r * P.sa_s[k];
+    g += r * P.gpos_s[k];
+    c += r * P.cw_s[k];
+  }
+  *src_off = s;
+  *g0 = g;
+  *crd = c;
+}
+LC_HD int32_t vector_dst_offset_ragged(const TransposeParams& P, uint32_t g, uint32_t* crd) {
+  int32_t d = 0;
+  uint32_t c = 0;
+  for (int k = 0; k < P.n_dst_modes; ++k) {
+    uint32_t q, r;
+    fd_divmod(g, P.ext_d[k], &q, &r);
+    g = q;
+    d += (int32_t)r * P.sb_d[k];
+    c += r * P.cw_d[k];
+  }
+  *crd = c;
+  return d;
+}
+// packed coordinates inside the tile against what is left of the two ragged modes from this tile's origin on
+LC_HD bool inside_ragged(uint32_t crd, uint32_t rem0, uint32_t rem1) { return (crd & 0xffffu) < rem0 && (crd >> 16) < rem1; }
+// tile id -> origin offsets and the remaining extents along the ragged modes
+LC_HD void tile_origin_ragged(const TransposeParams& P, uint32_t tile, int64_t* so, int64_t* dof, uint32_t* rem0, uint32_t* rem1) {
+  int64_t s = 0, d = 0;
+  uint32_t rem[2] = {P.n_ragged > 0 ? P.rag_extent[0] : 0x10000u, P.n_ragged > 1 ? P.rag_extent[1] : 0x10000u};
+  for (int k = 0; k < P.n_rest; ++k) {
+    uint32_t q, r;
+    fd_divmod(tile, P.rdiv[k], &q, &r);
+    s += (int64_t)r * P.ra[k];
+    d += (int64_t)r * P.rb[k];
+    tile = q;
+    for (int j = 0; j < 2; ++j)
+      if (j < P.n_ragged && P.rag_rest[j] == k) rem[j] = P.rag_extent[j] - r * P.rag_tile[j];
+  }
+  *so = s;
+  *dof = d;
+  *rem0 = rem[0];
+  *rem1 = rem[1];
 }
 // vector g (destination order) -> destination offset inside the tile
 LC_HD int32_t vector_dst_offset(const TransposeParams& P, uint32_t g) {

@@ -284,6 +284,94 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
 }
 
 // ---------------------------------------------------------------------------------------------
+// Ragged tiles: the same staging through LDS for shapes the tile does not divide (odd extents, extents
+// with large prime factors) and for element-wise transposes (V = 1, no vector on either side).  The
+// grid has ceil(extent / tile) tiles along a ragged mode; every access first compares its coordinate
+// with what is left of the mode (coordinate predication, Sec. 2.3.2).  Kept apart from the kernel above
+// so that its predicates do not reach into that kernel's straight-line loop; no software pipeline here,
+// several resident workgroups per CU overlap each other's phases.
+// ---------------------------------------------------------------------------------------------
+template <int ES, int V, int MT, int NT>
+__global__ __launch_bounds__(kBlock) void ragged_transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
+                                                                 unsigned char* __restrict__ dst) {
+  constexpr int SLOT = V * ES;
+  typedef typename Word<SLOT>::type Vec;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  touch_kernel_arguments<(int)sizeof(TransposeParams)>();
+
+  int32_t src_in[MT], dst_in[MT * V];
+  uint32_t park_g[MT], crd_s[MT], crd_d[MT * V];
+  bool act_s[MT], act_d[MT * V];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    const uint32_t u = threadIdx.x + (uint32_t)m * kBlock;
+    act_s[m] = u < P.n_micro;
+    src_in[m] = 0;
+    park_g[m] = 0;
+    crd_s[m] = 0;
+    if (act_s[m]) micro_from_src_order_ragged(P, u, &src_in[m], &park_g[m], &crd_s[m]);
+  }
+#pragma unroll
+  for (int j = 0; j < MT * V; ++j) {
+    const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+    act_d[j] = g < P.n_vec;
+    crd_d[j] = 0;
+    dst_in[j] = act_d[j] ? vector_dst_offset_ragged(P, g, &crd_d[j]) : 0;
+  }
+
+  uint32_t tile = blockIdx.x, tile_step = gridDim.x, tile_end = P.n_tiles;
+  if (P.blocked) {
+    const uint32_t per_wg = (P.n_tiles + gridDim.x - 1) / gridDim.x;
+    tile = blockIdx.x * per_wg;
+    tile_step = 1;
+    tile_end = min(P.n_tiles, tile + per_wg);
+  }
+  for (; tile < tile_end; tile += tile_step) {
+    int64_t so, dof;
+    uint32_t rem0, rem1;
+    tile_origin_ragged(P, tile, &so, &dof, &rem0, &rem1);
+    const unsigned char* sbase = src + so * ES;
+    unsigned char* dbase = dst + dof * ES;
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      if (act_s[m] && inside_ragged(crd_s[m], rem0, rem1)) {
+        if constexpr (V == 1) {
+          const Vec v = gload<NT>(reinterpret_cast<const Vec*>(sbase + (int64_t)src_in[m] * ES));
+          *reinterpret_cast<Vec*>(lds + lds_slot(P, park_g[m]) * SLOT) = v;
+        } else {
+          constexpr int DW = V * ES / 4;
+          uint32_t r[V][DW], o[V][DW];
+#pragma unroll
+          for (int iq = 0; iq < V; ++iq) {
+            const Vec v = gload<NT>(reinterpret_cast<const Vec*>(sbase + ((int64_t)src_in[m] + (int64_t)iq * P.a_q) * ES));
+            const uint32_t* w = reinterpret_cast<const uint32_t*>(&v);
+#pragma unroll
+            for (int k = 0; k < DW; ++k) r[iq][k] = w[k];
+          }
+          micro_transpose<ES, V>(r, o);
+#pragma unroll
+          for (int ip = 0; ip < V; ++ip) {
+            Vec v;
+            uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+            for (int k = 0; k < DW; ++k) w[k] = o[ip][k];
+            *reinterpret_cast<Vec*>(lds + lds_slot(P, park_g[m] + (uint32_t)ip * P.gpos_pv) * SLOT) = v;
+          }
+        }
+      }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < MT * V; ++j)
+      if (act_d[j] && inside_ragged(crd_d[j], rem0, rem1)) {
+        const uint32_t g = threadIdx.x + (uint32_t)j * kBlock;
+        const Vec v = *reinterpret_cast<const Vec*>(lds + lds_slot(P, g) * SLOT);
+        *reinterpret_cast<Vec*>(dbase + (int64_t)dst_in[j] * ES) = v;
+      }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------------
 static thread_local std::string g_last_hip_error;
@@ -377,6 +465,30 @@ static hipError_t launch_transpose(const lc_plan& plan, const void* src, void* d
   return hipErrorInvalidValue;
 }
 
+template <int ES, int V, int MT>
+static hipError_t launch_ragged_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  const unsigned char* sp = static_cast<const unsigned char*>(src);
+  unsigned char* dp = static_cast<unsigned char*>(dst);
+  if (plan.nontemporal & 1)
+    hipLaunchKernelGGL((ragged_transpose_kernel<ES, V, MT, 1>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  else
+    hipLaunchKernelGGL((ragged_transpose_kernel<ES, V, MT, 0>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  return hipSuccess;
+}
+template <int ES, int V>
+static hipError_t launch_ragged(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  if (plan.lds_bytes > 64 * 1024) return hipErrorInvalidValue;   // the planner keeps ragged tiles within the default LDS limit
+  switch (plan.micro_per_thread) {
+    case 1: return launch_ragged_m<ES, V, 1>(plan, src, dst, grid, s);
+    case 2: return launch_ragged_m<ES, V, 2>(plan, src, dst, grid, s);
+    case 4: return launch_ragged_m<ES, V, 4>(plan, src, dst, grid, s);
+    case 8:
+      if constexpr (V == 1) return launch_ragged_m<ES, V, 8>(plan, src, dst, grid, s);
+      break;
+  }
+  return hipErrorInvalidValue;
+}
+
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream) {
   if (!src || !dst) return LC_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(src) % plan.src_align) != 0 || (reinterpret_cast<uintptr_t>(dst) % plan.dst_align) != 0)
@@ -415,6 +527,21 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
   } else {
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(plan.transpose.n_tiles, (uint64_t)cus * plan.wgs_per_cu));
     const int key = plan.tile_elem_bytes * 100 + plan.V;
+    if (plan.transpose.n_ragged > 0 || (plan.V == 1 && plan.tile_elem_bytes != 16)) {
+      switch (key) {
+        case 1601: pre = launch_ragged<16, 1>(plan, src, dst, grid, s); break;
+        case 801: pre = launch_ragged<8, 1>(plan, src, dst, grid, s); break;
+        case 401: pre = launch_ragged<4, 1>(plan, src, dst, grid, s); break;
+        case 201: pre = launch_ragged<2, 1>(plan, src, dst, grid, s); break;
+        case 101: pre = launch_ragged<1, 1>(plan, src, dst, grid, s); break;
+        case 404: pre = launch_ragged<4, 4>(plan, src, dst, grid, s); break;
+        case 402: pre = launch_ragged<4, 2>(plan, src, dst, grid, s); break;
+        case 208: pre = launch_ragged<2, 8>(plan, src, dst, grid, s); break;
+        case 204: pre = launch_ragged<2, 4>(plan, src, dst, grid, s); break;
+        case 202: pre = launch_ragged<2, 2>(plan, src, dst, grid, s); break;
+        default: return LC_ERR_UNSUPPORTED_DTYPE;
+      }
+    } else
     switch (key) {
       case 1601: pre = launch_transpose<16, 1>(plan, src, dst, grid, s); break;
       case 404: pre = launch_transpose<4, 4>(plan, src, dst, grid, s); break;

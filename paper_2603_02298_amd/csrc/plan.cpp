@@ -209,22 +209,31 @@ static lc_status_t plan_generic(const Modes& S, const Modes& D, int64_t n, lc_pl
 static bool transpose_instantiated(int es, int V) {
   return (es == 4 && (V == 4 || V == 2)) || (es == 2 && (V == 8 || V == 4 || V == 2)) || (es == 16 && V == 1);
 }
+// the ragged kernel also moves single elements (V = 1) of any width
+static bool ragged_instantiated(int es, int V) {
+  return transpose_instantiated(es, V) || (V == 1 && (es == 1 || es == 2 || es == 4 || es == 8 || es == 16));
+}
 
 // Tiles a copy over joint modes J (extents and strides in units of `es` bytes) for the transposing
 // kernel with V x V micro-tiles; p / q are the modes the micro-tile extends along on the source /
 // destination side.  Fills the plan and returns true, or leaves the class undecided.
-static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, int q, int64_t n, const Tuning& tune, lc_plan* plan) {
+// ragged: tile extents are powers of two (times V along p and q) and need not divide the extents; the
+// grid has ceil(extent / tile) tiles along such a mode and the kernel checks coordinates at the edge.
+static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, int q, int64_t n, const Tuning& tune, lc_plan* plan,
+                       bool ragged = false) {
   const int nj = (int)J.size();
   // Tile size: up to 4 micro-tiles per lane (64 KiB of fp32), but never so large that fewer than
   // ~1024 tiles remain for the 256 CUs; growth stops early once both sides move >= 512-byte runs.
-  const int max_per_lane = V == 1 ? 8 : 4;   // 32 KiB of 16-byte words, 64 KiB of 4 x 4 fp32 micro-tiles
+  // 32 KiB of 16-byte words, 64 KiB of 4 x 4 fp32 micro-tiles; single elements: 4 per lane measured best (35 % of
+  // the HBM peak on a 4001 x 4003 fp32 transpose against 26 % with 8 and 24 % with 1)
+  const int max_per_lane = V == 1 ? (es == 16 ? 8 : 4) : 4;
   int64_t target = (int64_t)max_per_lane * kBlock;
   while (target > 64 && n / (target * V * V) < 1024) target /= 2;
   if (tune.micro_per_thread == 1 || tune.micro_per_thread == 2 || tune.micro_per_thread == 4 || (tune.micro_per_thread == 8 && V == 1))
     target = (int64_t)kBlock * tune.micro_per_thread;
   const int64_t enough_run_bytes = 512;
   // a lane should have about eight 16-byte loads in flight: one V = 8 micro-tile, or eight single words
-  const int64_t full_wg = (int64_t)kBlock * (V == 1 ? 8 : 1);
+  const int64_t full_wg = (int64_t)kBlock * (V == 1 ? max_per_lane : 1);
   const std::vector<int> src_order = stride_order(J, true), dst_order = stride_order(J, false);
   // a6: grow the tile one prime factor at a time, always helping the shorter contiguous run
   std::vector<int64_t> t((size_t)nj, 1);
@@ -237,7 +246,35 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     for (int k = 0; k < nj; ++k) { ss += (tt[(size_t)k] - 1) * J[(size_t)k].a; sd += (tt[(size_t)k] - 1) * J[(size_t)k].b; }
     return ss < (1ll << 30) && sd < (1ll << 30);
   };
-  for (;;) {
+  auto micro_of = [&](const std::vector<int64_t>& tt) {
+    int64_t m = 1;
+    for (int k = 0; k < nj; ++k) m *= (k == p || k == q) ? (tt[(size_t)k] + V - 1) / V : tt[(size_t)k];
+    return m;
+  };
+  while (ragged) {
+    // double the tile along the mode that lengthens the shorter run most; a tile that would reach past
+    // the extent takes the whole extent instead (that mode is then not ragged)
+    int best = -1;
+    int64_t best_min = -1, best_sum = -1, best_t = 1;
+    for (int k = 0; k < nj; ++k) {
+      const int64_t e = J[(size_t)k].extent, old = t[(size_t)k];
+      if (old >= e) continue;
+      const int64_t grown = std::min<int64_t>(old * 2, e);
+      t[(size_t)k] = grown;
+      const bool fits = spans_fit(t) && micro_of(t) <= target && grown < (1 << 15);
+      int64_t rs = run_length(J, src_order, t, true), rd = run_length(J, dst_order, t, false);
+      t[(size_t)k] = old;
+      if (!fits) continue;
+      int64_t mn = std::min(rs, rd), sm = rs + rd;
+      if (mn > best_min || (mn == best_min && sm > best_sum)) { best = k; best_min = mn; best_sum = sm; best_t = grown; }
+    }
+    if (best < 0) break;
+    const int64_t cur_s = run_length(J, src_order, t, true), cur_d = run_length(J, dst_order, t, false);
+    if (tune.micro_per_thread <= 0 && micro_of(t) >= full_wg && std::min(cur_s, cur_d) * es >= enough_run_bytes) break;
+    t[(size_t)best] = best_t;
+    micro = micro_of(t);
+  }
+  for (; !ragged;) {
     int best = -1;
     int64_t best_min = -1, best_sum = -1, best_f = 1;
     for (int k = 0; k < nj; ++k) {
@@ -261,7 +298,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     t[(size_t)best] *= best_f;
     micro *= best_f;
   }
-  if (tune.tile.size() == (size_t)nj) {   // explicit tile (tuning): must divide the extents and hold whole micro-tiles
+  if (tune.tile.size() == (size_t)nj && !ragged) {   // explicit tile (tuning): must divide the extents and hold whole micro-tiles
     bool valid = true;
     int64_t m2 = 1;
     for (int k = 0; k < nj; ++k) {
@@ -272,7 +309,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     if (valid && m2 <= (int64_t)max_per_lane * kBlock) { t = tune.tile; micro = m2; }
   }
   // no run can be lengthened any more: still fill the workgroup, smallest destination strides first
-  for (int k = 0; k < nj && tune.tile.size() != (size_t)nj; ++k)
+  for (int k = 0; k < nj && tune.tile.size() != (size_t)nj && !ragged; ++k)
     for (;;) {
       int64_t left = J[(size_t)k].extent / t[(size_t)k];
       int64_t f = left > 1 ? smallest_prime_factor(left) : 0;
@@ -293,26 +330,50 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
   Layout tiler = nj == 1 ? Layout::tuple({Layout::flat(tl)}) : Layout::flat(tl);
   Layout jsl = nj == 1 ? Layout::tuple({Layout::flat(js)}) : Layout::flat(js);
   Layout jdl = nj == 1 ? Layout::tuple({Layout::flat(jd)}) : Layout::flat(jd);
-  bool ok = zipped_divide(jsl, tiler, &zs) == LC_OK && zipped_divide(jdl, tiler, &zd) == LC_OK;
+  bool ok = true;
   Layout ts, td, rs_, rd_;
-  if (ok) {
-    ts = zs.mode(0); td = zd.mode(0); rs_ = zs.mode(1); rd_ = zd.mode(1);
-    ok = ts.leaves.size() == (size_t)nj && td.leaves.size() == (size_t)nj && rs_.leaves.size() == rd_.leaves.size();
+  std::vector<int> ragged_modes;
+  for (int k = 0; k < nj; ++k)
+    if (J[(size_t)k].extent % t[(size_t)k] != 0) ragged_modes.push_back(k);
+  if (ragged_modes.empty()) {
+    ok = zipped_divide(jsl, tiler, &zs) == LC_OK && zipped_divide(jdl, tiler, &zd) == LC_OK;
+    if (ok) {
+      ts = zs.mode(0); td = zd.mode(0); rs_ = zs.mode(1); rd_ = zd.mode(1);
+      ok = ts.leaves.size() == (size_t)nj && td.leaves.size() == (size_t)nj && rs_.leaves.size() == rd_.leaves.size();
+    }
+  } else {
+    // the tiler does not divide the shape, so the divide is not admissible (Sec. 3.3.1); the tile and
+    // the grid are written down directly: tile mode k = t_k : stride_k, grid mode k = ceil(e_k / t_k) : t_k stride_k
+    Modes tsm, tdm, rsm, rdm;
+    for (int k = 0; k < nj; ++k) {
+      const int64_t e = J[(size_t)k].extent, tk = t[(size_t)k], cnt = (e + tk - 1) / tk;
+      tsm.push_back({tk, J[(size_t)k].a}); tdm.push_back({tk, J[(size_t)k].b});
+      rsm.push_back({cnt, tk * J[(size_t)k].a}); rdm.push_back({cnt, tk * J[(size_t)k].b});
+    }
+    ts = Layout::flat(tsm); td = Layout::flat(tdm); rs_ = Layout::flat(rsm); rd_ = Layout::flat(rdm);
+    ok = ragged && ragged_modes.size() <= 2;
+    for (int k : ragged_modes)   // whole vectors only: the extent along p and q is a multiple of V by the choice of V
+      if ((k == p || k == q) && J[(size_t)k].extent % V != 0) ok = false;
   }
   TransposeParams& P = plan->transpose;
   std::memset(&P, 0, sizeof(P));
   int64_t max_in_tile = 0;
   if (ok) {
     // micro modes: the tile box with V taken out of p and q
-    struct MM { int64_t ext, sa, sb; bool is_p, is_q; };
+    struct MM { int64_t ext, sa, sb; bool is_p, is_q; uint32_t cw; };
     std::vector<MM> mm;
+    auto coord_weight = [&](int joint_mode, int64_t step) -> uint32_t {   // packed coordinate step along the ragged modes
+      for (size_t j = 0; j < ragged_modes.size(); ++j)
+        if (ragged_modes[j] == joint_mode) return (uint32_t)step << (16 * j);
+      return 0u;
+    };
     for (int k = 0; k < nj; ++k) {
       int64_t te = ts.leaves[(size_t)k].extent, ta = ts.leaves[(size_t)k].stride, tb = td.leaves[(size_t)k].stride;
       if (te != t[(size_t)k] || td.leaves[(size_t)k].extent != te) { ok = false; break; }
       max_in_tile = std::max(max_in_tile, std::max((te - 1) * ta, (te - 1) * tb));
       int64_t ext = (k == p || k == q) ? te / V : te;
       int64_t scale = (k == p || k == q) ? V : 1;
-      if (ext > 1) mm.push_back({ext, ta * scale, tb * scale, k == p, k == q});
+      if (ext > 1) mm.push_back({ext, ta * scale, tb * scale, k == p, k == q, coord_weight(k, scale)});
     }
     int64_t span_s = 0, span_d = 0;
     for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * J[(size_t)k].a; span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
@@ -320,7 +381,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     if (ok) {
       // destination order of the tile's vectors: the micro modes and the position ip along p
       // inside a micro-tile (extent V, destination stride b_p), by destination stride, q first
-      mm.push_back({V, 0, J[(size_t)p].b, false, false});
+      mm.push_back({V, 0, J[(size_t)p].b, false, false, coord_weight(p, 1)});
       const int pv = (int)mm.size() - 1;
       std::vector<int> so, dord;
       for (int k = 0; k < (int)mm.size(); ++k) { if (k != pv) so.push_back(k); dord.push_back(k); }
@@ -336,6 +397,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
         const MM& m = mm[(size_t)dord[j]];
         P.ext_d[j] = make_fastdiv((uint32_t)m.ext);
         P.sb_d[j] = (int32_t)m.sb;
+        P.cw_d[j] = m.cw;
         gpos[(size_t)dord[j]] = run;
         run *= (uint32_t)m.ext;
       }
@@ -346,6 +408,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
         P.ext_s[j] = make_fastdiv((uint32_t)m.ext);
         P.sa_s[j] = (int32_t)m.sa;
         P.gpos_s[j] = gpos[(size_t)so[j]];
+        P.cw_s[j] = m.cw;
       }
       P.n_micro_modes = (int32_t)so.size();
       // lane / trip split of the two decodes (see TransposeParams)
@@ -386,11 +449,12 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
   }
   if (ok) {
     // rest modes = grid of tiles
-    struct RM { int64_t ext, a, b; };
+    struct RM { int64_t ext, a, b; int joint; };
     std::vector<RM> rest;
-    for (size_t k = 0; k < rs_.leaves.size(); ++k) {
+    if (!ragged_modes.empty() && rs_.leaves.size() != (size_t)nj) ok = false;
+    for (size_t k = 0; k < rs_.leaves.size() && ok; ++k) {
       if (rs_.leaves[k].extent != rd_.leaves[k].extent) { ok = false; break; }
-      if (rs_.leaves[k].extent > 1) rest.push_back({rs_.leaves[k].extent, rs_.leaves[k].stride, rd_.leaves[k].stride});
+      if (rs_.leaves[k].extent > 1) rest.push_back({rs_.leaves[k].extent, rs_.leaves[k].stride, rd_.leaves[k].stride, (int)k});
     }
     // Tile ids run fastest along the smallest SOURCE stride: resident workgroups then read one
     // contiguous region together (measured 1-3 % better than destination order; writes are combined
@@ -399,8 +463,17 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
       std::stable_sort(rest.begin(), rest.end(), [](const RM& x, const RM& y) { return x.a < y.a; });
     int64_t tiles = 1;
     for (const RM& r : rest) tiles *= r.ext;
-    if (rest.size() > (size_t)kMaxModes || tiles >= (1ll << 31) || tiles * (int64_t)P.n_micro * V * V != n) ok = false;
+    if (rest.size() > (size_t)kMaxModes || tiles >= (1ll << 31)) ok = false;
+    if (ragged_modes.empty() ? tiles * (int64_t)P.n_micro * V * V != n : tiles * (int64_t)P.n_micro * V * V < n) ok = false;
     if (ok) {
+      P.n_ragged = (int32_t)ragged_modes.size();
+      for (size_t j = 0; j < ragged_modes.size(); ++j) {
+        P.rag_extent[j] = (uint32_t)J[(size_t)ragged_modes[j]].extent;
+        P.rag_tile[j] = (uint32_t)t[(size_t)ragged_modes[j]];
+        P.rag_rest[j] = -1;
+        for (size_t k = 0; k < rest.size(); ++k)
+          if (rest[k].joint == ragged_modes[j]) P.rag_rest[j] = (int32_t)k;
+      }
       P.n_rest = (int32_t)rest.size();
       for (size_t k = 0; k < rest.size(); ++k) {
         P.rdiv[k] = make_fastdiv((uint32_t)rest[k].ext);
@@ -449,6 +522,8 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     // loads overlap its current tile's stores); short grids need more workgroups to fill the chip.
     int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
     int want = P.n_tiles >= 16384 ? 1 : (P.n_tiles >= 4096 ? 2 : (P.n_tiles >= 2048 ? 3 : 4));
+    // the ragged / element-wise kernel has no software pipeline: resident workgroups overlap each other instead
+    if (P.n_ragged > 0 || (V == 1 && es != 16)) want = 8;
     plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(std::min(8, fit), want));
     plan->src_align = (unsigned)(V * es);
     plan->dst_align = (unsigned)(V * es);
@@ -536,9 +611,30 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     int V = common_pow2(cap, need);
     while (V >= 2 && !transpose_instantiated(es, V)) V /= 2;
     if (V >= 2) {
-      if (plan_tiled(J, es, V, p, q, n, tune, plan)) return LC_OK;
+      const bool exact = plan_tiled(J, es, V, p, q, n, tune, plan);
+      // Whole tiles need extents with small factors.  When they leave runs shorter than a cache line
+      // (prime-ish extents) the ragged tiling is tried too and taken if its shorter run is at least twice
+      // as long (its kernel is not pipelined: 4000 x 4000 fp32 runs at 63 % with whole 160 x 32 tiles and
+      // at 57 % with ragged 128 x 64 tiles, but 8000 x 8008 bf16 at 34 % against 46 %).
+      if (exact && (std::min(plan->src_run_bytes, plan->dst_run_bytes) >= 128 || tune.tile.size() == (size_t)nj)) return LC_OK;
+      lc_plan rag = *plan;
+      rag.cls = KernelClass::Generic;
+      if (plan_tiled(J, es, V, p, q, n, tune, &rag, true) && rag.transpose.n_ragged > 0 &&
+          (!exact || std::min(rag.src_run_bytes, rag.dst_run_bytes) >= 2 * std::min(plan->src_run_bytes, plan->dst_run_bytes))) {
+        *plan = rag;
+        return LC_OK;
+      }
+      if (exact) return LC_OK;
       plan->note = "tile did not fit the transpose kernel's index ranges";
     } else {
+      // No vector on one side (odd strides or extents): single elements through the same tiles (V = 1).
+      // In destination order a lane would read one element per source line; a tile reads and writes runs.
+      lc_plan rag = *plan;
+      if (ragged_instantiated(es, 1) && plan_tiled(J, es, 1, p, q, n, tune, &rag, true) &&
+          std::min(rag.src_run_bytes, rag.dst_run_bytes) >= 8 * es) {
+        *plan = rag;
+        return LC_OK;
+      }
       plan->note = "no common vector on both sides for a transposing tile";
     }
   }
@@ -672,6 +768,7 @@ std::string describe(const lc_plan& plan) {
     s += " swizzle_shift=" + std::to_string(plan.transpose.swz_mask ? (int)plan.transpose.swz_shift : -1);
     s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.tile_elem_bytes, 1u << 20, 64));
     s += " lane_split=" + std::to_string(plan.transpose.src_split) + "/" + std::to_string(plan.transpose.dst_split);
+    s += " ragged_modes=" + std::to_string(plan.transpose.n_ragged);
     s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
   } else if (plan.cls == KernelClass::Direct) {
     s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);

@@ -48,14 +48,20 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
     const uint32_t lanes = (uint32_t)kBlock * (uint32_t)plan.micro_per_thread;
     for (uint32_t tile = 0; tile < P.n_tiles && B.ok; ++tile) {
       int64_t sbase, dbase;
-      tile_origin(P, tile, &sbase, &dbase);
+      uint32_t rem0 = 0x10000u, rem1 = 0x10000u;
+      if (P.n_ragged > 0) tile_origin_ragged(P, tile, &sbase, &dbase, &rem0, &rem1);
+      else tile_origin(P, tile, &sbase, &dbase);
       // load phase: lane u reads V vectors along p (one per step along q), parks V vectors along q
       for (uint32_t u = 0; u < lanes; ++u) {
         if (u >= P.n_micro) continue;
         int32_t so;
         uint32_t g0;
         // the same choice of decode as the kernel's lanes make
-        if (P.src_split > 0) {
+        if (P.n_ragged > 0) {
+          uint32_t crd;
+          micro_from_src_order_ragged(P, u, &so, &g0, &crd);
+          if (!inside_ragged(crd, rem0, rem1)) continue;
+        } else if (P.src_split > 0) {
           micro_lane_part(P, u % (uint32_t)kBlock, &so, &g0);
           so += P.src_trip_off[u / (uint32_t)kBlock];
           g0 += P.src_trip_g[u / (uint32_t)kBlock];
@@ -75,7 +81,14 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
       // store phase: the tile's vectors in destination order, consecutive lanes taking consecutive vectors
       for (uint32_t g = 0; g < lanes * (uint32_t)V && B.ok; ++g) {
         if (g >= P.n_vec) continue;
-        const int32_t din = P.dst_split > 0 ? vector_lane_part(P, g % (uint32_t)kBlock) + P.dst_trip_off[g / (uint32_t)kBlock] : vector_dst_offset(P, g);
+        int32_t din;
+        if (P.n_ragged > 0) {
+          uint32_t crd;
+          din = vector_dst_offset_ragged(P, g, &crd);
+          if (!inside_ragged(crd, rem0, rem1)) continue;
+        } else {
+          din = P.dst_split > 0 ? vector_lane_part(P, g % (uint32_t)kBlock) + P.dst_trip_off[g / (uint32_t)kBlock] : vector_dst_offset(P, g);
+        }
         int64_t off = (dbase + din) * es;
         size_t l = (size_t)lds_slot(P, g) * (size_t)slot;
         if (off < 0 || off + slot > B.dst_bytes || l + (size_t)slot > lds.size()) { B.ok = false; break; }

@@ -93,6 +93,31 @@ def test_head_permute_through_word_tiles(oracle):
     assert torch.equal(dst.view(B, H, S, D), src.view(B, S, H, D).permute(0, 2, 1, 3))
 
 
+@pytest.mark.parametrize("M,N,dt", [(4001, 4003, "f32"), (8008, 8000, "bf16"), (8001, 8003, "bf16")])
+def test_odd_transposes_through_ragged_tiles(oracle, M, N, dt):
+    """Transposes whose extents the tiles do not divide (4001 and 4003 are primes, 8008 = 8 * 7 * 11 * 13)."""
+    dev = torch.device("cuda:0")
+    n = M * N
+    src_layout, dst_layout = "(%d,%d):(1,%d)" % (M, N, M), "(%d,%d):(%d,1)" % (M, N, N)
+    desc = lc.Plan(src_layout, dst_layout, dt).describe()
+    print(desc, flush=True)
+    assert "class=transpose" in desc and "ragged_modes=0" not in desc, desc
+    tdt = torch.int32 if dt == "f32" else torch.int16
+    g = torch.Generator(device=dev)
+    g.manual_seed(W.SEED_BASE + 8)
+    src = torch.randint(-32768, 32767, (n,), device=dev, generator=g, dtype=tdt)
+    dst = torch.full((n,), 0x5A5A, dtype=tdt, device=dev)
+    lc.copy_tensor(src, src_layout, dst, dst_layout, dt)
+    torch.cuda.synchronize()
+    sl, dl = oracle.Layout(src_layout), oracle.Layout(dst_layout)
+    rng = np.random.default_rng(14)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 400000), np.arange(0, 4096), np.arange(n - 4096, n)]))
+    so = torch.from_numpy(sl.offsets_at(idx)).to(dev)
+    do = torch.from_numpy(dl.offsets_at(idx)).to(dev)
+    assert torch.equal(dst[do], src[so])
+    assert torch.equal(dst.view(M, N), src.view(N, M).t())
+
+
 def test_c2_literal_strides(oracle):
     """Destination strides exactly as the benchmark spec prints them (not compact: 8.6 GB span, 16-byte runs)."""
     dev = torch.device("cuda:0")

@@ -207,6 +207,37 @@ def test_word_level_tiles(oracle, monkeypatch):
     assert "class=direct" in desc, desc
 
 
+def test_ragged_tiles(oracle):
+    # extents the tile does not divide: ceil(extent / tile) tiles along the mode, coordinates checked at the edge
+    for s, d, dt, want in [
+        ("(67,71):(1,67)", "(67,71):(71,1)", "f32", "V=1 tile_elem_bytes=4"),          # odd transpose, no vector at all
+        ("(131,77):(1,131)", "(131,77):(77,1)", "bf16", "V=1 tile_elem_bytes=2"),
+        ("(45,33):(1,45)", "(45,33):(33,1)", "b8", "V=1 tile_elem_bytes=1"),
+        ("(37,41):(1,37)", "(37,41):(41,1)", "b64", "V=1 tile_elem_bytes=8"),
+        ("(2006,26):(1,2006)", "(2006,26):(26,1)", "f32", "V=2"),                       # 2006 = 2 * 17 * 59: whole tiles would be slivers
+        ("(328,1016):(1,328)", "(328,1016):(1016,1)", "bf16", "V=8"),                   # 1016 = 8 * 127
+        ("(66,50,3):(1,66,3300)", "(66,50,3):(50,1,3300)", "f32", "V=2"),                # batched
+        ("(67,71,5):(1,67,4757)", "(67,71,5):(71,1,4757)", "f32", "V=1"),                 # batched, two ragged modes
+    ]:
+        desc, _ = _check(oracle, s, d, dt, "transpose")
+        assert want in desc and "ragged_modes=0" not in desc, desc
+    # power-of-two shapes keep whole tiles and the pipelined kernel
+    desc, _ = _check(oracle, "(64,128):(1,64)", "(64,128):(128,1)", "f32", "transpose")
+    assert "ragged_modes=0" in desc and "V=4" in desc, desc
+    rng = np.random.default_rng(99)
+    ragged = 0
+    for i in range(250):
+        M, N = int(rng.integers(9, 200)), int(rng.integers(9, 200))
+        B = int(rng.choice([1, 1, 2, 3]))
+        dt = ["f32", "bf16", "b8", "b64"][i % 4]
+        pad = int(rng.choice([0, 0, 1, 5]))
+        s = "(%d,%d,%d):(1,%d,%d)" % (M, N, B, M + pad, (M + pad) * N)
+        d = "(%d,%d,%d):(%d,1,%d)" % (M, N, B, N, M * N)
+        desc, _ = _check(oracle, s, d, dt, seed=i)
+        ragged += "class=transpose" in desc and "ragged_modes=0" not in desc
+    assert ragged > 150, ragged
+
+
 def test_shapes_without_common_refinement_use_generic_class(oracle):
     for s, d in [("(2,3):(3,1)", "(3,2):(2,1)"), ("(4,9):(9,1)", "(6,6):(1,6)"), ("(5,7,3):(21,3,1)", "(3,35):(1,3)")]:
         desc, _ = _check(oracle, s, d, "f32")
@@ -219,6 +250,7 @@ def test_large_copies_are_sliced_into_launches(oracle, monkeypatch):
     assert "launches=4 " in lc.Plan("%d:3" % (1 << 32), "%d:1" % (1 << 32), "bf16").describe()
     assert "launches=16 " in lc.Plan("%d:1" % (1 << 36), "%d:1" % (1 << 36), "f32").describe()
     monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
+    monkeypatch.setenv("LC_TUNE_FORCE_CLASS", "1")       # the third case would otherwise go through element-wise tiles
     for s, d, dt, launches in [("4096:3", "4096:1", "f32", 8), ("(64,240):(1,64)", "(64,240):(1,100)", "bf16", 4),
                                ("(30,7,11):(1,30,210)", "(30,7,11):(77,11,1)", "f32", 3), ("4099:1", "4099:1", "b8", 4099)]:
         desc, _ = _check(oracle, s, d, dt, "direct")
