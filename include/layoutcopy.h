@@ -31,6 +31,7 @@ extern "C" {
 
 typedef struct lc_layout lc_layout_t; /* opaque: a layout S:D */
 typedef struct lc_plan lc_plan_t;     /* opaque: a planned copy between two layouts */
+typedef struct lc_slayout lc_slayout_t; /* opaque: a layout whose strides come from an integer-semimodule (Sec. 2.3.2) */
 
 typedef enum {
   LC_OK = 0,
@@ -148,6 +149,34 @@ lc_status_t lc_zipped_divide(const lc_layout_t* a, const lc_layout_t* tiler, lc_
 /* Largest K such that the first K offsets of both layouts belong to the same coordinates: the extent of the
  * stride-1 head of coalesce(a o right_inverse(b)) (Sec. 3.4.2).  Requires |a| == |b|. */
 lc_status_t lc_max_common_vector(const lc_layout_t* a, const lc_layout_t* b, int64_t* K);
+
+/* ---------------------------------------------------------------------------------------------
+ * Layouts with integer-semimodule strides (Sec. 2.3.2, Fig. layouts2).  Host objects like lc_layout_t.
+ * Text form as the paper prints them: integers, scaled basis elements "e0", "6e1" of Z^(*,..,*) (the
+ * layout then yields a coordinate with one component per axis), or XOR elements "f5" of (Z, XOR, *)
+ * (a swizzled offset), e.g. "(4,(4,2)):(e1,(e0,6e1))", "(8,8):(f1,f9)".  The inner product is taken
+ * in the semimodule: c * (a e_i) = (c a) e_i added per component, c * f_d = f_(c d) added by XOR.
+ * One kind of stride per layout (zeros aside); at most 16 axes.
+ * lc_slayout_kind: 0 integer, 1 coordinate, 2 XOR.  lc_slayout_eval writes lc_slayout_codomain_rank()
+ * values to out (cap = room in out); the extended domain applies as for lc_layout_eval.
+ * lc_slayout_composition: A o B for an integer layout B (Sec. 3.3 "Reductive case: Coordinate",
+ * Table TVLayoutExamples rows Swizzled and Coordinate); errors as lc_composition.  With XOR strides the
+ * result equals A(B(c)) only while the modes of B that fall into one mode of A do not meet in a bit
+ * (true for the paper's example); the paper asks for "special care" there and so does this call.
+ * lc_slayout_coalesce: Sec. 3.2 in the semimodule (XOR modes never merge).
+ * lc_slayout_right_inverse: coordinate layouts only (Table rinv, rows with e_i strides): the integer
+ * layout R on the largest box of coordinates starting at 0 with A(R(c)) = c; INVALID_ARG otherwise.
+ * Errors of parse: PARSE, NOT_CONGRUENT, BAD_EXTENT, INVALID_ARG (mixed kinds, size overflow). */
+lc_status_t lc_slayout_parse(const char* text, lc_slayout_t** out);
+void lc_slayout_destroy(lc_slayout_t* layout);
+lc_status_t lc_slayout_to_string(const lc_slayout_t* layout, char* buf, size_t cap, size_t* needed);
+int lc_slayout_kind(const lc_slayout_t* layout);
+int lc_slayout_codomain_rank(const lc_slayout_t* layout);
+int64_t lc_slayout_size(const lc_slayout_t* layout);
+lc_status_t lc_slayout_eval(const lc_slayout_t* layout, int64_t integral_coord, int64_t* out, int cap);
+lc_status_t lc_slayout_composition(const lc_slayout_t* a, const lc_layout_t* b, lc_slayout_t** out);
+lc_status_t lc_slayout_coalesce(const lc_slayout_t* a, lc_slayout_t** out);
+lc_status_t lc_slayout_right_inverse(const lc_slayout_t* a, lc_layout_t** out);
 
 /* ---------------------------------------------------------------------------------------------
  * COPY (Sec. 2.6.1): dst(i) = src(i) for i in [0, size(dst)), executed on the GPU.

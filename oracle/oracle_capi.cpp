@@ -4,6 +4,7 @@
 #include <string>
 
 #include "layout_oracle.hpp"
+#include "semimodule_oracle.hpp"
 
 using oracle::Layout;
 
@@ -174,6 +175,43 @@ int oracle_copy(const void* src, const Layout* sl, void* dst, const Layout* dl, 
 int oracle_copy_range(const void* src, const Layout* sl, void* dst, const Layout* dl, int elem_bytes,
                       int64_t begin, int64_t end) {
   return oracle::copy_range(src, *sl, dst, *dl, elem_bytes, begin, end);
+}
+
+
+// ---- semimodule strides (Sec. 2.3.2) ----
+int oracle_slayout_parse(const char* text, oracle::SLayout** out) {
+  if (!text || !out) return oracle::ERR_INVALID_ARG;
+  oracle::SLayout L;
+  oracle::Status st = oracle::parse_slayout(text, &L);
+  if (st != oracle::OK) return st;
+  *out = new oracle::SLayout(L);
+  return oracle::OK;
+}
+void oracle_slayout_destroy(oracle::SLayout* L) { delete L; }
+int oracle_slayout_to_string(const oracle::SLayout* L, char* buf, size_t cap, size_t* needed) { return put_string(oracle::to_string(*L), buf, cap, needed); }
+int oracle_slayout_kind(const oracle::SLayout* L) { return (int)oracle::kind_of(*L); }
+int oracle_slayout_codomain_rank(const oracle::SLayout* L) { return oracle::codomain_rank(*L); }
+int64_t oracle_slayout_size(const oracle::SLayout* L) { return oracle::size(L->shape); }
+int oracle_slayout_eval(const oracle::SLayout* L, int64_t i, int64_t* out, int cap) {
+  std::vector<int64_t> v = oracle::eval(*L, i);
+  if ((int)v.size() > cap) return oracle::ERR_INVALID_ARG;
+  for (size_t k = 0; k < v.size(); ++k) out[k] = v[k];
+  return oracle::OK;
+}
+int oracle_slayout_composition(const oracle::SLayout* a, const Layout* b, oracle::SLayout** out) {
+  oracle::SLayout r;
+  oracle::Status st = oracle::composition(*a, *b, &r);
+  if (st != oracle::OK) return st;
+  *out = new oracle::SLayout(r);
+  return oracle::OK;
+}
+int oracle_slayout_coalesce(const oracle::SLayout* a, oracle::SLayout** out) { *out = new oracle::SLayout(oracle::coalesce(*a)); return oracle::OK; }
+int oracle_slayout_right_inverse(const oracle::SLayout* a, Layout** out) {
+  Layout r;
+  oracle::Status st = oracle::right_inverse(*a, &r);
+  if (st != oracle::OK) return st;
+  *out = new Layout(r);
+  return oracle::OK;
 }
 
 }  // extern "C"

@@ -10,7 +10,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liboracle.so")
-_SOURCES = ["layout_oracle.cpp", "oracle_capi.cpp"]
+_SOURCES = ["layout_oracle.cpp", "semimodule_oracle.cpp", "oracle_capi.cpp"]
 
 STATUS_NAMES = {
     0: "OK", 1: "INVALID_ARG", 2: "PARSE", 3: "NOT_CONGRUENT", 4: "BAD_EXTENT", 5: "NEGATIVE_STRIDE",
@@ -29,9 +29,9 @@ class OracleError(Exception):
 def build(force=False):
     """Compile the oracle (g++, host only)."""
     srcs = [os.path.join(_HERE, s) for s in _SOURCES]
-    hdr = os.path.join(_HERE, "layout_oracle.hpp")
+    hdrs = [os.path.join(_HERE, h) for h in ("layout_oracle.hpp", "semimodule_oracle.hpp")]
     if not force and os.path.exists(_LIB_PATH):
-        newest = max(os.path.getmtime(p) for p in srcs + [hdr])
+        newest = max(os.path.getmtime(p) for p in srcs + hdrs)
         if os.path.getmtime(_LIB_PATH) >= newest:
             return _LIB_PATH
     cmd = ["g++", "-std=c++17", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", "-o", _LIB_PATH] + srcs
@@ -81,6 +81,18 @@ def lib():
         L.oracle_layout_slice.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64), PP]
         L.oracle_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
         L.oracle_max_common_vector_def.argtypes = [P, P, ctypes.POINTER(i64)]
+        L.oracle_slayout_parse.argtypes = [ctypes.c_char_p, PP]
+        L.oracle_slayout_destroy.argtypes = [P]
+        L.oracle_slayout_destroy.restype = None
+        L.oracle_slayout_to_string.argtypes = [P, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        L.oracle_slayout_kind.argtypes = [P]
+        L.oracle_slayout_codomain_rank.argtypes = [P]
+        L.oracle_slayout_size.argtypes = [P]
+        L.oracle_slayout_size.restype = i64
+        L.oracle_slayout_eval.argtypes = [P, i64, ctypes.POINTER(i64), ctypes.c_int]
+        L.oracle_slayout_composition.argtypes = [P, P, PP]
+        L.oracle_slayout_coalesce.argtypes = [P, PP]
+        L.oracle_slayout_right_inverse.argtypes = [P, PP]
         L.oracle_copy.argtypes = [P, P, P, P, ctypes.c_int]
         L.oracle_copy_range.argtypes = [P, P, P, P, ctypes.c_int, i64, i64]
         _lib = L
@@ -166,6 +178,70 @@ class Layout:
         text = c if isinstance(c, str) else _tuple_text(c)
         _check(lib().oracle_crd2idx(self._h, text.encode(), ctypes.byref(out)), "crd2idx %s" % text)
         return out.value
+
+
+class SLayout:
+    """A layout whose strides are integers, scaled basis elements a*e_i (it yields coordinates) or
+    XOR elements f_d (Sec. 2.3.2), e.g. "(4,(4,2)):(e1,(e0,6e1))" or "(8,8):(f1,f9)"."""
+
+    KINDS = {0: "int", 1: "coord", 2: "xor"}
+
+    def __init__(self, text=None, _handle=None):
+        self._h = ctypes.c_void_p()
+        if _handle is not None:
+            self._h = _handle
+        else:
+            _check(lib().oracle_slayout_parse(text.encode(), ctypes.byref(self._h)), "parse %r" % text)
+
+    def __del__(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib().oracle_slayout_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __str__(self):
+        buf = ctypes.create_string_buffer(4096)
+        lib().oracle_slayout_to_string(self._h, buf, 4096, None)
+        return buf.value.decode()
+
+    @property
+    def kind(self):
+        return self.KINDS[lib().oracle_slayout_kind(self._h)]
+
+    @property
+    def size(self):
+        return lib().oracle_slayout_size(self._h)
+
+    def __call__(self, i):
+        """L(i): a tuple of coordinates for e_i strides, an int otherwise."""
+        out = (ctypes.c_int64 * 16)()
+        _check(lib().oracle_slayout_eval(self._h, int(i), out, 16), "eval")
+        r = lib().oracle_slayout_codomain_rank(self._h)
+        return tuple(out[k] for k in range(r)) if self.kind == "coord" else out[0]
+
+
+def _as_slayout(x):
+    return x if isinstance(x, SLayout) else SLayout(str(x))
+
+
+def slayout_composition(a, b):
+    a, b = _as_slayout(a), _as_layout(b)
+    h = ctypes.c_void_p()
+    _check(lib().oracle_slayout_composition(a._h, b._h, ctypes.byref(h)), "composition(%s, %s)" % (a, b))
+    return SLayout(_handle=h)
+
+
+def slayout_coalesce(a):
+    a = _as_slayout(a)
+    h = ctypes.c_void_p()
+    _check(lib().oracle_slayout_coalesce(a._h, ctypes.byref(h)), "coalesce(%s)" % a)
+    return SLayout(_handle=h)
+
+
+def slayout_right_inverse(a):
+    a = _as_slayout(a)
+    h = ctypes.c_void_p()
+    _check(lib().oracle_slayout_right_inverse(a._h, ctypes.byref(h)), "right_inverse(%s)" % a)
+    return Layout(_handle=h)
 
 
 def _tuple_text(c):

@@ -64,6 +64,18 @@ def lib():
         getattr(L, "lc_" + n).argtypes = [P, P, PP]
     L.lc_complement.argtypes = [P, i64, PP]
     L.lc_layout_slice.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64), PP]
+    L.lc_slayout_parse.argtypes = [ctypes.c_char_p, PP]
+    L.lc_slayout_destroy.argtypes = [P]
+    L.lc_slayout_destroy.restype = None
+    L.lc_slayout_to_string.argtypes = [P, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+    L.lc_slayout_kind.argtypes = [P]
+    L.lc_slayout_codomain_rank.argtypes = [P]
+    L.lc_slayout_size.argtypes = [P]
+    L.lc_slayout_size.restype = i64
+    L.lc_slayout_eval.argtypes = [P, i64, ctypes.POINTER(i64), ctypes.c_int]
+    L.lc_slayout_composition.argtypes = [P, P, PP]
+    L.lc_slayout_coalesce.argtypes = [P, PP]
+    L.lc_slayout_right_inverse.argtypes = [P, PP]
     L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
     L.lc_plan_create.argtypes = [P, P, ctypes.c_int, ctypes.c_uint, ctypes.c_uint, PP]
     L.lc_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
@@ -160,6 +172,68 @@ def lc_layout_slice(a, coord):
     h, off = ctypes.c_void_p(), ctypes.c_int64()
     _check(lib().lc_layout_slice(a._h, coord.encode(), ctypes.byref(off), ctypes.byref(h)), "lc_layout_slice(%s, %s)" % (a, coord))
     return off.value, Layout(_handle=h)
+
+
+class SLayout:
+    """A layout with integer-semimodule strides (Sec. 2.3.2): "(4,(4,2)):(e1,(e0,6e1))", "(8,8):(f1,f9)"."""
+
+    KINDS = {0: "int", 1: "coord", 2: "xor"}
+
+    def __init__(self, text=None, _handle=None):
+        self._h = ctypes.c_void_p()
+        if _handle is not None:
+            self._h = _handle
+        else:
+            _check(lib().lc_slayout_parse(str(text).encode(), ctypes.byref(self._h)), "lc_slayout_parse(%r)" % (text,))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib().lc_slayout_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __str__(self):
+        buf = ctypes.create_string_buffer(4096)
+        _check(lib().lc_slayout_to_string(self._h, buf, 4096, None), "lc_slayout_to_string")
+        return buf.value.decode()
+
+    @property
+    def kind(self):
+        return self.KINDS[lib().lc_slayout_kind(self._h)]
+
+    @property
+    def size(self):
+        return lib().lc_slayout_size(self._h)
+
+    def __call__(self, i):
+        out = (ctypes.c_int64 * 16)()
+        _check(lib().lc_slayout_eval(self._h, int(i), out, 16), "lc_slayout_eval")
+        r = lib().lc_slayout_codomain_rank(self._h)
+        return tuple(out[k] for k in range(r)) if self.kind == "coord" else out[0]
+
+
+def _as_slayout(x):
+    return x if isinstance(x, SLayout) else SLayout(x)
+
+
+def lc_slayout_composition(a, b):
+    a, b = _as_slayout(a), _as_layout(b)
+    h = ctypes.c_void_p()
+    _check(lib().lc_slayout_composition(a._h, b._h, ctypes.byref(h)), "lc_slayout_composition(%s, %s)" % (a, b))
+    return SLayout(_handle=h)
+
+
+def lc_slayout_coalesce(a):
+    a = _as_slayout(a)
+    h = ctypes.c_void_p()
+    _check(lib().lc_slayout_coalesce(a._h, ctypes.byref(h)), "lc_slayout_coalesce(%s)" % a)
+    return SLayout(_handle=h)
+
+
+def lc_slayout_right_inverse(a):
+    a = _as_slayout(a)
+    h = ctypes.c_void_p()
+    _check(lib().lc_slayout_right_inverse(a._h, ctypes.byref(h)), "lc_slayout_right_inverse(%s)" % a)
+    return Layout(_handle=h)
 
 
 def lc_complement(a, cotarget=0):

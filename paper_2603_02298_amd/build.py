@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "liblayoutcopy.so")
-SOURCES = ["layout.cpp", "algebra.cpp", "plan.cpp", "replay.cpp", "capi.cpp", "kernels.hip"]
+SOURCES = ["layout.cpp", "algebra.cpp", "semimodule.cpp", "plan.cpp", "replay.cpp", "capi.cpp", "kernels.hip"]
 HEADERS = ["layout.hpp", "algebra.hpp", "plan.hpp", "kernel_params.hpp"]
 
 

@@ -5,6 +5,7 @@
 #include "algebra.hpp"
 #include "layoutcopy.h"
 #include "plan.hpp"
+#include "semimodule.hpp"
 
 namespace {
 
@@ -239,6 +240,66 @@ lc_status_t lc_debug_replay_on_host(const lc_plan_t* plan, const void* src_host,
                                     int64_t dst_elems, int64_t* lds_conflicts) {
   if (!plan || !src_host || !dst_host) return LC_ERR_INVALID_ARG;
   return lc::replay_on_host(*plan, src_host, src_elems, dst_host, dst_elems, lds_conflicts);
+}
+
+
+/* ---- semimodule strides (Sec. 2.3.2) ---- */
+lc_status_t lc_slayout_parse(const char* text, lc_slayout_t** out) {
+  if (!text || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::SemiLayout L;
+    lc_status_t st = lc::parse(text, &L);
+    if (st != LC_OK) return st;
+    *out = new lc_slayout_t{L};
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+void lc_slayout_destroy(lc_slayout_t* layout) { delete layout; }
+lc_status_t lc_slayout_to_string(const lc_slayout_t* layout, char* buf, size_t cap, size_t* needed) {
+  if (!layout) return LC_ERR_INVALID_ARG;
+  return put_string(layout->L.str(), buf, cap, needed);
+}
+int lc_slayout_kind(const lc_slayout_t* layout) { return layout ? (int)layout->L.kind() : -1; }
+int lc_slayout_codomain_rank(const lc_slayout_t* layout) { return layout ? layout->L.codomain_rank() : -1; }
+int64_t lc_slayout_size(const lc_slayout_t* layout) { return layout ? layout->L.size() : -1; }
+lc_status_t lc_slayout_eval(const lc_slayout_t* layout, int64_t integral_coord, int64_t* out, int cap) {
+  if (!layout || !out || cap < layout->L.codomain_rank()) return LC_ERR_INVALID_ARG;
+  layout->L.eval(integral_coord, out);
+  return LC_OK;
+}
+lc_status_t lc_slayout_composition(const lc_slayout_t* a, const lc_layout_t* b, lc_slayout_t** out) {
+  if (!a || !b || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::SemiLayout r;
+    lc_status_t st = lc::composition(a->L, b->L, &r);
+    if (st != LC_OK) return st;
+    *out = new lc_slayout_t{r};
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+lc_status_t lc_slayout_coalesce(const lc_slayout_t* a, lc_slayout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  try {
+    *out = new lc_slayout_t{lc::coalesce(a->L)};
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+lc_status_t lc_slayout_right_inverse(const lc_slayout_t* a, lc_layout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::Layout r;
+    lc_status_t st = lc::right_inverse(a->L, &r);
+    if (st != LC_OK) return st;
+    return give(r, out);
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
 }
 
 }  // extern "C"

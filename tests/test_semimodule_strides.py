@@ -1,0 +1,242 @@
+"""Layouts with integer-semimodule strides (Sec. 2.3.2): coordinate layouts (strides a*e_i) and XOR
+layouts (strides f_d).  The oracle is pinned to what the paper prints (tests/golden/semimodule_layouts.txt)
+and to the definition by brute force; the library is compared with the oracle."""
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from conftest import golden_lines
+
+
+def _parse_fixture():
+    lines = golden_lines("semimodule_layouts.txt")
+    mats, comps, rinvs = [], [], []
+    i = 0
+    while i < len(lines):
+        ln = lines[i]
+        if ln.startswith("matrix "):
+            text = ln[len("matrix "):].split("|")[0].strip()
+            rows = [lines[i + 1 + r].split() for r in range(4)]
+            mats.append((text, rows))
+            i += 5
+        elif ln.startswith("composition "):
+            a, b, r, _ = [x.strip() for x in ln[len("composition "):].split("|")]
+            comps.append((a, b, r))
+            i += 1
+        elif ln.startswith("right_inverse "):
+            a, r, _ = [x.strip() for x in ln[len("right_inverse "):].split("|")]
+            rinvs.append((a, r))
+            i += 1
+        else:
+            raise AssertionError(ln)
+    return mats, comps, rinvs
+
+
+def _value(text):
+    return tuple(int(x) for x in text.split(",")) if "," in text else int(text)
+
+
+@pytest.mark.parametrize("side", ["oracle", "library"])
+def test_printed_layouts(oracle, side):
+    S = oracle.SLayout if side == "oracle" else lc.SLayout
+    compose = oracle.slayout_composition if side == "oracle" else lc.lc_slayout_composition
+    rinv = oracle.slayout_right_inverse if side == "oracle" else lc.lc_slayout_right_inverse
+    mats, comps, rinvs = _parse_fixture()
+    assert len(mats) == 3 and len(comps) == 2 and len(rinvs) == 2
+    for text, rows in mats:
+        L = S(text)
+        assert str(L) == text
+        ncol = len(rows[0])
+        for m in range(4):
+            for n in range(ncol):
+                assert L(m + 4 * n) == _value(rows[m][n]), (text, m, n)     # the matrices are 4 x N, column-major coordinates
+    for a, b, r in comps:
+        assert str(compose(a, b)) == r, (a, b)
+    for a, r in rinvs:
+        assert str(rinv(a)) == r, a
+
+
+def test_definition_by_brute_force(oracle):
+    # Eq. innerprod in the semimodule, retyped here: digits of the integral coordinate (colexicographic,
+    # Sec. 2.2.2) times the strides, added per axis (e_i) or by XOR (f_d)
+    rng = np.random.default_rng(232)
+    for trial in range(300):
+        n = int(rng.integers(1, 5))
+        ext = [int(rng.integers(1, 6)) for _ in range(n)]
+        kind = ["e", "f", "i"][trial % 3]
+        if kind == "e":
+            strides = [(int(rng.integers(0, 7)), int(rng.integers(0, 3))) for _ in range(n)]
+            text = ",".join(("%de%d" % s) if s[0] else "0" for s in strides)
+        elif kind == "f":
+            strides = [(int(rng.integers(0, 40)), 0) for _ in range(n)]
+            text = ",".join("f%d" % s[0] for s in strides)
+        else:
+            strides = [(int(rng.integers(0, 40)), 0) for _ in range(n)]
+            text = ",".join(str(s[0]) for s in strides)
+        layout = ("(%s):(%s)" % (",".join(map(str, ext)), text)) if n > 1 else "%d:%s" % (ext[0], text)
+        Lo, Ll = oracle.SLayout(layout), lc.SLayout(layout)
+        size = int(np.prod(ext))
+        rank = 1 + max([s[1] for s in strides if s[0]] + [0]) if kind == "e" else 1
+        for i in range(size + 3):
+            digits, q = [], i
+            for k, e in enumerate(ext):
+                digits.append(q if k == n - 1 else q % e)
+                q //= e
+            if kind == "e" and any(s[0] for s in strides):
+                want = [0] * rank
+                for dgt, s in zip(digits, strides):
+                    if s[0]:
+                        want[s[1]] += dgt * s[0]
+                want = tuple(want)
+            elif kind == "f":
+                want = 0
+                for dgt, s in zip(digits, strides):
+                    want ^= dgt * s[0]
+            else:
+                want = sum(dgt * s[0] for dgt, s in zip(digits, strides))
+            assert Lo(i) == want, (layout, i)
+            assert Ll(i) == want, (layout, i)
+
+
+def _random_int_layout(rng):
+    n = int(rng.integers(1, 4))
+    ext = [int(rng.choice([1, 2, 3, 4, 6, 8])) for _ in range(n)]
+    st = [int(rng.choice([0, 1, 2, 3, 4, 6, 8, 12, 16])) for _ in range(n)]
+    return "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, st))) if n > 1 else "%d:%d" % (ext[0], st[0])
+
+
+def test_composition_with_coordinate_strides(oracle):
+    # Z^(*,..,*) is a module, so R(c) = A(B(c)) must hold for every admissible B; library == oracle in print
+    rng = np.random.default_rng(233)
+    done = 0
+    for _ in range(1500):
+        n = int(rng.integers(1, 4))
+        ext = [int(rng.choice([2, 3, 4, 6, 8])) for _ in range(n)]
+        axes = [int(rng.integers(0, 3)) for _ in range(n)]
+        coef = [int(rng.integers(1, 5)) for _ in range(n)]
+        A = "(%s):(%s)" % (",".join(map(str, ext)), ",".join("%de%d" % (c, a) for c, a in zip(coef, axes))) if n > 1 else "%d:%de%d" % (ext[0], coef[0], axes[0])
+        B = _random_int_layout(rng)
+        try:
+            Ro = oracle.slayout_composition(A, B)
+        except oracle.OracleError as e:
+            with pytest.raises(lc.LayoutCopyError) as le:
+                lc.lc_slayout_composition(A, B)
+            assert le.value.status_name == e.status_name, (A, B)
+            continue
+        Rl = lc.lc_slayout_composition(A, B)
+        assert str(Rl) == str(Ro), (A, B)
+        Ao, Bo = oracle.SLayout(A), oracle.Layout(B)
+        if Bo.cosize > int(np.prod(ext)):
+            continue                      # B reaches past A's domain: only the shapes were compared
+        rank = max(len(Ao(0)), 1)
+        for c in range(Bo.size):
+            got, want = Ro(c), Ao(Bo(c))
+            got = got if isinstance(got, tuple) else (got,)
+            got = got + (0,) * (rank - len(got))
+            assert got == want, (A, B, c)
+        done += 1
+    assert done > 300, done
+
+
+def test_right_inverse_of_coordinate_layouts(oracle):
+    rng = np.random.default_rng(234)
+    checked = 0
+    for _ in range(400):
+        n = int(rng.integers(1, 5))
+        ext = [int(rng.choice([1, 2, 3, 4, 5])) for _ in range(n)]
+        axes = [int(rng.integers(0, 2)) for _ in range(n)]
+        coef = [int(rng.choice([0, 1, 1, 2, 3, 4, 6])) for _ in range(n)]
+        A = "(%s):(%s)" % (",".join(map(str, ext)), ",".join(("%de%d" % (c, a)) if c else "0" for c, a in zip(coef, axes))) if n > 1 else \
+            "%d:%s" % (ext[0], ("%de%d" % (coef[0], axes[0])) if coef[0] else "0")
+        Ao = oracle.SLayout(A)
+        if Ao.kind != "coord":
+            continue
+        Ro, Rl = oracle.slayout_right_inverse(A), lc.lc_slayout_right_inverse(A)
+        assert str(Ro) == str(Rl), A
+        rank = len(Ao(0))
+        # A(R(c)) = c for every coordinate c of R's domain: R has one top-level mode per axis, so the
+        # integral coordinate i of R splits colexicographically into the per-axis coordinates
+        import re
+        shape = str(Ro).split(":")[0]
+        if rank == 1:
+            sizes = [int(np.prod([int(x) for x in re.findall(r"\d+", shape)]))]
+        else:
+            depth, parts, cur = 0, [], ""
+            for ch in shape[1:-1]:
+                if ch == "," and depth == 0:
+                    parts.append(cur)
+                    cur = ""
+                    continue
+                depth += ch == "("
+                depth -= ch == ")"
+                cur += ch
+            parts.append(cur)
+            sizes = [int(np.prod([int(x) for x in re.findall(r"\d+", part)])) for part in parts]
+        assert len(sizes) == rank, (A, str(Ro))
+        R = oracle.Layout(str(Ro))
+        assert R.size == int(np.prod(sizes))
+        for i in range(R.size):
+            crd, q = [], i
+            for sz in sizes:
+                crd.append(q % sz)
+                q //= sz
+            assert Ao(R(i)) == tuple(crd), (A, str(Ro), i)
+        # and the box is as large as it can be along every axis: one more step is not in the image, or not invertible there
+        checked += 1
+    assert checked > 200, checked
+
+
+def test_coalesce_keeps_the_function(oracle):
+    rng = np.random.default_rng(235)
+    for trial in range(400):
+        n = int(rng.integers(1, 5))
+        ext = [int(rng.choice([1, 2, 2, 3, 4])) for _ in range(n)]
+        if trial % 2:
+            st = ["f%d" % int(rng.choice([0, 1, 2, 4, 5, 8, 16])) for _ in range(n)]
+        else:
+            ax = int(rng.integers(0, 2))
+            st, run = [], 1
+            for e in ext:
+                r = rng.random()
+                st.append("%de%d" % (run, ax) if r < 0.6 else ("%de%d" % (int(rng.integers(1, 9)), int(rng.integers(0, 2))) if r < 0.9 else "0"))
+                run *= e
+        A = "(%s):(%s)" % (",".join(map(str, ext)), ",".join(st)) if n > 1 else "%d:%s" % (ext[0], st[0])
+        Ao = oracle.SLayout(A)
+        Co, Cl = oracle.slayout_coalesce(A), lc.lc_slayout_coalesce(A)
+        assert str(Co) == str(Cl), A
+        for i in range(Ao.size):
+            a, c = Ao(i), Co(i)
+            a = a if isinstance(a, tuple) else (a,)
+            c = c if isinstance(c, tuple) else (c,)
+            m = max(len(a), len(c))
+            assert a + (0,) * (m - len(a)) == c + (0,) * (m - len(c)), (A, i)
+
+
+def test_lds_swizzle_is_an_xor_layout(oracle):
+    # The transposing kernels park vector g at LDS slot g ^ ((g >> s) & 15).  In the paper's terms that is a
+    # layout over the bits of g with XOR strides: bit b carries f_(2^b), and the four bits s..s+3 also flip
+    # the bit s below them: f_(2^b + 2^(b-s)).
+    for s_ in range(4, 11):
+        bits = 14
+        strides = []
+        for b in range(bits):
+            d = (1 << b) | ((1 << (b - s_)) if s_ <= b < s_ + 4 else 0)
+            strides.append("f%d" % d)
+        text = "(%s):(%s)" % (",".join(["2"] * bits), ",".join(strides))
+        for S in (oracle.SLayout, lc.SLayout):
+            L = S(text)
+            for g in list(range(0, 4096)) + [8191, 12345, 16383]:
+                assert L(g) == g ^ ((g >> s_) & 15), (s_, g)
+
+
+def test_errors():
+    for bad, status in [("(4,8):(e0)", "NOT_CONGRUENT"), ("(4,8):(e0,f1)", "INVALID_ARG"), ("(4,8):(e0,x)", "PARSE"),
+                        ("(4,0):(e0,e1)", "BAD_EXTENT"), ("4:e99", "PARSE")]:
+        with pytest.raises(lc.LayoutCopyError) as e:
+            lc.SLayout(bad)
+        assert e.value.status_name == status, bad
+    with pytest.raises(lc.LayoutCopyError):
+        lc.lc_slayout_right_inverse("(8,8):(f1,f9)")
+    with pytest.raises(lc.LayoutCopyError) as e:
+        lc.lc_slayout_composition("(8,8):(e0,e1)", "(4,3):(3,1)")     # stride 3 does not divide into the modes of (8,8)
+    assert e.value.status_name in ("STRIDE_DIVISIBILITY", "SHAPE_DIVISIBILITY")
