@@ -5,6 +5,7 @@
 
 #include "layout_oracle.hpp"
 #include "semimodule_oracle.hpp"
+#include "gemm_oracle.hpp"
 
 using oracle::Layout;
 
@@ -212,6 +213,18 @@ int oracle_slayout_right_inverse(const oracle::SLayout* a, Layout** out) {
   if (st != oracle::OK) return st;
   *out = new Layout(r);
   return oracle::OK;
+}
+
+// ---- GEMM (Sec. 2.6.2) ----
+int oracle_gemm_check(const Layout* a, const Layout* b, const Layout* c, int64_t* M, int64_t* N, int64_t* K) {
+  return oracle::gemm_check(*a, *b, *c, M, N, K);
+}
+int oracle_gemm(const double* A, const Layout* la, const double* B, const Layout* lb, double* C, const Layout* lc) {
+  return oracle::gemm(A, *la, B, *lb, C, *lc);
+}
+int oracle_gemm_at(const double* A, const Layout* la, const double* B, const Layout* lb, const double* C, const Layout* lc,
+                   const int64_t* ms, const int64_t* ns, int64_t count, double* out) {
+  return oracle::gemm_at(A, *la, B, *lb, C, *lc, ms, ns, count, out);
 }
 
 }  // extern "C"

@@ -10,7 +10,7 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liboracle.so")
-_SOURCES = ["layout_oracle.cpp", "semimodule_oracle.cpp", "oracle_capi.cpp"]
+_SOURCES = ["layout_oracle.cpp", "semimodule_oracle.cpp", "gemm_oracle.cpp", "oracle_capi.cpp"]
 
 STATUS_NAMES = {
     0: "OK", 1: "INVALID_ARG", 2: "PARSE", 3: "NOT_CONGRUENT", 4: "BAD_EXTENT", 5: "NEGATIVE_STRIDE",
@@ -29,7 +29,7 @@ class OracleError(Exception):
 def build(force=False):
     """Compile the oracle (g++, host only)."""
     srcs = [os.path.join(_HERE, s) for s in _SOURCES]
-    hdrs = [os.path.join(_HERE, h) for h in ("layout_oracle.hpp", "semimodule_oracle.hpp")]
+    hdrs = [os.path.join(_HERE, h) for h in ("layout_oracle.hpp", "semimodule_oracle.hpp", "gemm_oracle.hpp")]
     if not force and os.path.exists(_LIB_PATH):
         newest = max(os.path.getmtime(p) for p in srcs + hdrs)
         if os.path.getmtime(_LIB_PATH) >= newest:
@@ -95,6 +95,9 @@ def lib():
         L.oracle_slayout_right_inverse.argtypes = [P, PP]
         L.oracle_copy.argtypes = [P, P, P, P, ctypes.c_int]
         L.oracle_copy_range.argtypes = [P, P, P, P, ctypes.c_int, i64, i64]
+        L.oracle_gemm_check.argtypes = [P, P, P, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.oracle_gemm.argtypes = [P, P, P, P, P, P]
+        L.oracle_gemm_at.argtypes = [P, P, P, P, P, P, P, P, i64, P]
         _lib = L
     return _lib
 
@@ -339,3 +342,41 @@ def copy(src, src_layout, dst, dst_layout, begin=0, end=None, spans_checked=Fals
                                      dl._h, src.dtype.itemsize, begin, end)
     _check(st, "copy")
     return dst
+
+
+def gemm_sizes(a_layout, b_layout, c_layout):
+    """(M, N, K) when the three layouts meet the preconditions of the generic GEMM, else OracleError."""
+    la, lb, lc = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+    M, N, K = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().oracle_gemm_check(la._h, lb._h, lc._h, ctypes.byref(M), ctypes.byref(N), ctypes.byref(K)), "gemm_check")
+    return M.value, N.value, K.value
+
+
+def _f64(x, layout, what):
+    import numpy as np
+    assert x.dtype == np.float64 and x.flags.c_contiguous and x.ndim == 1, what + ": 1-D float64 buffer expected"
+    assert layout.cosize <= x.size, what + ": buffer smaller than the layout's cosize"
+    return x.ctypes.data_as(ctypes.c_void_p)
+
+
+def gemm(A, a_layout, B, b_layout, C, c_layout):
+    """C(m,n) += A(m,k) * B(n,k) over float64 numpy buffers, k outermost, in place; returns C."""
+    la, lb, lc = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+    st = lib().oracle_gemm(_f64(A, la, "A"), la._h, _f64(B, lb, "B"), lb._h, _f64(C, lc, "C"), lc._h)
+    _check(st, "gemm")
+    return C
+
+
+def gemm_at(A, a_layout, B, b_layout, C, c_layout, ms, ns):
+    """The value the generic GEMM leaves in C(m_j, n_j) for the listed coordinates (C itself untouched)."""
+    import numpy as np
+    la, lb, lc = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+    ms = np.ascontiguousarray(ms, dtype=np.int64)
+    ns = np.ascontiguousarray(ns, dtype=np.int64)
+    assert ms.shape == ns.shape and ms.ndim == 1
+    out = np.zeros(ms.size, dtype=np.float64)
+    st = lib().oracle_gemm_at(_f64(A, la, "A"), la._h, _f64(B, lb, "B"), lb._h, _f64(C, lc, "C"), lc._h,
+                              ms.ctypes.data_as(ctypes.c_void_p), ns.ctypes.data_as(ctypes.c_void_p), ms.size,
+                              out.ctypes.data_as(ctypes.c_void_p))
+    _check(st, "gemm_at")
+    return out
