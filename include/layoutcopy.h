@@ -32,6 +32,7 @@ extern "C" {
 typedef struct lc_layout lc_layout_t; /* opaque: a layout S:D */
 typedef struct lc_plan lc_plan_t;     /* opaque: a planned copy between two layouts */
 typedef struct lc_slayout lc_slayout_t; /* opaque: a layout whose strides come from an integer-semimodule (Sec. 2.3.2) */
+typedef struct lc_gemm_plan lc_gemm_plan_t; /* opaque: a planned GEMM over three layouts */
 
 typedef enum {
   LC_OK = 0,
@@ -210,6 +211,46 @@ int64_t lc_plan_algorithmic_bytes(const lc_plan_t* plan);
  * device pointers used round-robin, so that successive executions touch different memory. */
 lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers,
                          int warmup, int iters, void* hip_stream, float* ms_per_iter);
+
+/* ---------------------------------------------------------------------------------------------
+ * GEMM (Sec. 2.6.2): C(m,n) += A(m,k) * B(n,k) for every m < M, n < N, k < K, executed on the GPU's
+ * matrix cores.  Each tensor is a device pointer and a layout of rank 2 whose modes may be multi-modes
+ * (Table gemm: BLAS N/T variants, BLIS strides, GETT foldings, im2col views):
+ *     A over (M,K), B over (N,K), C over (M,N)
+ * with M = size<0>(A) = size<0>(C), N = size<0>(B) = size<1>(C), K = size<1>(A) = size<1>(B) (the
+ * preconditions of Sec. 2.6.2; SIZE_MISMATCH otherwise, INVALID_ARG for a layout that is not rank 2).
+ * A and B hold bf16 or fp16 elements (`ab_dtype` = LC_BF16 / LC_F16, the same for both), C holds fp32;
+ * products are exact and sums are accumulated in fp32, in an order that differs from the loop nest's
+ * (the result is within K * 2^-23 * sum_k |A(m,k) B(n,k)| of the exactly accumulated value).
+ * Strides count elements of the respective tensor.  The caller guarantees cosize(layout) elements
+ * behind each pointer; A and B may alias each other, C may alias neither.
+ * The planner coalesces every mode (Sec. 3.2), loads an operand with 16-byte vectors along whichever
+ * of its modes leads with a contiguous run of 8 elements (along k: straight into LDS; along m / n:
+ * through a register transpose), element by element otherwise, and exchanges the roles of A and B
+ * when C is contiguous along n rather than m.  Errors: DST_ALIASES (two coordinates of C share an
+ * offset), UNSUPPORTED_DTYPE, TOO_LARGE (a cosize or extent of 2^31 or more, more than 4 leaves left
+ * in a coalesced mode), MISALIGNED (execute: a pointer less aligned than the plan was created for), HIP.
+ * ------------------------------------------------------------------------------------------- */
+lc_status_t lc_gemm_plan_create(const lc_layout_t* a, const lc_layout_t* b, const lc_layout_t* c, lc_dtype_t ab_dtype,
+                                unsigned a_align_bytes, unsigned b_align_bytes, unsigned c_align_bytes, lc_gemm_plan_t** out);
+/* One line: tile, grid, how each operand is loaded, the coalesced modes. */
+lc_status_t lc_gemm_plan_describe(const lc_gemm_plan_t* plan, char* buf, size_t cap, size_t* needed);
+/* Enqueue on `hip_stream`; asynchronous; a, b, c are device pointers. */
+lc_status_t lc_gemm_plan_execute(const lc_gemm_plan_t* plan, const void* a, const void* b, void* c, void* hip_stream);
+void lc_gemm_plan_destroy(lc_gemm_plan_t* plan);
+/* lc_gemm_plan_create (alignment taken from the pointers) + lc_gemm_plan_execute. */
+lc_status_t lc_gemm(const void* a, const lc_layout_t* a_layout, const void* b, const lc_layout_t* b_layout, void* c,
+                    const lc_layout_t* c_layout, lc_dtype_t ab_dtype, void* hip_stream);
+int64_t lc_gemm_plan_flops(const lc_gemm_plan_t* plan); /* 2 M N K */
+/* Mean milliseconds of `iters` back-to-back executions after `warmup` untimed ones, by HIP events on
+ * `hip_stream`; synchronises the stream.  C accumulates across the executions. */
+lc_status_t lc_gemm_plan_time(const lc_gemm_plan_t* plan, const void* a, const void* b, void* c, int warmup, int iters,
+                              void* hip_stream, float* ms_per_iter);
+/* Thread-value layouts (Sec. 3.3.4, Table TVLayoutExamples) of the fragments of the matrix instruction the
+ * GEMM kernel uses, v_mfma_f32_32x32x16 (bf16 / f16): (lane, value) -> integral coordinate in the fragment's
+ * tile, column-major.  which = 0: A, (64,8) -> m + 32 k of the (32,16) tile; 1: B, (64,8) -> n + 32 k;
+ * 2: C, (64,16) -> m + 32 n of the (32,32) tile. */
+lc_status_t lc_mfma_fragment_layout(int which, lc_layout_t** out);
 
 #ifdef __cplusplus
 }

@@ -87,6 +87,18 @@ def lib():
     L.lc_plan_algorithmic_bytes.restype = i64
     L.lc_plan_time.argtypes = [P, PP, PP, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
     L.lc_debug_replay_on_host.argtypes = [P, P, i64, P, i64, ctypes.POINTER(i64)]
+    u = ctypes.c_uint
+    L.lc_gemm_plan_create.argtypes = [P, P, P, ctypes.c_int, u, u, u, PP]
+    L.lc_gemm_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
+    L.lc_gemm_plan_execute.argtypes = [P, P, P, P, P]
+    L.lc_gemm_plan_destroy.argtypes = [P]
+    L.lc_gemm_plan_destroy.restype = None
+    L.lc_gemm.argtypes = [P, P, P, P, P, P, ctypes.c_int, P]
+    L.lc_gemm_plan_flops.argtypes = [P]
+    L.lc_gemm_plan_flops.restype = i64
+    L.lc_gemm_plan_time.argtypes = [P, P, P, P, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
+    L.lc_mfma_fragment_layout.argtypes = [ctypes.c_int, PP]
+    L.lc_debug_gemm_replay_on_host.argtypes = [P, P, i64, P, i64, P, i64]
     _lib = L
     return L
 
@@ -316,3 +328,75 @@ def copy_tensor(src, src_layout, dst, dst_layout, dtype=None):
     if sl.cosize > src.numel() or dl.cosize > dst.numel():
         raise ValueError("tensor smaller than the layout's cosize")
     lc_copy(src.data_ptr(), sl, dst.data_ptr(), dl, dtype, torch.cuda.current_stream().cuda_stream)
+
+
+class GemmPlan:
+    """lc_gemm_plan_t handle: C(m,n) += A(m,k) * B(n,k) over three rank-2 layouts."""
+
+    def __init__(self, a_layout, b_layout, c_layout, ab_dtype="bf16", a_align=256, b_align=256, c_align=256):
+        self.a_layout, self.b_layout, self.c_layout = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+        self.ab_dtype = ab_dtype
+        self._h = ctypes.c_void_p()
+        _check(lib().lc_gemm_plan_create(self.a_layout._h, self.b_layout._h, self.c_layout._h, DTYPES[ab_dtype], a_align, b_align,
+                                         c_align, ctypes.byref(self._h)),
+               "lc_gemm_plan_create(%s, %s, %s, %s)" % (self.a_layout, self.b_layout, self.c_layout, ab_dtype))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.lc_gemm_plan_destroy(self._h)
+            self._h = None
+
+    def describe(self):
+        need = ctypes.c_size_t()
+        lib().lc_gemm_plan_describe(self._h, None, 0, ctypes.byref(need))
+        buf = ctypes.create_string_buffer(need.value)
+        lib().lc_gemm_plan_describe(self._h, buf, need.value, None)
+        return buf.value.decode()
+
+    @property
+    def flops(self):
+        return lib().lc_gemm_plan_flops(self._h)
+
+    def execute(self, a_ptr, b_ptr, c_ptr, stream=0):
+        """a_ptr / b_ptr / c_ptr: device addresses; stream: hipStream_t as int."""
+        _check(lib().lc_gemm_plan_execute(self._h, a_ptr, b_ptr, c_ptr, stream), "lc_gemm_plan_execute")
+
+    def time(self, a_ptr, b_ptr, c_ptr, warmup, iters, stream=0):
+        ms = ctypes.c_float()
+        _check(lib().lc_gemm_plan_time(self._h, a_ptr, b_ptr, c_ptr, warmup, iters, stream, ctypes.byref(ms)), "lc_gemm_plan_time")
+        return ms.value
+
+    def debug_replay_on_host(self, a, b, c):
+        """Test instrumentation: walk the plan's index arithmetic over numpy arrays on the host (uint16 bit
+        patterns for a and b, float32 c updated in place), every access bounds-checked."""
+        vp = ctypes.c_void_p
+        _check(lib().lc_debug_gemm_replay_on_host(self._h, a.ctypes.data_as(vp), a.size, b.ctypes.data_as(vp), b.size,
+                                                  c.ctypes.data_as(vp), c.size), "lc_debug_gemm_replay_on_host")
+        return c
+
+
+def lc_gemm(a_ptr, a_layout, b_ptr, b_layout, c_ptr, c_layout, ab_dtype="bf16", stream=0):
+    """GEMM on the GPU for device pointers: C(m,n) += A(m,k) * B(n,k)."""
+    la, lb, lc_ = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+    _check(lib().lc_gemm(a_ptr, la._h, b_ptr, lb._h, c_ptr, lc_._h, DTYPES[ab_dtype], stream),
+           "lc_gemm(%s, %s, %s)" % (la, lb, lc_))
+
+
+def lc_mfma_fragment_layout(which):
+    h = ctypes.c_void_p()
+    _check(lib().lc_mfma_fragment_layout(which, ctypes.byref(h)), "lc_mfma_fragment_layout(%d)" % which)
+    return Layout(_handle=h)
+
+
+def gemm_tensor(a, a_layout, b, b_layout, c, c_layout):
+    """Convenience for torch tensors on the GPU (a, b: bfloat16 or float16; c: float32)."""
+    import torch
+    if not (a.is_cuda and b.is_cuda and c.is_cuda):
+        raise RuntimeError("gemm_tensor needs GPU tensors: the GEMM only runs in the HIP kernel")
+    if a.dtype != b.dtype or a.dtype not in (torch.bfloat16, torch.float16) or c.dtype != torch.float32:
+        raise ValueError("a, b: both bfloat16 or both float16; c: float32")
+    la, lb, lc_ = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
+    if la.cosize > a.numel() or lb.cosize > b.numel() or lc_.cosize > c.numel():
+        raise ValueError("tensor smaller than the layout's cosize")
+    lc_gemm(a.data_ptr(), la, b.data_ptr(), lb, c.data_ptr(), lc_, "bf16" if a.dtype == torch.bfloat16 else "f16",
+            torch.cuda.current_stream().cuda_stream)

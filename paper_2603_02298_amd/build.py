@@ -1,29 +1,50 @@
-"""Builds liblayoutcopy.so (host algebra + planner + gfx950 kernels) in-tree with hipcc."""
+"""Builds liblayoutcopy.so (host algebra + planners + gfx950 kernels) in-tree with hipcc."""
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "liblayoutcopy.so")
-SOURCES = ["layout.cpp", "algebra.cpp", "semimodule.cpp", "plan.cpp", "replay.cpp", "capi.cpp", "kernels.hip"]
-HEADERS = ["layout.hpp", "algebra.hpp", "plan.hpp", "kernel_params.hpp"]
+OBJ_DIR = os.path.join(HERE, "_build")
+SOURCES = ["layout.cpp", "algebra.cpp", "semimodule.cpp", "plan.cpp", "replay.cpp", "gemm_plan.cpp", "gemm_replay.cpp", "capi.cpp",
+           "gemm_capi.cpp", "kernels.hip", "gemm_kernels.hip"]
+HEADERS = ["layout.hpp", "algebra.hpp", "semimodule.hpp", "plan.hpp", "kernel_params.hpp", "gemm_plan.hpp", "gemm_params.hpp"]
 
 
-def hipcc_command():
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    return [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-I" + INCLUDE,
+def _hipcc():
+    return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def compile_command(source):
+    return [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
             # packed-FP32 instruction selection is switched off for all device code
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-o", LIB_PATH] + [os.path.join(CSRC, s) for s in SOURCES]
+            "-c", os.path.join(CSRC, source), "-o", os.path.join(OBJ_DIR, source + ".o")]
+
+
+def link_command():
+    return [_hipcc(), "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB_PATH] + [os.path.join(OBJ_DIR, s + ".o") for s in SOURCES]
 
 
 def build(force=True):
-    """Compile the library.  With force=False an up-to-date library is kept."""
-    deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS] + [os.path.join(INCLUDE, "layoutcopy.h")]
-    if not force and os.path.exists(LIB_PATH) and os.path.getmtime(LIB_PATH) >= max(os.path.getmtime(d) for d in deps):
-        return LIB_PATH
-    subprocess.check_call(hipcc_command(), cwd=CSRC)
+    """Compile the library: one object per source (in parallel), then link.  With force=False objects and
+    library that are newer than every source and header are kept."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    common = [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(INCLUDE, "layoutcopy.h")]
+    newest_common = max(os.path.getmtime(d) for d in common)
+    todo = []
+    for s in SOURCES:
+        obj = os.path.join(OBJ_DIR, s + ".o")
+        src_time = max(newest_common, os.path.getmtime(os.path.join(CSRC, s)))
+        if force or not os.path.exists(obj) or os.path.getmtime(obj) < src_time:
+            todo.append(s)
+    if todo:
+        with ThreadPoolExecutor(max_workers=min(8, len(todo))) as pool:
+            list(pool.map(lambda s: subprocess.check_call(compile_command(s), cwd=CSRC), todo))
+    if todo or not os.path.exists(LIB_PATH):
+        subprocess.check_call(link_command(), cwd=CSRC)
     return LIB_PATH
 
 

@@ -1,0 +1,96 @@
+// extern "C" boundary of the generic GEMM (include/layoutcopy.h): argument checks and marshalling only.
+#include <cstring>
+#include <new>
+
+#include "gemm_plan.hpp"
+#include "layoutcopy.h"
+
+namespace {
+lc_status_t put_text(const std::string& s, char* buf, size_t cap, size_t* needed) {
+  if (needed) *needed = s.size() + 1;
+  if (buf && cap > 0) {
+    size_t n = s.size() < cap - 1 ? s.size() : cap - 1;
+    std::memcpy(buf, s.data(), n);
+    buf[n] = 0;
+  }
+  return LC_OK;
+}
+unsigned pointer_alignment(const void* p) {
+  uintptr_t v = reinterpret_cast<uintptr_t>(p);
+  unsigned a = 1;
+  while (a < 256 && (v % (2 * a)) == 0) a *= 2;
+  return a;
+}
+}  // namespace
+
+extern "C" {
+
+lc_status_t lc_gemm_plan_create(const lc_layout_t* a, const lc_layout_t* b, const lc_layout_t* c, lc_dtype_t ab_dtype, unsigned a_align_bytes,
+                                unsigned b_align_bytes, unsigned c_align_bytes, lc_gemm_plan_t** out) {
+  if (!a || !b || !c || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc_gemm_plan* p = new lc_gemm_plan;
+    lc_status_t st = lc::make_gemm_plan(a->L, b->L, c->L, (int)ab_dtype, a_align_bytes, b_align_bytes, c_align_bytes, p);
+    if (st != LC_OK) {
+      delete p;
+      return st;
+    }
+    *out = p;
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+void lc_gemm_plan_destroy(lc_gemm_plan_t* plan) { delete plan; }
+lc_status_t lc_gemm_plan_describe(const lc_gemm_plan_t* plan, char* buf, size_t cap, size_t* needed) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return put_text(lc::describe(*plan), buf, cap, needed);
+}
+int64_t lc_gemm_plan_flops(const lc_gemm_plan_t* plan) { return plan ? 2 * plan->M * plan->N * plan->K : -1; }
+lc_status_t lc_gemm_plan_execute(const lc_gemm_plan_t* plan, const void* a, const void* b, void* c, void* hip_stream) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::execute_gemm_plan(*plan, a, b, c, hip_stream);
+}
+lc_status_t lc_gemm(const void* a, const lc_layout_t* a_layout, const void* b, const lc_layout_t* b_layout, void* c,
+                    const lc_layout_t* c_layout, lc_dtype_t ab_dtype, void* hip_stream) {
+  if (!a || !b || !c || !a_layout || !b_layout || !c_layout) return LC_ERR_INVALID_ARG;
+  try {
+    lc_gemm_plan plan;
+    lc_status_t st = lc::make_gemm_plan(a_layout->L, b_layout->L, c_layout->L, (int)ab_dtype, pointer_alignment(a), pointer_alignment(b),
+                                        pointer_alignment(c), &plan);
+    if (st != LC_OK) return st;
+    return lc::execute_gemm_plan(plan, a, b, c, hip_stream);
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+lc_status_t lc_gemm_plan_time(const lc_gemm_plan_t* plan, const void* a, const void* b, void* c, int warmup, int iters, void* hip_stream,
+                              float* ms_per_iter) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::time_gemm_plan(*plan, a, b, c, warmup, iters, hip_stream, ms_per_iter);
+}
+lc_status_t lc_mfma_fragment_layout(int which, lc_layout_t** out) {
+  if (!out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::Layout L;
+    lc_status_t st = lc::mfma_fragment_layout(which, &L);
+    if (st != LC_OK) return st;
+    *out = new lc_layout_t{L};
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
+// Checking device for tests: walks the plan on HOST buffers (see gemm_plan.hpp).  Not in the public header.
+lc_status_t lc_debug_gemm_replay_on_host(const lc_gemm_plan_t* plan, const uint16_t* a, int64_t a_elems, const uint16_t* b, int64_t b_elems,
+                                         float* c, int64_t c_elems) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  try {
+    return lc::gemm_replay_on_host(*plan, a, a_elems, b, b_elems, c, c_elems);
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
+
+}  // extern "C"

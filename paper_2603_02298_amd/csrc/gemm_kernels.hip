@@ -1,0 +1,286 @@
+// Generic GEMM for gfx950 (CDNA4, wave64): C(m,n) += A(m,k) * B(n,k) (Sec. 2.6.2 of "CuTe Layout
+// Representation and Algebra") for operands described by layouts, on the matrix cores
+// (v_mfma_f32_32x32x16 bf16 / f16, fp32 accumulation).
+//
+// One workgroup of 4 wavefronts owns a BM x BN tile of C; wavefront (wm, wn) owns a (BM/2) x (BN/2)
+// quarter as WMB x WNB fragments of 32 x 32.  Per k tile of 64 the operand tiles pass through LDS,
+// double-buffered: the loads of k tile t+1 are issued before the MFMAs of k tile t and parked after
+// them.  How a tile is loaded depends on which mode of the operand is contiguous (GemmLoad).
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <string>
+
+#include "gemm_plan.hpp"
+#include "plan.hpp"
+
+namespace lc {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+template <bool BF16>
+__device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
+  if constexpr (BF16)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// 8x8 transpose of 16-bit elements held as 8 vectors of 8: out[i] element j = in[j] element i
+__device__ __forceinline__ void transpose_8x8_b16(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t lo = in[2 * d][i / 2], hi = in[2 * d + 1][i / 2];
+      out[i][d] = (i % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
+    }
+}
+
+// One operand (A or B) of one workgroup: issues the global loads of a k tile into registers, parks them in LDS.
+template <int BR>
+struct OperandLoader {
+  static constexpr int ROWS = BR / 32;   // rows per lane for k-vector / element loads
+  const uint16_t* base;
+  int32_t load;
+  uint32_t K, kv, row_in_tile;           // row_in_tile: first row of the lane (block row for row-vector loads)
+  uint32_t rowoff[ROWS];
+  bool active;
+  u32x4 regs[8];
+
+  __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, int32_t ld, uint32_t row0,
+                                       uint32_t extent, uint32_t Ktot, uint32_t tid) {
+    base = p;
+    load = ld;
+    K = Ktot;
+    kv = tid & 7u;
+    row_in_tile = gemm_lane_row(ld, tid, 0);
+    active = ld != kLoadRVec || tid < (uint32_t)BR;
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+      const uint32_t row = row0 + gemm_lane_row(ld, tid, (uint32_t)i);
+      rowoff[i] = (ld != kLoadRVec || i == 0) ? gemm_mode_eval(rmode, gemm_clamp_row(ld, row, extent)) : 0u;
+    }
+  }
+
+  __device__ __forceinline__ void fetch(uint32_t kt, const GemmMode& kmode) {
+    const uint32_t k0 = kt * kGemmBK + kv * 8u;
+    if (load == kLoadKVec) {
+      const bool in = k0 < K;
+      const uint32_t koff = gemm_mode_eval(kmode, in ? k0 : 0u);
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) {
+        regs[i] = u32x4{0u, 0u, 0u, 0u};
+        if (in) regs[i] = *reinterpret_cast<const u32x4*>(base + rowoff[i] + koff);
+      }
+    } else if (load == kLoadRVec) {
+      const bool in = active && k0 < K;
+      const uint32_t koff = gemm_mode_eval(kmode, in ? k0 : 0u);
+      const uint32_t kstep = kmode.stride[0];   // k0 .. k0 + 7 stay inside the leading leaf of the k mode
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        regs[j] = u32x4{0u, 0u, 0u, 0u};
+        if (in) regs[j] = *reinterpret_cast<const u32x4*>(base + rowoff[0] + koff + (uint32_t)j * kstep);
+      }
+    } else {
+      uint32_t koff[8];
+      bool in[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        in[j] = k0 + (uint32_t)j < K;
+        koff[j] = gemm_mode_eval(kmode, in[j] ? k0 + (uint32_t)j : 0u);
+      }
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) {
+        uint32_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = in[j] ? (uint32_t)base[rowoff[i] + koff[j]] : 0u;
+        regs[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+      }
+    }
+  }
+
+  __device__ __forceinline__ void park(unsigned char* tile) {
+    if (load == kLoadRVec) {
+      if (active) {
+        u32x4 t[8];
+        transpose_8x8_b16(regs, t);
+        const uint32_t flip = (row_in_tile >> 3) & 1u;   // neighbouring blocks write rows of opposite parity
+#pragma unroll
+        for (int ii = 0; ii < 8; ++ii) {
+          const uint32_t i = (uint32_t)ii ^ flip;
+          const u32x4 v = flip ? t[ii ^ 1] : t[ii];   // t[i], selected without indexing registers dynamically
+          *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + i, kv)) = v;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i)
+        *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + 32u * (uint32_t)i, kv)) = regs[i];
+    }
+  }
+};
+
+template <bool BF16, int WMB, int WNB>
+__global__ __launch_bounds__(kBlock) void gemm_kernel(GemmParams P, const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                      float* __restrict__ C) {
+  constexpr int BM = 64 * WMB, BN = 64 * WNB;
+  constexpr uint32_t A_BYTES = BM * 128u, STAGE = (BM + BN) * 128u;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+  const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+  const uint32_t wm = wave & 1u, wn = wave >> 1;
+  uint32_t tm, tn;
+  gemm_tile_of_order(P, gemm_tile_order_of_block(blockIdx.x, P.tiles_m * P.tiles_n), &tm, &tn);
+  const uint32_t m0 = tm * BM, n0 = tn * BN;
+
+  OperandLoader<BM> la;
+  OperandLoader<BN> lb;
+  la.init(A, P.a_r, P.a_load, m0, P.M, P.K, tid);
+  lb.init(B, P.b_r, P.b_load, n0, P.N, P.K, tid);
+
+  f32x16 acc[WMB][WNB];
+#pragma unroll
+  for (int i = 0; i < WMB; ++i)
+#pragma unroll
+    for (int j = 0; j < WNB; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  la.fetch(0, P.a_k);
+  lb.fetch(0, P.b_k);
+  la.park(lds);
+  lb.park(lds + A_BYTES);
+  __syncthreads();
+
+  const uint32_t a_row = wm * (WMB * 32u) + mfma_ab_row(lane), b_row = wn * (WNB * 32u) + mfma_ab_row(lane);
+  for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
+    unsigned char* cur = lds + (kt & 1u) * STAGE;
+    unsigned char* nxt = lds + ((kt & 1u) ^ 1u) * STAGE;
+    const bool more = kt + 1 < P.k_tiles;
+    if (more) {
+      la.fetch(kt + 1, P.a_k);
+      lb.fetch(kt + 1, P.b_k);
+    }
+#pragma unroll
+    for (int kk = 0; kk < kGemmBK / 16; ++kk) {
+      u32x4 af[WMB], bf[WNB];
+      const uint32_t kvec = 2u * (uint32_t)kk + mfma_ab_kvec(lane);
+#pragma unroll
+      for (int i = 0; i < WMB; ++i) af[i] = *reinterpret_cast<const u32x4*>(cur + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec));
+#pragma unroll
+      for (int j = 0; j < WNB; ++j) bf[j] = *reinterpret_cast<const u32x4*>(cur + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec));
+#pragma unroll
+      for (int i = 0; i < WMB; ++i)
+#pragma unroll
+        for (int j = 0; j < WNB; ++j) acc[i][j] = mfma_32x32x16<BF16>(af[i], bf[j], acc[i][j]);
+    }
+    if (more) {
+      la.park(nxt);
+      lb.park(nxt + A_BYTES);
+    }
+    __syncthreads();
+  }
+
+  // C(m,n) += acc: lane holds column n = lane % 32 of each fragment and 4 groups of 4 consecutive rows
+#pragma unroll
+  for (int j = 0; j < WNB; ++j) {
+    const uint32_t n = n0 + wn * (WNB * 32u) + 32u * (uint32_t)j + mfma_c_col(lane);
+    if (n >= P.N) continue;
+    const uint32_t noff = gemm_mode_eval(P.c_n, n);
+#pragma unroll
+    for (int i = 0; i < WMB; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
+        if (P.c_vec) {
+          if (m < P.M) {
+            f32x4* p = reinterpret_cast<f32x4*>(C + gemm_mode_eval(P.c_m, m) + noff);
+            f32x4 c = *p;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) c[v] += acc[i][j][4 * g + v];
+            *p = c;
+          }
+        } else {
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (m + (uint32_t)v < P.M) C[gemm_mode_eval(P.c_m, m + (uint32_t)v) + noff] += acc[i][j][4 * g + v];
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------------
+static bool gemm_hip_failed(hipError_t e, const char* what) {
+  if (e == hipSuccess) return false;
+  set_last_hip_error(std::string(what) + ": " + hipGetErrorName(e) + " (" + hipGetErrorString(e) + ")");
+  return true;
+}
+
+template <bool BF16, int WB>
+static hipError_t launch_gemm(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
+  if (plan.lds_bytes > 64 * 1024) {
+    static std::atomic<bool> raised{false};
+    if (!raised.load(std::memory_order_acquire)) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BF16, WB, WB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         160 * 1024);
+      if (e != hipSuccess) return e;
+      raised.store(true, std::memory_order_release);
+    }
+  }
+  const unsigned grid = plan.params.tiles_m * plan.params.tiles_n;
+  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
+  return hipSuccess;
+}
+
+lc_status_t execute_gemm_plan(const lc_gemm_plan& plan, const void* a, const void* b, void* c, void* stream) {
+  if (!a || !b || !c) return LC_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(a) % plan.a_align || reinterpret_cast<uintptr_t>(b) % plan.b_align ||
+      reinterpret_cast<uintptr_t>(c) % plan.c_align)
+    return LC_ERR_MISALIGNED;
+  // the kernel's A is the operand whose rows run along the kernel's m
+  const uint16_t* ka = static_cast<const uint16_t*>(plan.exchanged ? b : a);
+  const uint16_t* kb = static_cast<const uint16_t*>(plan.exchanged ? a : b);
+  float* kc = static_cast<float*>(c);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  hipError_t pre;
+  const bool bf16 = plan.ab_dtype == LC_BF16;
+  if (plan.tile_m == 256 && plan.tile_n == 256 && plan.lds_bytes == 2u * 512u * 128u)
+    pre = bf16 ? launch_gemm<true, 4>(plan, ka, kb, kc, s) : launch_gemm<false, 4>(plan, ka, kb, kc, s);
+  else if (plan.tile_m == 128 && plan.tile_n == 128 && plan.lds_bytes == 2u * 256u * 128u)
+    pre = bf16 ? launch_gemm<true, 2>(plan, ka, kb, kc, s) : launch_gemm<false, 2>(plan, ka, kb, kc, s);
+  else
+    return LC_ERR_INVALID_ARG;
+  if (gemm_hip_failed(pre, "hipFuncSetAttribute") || gemm_hip_failed(hipGetLastError(), "kernel launch")) return LC_ERR_HIP;
+  return LC_OK;
+}
+
+lc_status_t time_gemm_plan(const lc_gemm_plan& plan, const void* a, const void* b, void* c, int warmup, int iters, void* stream,
+                           float* ms_per_iter) {
+  if (iters < 1 || warmup < 0 || !ms_per_iter) return LC_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  if (gemm_hip_failed(hipEventCreate(&e0), "hipEventCreate")) return LC_ERR_HIP;
+  if (gemm_hip_failed(hipEventCreate(&e1), "hipEventCreate")) { (void)hipEventDestroy(e0); return LC_ERR_HIP; }
+  lc_status_t st = LC_OK;
+  for (int i = 0; i < warmup && st == LC_OK; ++i) st = execute_gemm_plan(plan, a, b, c, stream);
+  if (st == LC_OK && gemm_hip_failed(hipEventRecord(e0, s), "hipEventRecord")) st = LC_ERR_HIP;
+  for (int i = 0; i < iters && st == LC_OK; ++i) st = execute_gemm_plan(plan, a, b, c, stream);
+  if (st == LC_OK && gemm_hip_failed(hipEventRecord(e1, s), "hipEventRecord")) st = LC_ERR_HIP;
+  if (st == LC_OK && gemm_hip_failed(hipEventSynchronize(e1), "hipEventSynchronize")) st = LC_ERR_HIP;
+  float ms = 0.f;
+  if (st == LC_OK && gemm_hip_failed(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime")) st = LC_ERR_HIP;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (st == LC_OK) *ms_per_iter = ms / (float)iters;
+  return st;
+}
+
+}  // namespace lc

@@ -1,0 +1,105 @@
+// Kernel arguments and index arithmetic of the generic GEMM (Sec. 2.6.2 of "CuTe Layout Representation
+// and Algebra"): C(m,n) += A(m,k) * B(n,k) for tensors given by rank-2 layouts.  A rank-2 layout is
+// the sum of the layout functions of its two modes, L(r,k) = L_0(r) + L_1(k) (Eq. innerprod over the
+// concatenation, Eq. concat), so each operand travels as two coalesced modes.  The functions here are
+// shared by the device kernel and by the host walk that checks a plan's addresses without a GPU.
+#pragma once
+#include "kernel_params.hpp"
+
+namespace lc {
+
+constexpr int kGemmMaxLeaves = 4;   // leaves of one coalesced top-level mode
+constexpr int kGemmBK = 64;         // k extent of a tile: 8 vectors of 8 sixteen-bit elements = one 128-byte LDS row
+
+// how an operand tile is brought from global memory into LDS
+enum GemmLoad : int32_t {
+  kLoadKVec = 0,   // 16-byte vectors along k (k-mode leads with a stride-1 leaf): straight into place
+  kLoadRVec = 1,   // 16-byte vectors along the row mode (m or n): 8x8 blocks transposed in registers
+  kLoadElem = 2    // element by element: any layout, any extent
+};
+
+// One coalesced mode: integral coordinate -> offset in elements (all offsets of a GEMM operand fit 31 bits).
+struct GemmMode {
+  int32_t n;
+  FastDiv div[kGemmMaxLeaves];
+  uint32_t stride[kGemmMaxLeaves];
+};
+LC_HD uint32_t gemm_mode_eval(const GemmMode& g, uint32_t i) {
+  uint32_t off = 0;
+#pragma unroll
+  for (int k = 0; k < kGemmMaxLeaves - 1; ++k) {
+    if (k + 1 < g.n) {
+      uint32_t q, r;
+      fd_divmod(i, g.div[k], &q, &r);
+      off += r * g.stride[k];
+      i = q;
+    }
+  }
+  return off + i * g.stride[g.n - 1];
+}
+
+struct GemmParams {
+  GemmMode a_r, a_k, b_r, b_k, c_m, c_n;   // A over (M,K), B over (N,K), C over (M,N)
+  uint32_t M, N, K;
+  uint32_t tiles_m, tiles_n, k_tiles;
+  int32_t a_load, b_load;                  // GemmLoad
+  int32_t c_vec;                           // 1: four consecutive m are contiguous and 16-byte aligned in C
+  uint32_t group_m;                        // tile rows walked together before moving on along n
+};
+
+// ---------------------------------------------------------------------------------------------
+// Workgroup -> tile.  Workgroups are handed to the 8 XCDs round-robin and every XCD has its own L2,
+// so XCD x takes a contiguous stretch of the tile order; the order itself walks group_m tile rows
+// together along n, which keeps the A rows and B rows of concurrently running tiles few.
+// ---------------------------------------------------------------------------------------------
+constexpr uint32_t kXcds = 8;
+LC_HD uint32_t gemm_tile_order_of_block(uint32_t block, uint32_t n_tiles) {
+  const uint32_t xcd = block % kXcds, slot = block / kXcds;
+  const uint32_t base = n_tiles / kXcds, extra = n_tiles % kXcds;
+  return xcd * base + (xcd < extra ? xcd : extra) + slot;
+}
+LC_HD void gemm_tile_of_order(const GemmParams& P, uint32_t t, uint32_t* tm, uint32_t* tn) {
+  const uint32_t width = P.group_m * P.tiles_n;
+  const uint32_t group = t / width, in = t % width;
+  const uint32_t first = group * P.group_m;
+  const uint32_t rows = (P.tiles_m - first) < P.group_m ? (P.tiles_m - first) : P.group_m;
+  *tm = first + in % rows;
+  *tn = in / rows;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Operand tile in LDS: BR rows (m or n) of kGemmBK elements, 128 bytes per row, eight 16-byte
+// vectors per row.  Vector kv of row r sits at slot kv ^ r ^ (r >> 3) (low three bits): this is the
+// XOR layout (Sec. 2.3.2) under which all three access patterns below touch 16 distinct 16-byte
+// bank groups per 16 lanes: fragment reads (16 rows, one kv), k-vector writes (2 rows x 8 kv) and
+// the writes of transposed 8x8 blocks (8 kv x 2 row groups, rows of opposite parity).
+// ---------------------------------------------------------------------------------------------
+LC_HD uint32_t gemm_lds_offset(uint32_t row, uint32_t kv) { return row * 128u + (((kv ^ row ^ (row >> 3)) & 7u) << 4); }
+
+// ---------------------------------------------------------------------------------------------
+// Lane -> what it loads.  256 lanes; kv = lane % 8 is the lane's k vector within the tile.
+//   kLoadKVec / kLoadElem: rows lane / 8 + 32 i, i < BR / 32
+//   kLoadRVec            : the 8x8 block at rows 8 (lane / 8) .. + 7 (lanes < BR only)
+// Rows past the end of the mode are clamped to its last row (last 8-row group for kLoadRVec): the
+// tile then holds a copy of valid data there, which only feeds entries of C that are never stored.
+// k past K reads nothing and parks zeros.
+// ---------------------------------------------------------------------------------------------
+LC_HD uint32_t gemm_lane_row(int32_t load, uint32_t lane, uint32_t i) { return load == kLoadRVec ? (lane >> 3) * 8u : (lane >> 3) + 32u * i; }
+LC_HD uint32_t gemm_clamp_row(int32_t load, uint32_t row, uint32_t extent) {
+  const uint32_t last = load == kLoadRVec ? extent - 8u : extent - 1u;
+  return row < last ? row : last;
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA fragments of v_mfma_f32_32x32x16 (bf16 / f16), as thread-value layouts (Sec. 3.3.4):
+//   A fragment (32 x 16): lane t holds A(t % 32, 8 (t / 32) + v), v < 8   -> ((32,2),8):((1,256),32) on m + 32 k
+//   B fragment (32 x 16): lane t holds B(t % 32, 8 (t / 32) + v)          -> the same on n + 32 k
+//   C fragment (32 x 32): lane t holds C(8 (v / 4) + 4 (t / 32) + v % 4, t % 32), v < 16
+//                                                                          -> ((32,2),(4,4)):((32,4),(1,8)) on m + 32 n
+// ---------------------------------------------------------------------------------------------
+LC_HD uint32_t mfma_ab_row(uint32_t lane) { return lane & 31u; }
+LC_HD uint32_t mfma_ab_kvec(uint32_t lane) { return lane >> 5; }            // which 8-element k vector of the 16
+LC_HD uint32_t mfma_c_row(uint32_t lane, uint32_t v) { return 8u * (v >> 2) + 4u * (lane >> 5) + (v & 3u); }
+LC_HD uint32_t mfma_c_col(uint32_t lane) { return lane & 31u; }
+
+}  // namespace lc

@@ -1,0 +1,182 @@
+// Host walk of a GEMM plan (a checking device for tests, see gemm_plan.hpp): the kernel's loops over
+// workgroups, lanes and k tiles with the same index functions (gemm_params.hpp), every global access
+// checked against the buffers, the operand tiles passed through a byte model of LDS, and the matrix
+// instruction replaced by its definition taken through the fragments' thread-value layouts.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "gemm_plan.hpp"
+
+namespace lc {
+
+namespace {
+
+float bf16_to_float(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+float f16_to_float(uint16_t h) {
+  const int sign = h >> 15, exp = (h >> 10) & 31, man = h & 1023;
+  float v;
+  if (exp == 0) v = std::ldexp((float)man, -24);
+  else if (exp == 31) v = man ? NAN : INFINITY;
+  else v = std::ldexp((float)(man + 1024), exp - 25);
+  return sign ? -v : v;
+}
+
+struct Walker {
+  const lc_gemm_plan& plan;
+  const GemmParams& P;
+  const uint16_t* A;
+  const uint16_t* B;
+  float* C;
+  int64_t a_elems, b_elems, c_elems;
+  bool ok = true;
+
+  // loads one operand tile of k tile kt into the LDS model, lane by lane
+  void stage(const uint16_t* base, int64_t elems, const GemmMode& rmode, const GemmMode& kmode, int32_t load, uint32_t row0, uint32_t extent,
+             uint32_t BR, uint32_t kt, unsigned char* tile) {
+    for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
+      const uint32_t kv = tid & 7u, k0 = kt * kGemmBK + kv * 8u;
+      if (load == kLoadRVec) {
+        if (tid >= BR) continue;
+        const uint32_t block_row = gemm_lane_row(load, tid, 0);
+        uint16_t blk[8][8] = {};   // [k][row]
+        if (k0 < P.K) {
+          const uint32_t rowoff = gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + block_row, extent));
+          const uint32_t koff = gemm_mode_eval(kmode, k0);
+          for (uint32_t j = 0; j < 8; ++j) {
+            const int64_t off = (int64_t)rowoff + koff + (int64_t)j * kmode.stride[0];
+            if (off % 8 != 0 || off + 8 > elems) { ok = false; return; }
+            std::memcpy(blk[j], base + off, 16);
+          }
+        }
+        for (uint32_t i = 0; i < 8; ++i) {
+          uint16_t v[8];
+          for (uint32_t j = 0; j < 8; ++j) v[j] = blk[j][i];
+          std::memcpy(tile + gemm_lds_offset(block_row + i, kv), v, 16);
+        }
+      } else {
+        for (uint32_t i = 0; i < BR / 32; ++i) {
+          const uint32_t row = gemm_lane_row(load, tid, i);
+          const uint32_t rowoff = gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + row, extent));
+          uint16_t v[8] = {};
+          if (load == kLoadKVec) {
+            if (k0 < P.K) {
+              const int64_t off = (int64_t)rowoff + gemm_mode_eval(kmode, k0);
+              if (off % 8 != 0 || off + 8 > elems) { ok = false; return; }
+              std::memcpy(v, base + off, 16);
+            }
+          } else {
+            for (uint32_t j = 0; j < 8; ++j)
+              if (k0 + j < P.K) {
+                const int64_t off = (int64_t)rowoff + gemm_mode_eval(kmode, k0 + j);
+                if (off >= elems) { ok = false; return; }
+                v[j] = base[off];
+              }
+          }
+          std::memcpy(tile + gemm_lds_offset(row, kv), v, 16);
+        }
+      }
+    }
+  }
+};
+
+}  // namespace
+
+lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int64_t a_elems, const uint16_t* b, int64_t b_elems, float* c,
+                                int64_t c_elems) {
+  if (!a || !b || !c) return LC_ERR_INVALID_ARG;
+  if (a_elems < plan.a_cosize || b_elems < plan.b_cosize || c_elems < plan.c_cosize) return LC_ERR_INVALID_ARG;
+  const GemmParams& P = plan.params;
+  Walker w{plan, P, plan.exchanged ? b : a, plan.exchanged ? a : b, c, plan.exchanged ? b_elems : a_elems,
+           plan.exchanged ? a_elems : b_elems, c_elems};
+  const uint32_t BM = (uint32_t)plan.tile_m, BN = (uint32_t)plan.tile_n, WMB = BM / 64, WNB = BN / 64;
+  if (plan.lds_bytes != 2u * (BM + BN) * 128u) return LC_ERR_INVALID_ARG;
+  Layout tv_a, tv_b, tv_c;
+  mfma_fragment_layout(0, &tv_a);
+  mfma_fragment_layout(1, &tv_b);
+  mfma_fragment_layout(2, &tv_c);
+  auto to_float = plan.ab_dtype == LC_BF16 ? bf16_to_float : f16_to_float;
+  std::vector<unsigned char> lds(plan.lds_bytes / 2);   // one stage is enough for a sequential walk
+  std::vector<float> acc((size_t)BM * BN);
+  std::vector<char> covered((size_t)P.tiles_m * P.tiles_n, 0);
+  const uint32_t n_tiles = P.tiles_m * P.tiles_n;
+  for (uint32_t block = 0; block < n_tiles; ++block) {
+    uint32_t tm, tn;
+    const uint32_t order = gemm_tile_order_of_block(block, n_tiles);
+    if (order >= n_tiles) return LC_ERR_INVALID_ARG;
+    gemm_tile_of_order(P, order, &tm, &tn);
+    if (tm >= P.tiles_m || tn >= P.tiles_n || covered[(size_t)tm * P.tiles_n + tn]) return LC_ERR_INVALID_ARG;   // every tile exactly once
+    covered[(size_t)tm * P.tiles_n + tn] = 1;
+    const uint32_t m0 = tm * BM, n0 = tn * BN;
+    std::fill(acc.begin(), acc.end(), 0.f);
+    for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
+      w.stage(w.A, w.a_elems, P.a_r, P.a_k, P.a_load, m0, P.M, BM, kt, lds.data());
+      w.stage(w.B, w.b_elems, P.b_r, P.b_k, P.b_load, n0, P.N, BN, kt, lds.data() + BM * 128u);
+      if (!w.ok) return LC_ERR_INVALID_ARG;
+      for (uint32_t wave = 0; wave < 4; ++wave) {
+        const uint32_t wm = wave & 1u, wn = wave >> 1;
+        for (uint32_t kk = 0; kk < kGemmBK / 16; ++kk)
+          for (uint32_t i = 0; i < WMB; ++i)
+            for (uint32_t j = 0; j < WNB; ++j) {
+              // gather the two 32 x 16 fragments from the lanes' LDS reads, through the thread-value layouts
+              float fa[32][16], fb[32][16];
+              for (uint32_t lane = 0; lane < 64; ++lane) {
+                const uint32_t kvec = 2u * kk + mfma_ab_kvec(lane);
+                uint16_t va[8], vb[8];
+                std::memcpy(va, lds.data() + gemm_lds_offset(wm * WMB * 32u + 32u * i + mfma_ab_row(lane), kvec), 16);
+                std::memcpy(vb, lds.data() + BM * 128u + gemm_lds_offset(wn * WNB * 32u + 32u * j + mfma_ab_row(lane), kvec), 16);
+                for (uint32_t v = 0; v < 8; ++v) {
+                  const int64_t ca = tv_a((int64_t)lane + 64 * v), cb = tv_b((int64_t)lane + 64 * v);   // row + 32 k
+                  fa[ca % 32][ca / 32] = to_float(va[v]);
+                  fb[cb % 32][cb / 32] = to_float(vb[v]);
+                }
+              }
+              // D = A B^T + D, then back to the lanes' accumulators through the C fragment layout
+              for (uint32_t lane = 0; lane < 64; ++lane)
+                for (uint32_t v = 0; v < 16; ++v) {
+                  const int64_t cc = tv_c((int64_t)lane + 64 * v);   // m + 32 n
+                  const uint32_t r = (uint32_t)(cc % 32), col = (uint32_t)(cc / 32);
+                  if (r != mfma_c_row(lane, v) || col != mfma_c_col(lane)) return LC_ERR_INVALID_ARG;
+                  float s = 0.f;
+                  for (uint32_t k = 0; k < 16; ++k) s += fa[r][k] * fb[col][k];
+                  acc[(size_t)(wm * WMB * 32u + 32u * i + r) * BN + (wn * WNB * 32u + 32u * j + col)] += s;
+                }
+            }
+      }
+    }
+    // epilogue, lane by lane
+    for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
+      const uint32_t lane = tid & 63u, wave = tid >> 6, wm = wave & 1u, wn = wave >> 1;
+      for (uint32_t j = 0; j < WNB; ++j) {
+        const uint32_t nl = wn * WNB * 32u + 32u * j + mfma_c_col(lane), n = n0 + nl;
+        if (n >= P.N) continue;
+        const uint32_t noff = gemm_mode_eval(P.c_n, n);
+        for (uint32_t i = 0; i < WMB; ++i)
+          for (uint32_t g = 0; g < 4; ++g) {
+            const uint32_t ml = wm * WMB * 32u + 32u * i + mfma_c_row(lane, 4u * g), m = m0 + ml;
+            if (P.c_vec) {
+              if (m >= P.M) continue;
+              const int64_t off = (int64_t)gemm_mode_eval(P.c_m, m) + noff;
+              if (off % 4 != 0 || off + 4 > c_elems || m + 4 > P.M) return LC_ERR_INVALID_ARG;
+              for (uint32_t v = 0; v < 4; ++v) c[off + v] += acc[(size_t)(ml + v) * BN + nl];
+            } else {
+              for (uint32_t v = 0; v < 4; ++v)
+                if (m + v < P.M) {
+                  const int64_t off = (int64_t)gemm_mode_eval(P.c_m, m + v) + noff;
+                  if (off >= c_elems) return LC_ERR_INVALID_ARG;
+                  c[off] += acc[(size_t)(ml + v) * BN + nl];
+                }
+            }
+          }
+      }
+    }
+  }
+  return LC_OK;
+}
+
+}  // namespace lc

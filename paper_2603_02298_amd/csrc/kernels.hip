@@ -376,6 +376,7 @@ __global__ __launch_bounds__(kBlock) void ragged_transpose_kernel(TransposeParam
 // ---------------------------------------------------------------------------------------------
 static thread_local std::string g_last_hip_error;
 const char* last_hip_error() { return g_last_hip_error.c_str(); }
+void set_last_hip_error(const std::string& text) { g_last_hip_error = text; }
 static bool hip_failed(hipError_t e, const char* what) {
   if (e == hipSuccess) return false;
   g_last_hip_error = std::string(what) + ": " + hipGetErrorName(e) + " (" + hipGetErrorString(e) + ")";

@@ -36,7 +36,7 @@ Tuning tuning_from_env() {
 // a1: is the destination layout injective?  Nested strides prove it; otherwise small layouts are
 // enumerated and large ones are refused.
 // ---------------------------------------------------------------------------------------------
-static bool dst_is_injective(const Modes& coalesced, int64_t n) {
+bool layout_is_injective(const Modes& coalesced, int64_t n) {
   Modes m;
   for (const Mode& x : coalesced) {
     if (x.extent == 1) continue;
@@ -548,7 +548,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
   Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
   // a1: the destination must be injective, otherwise the result would depend on the iteration order
-  if (n > 1 && !dst_is_injective(D, n)) return LC_ERR_DST_ALIASES;
+  if (n > 1 && !layout_is_injective(D, n)) return LC_ERR_DST_ALIASES;
 
   // a5 (the paper's route): K = stride-1 head of src o dst^ (Sec. 3.4.2); kept for reporting and
   // cross-checked against the joint modes below

@@ -73,6 +73,9 @@ namespace lc {
 lc_status_t make_plan(const Layout& src, const Layout& dst, int elem_bytes, unsigned src_align,
                       unsigned dst_align, const Tuning& tune, lc_plan* out);
 std::string describe(const lc_plan& plan);
+// Do distinct coordinates of the (coalesced) layout of size n reach distinct offsets?  Nested strides prove it,
+// small layouts are enumerated, large ones that cannot be proved cheaply count as aliasing.
+bool layout_is_injective(const Modes& coalesced, int64_t n);
 
 // Walks the plan on the host exactly along the kernels' index arithmetic and moves the bytes in
 // host memory.  It exists to prove the routing of a plan (and that every access stays inside the
@@ -82,6 +85,7 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
 
 // Defined with the kernels: enqueue the plan's kernel on a HIP stream / time repeated executions.
 const char* last_hip_error();
+void set_last_hip_error(const std::string& text);
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream);
 lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
                       int iters, void* stream, float* ms_per_iter);

@@ -134,3 +134,77 @@ def source_bits(w, elems=None, chunk=1 << 24):
         else:
             out[lo:hi] = _bf16_bits(x)
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# GEMM workloads: stand-ins shaped like the rows of the paper's table of GEMM applications
+# (Sec. 2.6.2): layouts as text, buffer sizes as plain numbers, seeded values.
+# ---------------------------------------------------------------------------------------------
+class GemmWorkload:
+    def __init__(self, name, ab_dtype, a_layout, b_layout, c_layout, a_elems, b_elems, c_elems, M, N, K, values="normal", note=""):
+        self.name, self.ab_dtype = name, ab_dtype
+        self.a_layout, self.b_layout, self.c_layout = a_layout, b_layout, c_layout
+        self.a_elems, self.b_elems, self.c_elems = a_elems, b_elems, c_elems
+        self.M, self.N, self.K = M, N, K
+        self.values, self.note = values, note
+
+    @property
+    def flops(self):
+        return 2 * self.M * self.N * self.K
+
+
+def gemm_workload(name, M=8192, N=8192, K=8192, ab_dtype="bf16", values="normal"):
+    if name == "tn":      # BLAS TN: both operands contiguous along k; C column-major
+        return GemmWorkload("gemm_tn_" + ab_dtype, ab_dtype, "(%d,%d):(%d,1)" % (M, K, K), "(%d,%d):(%d,1)" % (N, K, K),
+                            "(%d,%d):(1,%d)" % (M, N, M), M * K, N * K, M * N, M, N, K, values, "TN GEMM")
+    if name == "nt":      # BLAS NT: both operands contiguous along m / n
+        return GemmWorkload("gemm_nt_" + ab_dtype, ab_dtype, "(%d,%d):(1,%d)" % (M, K, M), "(%d,%d):(1,%d)" % (N, K, N),
+                            "(%d,%d):(1,%d)" % (M, N, M), M * K, N * K, M * N, M, N, K, values, "NT GEMM")
+    if name == "nn_rowmajor_c":   # A contiguous along m, B along k, C row-major (contiguous along n)
+        return GemmWorkload("gemm_nn_rowc_" + ab_dtype, ab_dtype, "(%d,%d):(1,%d)" % (M, K, M), "(%d,%d):(%d,1)" % (N, K, K),
+                            "(%d,%d):(%d,1)" % (M, N, N), M * K, N * K, M * N, M, N, K, values, "mixed operands, row-major C")
+    if name == "gett":    # GETT: the row mode of A and C is the multi-mode (M1,M2) with a padded second stride
+        M1 = 64
+        M2 = M // M1
+        W, Y = M1 + 8, M1 + 4
+        X, Z = W * M2, Y * M2
+        return GemmWorkload("gemm_gett_" + ab_dtype, ab_dtype, "((%d,%d),%d):((1,%d),%d)" % (M1, M2, K, W, X),
+                            "(%d,%d):(%d,1)" % (N, K, K), "((%d,%d),%d):((1,%d),%d)" % (M1, M2, N, Y, Z),
+                            X * K, N * K, Z * N, M1 * M2, N, K, values, "GETT with a folded, padded row mode")
+    if name == "blis":    # general strides in every mode: no vector on any side
+        dma, dka, dnb, dkb, dmc, dnc = 3, 3 * M + 1, 2 * K + 3, 2, 2, 2 * M + 1
+        return GemmWorkload("gemm_blis_" + ab_dtype, ab_dtype, "(%d,%d):(%d,%d)" % (M, K, dma, dka), "(%d,%d):(%d,%d)" % (N, K, dnb, dkb),
+                            "(%d,%d):(%d,%d)" % (M, N, dmc, dnc), dma * M + dka * K, dnb * N + dkb * K, dmc * M + dnc * N, M, N, K,
+                            values, "BLIS-style general strides")
+    raise KeyError(name)
+
+
+def _f16_bits(x32):
+    return x32.astype(np.float16).view(np.uint16)
+
+
+def gemm_operand_bits(w, which, elems=None):
+    """Seeded bit patterns (uint16) of operand 'a' or 'b'; values N(0,1) or small integers."""
+    elems = (w.a_elems if which == "a" else w.b_elems) if elems is None else elems
+    rng = np.random.default_rng(SEED_BASE + 100 + (0 if which == "a" else 1))
+    if w.values == "normal":
+        x = rng.standard_normal(elems, dtype=np.float32)
+    else:   # integers in [-4, 4]: every product and every partial sum is exact in fp32
+        x = rng.integers(-4, 5, elems).astype(np.float32)
+    return _bf16_bits(x) if w.ab_dtype == "bf16" else _f16_bits(x)
+
+
+def gemm_c_values(w, elems=None):
+    """Seeded initial contents of C (float32)."""
+    elems = w.c_elems if elems is None else elems
+    rng = np.random.default_rng(SEED_BASE + 102)
+    if w.values == "normal":
+        return rng.standard_normal(elems, dtype=np.float32)
+    return rng.integers(-8, 9, elems).astype(np.float32)
+
+
+def bits_to_float64(bits, ab_dtype):
+    """Decode bf16 / f16 bit patterns exactly (both are subsets of float64)."""
+    if ab_dtype == "bf16":
+        return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return bits.view(np.float16).astype(np.float64)

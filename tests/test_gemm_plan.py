@@ -1,0 +1,109 @@
+"""The GEMM planner and the kernel's index arithmetic, checked on the host (no GPU): plans are walked
+with the library's checking device (every global access bounds-checked, tiles through a model of the
+LDS arrangement and of the MFMA fragment layouts) and the result is compared with the oracle."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from paper_2603_02298_amd import workloads as W
+
+
+def _walk_and_compare(oracle, w, env=None, expect=None):
+    env = env or {}
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update({k: str(v) for k, v in env.items()})
+    try:
+        plan = lc.GemmPlan(w.a_layout, w.b_layout, w.c_layout, w.ab_dtype)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                del os.environ[k]
+            else:
+                os.environ[k] = v
+    text = plan.describe()
+    for piece in (expect or []):
+        assert piece in text, (piece, text)
+    a, b, c0 = W.gemm_operand_bits(w, "a"), W.gemm_operand_bits(w, "b"), W.gemm_c_values(w)
+    got = plan.debug_replay_on_host(a, b, c0.copy())
+    want = oracle.gemm(W.bits_to_float64(a, w.ab_dtype), w.a_layout, W.bits_to_float64(b, w.ab_dtype), w.b_layout,
+                       c0.astype(np.float64), w.c_layout)
+    assert (got.astype(np.float64) == want).all(), text     # integer-valued inputs: every sum is exact
+    return text
+
+
+CASES = [
+    # name, (M, N, K), pieces the plan's description must contain
+    ("tn", (200, 136, 96), ["a_load=k-vectors", "b_load=k-vectors", "c_vec=1", "exchanged=0"]),
+    ("nt", (136, 264, 72), ["a_load=row-vectors+transpose", "b_load=row-vectors+transpose", "c_vec=1"]),
+    ("nn_rowmajor_c", (72, 140, 40), ["exchanged=1", "c_vec=1", "a_load=k-vectors", "b_load=row-vectors+transpose"]),
+    ("gett", (192, 100, 48), ["a_load=row-vectors+transpose", "b_load=k-vectors", "c_vec=1"]),
+    ("blis", (70, 45, 37), ["a_load=elements", "b_load=elements", "c_vec=0"]),
+]
+
+
+@pytest.mark.parametrize("name,mnk,expect", CASES)
+@pytest.mark.parametrize("tile", [128, 256])
+def test_walk_matches_oracle(oracle, name, mnk, expect, tile):
+    w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values="ints")
+    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile}, expect + ["tile=%dx%d" % (tile, tile)])
+
+
+def test_walk_f16_and_forced_element_loads(oracle):
+    w = W.gemm_workload("tn", 130, 70, 40, ab_dtype="f16", values="ints")
+    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, ["ab=f16"])
+    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128, "LC_TUNE_GEMM_LOAD": 2, "LC_TUNE_GEMM_CVEC": 0},
+                      ["a_load=elements", "b_load=elements", "c_vec=0"])
+
+
+def test_walk_group_and_xcd_mapping_cover_every_tile_once(oracle):
+    # 3 x 5 tiles of 128: neither a multiple of the group height nor of the 8 XCDs
+    w = W.gemm_workload("tn", 300, 600, 16, ab_dtype="bf16", values="ints")
+    for g in (1, 2, 4):
+        _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128, "LC_TUNE_GEMM_GROUP_M": g}, ["tiles=3x5"])
+
+
+def test_hierarchical_k_and_broadcast_operand(oracle):
+    # GETT row 2 of the table: K folded as (K1,K2) with different leading leaves in A and B; and a
+    # stride-0 row mode in B (every n reads the same row)
+    M, N, K1, K2 = 64, 24, 16, 3
+    w = W.GemmWorkload("gett2", "bf16", "(%d,(%d,%d)):(1,(%d,%d))" % (M, K1, K2, M, M * K1 + 8),
+                       "(%d,(%d,%d)):(%d,(1,%d))" % (N, K1, K2, K1, K1 * N + 16), "(%d,%d):(1,%d)" % (M, N, M),
+                       (M * K1 + 8) * K2, (K1 * N + 16) * K2, M * N, M, N, K1 * K2, "ints")
+    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, ["a_load=row-vectors+transpose", "b_load=k-vectors"])
+    w = W.GemmWorkload("bcast", "bf16", "(40,24):(24,1)", "(16,24):(0,1)", "(40,16):(16,1)", 960, 24, 640, 40, 16, 24, "ints")
+    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, ["exchanged=1"])
+
+
+def test_fragment_layouts_are_the_thread_value_layouts():
+    a, b, c = (lc.lc_mfma_fragment_layout(i) for i in range(3))
+    assert str(a) == "((32,2),8):((1,256),32)" and str(b) == str(a) and str(c) == "((32,2),(4,4)):((32,4),(1,8))"
+    # each is a bijection of (lane, value) onto the fragment's tile
+    assert sorted(a(i) for i in range(512)) == list(range(512))
+    assert sorted(c(i) for i in range(1024)) == list(range(1024))
+    # a lane's values of A are 8 consecutive k of one row; of C, four runs of 4 consecutive rows of one column
+    for lane in (0, 5, 31, 32, 63):
+        ks = [a(lane + 64 * v) // 32 for v in range(8)]
+        assert ks == list(range(8 * (lane // 32), 8 * (lane // 32) + 8)) and {a(lane + 64 * v) % 32 for v in range(8)} == {lane % 32}
+        rows = [c(lane + 64 * v) % 32 for v in range(16)]
+        assert rows == [8 * (v // 4) + 4 * (lane // 32) + v % 4 for v in range(16)]
+        assert {c(lane + 64 * v) // 32 for v in range(16)} == {lane % 32}
+
+
+def test_preconditions_and_refusals():
+    def status(*args, **kw):
+        with pytest.raises(lc.LayoutCopyError) as e:
+            lc.GemmPlan(*args, **kw)
+        return e.value.status_name
+    assert status("(4,3):(1,4)", "(5,3):(1,5)", "(3,5):(1,3)") == "SIZE_MISMATCH"
+    assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,6):(1,4)") == "SIZE_MISMATCH"
+    assert status("(4,3):(1,4)", "(5,2):(1,5)", "(4,5):(1,4)") == "SIZE_MISMATCH"
+    assert status("12:1", "(5,3):(1,5)", "(4,5):(1,4)") == "INVALID_ARG"
+    assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,5):(0,1)") == "DST_ALIASES"
+    assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,5):(1,4)", "f32") == "UNSUPPORTED_DTYPE"
+    assert status("(4,3):(1,%d)" % (1 << 30), "(5,3):(1,5)", "(4,5):(1,4)") == "TOO_LARGE"
+    # less aligned pointers than vectors need: the planner falls back to element loads instead of refusing
+    p = lc.GemmPlan("(64,64):(64,1)", "(64,64):(64,1)", "(64,64):(1,64)", "bf16", a_align=2, b_align=16, c_align=4)
+    assert "a_load=elements" in p.describe() and "b_load=k-vectors" in p.describe() and "c_vec=0" in p.describe()
+    assert p.flops == 2 * 64 ** 3

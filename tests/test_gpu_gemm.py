@@ -1,0 +1,148 @@
+"""GPU parity of the generic GEMM: the MFMA kernel (through the C ABI) against the CPU oracle on the same
+seeded inputs.  Integer-valued inputs must agree exactly (every product and partial sum is exact in
+fp32 whatever the order); N(0,1) inputs within K * 2^-23 * (|C0| + sum_k |A B|), the bound on fp32
+accumulation of exact products in any order and rounding mode.  Run on the MI355X machine with `-m gpu`."""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2603_02298_amd as lc
+from paper_2603_02298_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _plan_env(env):
+    class Ctx:
+        def __enter__(self):
+            self.old = {k: os.environ.get(k) for k in env}
+            os.environ.update({k: str(v) for k, v in env.items()})
+
+        def __exit__(self, *a):
+            for k, v in self.old.items():
+                if v is None:
+                    del os.environ[k]
+                else:
+                    os.environ[k] = v
+    return Ctx()
+
+
+def _gpu_gemm(w, a_bits, b_bits, c0, env=None):
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if w.ab_dtype == "bf16" else torch.float16
+    a_t = torch.from_numpy(a_bits.view(np.int16)).to(dev).view(tdt)
+    b_t = torch.from_numpy(b_bits.view(np.int16)).to(dev).view(tdt)
+    c_t = torch.from_numpy(c0.copy()).to(dev)
+    with _plan_env(env or {}):
+        desc = lc.GemmPlan(w.a_layout, w.b_layout, w.c_layout, w.ab_dtype).describe()
+        print("case", w.name, (w.M, w.N, w.K), desc, flush=True)
+        lc.gemm_tensor(a_t, w.a_layout, b_t, w.b_layout, c_t, w.c_layout)
+    torch.cuda.synchronize()
+    return c_t.cpu().numpy(), desc
+
+
+def _parity(oracle, w, env=None):
+    a, b, c0 = W.gemm_operand_bits(w, "a"), W.gemm_operand_bits(w, "b"), W.gemm_c_values(w)
+    got, desc = _gpu_gemm(w, a, b, c0, env)
+    a64, b64 = W.bits_to_float64(a, w.ab_dtype), W.bits_to_float64(b, w.ab_dtype)
+    want = oracle.gemm(a64, w.a_layout, b64, w.b_layout, c0.astype(np.float64), w.c_layout)
+    if w.values == "ints":
+        assert (got.astype(np.float64) == want).all(), desc
+    else:
+        bound = oracle.gemm(np.abs(a64), w.a_layout, np.abs(b64), w.b_layout, np.abs(c0).astype(np.float64), w.c_layout)
+        err = np.abs(got.astype(np.float64) - want)
+        assert (err <= w.K * 2.0 ** -23 * bound).all(), (desc, float(err.max()))
+        # entries outside the image of C's layout keep their bits
+        touched = bound != np.abs(c0).astype(np.float64)
+        assert (got[~touched] == c0[~touched]).all(), desc
+    return desc
+
+
+# sizes the oracle finishes in seconds; each spans several tiles of the chosen size and has ragged edges
+CASES = [
+    ("tn", (520, 392, 200)),
+    ("nt", (392, 520, 136)),
+    ("nn_rowmajor_c", (264, 300, 96)),
+    ("gett", (320, 200, 72)),
+    ("blis", (150, 133, 77)),
+]
+
+
+@pytest.mark.parametrize("values", ["ints", "normal"])
+@pytest.mark.parametrize("tile", [128, 256])
+@pytest.mark.parametrize("name,mnk", CASES)
+def test_gemm_table_rows(oracle, name, mnk, tile, values):
+    w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values=values)
+    desc = _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
+    assert "tile=%dx%d" % (tile, tile) in desc
+
+
+def test_gemm_f16_and_element_loads(oracle):
+    for values in ("ints", "normal"):
+        w = W.gemm_workload("tn", 200, 136, 104, ab_dtype="f16", values=values)
+        _parity(oracle, w)
+        _parity(oracle, w, {"LC_TUNE_GEMM_LOAD": 2, "LC_TUNE_GEMM_CVEC": 0})
+        w = W.gemm_workload("nt", 136, 200, 64, ab_dtype="f16", values=values)
+        _parity(oracle, w)
+
+
+def test_gemm_degenerate_shapes(oracle):
+    # a single row / column / k, and extents below one fragment
+    for M, N, K in [(1, 1, 1), (1, 40, 8), (33, 1, 5), (8, 8, 8), (31, 33, 17)]:
+        w = W.gemm_workload("blis", M, N, K, values="ints")
+        _parity(oracle, w)
+    w = W.gemm_workload("tn", 8, 16, 8, values="ints")
+    _parity(oracle, w)
+    w = W.gemm_workload("nt", 8, 16, 8, values="ints")
+    _parity(oracle, w)
+
+
+def test_gemm_hierarchical_k_broadcast_and_accumulate(oracle):
+    M, N, K1, K2 = 64, 24, 16, 3
+    w = W.GemmWorkload("gett2", "bf16", "(%d,(%d,%d)):(1,(%d,%d))" % (M, K1, K2, M, M * K1 + 8),
+                       "(%d,(%d,%d)):(%d,(1,%d))" % (N, K1, K2, K1, K1 * N + 16), "(%d,%d):(1,%d)" % (M, N, M),
+                       (M * K1 + 8) * K2, (K1 * N + 16) * K2, M * N, M, N, K1 * K2, "ints")
+    _parity(oracle, w)
+    w = W.GemmWorkload("bcast", "bf16", "(40,24):(24,1)", "(16,24):(0,1)", "(40,16):(16,1)", 960, 24, 640, 40, 16, 24, "ints")
+    _parity(oracle, w)
+    # two executions accumulate twice (the `+=` of the loop nest)
+    w = W.gemm_workload("tn", 136, 72, 40, values="ints")
+    a, b, c0 = W.gemm_operand_bits(w, "a"), W.gemm_operand_bits(w, "b"), W.gemm_c_values(w)
+    dev = torch.device("cuda:0")
+    a_t = torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    b_t = torch.from_numpy(b.view(np.int16)).to(dev).view(torch.bfloat16)
+    c_t = torch.from_numpy(c0.copy()).to(dev)
+    lc.gemm_tensor(a_t, w.a_layout, b_t, w.b_layout, c_t, w.c_layout)
+    lc.gemm_tensor(a_t, w.a_layout, b_t, w.b_layout, c_t, w.c_layout)
+    torch.cuda.synchronize()
+    a64, b64 = W.bits_to_float64(a, "bf16"), W.bits_to_float64(b, "bf16")
+    want = oracle.gemm(a64, w.a_layout, b64, w.b_layout, c0.astype(np.float64), w.c_layout)
+    want = oracle.gemm(a64, w.a_layout, b64, w.b_layout, want, w.c_layout)
+    assert (c_t.cpu().numpy().astype(np.float64) == want).all()
+
+
+@pytest.mark.parametrize("name", ["tn", "nt"])
+def test_gemm_full_size_sampled(oracle, name):
+    # the benchmark's problem (8192^3 bf16) in the launch configuration the bench times; the oracle
+    # computes sampled entries of C one by one
+    M = N = K = 8192
+    for values in ("ints", "normal"):
+        w = W.gemm_workload(name, M, N, K, values=values)
+        a, b = W.gemm_operand_bits(w, "a"), W.gemm_operand_bits(w, "b")
+        c0 = W.gemm_c_values(w)
+        got, desc = _gpu_gemm(w, a, b, c0)
+        assert "tile=256x256" in desc
+        rng = np.random.default_rng(7)
+        ms = np.concatenate([rng.integers(0, M, 300), [0, M - 1, 255, 256, 4095]])
+        ns = np.concatenate([rng.integers(0, N, 300), [0, N - 1, 256, 255, 4096]])
+        a64, b64, c64 = W.bits_to_float64(a, "bf16"), W.bits_to_float64(b, "bf16"), c0.astype(np.float64)
+        want = oracle.gemm_at(a64, w.a_layout, b64, w.b_layout, c64, w.c_layout, ms, ns)
+        have = got[ms + M * ns].astype(np.float64)       # C is (M,N):(1,M)
+        if values == "ints":
+            assert (have == want).all(), desc
+        else:
+            bound = oracle.gemm_at(np.abs(a64), w.a_layout, np.abs(b64), w.b_layout, np.abs(c64), w.c_layout, ms, ns)
+            assert (np.abs(have - want) <= K * 2.0 ** -23 * bound).all(), desc
