@@ -10,6 +10,7 @@
 
 #include <atomic>
 #include <string>
+#include <type_traits>
 
 #include "gemm_plan.hpp"
 #include "plan.hpp"
@@ -41,50 +42,62 @@ __device__ __forceinline__ void transpose_8x8_b16(const u32x4 (&in)[8], u32x4 (&
     }
 }
 
-// One operand (A or B) of one workgroup: issues the global loads of a k tile into registers, parks them in LDS.
-template <int BR>
-struct OperandLoader {
-  static constexpr int ROWS = BR / 32;   // rows per lane for k-vector / element loads
-  const uint16_t* base;
-  int32_t load;
-  uint32_t K, kv, row_in_tile;           // row_in_tile: first row of the lane (block row for row-vector loads)
-  uint32_t rowoff[ROWS];
-  bool active;
-  u32x4 regs[8];
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>); the accumulators are
+// only ever indexed with constants, so they stay in registers
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
 
-  __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, int32_t ld, uint32_t row0,
-                                       uint32_t extent, uint32_t Ktot, uint32_t tid) {
+__device__ __forceinline__ u32x4 select_or_zero(bool keep, u32x4 v) {
+  return u32x4{keep ? v[0] : 0u, keep ? v[1] : 0u, keep ? v[2] : 0u, keep ? v[3] : 0u};
+}
+
+// One operand (A or B) of one workgroup: issues the global loads of a k tile into registers, parks them in LDS.
+// Loads are unconditional from clamped coordinates (always inside the tensor); what lies past K is zeroed
+// in registers afterwards, so the loop carries no divergent branch.
+template <int BR, int LOAD>
+struct OperandLoader {
+  static constexpr int ROWS = BR / 32;                                    // rows per lane for k-vector / element loads
+  static constexpr int NREG = LOAD == kLoadRVec ? 8 : ROWS;
+  const uint16_t* base;
+  uint32_t K, kv, row_in_tile;           // row_in_tile: first row of the lane (block row for row-vector loads)
+  uint32_t rowoff[LOAD == kLoadRVec ? 1 : ROWS];
+  bool active, k_inside;
+  u32x4 regs[NREG];
+
+  __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, uint32_t row0, uint32_t extent, uint32_t Ktot,
+                                       uint32_t tid) {
     base = p;
-    load = ld;
     K = Ktot;
     kv = tid & 7u;
-    row_in_tile = gemm_lane_row(ld, tid, 0);
-    active = ld != kLoadRVec || tid < (uint32_t)BR;
+    row_in_tile = gemm_lane_row(LOAD, tid, 0);
+    active = LOAD != kLoadRVec || BR >= kBlock || tid < (uint32_t)BR;   // whole wavefronts: lanes 128.. of a 128-row tile
+    if constexpr (LOAD == kLoadRVec) {
+      rowoff[0] = gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + (active ? row_in_tile : 0u), extent));
+    } else {
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i) {
-      const uint32_t row = row0 + gemm_lane_row(ld, tid, (uint32_t)i);
-      rowoff[i] = (ld != kLoadRVec || i == 0) ? gemm_mode_eval(rmode, gemm_clamp_row(ld, row, extent)) : 0u;
+      for (int i = 0; i < ROWS; ++i) rowoff[i] = gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + gemm_lane_row(LOAD, tid, (uint32_t)i), extent));
     }
   }
 
   __device__ __forceinline__ void fetch(uint32_t kt, const GemmMode& kmode) {
     const uint32_t k0 = kt * kGemmBK + kv * 8u;
-    if (load == kLoadKVec) {
-      const bool in = k0 < K;
-      const uint32_t koff = gemm_mode_eval(kmode, in ? k0 : 0u);
+    if constexpr (LOAD == kLoadKVec) {
+      k_inside = k0 < K;
+      const uint16_t* p = base + gemm_mode_eval(kmode, k_inside ? k0 : 0u);
 #pragma unroll
-      for (int i = 0; i < ROWS; ++i) {
-        regs[i] = u32x4{0u, 0u, 0u, 0u};
-        if (in) regs[i] = *reinterpret_cast<const u32x4*>(base + rowoff[i] + koff);
-      }
-    } else if (load == kLoadRVec) {
-      const bool in = active && k0 < K;
-      const uint32_t koff = gemm_mode_eval(kmode, in ? k0 : 0u);
-      const uint32_t kstep = kmode.stride[0];   // k0 .. k0 + 7 stay inside the leading leaf of the k mode
+      for (int i = 0; i < ROWS; ++i) regs[i] = *reinterpret_cast<const u32x4*>(p + rowoff[i]);
+    } else if constexpr (LOAD == kLoadRVec) {
+      k_inside = k0 < K;
+      if (active) {
+        const uint16_t* p = base + rowoff[0] + gemm_mode_eval(kmode, k_inside ? k0 : 0u);
+        const uint32_t kstep = kmode.lead_stride;   // k0 .. k0 + 7 stay inside the leading leaf of the k mode
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        regs[j] = u32x4{0u, 0u, 0u, 0u};
-        if (in) regs[j] = *reinterpret_cast<const u32x4*>(base + rowoff[0] + koff + (uint32_t)j * kstep);
+        for (int j = 0; j < 8; ++j) regs[j] = *reinterpret_cast<const u32x4*>(p + (uint32_t)j * kstep);
       }
     } else {
       uint32_t koff[8];
@@ -98,36 +111,42 @@ struct OperandLoader {
       for (int i = 0; i < ROWS; ++i) {
         uint32_t e[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) e[j] = in[j] ? (uint32_t)base[rowoff[i] + koff[j]] : 0u;
+        for (int j = 0; j < 8; ++j) {
+          e[j] = (uint32_t)base[rowoff[i] + koff[j]];
+          e[j] = in[j] ? e[j] : 0u;
+        }
         regs[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
       }
     }
   }
 
   __device__ __forceinline__ void park(unsigned char* tile) {
-    if (load == kLoadRVec) {
+    if constexpr (LOAD == kLoadRVec) {
       if (active) {
         u32x4 t[8];
         transpose_8x8_b16(regs, t);
-        const uint32_t flip = (row_in_tile >> 3) & 1u;   // neighbouring blocks write rows of opposite parity
+        const bool flip = ((row_in_tile >> 3) & 1u) != 0;   // neighbouring blocks write rows of opposite parity
 #pragma unroll
         for (int ii = 0; ii < 8; ++ii) {
-          const uint32_t i = (uint32_t)ii ^ flip;
+          const uint32_t i = (uint32_t)ii ^ (flip ? 1u : 0u);
           const u32x4 v = flip ? t[ii ^ 1] : t[ii];   // t[i], selected without indexing registers dynamically
-          *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + i, kv)) = v;
+          *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + i, kv)) = select_or_zero(k_inside, v);
         }
       }
-    } else {
+    } else if constexpr (LOAD == kLoadKVec) {
 #pragma unroll
       for (int i = 0; i < ROWS; ++i)
-        *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + 32u * (uint32_t)i, kv)) = regs[i];
+        *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + 32u * (uint32_t)i, kv)) = select_or_zero(k_inside, regs[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + 32u * (uint32_t)i, kv)) = regs[i];
     }
   }
 };
 
-template <bool BF16, int WMB, int WNB>
-__global__ __launch_bounds__(kBlock) void gemm_kernel(GemmParams P, const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
-                                                      float* __restrict__ C) {
+template <bool BF16, int WMB, int WNB, int A_LOAD, int B_LOAD>
+__global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmParams P, const uint16_t* __restrict__ A,
+                                                                          const uint16_t* __restrict__ B, float* __restrict__ C) {
   constexpr int BM = 64 * WMB, BN = 64 * WNB;
   constexpr uint32_t A_BYTES = BM * 128u, STAGE = (BM + BN) * 128u;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -138,18 +157,18 @@ __global__ __launch_bounds__(kBlock) void gemm_kernel(GemmParams P, const uint16
   gemm_tile_of_order(P, gemm_tile_order_of_block(blockIdx.x, P.tiles_m * P.tiles_n), &tm, &tn);
   const uint32_t m0 = tm * BM, n0 = tn * BN;
 
-  OperandLoader<BM> la;
-  OperandLoader<BN> lb;
-  la.init(A, P.a_r, P.a_load, m0, P.M, P.K, tid);
-  lb.init(B, P.b_r, P.b_load, n0, P.N, P.K, tid);
+  OperandLoader<BM, A_LOAD> la;
+  OperandLoader<BN, B_LOAD> lb;
+  la.init(A, P.a_r, m0, P.M, P.K, tid);
+  lb.init(B, P.b_r, n0, P.N, P.K, tid);
 
   f32x16 acc[WMB][WNB];
-#pragma unroll
-  for (int i = 0; i < WMB; ++i)
-#pragma unroll
-    for (int j = 0; j < WNB; ++j)
+  static_for<WMB>([&](auto i) {
+    static_for<WNB>([&](auto j) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    });
+  });
 
   la.fetch(0, P.a_k);
   lb.fetch(0, P.b_k);
@@ -157,28 +176,25 @@ __global__ __launch_bounds__(kBlock) void gemm_kernel(GemmParams P, const uint16
   lb.park(lds + A_BYTES);
   __syncthreads();
 
+  // fragment addresses inside a stage: row part fixed per lane, the k vector toggles with kk
   const uint32_t a_row = wm * (WMB * 32u) + mfma_ab_row(lane), b_row = wn * (WNB * 32u) + mfma_ab_row(lane);
   for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
-    unsigned char* cur = lds + (kt & 1u) * STAGE;
+    const unsigned char* cur = lds + (kt & 1u) * STAGE;
     unsigned char* nxt = lds + ((kt & 1u) ^ 1u) * STAGE;
     const bool more = kt + 1 < P.k_tiles;
     if (more) {
       la.fetch(kt + 1, P.a_k);
       lb.fetch(kt + 1, P.b_k);
     }
-#pragma unroll
-    for (int kk = 0; kk < kGemmBK / 16; ++kk) {
+    static_for<kGemmBK / 16>([&](auto kk) {
       u32x4 af[WMB], bf[WNB];
       const uint32_t kvec = 2u * (uint32_t)kk + mfma_ab_kvec(lane);
-#pragma unroll
-      for (int i = 0; i < WMB; ++i) af[i] = *reinterpret_cast<const u32x4*>(cur + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec));
-#pragma unroll
-      for (int j = 0; j < WNB; ++j) bf[j] = *reinterpret_cast<const u32x4*>(cur + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec));
-#pragma unroll
-      for (int i = 0; i < WMB; ++i)
-#pragma unroll
-        for (int j = 0; j < WNB; ++j) acc[i][j] = mfma_32x32x16<BF16>(af[i], bf[j], acc[i][j]);
-    }
+      static_for<WMB>([&](auto i) { af[i] = *reinterpret_cast<const u32x4*>(cur + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec)); });
+      static_for<WNB>([&](auto j) { bf[j] = *reinterpret_cast<const u32x4*>(cur + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec)); });
+      static_for<WMB>([&](auto i) {
+        static_for<WNB>([&](auto j) { acc[i][j] = mfma_32x32x16<BF16>(af[i], bf[j], acc[i][j]); });
+      });
+    });
     if (more) {
       la.park(nxt);
       lb.park(nxt + A_BYTES);
@@ -186,32 +202,29 @@ __global__ __launch_bounds__(kBlock) void gemm_kernel(GemmParams P, const uint16
     __syncthreads();
   }
 
-  // C(m,n) += acc: lane holds column n = lane % 32 of each fragment and 4 groups of 4 consecutive rows
-#pragma unroll
-  for (int j = 0; j < WNB; ++j) {
+  // C(m,n) += acc: a lane holds column n = lane % 32 of each fragment and 4 groups of 4 consecutive rows
+  static_for<WNB>([&](auto j) {
     const uint32_t n = n0 + wn * (WNB * 32u) + 32u * (uint32_t)j + mfma_c_col(lane);
-    if (n >= P.N) continue;
-    const uint32_t noff = gemm_mode_eval(P.c_n, n);
-#pragma unroll
-    for (int i = 0; i < WMB; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
+    const bool n_in = n < P.N;
+    const uint32_t noff = gemm_mode_eval(P.c_n, n_in ? n : 0u);
+    static_for<WMB>([&](auto i) {
+      static_for<4>([&](auto g) {
         const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
         if (P.c_vec) {
-          if (m < P.M) {
+          if (n_in && m < P.M) {
             f32x4* p = reinterpret_cast<f32x4*>(C + gemm_mode_eval(P.c_m, m) + noff);
             f32x4 c = *p;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) c[v] += acc[i][j][4 * g + v];
+            static_for<4>([&](auto v) { c[(int)v] += acc[i][j][4 * g + v]; });
             *p = c;
           }
         } else {
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (m + (uint32_t)v < P.M) C[gemm_mode_eval(P.c_m, m + (uint32_t)v) + noff] += acc[i][j][4 * g + v];
+          static_for<4>([&](auto v) {
+            if (n_in && m + (uint32_t)v < P.M) C[gemm_mode_eval(P.c_m, m + (uint32_t)v) + noff] += acc[i][j][4 * g + v];
+          });
         }
-      }
-  }
+      });
+    });
+  });
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -223,20 +236,31 @@ static bool gemm_hip_failed(hipError_t e, const char* what) {
   return true;
 }
 
-template <bool BF16, int WB>
-static hipError_t launch_gemm(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
+template <bool BF16, int WB, int A_LOAD, int B_LOAD>
+static hipError_t launch_gemm_ab(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
   if (plan.lds_bytes > 64 * 1024) {
-    static std::atomic<bool> raised{false};
+    static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
     if (!raised.load(std::memory_order_acquire)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BF16, WB, WB>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         160 * 1024);
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
       raised.store(true, std::memory_order_release);
     }
   }
   const unsigned grid = plan.params.tiles_m * plan.params.tiles_n;
-  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
+  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
   return hipSuccess;
+}
+// vector loads are compiled per pair of modes; an operand that needs element loads takes the other one along
+template <bool BF16, int WB>
+static hipError_t launch_gemm(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
+  const int la = plan.params.a_load, lb = plan.params.b_load;
+  if (la == kLoadKVec && lb == kLoadKVec) return launch_gemm_ab<BF16, WB, kLoadKVec, kLoadKVec>(plan, a, b, c, s);
+  if (la == kLoadKVec && lb == kLoadRVec) return launch_gemm_ab<BF16, WB, kLoadKVec, kLoadRVec>(plan, a, b, c, s);
+  if (la == kLoadRVec && lb == kLoadKVec) return launch_gemm_ab<BF16, WB, kLoadRVec, kLoadKVec>(plan, a, b, c, s);
+  if (la == kLoadRVec && lb == kLoadRVec) return launch_gemm_ab<BF16, WB, kLoadRVec, kLoadRVec>(plan, a, b, c, s);
+  if (la == kLoadElem && lb == kLoadElem) return launch_gemm_ab<BF16, WB, kLoadElem, kLoadElem>(plan, a, b, c, s);
+  return hipErrorInvalidValue;
 }
 
 lc_status_t execute_gemm_plan(const lc_gemm_plan& plan, const void* a, const void* b, void* c, void* stream) {

@@ -19,23 +19,26 @@ enum GemmLoad : int32_t {
 };
 
 // One coalesced mode: integral coordinate -> offset in elements (all offsets of a GEMM operand fit 31 bits).
+// The leaves but the last are reduced modulo their extents, the last one takes what is left (Eq. idx2crd).
+// Storage is branch-free for the kernel: the reduced leaves sit in front, padded with extent-1 leaves
+// (quotient passes through, remainder 0), and the last leaf's stride always sits in last_stride.
 struct GemmMode {
-  int32_t n;
-  FastDiv div[kGemmMaxLeaves];
-  uint32_t stride[kGemmMaxLeaves];
+  int32_t n;                              // leaves of the coalesced mode (1 .. kGemmMaxLeaves)
+  FastDiv div[kGemmMaxLeaves - 1];
+  uint32_t stride[kGemmMaxLeaves - 1];
+  uint32_t last_stride;
+  uint32_t lead_stride;                   // stride of the first leaf (one step of the coordinate while it stays inside that leaf)
 };
 LC_HD uint32_t gemm_mode_eval(const GemmMode& g, uint32_t i) {
   uint32_t off = 0;
 #pragma unroll
   for (int k = 0; k < kGemmMaxLeaves - 1; ++k) {
-    if (k + 1 < g.n) {
-      uint32_t q, r;
-      fd_divmod(i, g.div[k], &q, &r);
-      off += r * g.stride[k];
-      i = q;
-    }
+    uint32_t q, r;
+    fd_divmod(i, g.div[k], &q, &r);
+    off += r * g.stride[k];
+    i = q;
   }
-  return off + i * g.stride[g.n - 1];
+  return off + i * g.last_stride;
 }
 
 struct GemmParams {

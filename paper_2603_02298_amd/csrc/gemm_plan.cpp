@@ -13,15 +13,15 @@ namespace {
 lc_status_t fill_mode(const Modes& m, GemmMode* out) {
   if (m.empty() || (int)m.size() > kGemmMaxLeaves) return LC_ERR_TOO_LARGE;
   out->n = (int32_t)m.size();
-  for (size_t k = 0; k < m.size(); ++k) {
-    if (m[k].extent >= (int64_t(1) << 31) || m[k].stride >= (int64_t(1) << 31)) return LC_ERR_TOO_LARGE;
-    out->div[k] = make_fastdiv((uint32_t)m[k].extent);
-    out->stride[k] = (uint32_t)m[k].stride;
+  for (const Mode& x : m)
+    if (x.extent >= (int64_t(1) << 31) || x.stride >= (int64_t(1) << 31)) return LC_ERR_TOO_LARGE;
+  for (int k = 0; k < kGemmMaxLeaves - 1; ++k) {
+    const bool reduced = k + 1 < (int)m.size();
+    out->div[k] = make_fastdiv(reduced ? (uint32_t)m[k].extent : 1u);
+    out->stride[k] = reduced ? (uint32_t)m[k].stride : 0u;
   }
-  for (int k = (int)m.size(); k < kGemmMaxLeaves; ++k) {
-    out->div[k] = make_fastdiv(1);
-    out->stride[k] = 0;
-  }
+  out->last_stride = (uint32_t)m.back().stride;
+  out->lead_stride = (uint32_t)m.front().stride;
   return LC_OK;
 }
 
@@ -130,7 +130,8 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   P.a_load = classify_operand(a_r, a_k, ka_align);
   P.b_load = classify_operand(b_r, b_k, kb_align);
   const int force = env_int("LC_TUNE_GEMM_LOAD", -1);   // tests: force the element-wise loads
-  if (force == kLoadElem) P.a_load = P.b_load = kLoadElem;
+  // element loads are compiled for both operands together: one operand that needs them takes the other along
+  if (force == kLoadElem || P.a_load == kLoadElem || P.b_load == kLoadElem) P.a_load = P.b_load = kLoadElem;
   P.c_vec = c_vec_ok(c_m, c_n) ? 1 : 0;
   if (env_int("LC_TUNE_GEMM_CVEC", 1) == 0) P.c_vec = 0;
   unsigned need_a = P.a_load == kLoadElem ? 2u : 16u, need_b = P.b_load == kLoadElem ? 2u : 16u;

@@ -49,7 +49,7 @@ struct Walker {
           const uint32_t rowoff = gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + block_row, extent));
           const uint32_t koff = gemm_mode_eval(kmode, k0);
           for (uint32_t j = 0; j < 8; ++j) {
-            const int64_t off = (int64_t)rowoff + koff + (int64_t)j * kmode.stride[0];
+            const int64_t off = (int64_t)rowoff + koff + (int64_t)j * kmode.lead_stride;
             if (off % 8 != 0 || off + 8 > elems) { ok = false; return; }
             std::memcpy(blk[j], base + off, 16);
           }

@@ -103,7 +103,10 @@ def test_preconditions_and_refusals():
     assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,5):(0,1)") == "DST_ALIASES"
     assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,5):(1,4)", "f32") == "UNSUPPORTED_DTYPE"
     assert status("(4,3):(1,%d)" % (1 << 30), "(5,3):(1,5)", "(4,5):(1,4)") == "TOO_LARGE"
-    # less aligned pointers than vectors need: the planner falls back to element loads instead of refusing
+    # less aligned pointers than vectors need: the planner falls back to element loads (for both operands
+    # together) and scalar updates of C instead of refusing
     p = lc.GemmPlan("(64,64):(64,1)", "(64,64):(64,1)", "(64,64):(1,64)", "bf16", a_align=2, b_align=16, c_align=4)
-    assert "a_load=elements" in p.describe() and "b_load=k-vectors" in p.describe() and "c_vec=0" in p.describe()
+    assert "a_load=elements" in p.describe() and "b_load=elements" in p.describe() and "c_vec=0" in p.describe()
+    p = lc.GemmPlan("(64,64):(64,1)", "(64,64):(64,1)", "(64,64):(1,64)", "bf16", a_align=16, b_align=16, c_align=4)
+    assert "a_load=k-vectors" in p.describe() and "b_load=k-vectors" in p.describe() and "c_vec=0" in p.describe()
     assert p.flops == 2 * 64 ** 3
