@@ -31,15 +31,16 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// 8x8 transpose of 16-bit elements held as 8 vectors of 8: out[i] element j = in[j] element i
-__device__ __forceinline__ void transpose_8x8_b16(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+// Row i of the transpose of an 8x8 block of 16-bit elements held as 8 vectors of 8 (in[j] = the 8 rows' elements
+// at column j): element j of the result is element i of in[j].  `odd` says whether i is odd (it may be a run-time
+// value: it only picks the halves of the dwords, never a register); half = i / 2 picks the dword.
+__device__ __forceinline__ u32x4 transposed_row_b16(const u32x4 (&in)[8], int half, bool odd) {
+  // v_perm_b32 picks 4 of the 8 bytes {in[2d+1] dword : in[2d] dword}: low halves of both, or high halves of both
+  const uint32_t sel = odd ? 0x07060302u : 0x05040100u;
+  u32x4 out;
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      const uint32_t lo = in[2 * d][i / 2], hi = in[2 * d + 1][i / 2];
-      out[i][d] = (i % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
-    }
+  for (int d = 0; d < 4; ++d) out[d] = __builtin_amdgcn_perm(in[2 * d + 1][half], in[2 * d][half], sel);
+  return out;
 }
 
 // compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>); the accumulators are
@@ -73,7 +74,7 @@ struct OperandLoader {
                                        uint32_t tid) {
     base = p;
     K = Ktot;
-    kv = tid & 7u;
+    kv = gemm_lane_kvec(LOAD, tid);
     row_in_tile = gemm_lane_row(LOAD, tid, 0);
     active = LOAD != kLoadRVec || BR >= kBlock || tid < (uint32_t)BR;   // whole wavefronts: lanes 128.. of a 128-row tile
     if constexpr (LOAD == kLoadRVec) {
@@ -123,15 +124,14 @@ struct OperandLoader {
   __device__ __forceinline__ void park(unsigned char* tile) {
     if constexpr (LOAD == kLoadRVec) {
       if (active) {
-        u32x4 t[8];
-        transpose_8x8_b16(regs, t);
-        const bool flip = ((row_in_tile >> 3) & 1u) != 0;   // neighbouring blocks write rows of opposite parity
-#pragma unroll
-        for (int ii = 0; ii < 8; ++ii) {
+        // the two k vectors of a quarter wavefront write rows of opposite parity (distinct LDS banks):
+        // step ii of a lane with odd kv handles row ii ^ 1
+        const bool flip = (kv & 1u) != 0;
+        static_for<8>([&](auto ii) {
+          const u32x4 v = transposed_row_b16(regs, ii / 2, ((ii & 1) != 0) != flip);
           const uint32_t i = (uint32_t)ii ^ (flip ? 1u : 0u);
-          const u32x4 v = flip ? t[ii ^ 1] : t[ii];   // t[i], selected without indexing registers dynamically
           *reinterpret_cast<u32x4*>(tile + gemm_lds_offset(row_in_tile + i, kv)) = select_or_zero(k_inside, v);
-        }
+        });
       }
     } else if constexpr (LOAD == kLoadKVec) {
 #pragma unroll
@@ -176,8 +176,17 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
   lb.park(lds + A_BYTES);
   __syncthreads();
 
-  // fragment addresses inside a stage: row part fixed per lane, the k vector toggles with kk
+  // Fragments are double-buffered in registers: those of k step kk + 1 are read from LDS while the MFMAs of
+  // step kk run (one wavefront per SIMD: nothing else would cover the LDS latency).
   const uint32_t a_row = wm * (WMB * 32u) + mfma_ab_row(lane), b_row = wn * (WNB * 32u) + mfma_ab_row(lane);
+  u32x4 af[2][WMB], bf[2][WNB];
+  auto read_fragments = [&](const unsigned char* stage, auto kk, auto buf) {
+    const uint32_t kvec = 2u * (uint32_t)kk + mfma_ab_kvec(lane);
+    static_for<WMB>([&](auto i) { af[buf][i] = *reinterpret_cast<const u32x4*>(stage + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec)); });
+    static_for<WNB>([&](auto j) { bf[buf][j] = *reinterpret_cast<const u32x4*>(stage + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec)); });
+  };
+  constexpr int KSTEPS = kGemmBK / 16;
+  read_fragments(lds, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
   for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
     const unsigned char* cur = lds + (kt & 1u) * STAGE;
     unsigned char* nxt = lds + ((kt & 1u) ^ 1u) * STAGE;
@@ -186,20 +195,26 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
       la.fetch(kt + 1, P.a_k);
       lb.fetch(kt + 1, P.b_k);
     }
-    static_for<kGemmBK / 16>([&](auto kk) {
-      u32x4 af[WMB], bf[WNB];
-      const uint32_t kvec = 2u * (uint32_t)kk + mfma_ab_kvec(lane);
-      static_for<WMB>([&](auto i) { af[i] = *reinterpret_cast<const u32x4*>(cur + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec)); });
-      static_for<WNB>([&](auto j) { bf[j] = *reinterpret_cast<const u32x4*>(cur + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec)); });
+    static_for<KSTEPS>([&](auto kk) {
+      constexpr int buf = kk % 2;
+      if constexpr (kk + 1 < KSTEPS) read_fragments(cur, std::integral_constant<int, kk + 1>{}, std::integral_constant<int, buf ^ 1>{});
       static_for<WMB>([&](auto i) {
-        static_for<WNB>([&](auto j) { acc[i][j] = mfma_32x32x16<BF16>(af[i], bf[j], acc[i][j]); });
+        static_for<WNB>([&](auto j) { acc[i][j] = mfma_32x32x16<BF16>(af[buf][i], bf[buf][j], acc[i][j]); });
       });
+      if constexpr (kk + 1 < KSTEPS) {
+        // issue order: one LDS read, then two MFMAs, repeated
+        static_for<WMB + WNB>([&](auto) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, (WMB * WNB) / (WMB + WNB), 0);
+        });
+      }
     });
     if (more) {
       la.park(nxt);
       lb.park(nxt + A_BYTES);
     }
     __syncthreads();
+    if (more) read_fragments(nxt, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
   }
 
   // C(m,n) += acc: a lane holds column n = lane % 32 of each fragment and 4 groups of 4 consecutive rows

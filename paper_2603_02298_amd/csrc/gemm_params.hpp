@@ -75,19 +75,25 @@ LC_HD void gemm_tile_of_order(const GemmParams& P, uint32_t t, uint32_t* tm, uin
 // vectors per row.  Vector kv of row r sits at slot kv ^ r ^ (r >> 3) (low three bits): this is the
 // XOR layout (Sec. 2.3.2) under which all three access patterns below touch 16 distinct 16-byte
 // bank groups per 16 lanes: fragment reads (16 rows, one kv), k-vector writes (2 rows x 8 kv) and
-// the writes of transposed 8x8 blocks (8 kv x 2 row groups, rows of opposite parity).
+// the writes of transposed 8x8 blocks (8 row groups x 2 kv, rows of opposite parity for odd kv).
 // ---------------------------------------------------------------------------------------------
 LC_HD uint32_t gemm_lds_offset(uint32_t row, uint32_t kv) { return row * 128u + (((kv ^ row ^ (row >> 3)) & 7u) << 4); }
 
 // ---------------------------------------------------------------------------------------------
-// Lane -> what it loads.  256 lanes; kv = lane % 8 is the lane's k vector within the tile.
-//   kLoadKVec / kLoadElem: rows lane / 8 + 32 i, i < BR / 32
-//   kLoadRVec            : the 8x8 block at rows 8 (lane / 8) .. + 7 (lanes < BR only)
+// Lane -> what it loads (256 lanes).
+//   kLoadKVec / kLoadElem: k vector lane % 8 of rows lane / 8 + 32 i, i < BR / 32: a quarter wavefront
+//                          (16 lanes, one pass of a 16-byte load) reads two rows of 128 contiguous bytes
+//   kLoadRVec            : the 8x8 block of rows 8 b .. 8 b + 7, b = lane % 8 + 8 (lane / 64), and k vector
+//                          (lane / 8) % 8 (lanes < BR only): a quarter wavefront reads, for each of its two k
+//                          vectors, 128 contiguous bytes along the row mode
 // Rows past the end of the mode are clamped to its last row (last 8-row group for kLoadRVec): the
 // tile then holds a copy of valid data there, which only feeds entries of C that are never stored.
-// k past K reads nothing and parks zeros.
+// k past K parks zeros.
 // ---------------------------------------------------------------------------------------------
-LC_HD uint32_t gemm_lane_row(int32_t load, uint32_t lane, uint32_t i) { return load == kLoadRVec ? (lane >> 3) * 8u : (lane >> 3) + 32u * i; }
+LC_HD uint32_t gemm_lane_kvec(int32_t load, uint32_t lane) { return load == kLoadRVec ? (lane >> 3) & 7u : lane & 7u; }
+LC_HD uint32_t gemm_lane_row(int32_t load, uint32_t lane, uint32_t i) {
+  return load == kLoadRVec ? ((lane & 7u) + 8u * (lane >> 6)) * 8u : (lane >> 3) + 32u * i;
+}
 LC_HD uint32_t gemm_clamp_row(int32_t load, uint32_t row, uint32_t extent) {
   const uint32_t last = load == kLoadRVec ? extent - 8u : extent - 1u;
   return row < last ? row : last;

@@ -40,7 +40,7 @@ struct Walker {
   void stage(const uint16_t* base, int64_t elems, const GemmMode& rmode, const GemmMode& kmode, int32_t load, uint32_t row0, uint32_t extent,
              uint32_t BR, uint32_t kt, unsigned char* tile) {
     for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
-      const uint32_t kv = tid & 7u, k0 = kt * kGemmBK + kv * 8u;
+      const uint32_t kv = gemm_lane_kvec(load, tid), k0 = kt * kGemmBK + kv * 8u;
       if (load == kLoadRVec) {
         if (tid >= BR) continue;
         const uint32_t block_row = gemm_lane_row(load, tid, 0);
