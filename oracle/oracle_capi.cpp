@@ -216,15 +216,15 @@ int oracle_slayout_right_inverse(const oracle::SLayout* a, Layout** out) {
 }
 
 // ---- GEMM (Sec. 2.6.2) ----
-int oracle_gemm_check(const Layout* a, const Layout* b, const Layout* c, int64_t* M, int64_t* N, int64_t* K) {
-  return oracle::gemm_check(*a, *b, *c, M, N, K);
+int oracle_gemm_check(const Layout* a, const Layout* b, const Layout* c, int64_t* M, int64_t* N, int64_t* K, int64_t* L) {
+  return oracle::gemm_check(*a, *b, *c, M, N, K, L);
 }
 int oracle_gemm(const double* A, const Layout* la, const double* B, const Layout* lb, double* C, const Layout* lc) {
   return oracle::gemm(A, *la, B, *lb, C, *lc);
 }
 int oracle_gemm_at(const double* A, const Layout* la, const double* B, const Layout* lb, const double* C, const Layout* lc,
-                   const int64_t* ms, const int64_t* ns, int64_t count, double* out) {
-  return oracle::gemm_at(A, *la, B, *lb, C, *lc, ms, ns, count, out);
+                   const int64_t* ms, const int64_t* ns, const int64_t* ls, int64_t count, double* out) {
+  return oracle::gemm_at(A, *la, B, *lb, C, *lc, ms, ns, ls, count, out);
 }
 
 }  // extern "C"

@@ -95,9 +95,9 @@ def lib():
         L.oracle_slayout_right_inverse.argtypes = [P, PP]
         L.oracle_copy.argtypes = [P, P, P, P, ctypes.c_int]
         L.oracle_copy_range.argtypes = [P, P, P, P, ctypes.c_int, i64, i64]
-        L.oracle_gemm_check.argtypes = [P, P, P, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.oracle_gemm_check.argtypes = [P, P, P, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.oracle_gemm.argtypes = [P, P, P, P, P, P]
-        L.oracle_gemm_at.argtypes = [P, P, P, P, P, P, P, P, i64, P]
+        L.oracle_gemm_at.argtypes = [P, P, P, P, P, P, P, P, P, i64, P]
         _lib = L
     return _lib
 
@@ -345,11 +345,12 @@ def copy(src, src_layout, dst, dst_layout, begin=0, end=None, spans_checked=Fals
 
 
 def gemm_sizes(a_layout, b_layout, c_layout):
-    """(M, N, K) when the three layouts meet the preconditions of the generic GEMM, else OracleError."""
+    """(M, N, K) — (M, N, K, L) for rank-3 layouts — when the three layouts meet the preconditions of the generic
+    (batched) GEMM, else OracleError."""
     la, lb, lc = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
-    M, N, K = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
-    _check(lib().oracle_gemm_check(la._h, lb._h, lc._h, ctypes.byref(M), ctypes.byref(N), ctypes.byref(K)), "gemm_check")
-    return M.value, N.value, K.value
+    M, N, K, L = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().oracle_gemm_check(la._h, lb._h, lc._h, ctypes.byref(M), ctypes.byref(N), ctypes.byref(K), ctypes.byref(L)), "gemm_check")
+    return (M.value, N.value, K.value) if la.rank == 2 else (M.value, N.value, K.value, L.value)
 
 
 def _f64(x, layout, what):
@@ -367,16 +368,21 @@ def gemm(A, a_layout, B, b_layout, C, c_layout):
     return C
 
 
-def gemm_at(A, a_layout, B, b_layout, C, c_layout, ms, ns):
-    """The value the generic GEMM leaves in C(m_j, n_j) for the listed coordinates (C itself untouched)."""
+def gemm_at(A, a_layout, B, b_layout, C, c_layout, ms, ns, ls=None):
+    """The value the generic GEMM leaves in C(m_j, n_j) — C(m_j, n_j, l_j) for rank-3 layouts — for the listed
+    coordinates (C itself untouched)."""
     import numpy as np
     la, lb, lc = _as_layout(a_layout), _as_layout(b_layout), _as_layout(c_layout)
     ms = np.ascontiguousarray(ms, dtype=np.int64)
     ns = np.ascontiguousarray(ns, dtype=np.int64)
     assert ms.shape == ns.shape and ms.ndim == 1
+    if ls is not None:
+        ls = np.ascontiguousarray(ls, dtype=np.int64)
+        assert ls.shape == ms.shape
     out = np.zeros(ms.size, dtype=np.float64)
     st = lib().oracle_gemm_at(_f64(A, la, "A"), la._h, _f64(B, lb, "B"), lb._h, _f64(C, lc, "C"), lc._h,
-                              ms.ctypes.data_as(ctypes.c_void_p), ns.ctypes.data_as(ctypes.c_void_p), ms.size,
+                              ms.ctypes.data_as(ctypes.c_void_p), ns.ctypes.data_as(ctypes.c_void_p),
+                              ls.ctypes.data_as(ctypes.c_void_p) if ls is not None else None, ms.size,
                               out.ctypes.data_as(ctypes.c_void_p))
     _check(st, "gemm_at")
     return out

@@ -189,3 +189,52 @@ def test_preconditions(oracle):
         oracle.gemm(a, "12:1", a, "(5,3):(1,5)", a, "(4,5):(1,4)")             # A is not a matrix
     assert e.value.status_name == "INVALID_ARG"
     assert oracle.gemm_sizes("((2,2),3):((1,2),4)", "(5,(3,1)):(1,(5,0))", "(4,5):(1,4)") == (4, 5, 3)
+
+
+def test_batched_contraction_is_einsum(oracle):
+    # Sec. 1: C(m,n,l) += A(m,k,l) B(n,k,l) with every mode possibly a multi-mode; compared with einsum on strided views
+    M, N, K, L = 5, 4, 6, 3
+    A, B = _ints(M * K * L + 7, 1), _ints(N * K * L, 2)
+    C0 = _ints(M * N * L, 3)
+    la = "(%d,%d,%d):(1,%d,%d)" % (M, K, L, M, M * K)              # column-major matrices, batch outermost
+    lb = "(%d,%d,%d):(%d,1,%d)" % (N, K, L, K * L, K)              # batch interleaved between n and k
+    lc = "(%d,%d,%d):(%d,%d,1)" % (M, N, L, L, M * L)              # batch innermost
+    C = C0.copy()
+    oracle.gemm(A, la, B, lb, C, lc)
+    a, b = _strided(A, (M, K, L), (1, M, M * K)), _strided(B, (N, K, L), (K * L, 1, K))
+    want = _strided(C0, (M, N, L), (L, M * L, 1)) + np.einsum("mkl,nkl->mnl", a, b)
+    assert (_strided(C, (M, N, L), (L, M * L, 1)) == want).all()
+    assert oracle.gemm_sizes(la, lb, lc) == (M, N, K, L)
+    # a folded batch mode (L1,L2) and a stride-0 batch mode of B (one B for every l): a GETT with two batch indices
+    L1, L2 = 2, 3
+    A = _ints(M * K * L1 * L2, 4)
+    Bm = _ints(N * K, 5)
+    la = "(%d,%d,(%d,%d)):(%d,1,(%d,%d))" % (M, K, L1, L2, K, M * K * L2, M * K)
+    lb = "(%d,%d,(%d,%d)):(%d,1,(0,0))" % (N, K, L1, L2, K)
+    lc = "(%d,%d,(%d,%d)):(1,%d,(%d,%d))" % (M, N, L1, L2, M, M * N, M * N * L1)
+    C = np.zeros(M * N * L1 * L2)
+    oracle.gemm(A, la, Bm, lb, C, lc)
+    a = _strided(A, (M, K, L1, L2), (K, 1, M * K * L2, M * K))
+    want = np.einsum("mkab,nk->mnab", a, Bm.reshape(N, K))
+    assert (_strided(C, (M, N, L1, L2), (1, M, M * N, M * N * L1)) == want).all()
+    # sampled entries agree with the loop nest (same sums, same order)
+    rng = np.random.default_rng(3)
+    A, Bm, C0 = rng.standard_normal(A.size), rng.standard_normal(Bm.size), rng.standard_normal(C.size)
+    C = C0.copy()
+    oracle.gemm(A, la, Bm, lb, C, lc)
+    ms, ns, ls = rng.integers(0, M, 40), rng.integers(0, N, 40), rng.integers(0, L1 * L2, 40)
+    got = oracle.gemm_at(A, la, Bm, lb, C0, lc, ms, ns, ls)
+    assert (got == C[ms + M * ns + M * N * ((ls % L1) + L1 * (ls // L1))]).all()
+
+
+def test_batched_preconditions(oracle):
+    a = np.zeros(256)
+    with pytest.raises(OracleError) as e:
+        oracle.gemm(a, "(4,3,2):(1,4,12)", a, "(5,3,3):(1,5,15)", a, "(4,5,2):(1,4,20)")      # L differs in B
+    assert e.value.status_name == "SIZE_MISMATCH"
+    with pytest.raises(OracleError) as e:
+        oracle.gemm(a, "(4,3,2):(1,4,12)", a, "(5,3):(1,5)", a, "(4,5,2):(1,4,20)")            # ranks differ
+    assert e.value.status_name == "INVALID_ARG"
+    with pytest.raises(OracleError) as e:
+        oracle.gemm(a, "(4,3,2,2):(1,4,12,24)", a, "(5,3,2,2):(1,5,15,30)", a, "(4,5,2,2):(1,4,20,40)")   # rank 4
+    assert e.value.status_name == "INVALID_ARG"
