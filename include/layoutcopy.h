@@ -219,6 +219,9 @@ lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* c
  *     A over (M,K), B over (N,K), C over (M,N)
  * with M = size<0>(A) = size<0>(C), N = size<0>(B) = size<1>(C), K = size<1>(A) = size<1>(B) (the
  * preconditions of Sec. 2.6.2; SIZE_MISMATCH otherwise, INVALID_ARG for a layout that is not rank 2).
+ * Batched form (Sec. 1, the canonical contraction C(m,n,l) += A(m,k,l) * B(n,k,l)): all three layouts of rank 3,
+ * A over (M,K,L), B over (N,K,L), C over (M,N,L), the third modes of equal size L <= 65535 (a stride-0 batch
+ * mode shares one operand between all batch entries); the flop count is then 2 M N K L.
  * A and B hold bf16 or fp16 elements (`ab_dtype` = LC_BF16 / LC_F16, the same for both), C holds fp32;
  * products are exact and sums are accumulated in fp32, in an order that differs from the loop nest's
  * (the result is within K * 2^-23 * sum_k |A(m,k) B(n,k)| of the exactly accumulated value).
@@ -241,7 +244,7 @@ void lc_gemm_plan_destroy(lc_gemm_plan_t* plan);
 /* lc_gemm_plan_create (alignment taken from the pointers) + lc_gemm_plan_execute. */
 lc_status_t lc_gemm(const void* a, const lc_layout_t* a_layout, const void* b, const lc_layout_t* b_layout, void* c,
                     const lc_layout_t* c_layout, lc_dtype_t ab_dtype, void* hip_stream);
-int64_t lc_gemm_plan_flops(const lc_gemm_plan_t* plan); /* 2 M N K */
+int64_t lc_gemm_plan_flops(const lc_gemm_plan_t* plan); /* 2 M N K (L) */
 /* Mean milliseconds of `iters` back-to-back executions after `warmup` untimed ones, by HIP events on
  * `hip_stream`; synchronises the stream.  C accumulates across the executions. */
 lc_status_t lc_gemm_plan_time(const lc_gemm_plan_t* plan, const void* a, const void* b, void* c, int warmup, int iters,

@@ -46,7 +46,7 @@ lc_status_t lc_gemm_plan_describe(const lc_gemm_plan_t* plan, char* buf, size_t 
   if (!plan) return LC_ERR_INVALID_ARG;
   return put_text(lc::describe(*plan), buf, cap, needed);
 }
-int64_t lc_gemm_plan_flops(const lc_gemm_plan_t* plan) { return plan ? 2 * plan->M * plan->N * plan->K : -1; }
+int64_t lc_gemm_plan_flops(const lc_gemm_plan_t* plan) { return plan ? 2 * plan->M * plan->N * plan->K * plan->L : -1; }
 lc_status_t lc_gemm_plan_execute(const lc_gemm_plan_t* plan, const void* a, const void* b, void* c, void* hip_stream) {
   if (!plan) return LC_ERR_INVALID_ARG;
   return lc::execute_gemm_plan(*plan, a, b, c, hip_stream);

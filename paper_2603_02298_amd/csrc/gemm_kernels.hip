@@ -156,6 +156,10 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
   uint32_t tm, tn;
   gemm_tile_of_order(P, gemm_tile_order_of_block(blockIdx.x, P.tiles_m * P.tiles_n), &tm, &tn);
   const uint32_t m0 = tm * BM, n0 = tn * BN;
+  // batch entry (the third mode of the rank-3 form): slicing folds its offset into the three accessors (Sec. 2.5.1)
+  A += gemm_mode_eval(P.a_l, blockIdx.y);
+  B += gemm_mode_eval(P.b_l, blockIdx.y);
+  C += gemm_mode_eval(P.c_l, blockIdx.y);
 
   OperandLoader<BM, A_LOAD> la;
   OperandLoader<BN, B_LOAD> lb;
@@ -263,7 +267,7 @@ static hipError_t launch_gemm_ab(const lc_gemm_plan& plan, const uint16_t* a, co
     }
   }
   const unsigned grid = plan.params.tiles_m * plan.params.tiles_n;
-  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
+  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD>), dim3(grid, plan.params.L), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
   return hipSuccess;
 }
 // vector loads are compiled per pair of modes; an operand that needs element loads takes the other one along

@@ -43,7 +43,8 @@ LC_HD uint32_t gemm_mode_eval(const GemmMode& g, uint32_t i) {
 
 struct GemmParams {
   GemmMode a_r, a_k, b_r, b_k, c_m, c_n;   // A over (M,K), B over (N,K), C over (M,N)
-  uint32_t M, N, K;
+  GemmMode a_l, b_l, c_l;                  // batch modes of the rank-3 form (Sec. 1): "1:0" for plain matrices
+  uint32_t M, N, K, L;
   uint32_t tiles_m, tiles_n, k_tiles;
   int32_t a_load, b_load;                  // GemmLoad
   int32_t c_vec;                           // 1: four consecutive m are contiguous and 16-byte aligned in C

@@ -37,11 +37,15 @@ bool strides_aligned(const Modes& lead, const Modes& other, int64_t vec) {
   return true;
 }
 
-int classify_operand(const Modes& row, const Modes& k, unsigned align_bytes) {
+int classify_operand(const Modes& row, const Modes& k, const Modes& batch, unsigned align_bytes) {
+  auto plus_batch = [&](Modes other) {
+    other.insert(other.end(), batch.begin(), batch.end());
+    return other;
+  };
   if (align_bytes % 16 == 0) {
-    if (leads_contiguous(k, 8) && strides_aligned(k, row, 8)) return kLoadKVec;
+    if (leads_contiguous(k, 8) && strides_aligned(k, plus_batch(row), 8)) return kLoadKVec;
     // vectors along the row mode, eight of them (k .. k + 7) per block: k must step evenly inside a block
-    if (leads_contiguous(row, 8) && strides_aligned(row, k, 8) && k[0].extent % 8 == 0) return kLoadRVec;
+    if (leads_contiguous(row, 8) && strides_aligned(row, plus_batch(k), 8) && k[0].extent % 8 == 0) return kLoadRVec;
   }
   return kLoadElem;
 }
@@ -73,16 +77,22 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   for (const Layout* L : {&A_in, &B_in, &C_in}) {
     lc_status_t st = validate(*L);
     if (st != LC_OK) return st;
-    if (L->is_leaf() || L->rank() != 2) return LC_ERR_INVALID_ARG;   // matrices: shapes of rank 2 (Sec. 2.6.2)
+    // matrices: shapes of rank 2 (Sec. 2.6.2); or all three of rank 3: the batched form of Sec. 1
+    if (L->is_leaf() || (L->rank() != 2 && L->rank() != 3) || L->rank() != A_in.rank()) return LC_ERR_INVALID_ARG;
   }
   // preconditions of Sec. 2.6.2
   const int64_t M = A_in.mode(0).size(), K = A_in.mode(1).size(), N = B_in.mode(0).size();
   if (M != C_in.mode(0).size() || N != C_in.mode(1).size() || K != B_in.mode(1).size()) return LC_ERR_SIZE_MISMATCH;
+  const bool batched = A_in.rank() == 3;
+  const int64_t Lb = batched ? A_in.mode(2).size() : 1;
+  if (batched && (Lb != B_in.mode(2).size() || Lb != C_in.mode(2).size())) return LC_ERR_SIZE_MISMATCH;
+  if (Lb > 65535) return LC_ERR_TOO_LARGE;   // the batch index is the second grid dimension
   lc_gemm_plan plan;
   plan.ab_dtype = ab_dtype;
   plan.M = M;
   plan.N = N;
   plan.K = K;
+  plan.L = Lb;
   plan.a_cosize = A_in.cosize();
   plan.b_cosize = B_in.cosize();
   plan.c_cosize = C_in.cosize();
@@ -93,19 +103,27 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   Modes a_r = coalesce_modes(A_in.mode(0).leaves), a_k = coalesce_modes(A_in.mode(1).leaves);
   Modes b_r = coalesce_modes(B_in.mode(0).leaves), b_k = coalesce_modes(B_in.mode(1).leaves);
   Modes c_m = coalesce_modes(C_in.mode(0).leaves), c_n = coalesce_modes(C_in.mode(1).leaves);
+  const Modes unit = {{1, 0}};
+  Modes a_l = batched ? coalesce_modes(A_in.mode(2).leaves) : unit, b_l = batched ? coalesce_modes(B_in.mode(2).leaves) : unit;
+  Modes c_l = batched ? coalesce_modes(C_in.mode(2).leaves) : unit;
 
   // C must not alias: many lanes add into it concurrently
   {
     Modes all = c_m;
     all.insert(all.end(), c_n.begin(), c_n.end());
-    if (M * N > 1 && !layout_is_injective(all, M * N)) return LC_ERR_DST_ALIASES;
+    all.insert(all.end(), c_l.begin(), c_l.end());
+    if (M * N * Lb > 1 && !layout_is_injective(all, M * N * Lb)) return LC_ERR_DST_ALIASES;
   }
 
   // The MFMA result fragment holds four consecutive rows (m) per lane and column.  When C is
   // contiguous along n instead, the roles are exchanged: C^T(n,m) += B(n,k) A(m,k) is the same GEMM
   // with the operands swapped and C's modes exchanged (Table gemm, row "NTT").
+  auto with_batch = [](Modes other, const Modes& batch) {
+    other.insert(other.end(), batch.begin(), batch.end());
+    return other;
+  };
   auto c_vec_ok = [&](const Modes& lead, const Modes& other) {
-    return c_align % 16 == 0 && leads_contiguous(lead, 4) && strides_aligned(lead, other, 4);
+    return c_align % 16 == 0 && leads_contiguous(lead, 4) && strides_aligned(lead, with_batch(other, c_l), 4);
   };
   bool exchange = !c_vec_ok(c_m, c_n) && c_vec_ok(c_n, c_m);
   if (env_int("LC_TUNE_GEMM_EXCHANGE", -1) >= 0) exchange = env_int("LC_TUNE_GEMM_EXCHANGE", 0) != 0;
@@ -113,6 +131,7 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   if (exchange) {
     std::swap(a_r, b_r);
     std::swap(a_k, b_k);
+    std::swap(a_l, b_l);
     std::swap(c_m, c_n);
     std::swap(ka_align, kb_align);
   }
@@ -122,13 +141,15 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   GemmParams& P = plan.params;
   lc_status_t st;
   if ((st = fill_mode(a_r, &P.a_r)) != LC_OK || (st = fill_mode(a_k, &P.a_k)) != LC_OK || (st = fill_mode(b_r, &P.b_r)) != LC_OK ||
-      (st = fill_mode(b_k, &P.b_k)) != LC_OK || (st = fill_mode(c_m, &P.c_m)) != LC_OK || (st = fill_mode(c_n, &P.c_n)) != LC_OK)
+      (st = fill_mode(b_k, &P.b_k)) != LC_OK || (st = fill_mode(c_m, &P.c_m)) != LC_OK || (st = fill_mode(c_n, &P.c_n)) != LC_OK ||
+      (st = fill_mode(a_l, &P.a_l)) != LC_OK || (st = fill_mode(b_l, &P.b_l)) != LC_OK || (st = fill_mode(c_l, &P.c_l)) != LC_OK)
     return st;
   P.M = (uint32_t)kM;
   P.N = (uint32_t)kN;
   P.K = (uint32_t)K;
-  P.a_load = classify_operand(a_r, a_k, ka_align);
-  P.b_load = classify_operand(b_r, b_k, kb_align);
+  P.L = (uint32_t)Lb;
+  P.a_load = classify_operand(a_r, a_k, a_l, ka_align);
+  P.b_load = classify_operand(b_r, b_k, b_l, kb_align);
   const int force = env_int("LC_TUNE_GEMM_LOAD", -1);   // tests: force the element-wise loads
   // element loads are compiled for both operands together: one operand that needs them takes the other along
   if (force == kLoadElem || P.a_load == kLoadElem || P.b_load == kLoadElem) P.a_load = P.b_load = kLoadElem;
@@ -140,7 +161,7 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   plan.c_align = P.c_vec ? 16u : 4u;
 
   // tile: 256 x 256 when that still gives every CU a tile, else 128 x 128
-  int tile = ((kM + 255) / 256) * ((kN + 255) / 256) >= 256 ? 256 : 128;
+  int tile = ((kM + 255) / 256) * ((kN + 255) / 256) * Lb >= 256 ? 256 : 128;
   const int t_env = env_int("LC_TUNE_GEMM_TILE", 0);
   if (t_env == 128 || t_env == 256) tile = t_env;
   plan.tile_m = plan.tile_n = tile;
@@ -153,6 +174,11 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   plan.a_text = mode_text(a_r) + " x " + mode_text(a_k);
   plan.b_text = mode_text(b_r) + " x " + mode_text(b_k);
   plan.c_text = mode_text(c_m) + " x " + mode_text(c_n);
+  if (batched) {
+    plan.a_text += " x " + mode_text(a_l);
+    plan.b_text += " x " + mode_text(b_l);
+    plan.c_text += " x " + mode_text(c_l);
+  }
   *out = plan;
   return LC_OK;
 }
@@ -162,6 +188,7 @@ std::string describe(const lc_gemm_plan& plan) {
   std::string s = "class=gemm-mfma32x32x16 ab=";
   s += plan.ab_dtype == LC_BF16 ? "bf16" : "f16";
   s += " c=f32 M=" + std::to_string(plan.M) + " N=" + std::to_string(plan.N) + " K=" + std::to_string(plan.K);
+  if (plan.L != 1 || plan.a_text.find(" x ", plan.a_text.find(" x ") + 1) != std::string::npos) s += " L=" + std::to_string(plan.L);
   s += " exchanged=" + std::to_string((int)plan.exchanged);
   s += " tile=" + std::to_string(plan.tile_m) + "x" + std::to_string(plan.tile_n) + "x" + std::to_string(kGemmBK);
   s += " tiles=" + std::to_string(plan.params.tiles_m) + "x" + std::to_string(plan.params.tiles_n) + " k_tiles=" + std::to_string(plan.params.k_tiles);

@@ -7,7 +7,7 @@
 
 struct lc_gemm_plan {
   int ab_dtype = 0;                  // LC_BF16 or LC_F16 (A and B); C is fp32
-  int64_t M = 0, N = 0, K = 0;       // of the caller's problem
+  int64_t M = 0, N = 0, K = 0, L = 1; // of the caller's problem (L: batch entries of the rank-3 form)
   bool exchanged = false;            // the kernel computes C^T = B A^T: roles of A and B exchanged, C's modes exchanged
   int tile_m = 0, tile_n = 0;        // workgroup tile (kernel's m x n)
   lc::GemmParams params{};

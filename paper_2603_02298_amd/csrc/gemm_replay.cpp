@@ -105,6 +105,21 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
   std::vector<float> acc((size_t)BM * BN);
   std::vector<char> covered((size_t)P.tiles_m * P.tiles_n, 0);
   const uint32_t n_tiles = P.tiles_m * P.tiles_n;
+  const uint16_t* const a_all = w.A;
+  const uint16_t* const b_all = w.B;
+  float* const c_all = c;
+  const int64_t a_all_elems = w.a_elems, b_all_elems = w.b_elems, c_all_elems = c_elems;
+  for (uint32_t batch = 0; batch < P.L; ++batch) {
+  // the batch entry's offsets are folded into the three base pointers, as the kernel does with blockIdx.y
+  const uint32_t ao = gemm_mode_eval(P.a_l, batch), bo = gemm_mode_eval(P.b_l, batch), co = gemm_mode_eval(P.c_l, batch);
+  if (ao > a_all_elems || bo > b_all_elems || co > c_all_elems) return LC_ERR_INVALID_ARG;
+  w.A = a_all + ao;
+  w.B = b_all + bo;
+  w.a_elems = a_all_elems - ao;
+  w.b_elems = b_all_elems - bo;
+  c = c_all + co;
+  c_elems = c_all_elems - co;
+  std::fill(covered.begin(), covered.end(), 0);
   for (uint32_t block = 0; block < n_tiles; ++block) {
     uint32_t tm, tn;
     const uint32_t order = gemm_tile_order_of_block(block, n_tiles);
@@ -175,6 +190,7 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
           }
       }
     }
+  }
   }
   return LC_OK;
 }

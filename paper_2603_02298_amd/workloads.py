@@ -141,16 +141,16 @@ def source_bits(w, elems=None, chunk=1 << 24):
 # (Sec. 2.6.2): layouts as text, buffer sizes as plain numbers, seeded values.
 # ---------------------------------------------------------------------------------------------
 class GemmWorkload:
-    def __init__(self, name, ab_dtype, a_layout, b_layout, c_layout, a_elems, b_elems, c_elems, M, N, K, values="normal", note=""):
+    def __init__(self, name, ab_dtype, a_layout, b_layout, c_layout, a_elems, b_elems, c_elems, M, N, K, values="normal", note="", L=1):
         self.name, self.ab_dtype = name, ab_dtype
         self.a_layout, self.b_layout, self.c_layout = a_layout, b_layout, c_layout
         self.a_elems, self.b_elems, self.c_elems = a_elems, b_elems, c_elems
-        self.M, self.N, self.K = M, N, K
+        self.M, self.N, self.K, self.L = M, N, K, L
         self.values, self.note = values, note
 
     @property
     def flops(self):
-        return 2 * self.M * self.N * self.K
+        return 2 * self.M * self.N * self.K * self.L
 
 
 def gemm_workload(name, M=8192, N=8192, K=8192, ab_dtype="bf16", values="normal"):
@@ -176,6 +176,27 @@ def gemm_workload(name, M=8192, N=8192, K=8192, ab_dtype="bf16", values="normal"
         return GemmWorkload("gemm_blis_" + ab_dtype, ab_dtype, "(%d,%d):(%d,%d)" % (M, K, dma, dka), "(%d,%d):(%d,%d)" % (N, K, dnb, dkb),
                             "(%d,%d):(%d,%d)" % (M, N, dmc, dnc), dma * M + dka * K, dnb * N + dkb * K, dmc * M + dnc * N, M, N, K,
                             values, "BLIS-style general strides")
+    raise KeyError(name)
+
+
+def batched_gemm_workload(name, M, N, K, L, ab_dtype="bf16", values="normal"):
+    """Rank-3 layouts of the batched form C(m,n,l) += A(m,k,l) B(n,k,l)."""
+    if name == "strided_batch":   # the strided-batched BLAS extension: TN matrices one after the other, padded batch stride
+        sa, sb, sc = M * K + 8, N * K + 16, M * N + 4
+        return GemmWorkload("bgemm_strided_" + ab_dtype, ab_dtype, "(%d,%d,%d):(%d,1,%d)" % (M, K, L, K, sa),
+                            "(%d,%d,%d):(%d,1,%d)" % (N, K, L, K, sb), "(%d,%d,%d):(1,%d,%d)" % (M, N, L, M, sc),
+                            sa * L, sb * L, sc * L, M, N, K, values, "strided-batched TN GEMM", L)
+    if name == "shared_b":        # one B for every batch entry (stride-0 batch mode), A and C with the batch innermost of the rows
+        return GemmWorkload("bgemm_shared_b_" + ab_dtype, ab_dtype, "(%d,%d,%d):(1,%d,%d)" % (M, K, L, M * L, M),
+                            "(%d,%d,%d):(%d,1,0)" % (N, K, L, K), "(%d,%d,%d):(1,%d,%d)" % (M, N, L, M * L, M),
+                            M * K * L, N * K, M * N * L, M, N, K, values, "batch interleaved along the rows, B shared", L)
+    if name == "folded_batch":    # a GETT with two batch indices folded into one mode, general strides (element loads)
+        L1 = 2
+        L2 = L // L1
+        return GemmWorkload("bgemm_folded_" + ab_dtype, ab_dtype, "(%d,%d,(%d,%d)):(%d,1,(%d,%d))" % (M, K, L1, L2, K + 1, (K + 1) * M * L2, (K + 1) * M),
+                            "(%d,%d,(%d,%d)):(1,%d,(%d,%d))" % (N, K, L1, L2, N + 3, (N + 3) * K, (N + 3) * K * L1),
+                            "(%d,%d,(%d,%d)):(%d,1,(%d,%d))" % (M, N, L1, L2, N, M * N, M * N * L1),
+                            (K + 1) * M * L1 * L2, (N + 3) * K * L1 * L2, M * N * L1 * L2, M, N, K, values, "folded batch mode", L1 * L2)
     raise KeyError(name)
 
 

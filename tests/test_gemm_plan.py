@@ -76,6 +76,18 @@ def test_hierarchical_k_and_broadcast_operand(oracle):
     _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, ["exchanged=1"])
 
 
+@pytest.mark.parametrize("name,mnkl,expect", [
+    ("strided_batch", (136, 72, 40, 3), ["L=3", "a_load=k-vectors", "b_load=k-vectors", "c_vec=1"]),
+    ("shared_b", (64, 40, 24, 4), ["L=4", "a_load=row-vectors+transpose", "b_load=k-vectors", "c_vec=1"]),
+    ("folded_batch", (33, 20, 9, 6), ["L=6", "a_load=elements", "exchanged=1"]),
+])
+def test_walk_batched_matches_oracle(oracle, name, mnkl, expect):
+    # the batched form of Sec. 1: rank-3 layouts, the batch index is the second grid dimension
+    w = W.batched_gemm_workload(name, *mnkl, values="ints")
+    assert oracle.gemm_sizes(w.a_layout, w.b_layout, w.c_layout) == (w.M, w.N, w.K, w.L)
+    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, expect)
+
+
 def test_fragment_layouts_are_the_thread_value_layouts():
     a, b, c = (lc.lc_mfma_fragment_layout(i) for i in range(3))
     assert str(a) == "((32,2),8):((1,256),32)" and str(b) == str(a) and str(c) == "((32,2),(4,4)):((32,4),(1,8))"
@@ -100,6 +112,9 @@ def test_preconditions_and_refusals():
     assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,6):(1,4)") == "SIZE_MISMATCH"
     assert status("(4,3):(1,4)", "(5,2):(1,5)", "(4,5):(1,4)") == "SIZE_MISMATCH"
     assert status("12:1", "(5,3):(1,5)", "(4,5):(1,4)") == "INVALID_ARG"
+    assert status("(4,3,2):(1,4,12)", "(5,3):(1,5)", "(4,5,2):(1,4,20)") == "INVALID_ARG"            # ranks differ
+    assert status("(4,3,2):(1,4,12)", "(5,3,3):(1,5,15)", "(4,5,2):(1,4,20)") == "SIZE_MISMATCH"     # batch sizes differ
+    assert status("(4,3,2):(1,4,12)", "(5,3,2):(1,5,15)", "(4,5,2):(1,4,0)") == "DST_ALIASES"        # every batch entry into one C
     assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,5):(0,1)") == "DST_ALIASES"
     assert status("(4,3):(1,4)", "(5,3):(1,5)", "(4,5):(1,4)", "f32") == "UNSUPPORTED_DTYPE"
     assert status("(4,3):(1,%d)" % (1 << 30), "(5,3):(1,5)", "(4,5):(1,4)") == "TOO_LARGE"

@@ -124,6 +124,16 @@ def test_gemm_hierarchical_k_broadcast_and_accumulate(oracle):
     assert (c_t.cpu().numpy().astype(np.float64) == want).all()
 
 
+@pytest.mark.parametrize("values", ["ints", "normal"])
+@pytest.mark.parametrize("name,mnkl", [("strided_batch", (264, 136, 72, 5)), ("shared_b", (128, 300, 40, 4)),
+                                       ("folded_batch", (70, 45, 33, 6))])
+def test_batched_gemm(oracle, name, mnkl, values):
+    # the batched form of Sec. 1 (rank-3 layouts): strided batch, a shared (stride-0) operand, a folded batch mode
+    w = W.batched_gemm_workload(name, *mnkl, values=values)
+    desc = _parity(oracle, w)
+    assert "L=%d" % w.L in desc
+
+
 @pytest.mark.parametrize("name", ["tn", "nt"])
 def test_gemm_full_size_sampled(oracle, name):
     # the benchmark's problem (8192^3 bf16) in the launch configuration the bench times; the oracle
