@@ -9,8 +9,10 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "liblayoutcopy.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["layout.cpp", "algebra.cpp", "semimodule.cpp", "plan.cpp", "replay.cpp", "gemm_plan.cpp", "gemm_replay.cpp", "capi.cpp",
-           "gemm_capi.cpp", "kernels.hip", "gemm_kernels.hip"]
+           "gemm_capi.cpp", "kernels.hip", "gemm_kernels.hip", "gemm_inst_bf16_256.hip", "gemm_inst_bf16_128.hip",
+           "gemm_inst_f16_256.hip", "gemm_inst_f16_128.hip"]
 HEADERS = ["layout.hpp", "algebra.hpp", "semimodule.hpp", "plan.hpp", "kernel_params.hpp", "gemm_plan.hpp", "gemm_params.hpp"]
+KERNEL_HEADERS = {"gemm_kernel.hpp": "gemm_inst_"}   # header -> prefix of the only sources that include it
 
 
 def _hipcc():
@@ -38,6 +40,9 @@ def build(force=True):
     for s in SOURCES:
         obj = os.path.join(OBJ_DIR, s + ".o")
         src_time = max(newest_common, os.path.getmtime(os.path.join(CSRC, s)))
+        for header, prefix in KERNEL_HEADERS.items():
+            if s.startswith(prefix):
+                src_time = max(src_time, os.path.getmtime(os.path.join(CSRC, header)))
         if force or not os.path.exists(obj) or os.path.getmtime(obj) < src_time:
             todo.append(s)
     if todo:

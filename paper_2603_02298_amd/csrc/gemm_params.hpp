@@ -15,7 +15,10 @@ constexpr int kGemmBK = 64;         // k extent of a tile: 8 vectors of 8 sixtee
 enum GemmLoad : int32_t {
   kLoadKVec = 0,   // 16-byte vectors along k (k-mode leads with a stride-1 leaf): straight into place
   kLoadRVec = 1,   // 16-byte vectors along the row mode (m or n): 8x8 blocks transposed in registers
-  kLoadElem = 2    // element by element: any layout, any extent
+  kLoadElem = 2,   // element by element: any layout, any extent
+  // kLoadKVec without the registers: 16-byte vectors along k sent by the memory pipeline straight into LDS.  Needs whole
+  // k tiles (K a multiple of 64, each tile contiguous along k); chosen at launch, a plan still says kLoadKVec.
+  kLoadKDirect = 3
 };
 
 // One coalesced mode: integral coordinate -> offset in elements (all offsets of a GEMM operand fit 31 bits).
@@ -47,6 +50,7 @@ struct GemmParams {
   uint32_t M, N, K, L;
   uint32_t tiles_m, tiles_n, k_tiles;
   int32_t a_load, b_load;                  // GemmLoad
+  int32_t a_direct, b_direct;              // 1: the operand qualifies for kLoadKDirect
   int32_t c_vec;                           // 1: four consecutive m are contiguous and 16-byte aligned in C
   uint32_t group_m;                        // tile rows walked together before moving on along n
 };
@@ -95,6 +99,11 @@ LC_HD uint32_t gemm_lane_kvec(int32_t load, uint32_t lane) { return load == kLoa
 LC_HD uint32_t gemm_lane_row(int32_t load, uint32_t lane, uint32_t i) {
   return load == kLoadRVec ? ((lane & 7u) + 8u * (lane >> 6)) * 8u : (lane >> 3) + 32u * i;
 }
+// kLoadKDirect: instruction i of wavefront w fills the 1 KiB of LDS that holds rows 8 (w R + i) .. + 7 of the tile
+// (R = BR / 32 instructions per lane); lane l lands at byte 16 l of it, i.e. row + l / 8, slot l % 8, and therefore
+// asks for the k vector that lives in that slot: kv = slot ^ row ^ (row >> 3).
+LC_HD uint32_t gemm_direct_row(uint32_t rows_per_lane, uint32_t tid, uint32_t i) { return ((tid >> 6) * rows_per_lane + i) * 8u + ((tid & 63u) >> 3); }
+LC_HD uint32_t gemm_direct_kvec(uint32_t row, uint32_t tid) { return ((tid & 7u) ^ row ^ (row >> 3)) & 7u; }
 LC_HD uint32_t gemm_clamp_row(int32_t load, uint32_t row, uint32_t extent) {
   const uint32_t last = load == kLoadRVec ? extent - 8u : extent - 1u;
   return row < last ? row : last;

@@ -153,6 +153,10 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   const int force = env_int("LC_TUNE_GEMM_LOAD", -1);   // tests: force the element-wise loads
   // element loads are compiled for both operands together: one operand that needs them takes the other along
   if (force == kLoadElem || P.a_load == kLoadElem || P.b_load == kLoadElem) P.a_load = P.b_load = kLoadElem;
+  // straight into LDS: whole k tiles, each contiguous along k
+  auto direct_ok = [&](int load, const Modes& k) { return load == kLoadKVec && K % kGemmBK == 0 && k[0].extent % kGemmBK == 0; };
+  P.a_direct = direct_ok(P.a_load, a_k) && env_int("LC_TUNE_GEMM_DIRECT", 1) != 0 ? 1 : 0;
+  P.b_direct = direct_ok(P.b_load, b_k) && env_int("LC_TUNE_GEMM_DIRECT", 1) != 0 ? 1 : 0;
   P.c_vec = c_vec_ok(c_m, c_n) ? 1 : 0;
   if (env_int("LC_TUNE_GEMM_CVEC", 1) == 0) P.c_vec = 0;
   unsigned need_a = P.a_load == kLoadElem ? 2u : 16u, need_b = P.b_load == kLoadElem ? 2u : 16u;
@@ -193,7 +197,8 @@ std::string describe(const lc_gemm_plan& plan) {
   s += " tile=" + std::to_string(plan.tile_m) + "x" + std::to_string(plan.tile_n) + "x" + std::to_string(kGemmBK);
   s += " tiles=" + std::to_string(plan.params.tiles_m) + "x" + std::to_string(plan.params.tiles_n) + " k_tiles=" + std::to_string(plan.params.k_tiles);
   s += " group_m=" + std::to_string(plan.params.group_m);
-  s += std::string(" a_load=") + load_name[plan.params.a_load] + " b_load=" + load_name[plan.params.b_load];
+  s += std::string(" a_load=") + load_name[plan.params.a_load] + (plan.params.a_direct ? "(direct-to-LDS)" : "");
+  s += std::string(" b_load=") + load_name[plan.params.b_load] + (plan.params.b_direct ? "(direct-to-LDS)" : "");
   s += " c_vec=" + std::to_string(plan.params.c_vec) + " lds_bytes=" + std::to_string(plan.lds_bytes);
   s += " A=[" + plan.a_text + "] B=[" + plan.b_text + "] C=[" + plan.c_text + "]";
   return s;

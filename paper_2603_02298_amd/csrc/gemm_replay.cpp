@@ -39,6 +39,19 @@ struct Walker {
   // loads one operand tile of k tile kt into the LDS model, lane by lane
   void stage(const uint16_t* base, int64_t elems, const GemmMode& rmode, const GemmMode& kmode, int32_t load, uint32_t row0, uint32_t extent,
              uint32_t BR, uint32_t kt, unsigned char* tile) {
+    if (load == kLoadKDirect) {
+      // every lane's 16 bytes land at byte 16 * lane of the 1 KiB its wavefront's instruction i fills
+      const uint32_t rows_per_lane = BR / 32;
+      for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid)
+        for (uint32_t i = 0; i < rows_per_lane; ++i) {
+          const uint32_t row = gemm_direct_row(rows_per_lane, tid, i), kv = gemm_direct_kvec(row, tid);
+          const int64_t off = (int64_t)gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + row, extent)) + 8u * kv + gemm_mode_eval(kmode, kt * kGemmBK);
+          const uint32_t lds_at = ((tid >> 6) * rows_per_lane + i) * 1024u + (tid & 63u) * 16u;
+          if (off % 8 != 0 || off + 8 > elems || lds_at != gemm_lds_offset(row, kv) || kt * kGemmBK + 8u * kv + 8u > P.K) { ok = false; return; }
+          std::memcpy(tile + lds_at, base + off, 16);
+        }
+      return;
+    }
     for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
       const uint32_t kv = gemm_lane_kvec(load, tid), k0 = kt * kGemmBK + kv * 8u;
       if (load == kLoadRVec) {
@@ -130,8 +143,8 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
     const uint32_t m0 = tm * BM, n0 = tn * BN;
     std::fill(acc.begin(), acc.end(), 0.f);
     for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
-      w.stage(w.A, w.a_elems, P.a_r, P.a_k, P.a_load, m0, P.M, BM, kt, lds.data());
-      w.stage(w.B, w.b_elems, P.b_r, P.b_k, P.b_load, n0, P.N, BN, kt, lds.data() + BM * 128u);
+      w.stage(w.A, w.a_elems, P.a_r, P.a_k, P.a_direct ? (int32_t)kLoadKDirect : P.a_load, m0, P.M, BM, kt, lds.data());
+      w.stage(w.B, w.b_elems, P.b_r, P.b_k, P.b_direct ? (int32_t)kLoadKDirect : P.b_load, n0, P.N, BN, kt, lds.data() + BM * 128u);
       if (!w.ok) return LC_ERR_INVALID_ARG;
       for (uint32_t wave = 0; wave < 4; ++wave) {
         const uint32_t wm = wave & 1u, wn = wave >> 1;

@@ -50,6 +50,19 @@ def test_walk_matches_oracle(oracle, name, mnk, expect, tile):
     _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile}, expect + ["tile=%dx%d" % (tile, tile)])
 
 
+def test_walk_direct_to_lds_loads(oracle):
+    # whole k tiles (K a multiple of 64, contiguous along k): k-vector operands go straight into LDS; the walk checks
+    # that every lane's 16 bytes land in the slot the fragment reads expect
+    for name, mnk, pieces in (("tn", (200, 136, 128), ["a_load=k-vectors(direct-to-LDS)", "b_load=k-vectors(direct-to-LDS)"]),
+                              ("nn_rowmajor_c", (72, 140, 64), ["a_load=k-vectors(direct-to-LDS)", "b_load=row-vectors+transpose"])):
+        for tile in (128, 256):
+            w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values="ints")
+            _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile}, pieces)
+    w = W.gemm_workload("tn", 200, 136, 128, ab_dtype="bf16", values="ints")
+    text = _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
+    assert "direct" not in text
+
+
 def test_walk_f16_and_forced_element_loads(oracle):
     w = W.gemm_workload("tn", 130, 70, 40, ab_dtype="f16", values="ints")
     _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, ["ab=f16"])

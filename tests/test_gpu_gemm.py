@@ -80,6 +80,18 @@ def test_gemm_table_rows(oracle, name, mnk, tile, values):
     assert "tile=%dx%d" % (tile, tile) in desc
 
 
+@pytest.mark.parametrize("values", ["ints", "normal"])
+def test_gemm_direct_to_lds_loads(oracle, values):
+    # K a multiple of 64 and contiguous k tiles: k-vector operands bypass the registers on their way into LDS
+    for name, mnk in (("tn", (520, 392, 256)), ("nn_rowmajor_c", (264, 300, 128))):
+        for tile in (128, 256):
+            w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values=values)
+            assert "direct-to-LDS" in _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
+    w = W.gemm_workload("tn", 200, 136, 192, ab_dtype="f16", values=values)
+    assert "direct-to-LDS" in _parity(oracle, w)
+    assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
+
+
 def test_gemm_f16_and_element_loads(oracle):
     for values in ("ints", "normal"):
         w = W.gemm_workload("tn", 200, 136, 104, ab_dtype="f16", values=values)
