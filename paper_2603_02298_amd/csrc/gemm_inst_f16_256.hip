@@ -2,17 +2,17 @@
 #include "gemm_kernel.hpp"
 
 namespace lc {
-// every pair of load kinds the launcher can ask for (0 k-vectors, 1 row-vectors, 3 k-vectors straight into LDS; 2 elements),
-// instantiated explicitly: left to implicit instantiation through the launcher's chain of templates, some pairs stay undefined
+// every pair of load kinds the launcher can ask for (0 k-vectors, 1 row-vectors, 2 elements; 3 and 4: k-vectors and row-vectors
+// straight into LDS), instantiated explicitly: left to implicit instantiation through the launcher's chain of templates,
+// some pairs stay undefined
 template __global__ void gemm_kernel<false, 4, 4, 0, 0>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<false, 4, 4, 0, 1>(GemmParams, const uint16_t*, const uint16_t*, float*);
-template __global__ void gemm_kernel<false, 4, 4, 0, 3>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<false, 4, 4, 1, 0>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<false, 4, 4, 1, 1>(GemmParams, const uint16_t*, const uint16_t*, float*);
-template __global__ void gemm_kernel<false, 4, 4, 1, 3>(GemmParams, const uint16_t*, const uint16_t*, float*);
-template __global__ void gemm_kernel<false, 4, 4, 3, 0>(GemmParams, const uint16_t*, const uint16_t*, float*);
-template __global__ void gemm_kernel<false, 4, 4, 3, 1>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<false, 4, 4, 3, 3>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<false, 4, 4, 3, 4>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<false, 4, 4, 4, 3>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<false, 4, 4, 4, 4>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<false, 4, 4, 2, 2>(GemmParams, const uint16_t*, const uint16_t*, float*);
 
 hipError_t launch_gemm_f16_256(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {

@@ -56,6 +56,24 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
+// One 32 x 16 fragment's share of a lane from a k-major tile (row k of the tile = BR elements, see gemm_rdirect_lds_offset):
+// two LDS transpose loads (ds_read_b64_tr_b16) of k .. k + 3 and k + 4 .. k + 7; `at` is the lane's address for the
+// tile's first 16 k, kk the k step.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+// The restrict qualifier gives the load alias information once inlined; without any, the compiler makes every such load wait
+// for all direct loads in flight (they write LDS too), although those go to the other stage.
+__device__ __forceinline__ s16x4 lds_transpose_load(lds_s16x4* __restrict__ p) { return __builtin_amdgcn_ds_read_tr16_b64_v4i16(p); }
+template <int BR, typename KK>
+__device__ __forceinline__ u32x4 lds_read_tr_16x8(const unsigned char* at, KK kk) {
+  const unsigned char* p = at + (uint32_t)kk * 16u * (BR * 2u);
+  const s16x4 lo = lds_transpose_load((lds_s16x4*)(p));
+  const s16x4 hi = lds_transpose_load((lds_s16x4*)(p + 4u * (BR * 2u)));
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 l = __builtin_bit_cast(u32x2, lo), h = __builtin_bit_cast(u32x2, hi);
+  return u32x4{l[0], l[1], h[0], h[1]};
+}
+
 __device__ __forceinline__ u32x4 select_or_zero(bool keep, u32x4 v) {
   return u32x4{keep ? v[0] : 0u, keep ? v[1] : 0u, keep ? v[2] : 0u, keep ? v[3] : 0u};
 }
@@ -66,15 +84,16 @@ __device__ __forceinline__ u32x4 select_or_zero(bool keep, u32x4 v) {
 template <int BR, int LOAD>
 struct OperandLoader {
   static constexpr int ROWS = BR / 32;                                    // rows per lane for k-vector / element loads
-  static constexpr int NREG = LOAD == kLoadRVec ? 8 : (LOAD == kLoadKDirect ? 1 : ROWS);
+  static constexpr bool DIRECT = LOAD == kLoadKDirect || LOAD == kLoadRDirect;
+  static constexpr int NREG = LOAD == kLoadRVec ? 8 : (DIRECT ? 1 : ROWS);
   const uint16_t* base;
   uint32_t K, kv, row_in_tile;           // row_in_tile: first row of the lane (block row for row-vector loads)
   uint32_t rowoff[LOAD == kLoadRVec ? 1 : ROWS];
   bool active, k_inside;
   u32x4 regs[NREG];
 
-  __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, uint32_t row0, uint32_t extent, uint32_t Ktot,
-                                       uint32_t tid) {
+  __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, const GemmMode& kmode, uint32_t row0, uint32_t extent,
+                                       uint32_t Ktot, uint32_t tid) {
     base = p;
     K = Ktot;
     kv = gemm_lane_kvec(LOAD, tid);
@@ -87,9 +106,19 @@ struct OperandLoader {
 #pragma unroll
       for (int i = 0; i < ROWS; ++i) {
         const uint32_t row = gemm_direct_row(ROWS, tid, (uint32_t)i);
-        rowoff[i] = gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + row, extent)) + 8u * gemm_direct_kvec(row, tid);
+        rowoff[i] = 2u * (gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + row, extent)) + 8u * gemm_direct_kvec(row, tid));   // bytes
       }
-      row_in_tile = (tid >> 6) * ROWS * 8u;   // first row this wavefront fills
+      row_in_tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6)) * ROWS;   // the wavefront's first KiB of the tile (uniform)
+    } else if constexpr (LOAD == kLoadRDirect) {
+      // per instruction: offset of the 8 rows its slot holds plus that of the slot's k row (an even step of the k mode's
+      // first leaf from the tile's first k)
+#pragma unroll
+      for (int i = 0; i < ROWS; ++i) {
+        uint32_t k, row;
+        gemm_rdirect_unit(BR, ROWS, tid, (uint32_t)i, &k, &row);
+        rowoff[i] = 2u * (gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + row, extent)) + k * kmode.lead_stride);   // bytes
+      }
+      row_in_tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6)) * ROWS;   // the wavefront's first KiB of the tile (uniform)
     } else {
 #pragma unroll
       for (int i = 0; i < ROWS; ++i) rowoff[i] = gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + gemm_lane_row(LOAD, tid, (uint32_t)i), extent));
@@ -99,12 +128,14 @@ struct OperandLoader {
   // stage_tile: LDS byte offset of this operand's tile in the stage the k tile goes to (used by kLoadKDirect only)
   __device__ __forceinline__ void fetch(uint32_t kt, const GemmMode& kmode, uint32_t stage_tile) {
     const uint32_t k0 = kt * kGemmBK + kv * 8u;
-    if constexpr (LOAD == kLoadKDirect) {
+    if constexpr (DIRECT) {
       extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
-      const uint16_t* p = base + gemm_mode_eval(kmode, kt * kGemmBK);
+      // uniform base + 32-bit byte offset per lane (an operand is smaller than 2^31 elements); the LDS address is uniform
+      const unsigned char* p = reinterpret_cast<const unsigned char*>(base + gemm_mode_eval(kmode, kt * kGemmBK));
 #pragma unroll
       for (int i = 0; i < ROWS; ++i)
-        __builtin_amdgcn_global_load_lds(p + rowoff[i], reinterpret_cast<uint32_t*>(lds_bytes + stage_tile + (row_in_tile + 8u * (uint32_t)i) * 128u), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(p + rowoff[i]),
+                                         reinterpret_cast<uint32_t*>(lds_bytes + stage_tile + (row_in_tile + (uint32_t)i) * 1024u), 16, 0, 0);
     } else if constexpr (LOAD == kLoadKVec) {
       k_inside = k0 < K;
       const uint16_t* p = base + gemm_mode_eval(kmode, k_inside ? k0 : 0u);
@@ -140,7 +171,7 @@ struct OperandLoader {
   }
 
   __device__ __forceinline__ void park(unsigned char* tile) {
-    if constexpr (LOAD == kLoadKDirect) {
+    if constexpr (DIRECT) {
       (void)tile;   // already on its way into LDS
     } else if constexpr (LOAD == kLoadRVec) {
       if (active) {
@@ -183,8 +214,8 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
 
   OperandLoader<BM, A_LOAD> la;
   OperandLoader<BN, B_LOAD> lb;
-  la.init(A, P.a_r, m0, P.M, P.K, tid);
-  lb.init(B, P.b_r, n0, P.N, P.K, tid);
+  la.init(A, P.a_r, P.a_k, m0, P.M, P.K, tid);
+  lb.init(B, P.b_r, P.b_k, n0, P.N, P.K, tid);
 
   f32x16 acc[WMB][WNB];
   static_for<WMB>([&](auto i) {
@@ -194,55 +225,131 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     });
   });
 
-  constexpr bool ANY_DIRECT = A_LOAD == kLoadKDirect || B_LOAD == kLoadKDirect;
-  la.fetch(0, P.a_k, 0u);
-  lb.fetch(0, P.b_k, A_BYTES);
-  la.park(lds);
-  lb.park(lds + A_BYTES);
-  if constexpr (ANY_DIRECT) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's direct loads have landed in LDS
-  __syncthreads();
-
-  // Fragments are double-buffered in registers: those of k step kk + 1 are read from LDS while the MFMAs of
-  // step kk run (one wavefront per SIMD: nothing else would cover the LDS latency).
-  const uint32_t a_row = wm * (WMB * 32u) + mfma_ab_row(lane), b_row = wn * (WNB * 32u) + mfma_ab_row(lane);
-  u32x4 af[2][WMB], bf[2][WNB];
-  auto read_fragments = [&](const unsigned char* stage, auto kk, auto buf) {
-    const uint32_t kvec = 2u * (uint32_t)kk + mfma_ab_kvec(lane);
-    static_for<WMB>([&](auto i) { af[buf][i] = *reinterpret_cast<const u32x4*>(stage + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec)); });
-    static_for<WNB>([&](auto j) { bf[buf][j] = *reinterpret_cast<const u32x4*>(stage + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec)); });
-  };
+  constexpr bool A_DIRECT = A_LOAD == kLoadKDirect || A_LOAD == kLoadRDirect, B_DIRECT = B_LOAD == kLoadKDirect || B_LOAD == kLoadRDirect;
+  static_assert(A_DIRECT == B_DIRECT, "operands go straight into LDS as a pair");
   constexpr int KSTEPS = kGemmBK / 16;
-  read_fragments(lds, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-  for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
-    const unsigned char* cur = lds + (kt & 1u) * STAGE;
-    unsigned char* nxt = lds + ((kt & 1u) ^ 1u) * STAGE;
-    const bool more = kt + 1 < P.k_tiles;
-    const uint32_t nxt_offset = ((kt & 1u) ^ 1u) * STAGE;
-    if (more) {
-      la.fetch(kt + 1, P.a_k, nxt_offset);
-      lb.fetch(kt + 1, P.b_k, nxt_offset + A_BYTES);
-    }
-    static_for<KSTEPS>([&](auto kk) {
-      constexpr int buf = kk % 2;
-      if constexpr (kk + 1 < KSTEPS) read_fragments(cur, std::integral_constant<int, kk + 1>{}, std::integral_constant<int, buf ^ 1>{});
-      static_for<WMB>([&](auto i) {
-        static_for<WNB>([&](auto j) { acc[i][j] = mfma_32x32x16<BF16>(af[buf][i], bf[buf][j], acc[i][j]); });
-      });
-      if constexpr (kk + 1 < KSTEPS) {
-        // issue order: one LDS read, then two MFMAs, repeated
-        static_for<WMB + WNB>([&](auto) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x008, (WMB * WNB) / (WMB + WNB), 0);
-        });
-      }
+  // LDS read instructions per k step: two transpose loads, or one 16-byte load, per fragment
+  constexpr int DS_READS = WMB * (A_LOAD == kLoadRDirect ? 2 : 1) + WNB * (B_LOAD == kLoadRDirect ? 2 : 1);
+  u32x4 af[2][WMB], bf[2][WNB];   // fragments, double-buffered in registers (one wavefront per SIMD: nothing else covers the LDS latency)
+  auto multiply = [&](auto buf) {
+    static_for<WMB>([&](auto i) {
+      static_for<WNB>([&](auto j) { acc[i][j] = mfma_32x32x16<BF16>(af[buf][i], bf[buf][j], acc[i][j]); });
     });
-    if (more) {
-      la.park(nxt);
-      lb.park(nxt + A_BYTES);
-    }
-    if constexpr (ANY_DIRECT) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) before telling the others the stage is complete
+  };
+
+  if constexpr (A_DIRECT) {
+    // Both tiles arrive by direct loads: no registers are held for them, so the loop is one basic block, software-pipelined
+    // around a single barrier per k tile.  Stage kt % 2 holds k tile kt.  After the MFMAs of k step 2 are issued every
+    // wavefront has read its last fragments of the stage; past the barrier the stage is free for k tile kt + 2, whose loads
+    // are issued at once, and k tile kt + 1 (loaded a whole tile earlier) is complete: its first fragments are read while
+    // the MFMAs of k step 3 run.  Past the last k tile the loads repeat it (in bounds, into a stage nobody reads again).
+    static_assert((STAGE & (STAGE - 1)) == 0, "stages are told apart by one address bit");
+    // per fragment: the lane's LDS address for the tile's first k step in the current stage.  Row-major tiles: k step kk
+    // flips slot bits (address ^ 32 kk); k-major tiles: k step kk is a constant offset.
+    uint32_t a_fr[WMB], b_fr[WNB];
+    static_for<WMB>([&](auto i) {
+      const uint32_t row = wm * (WMB * 32u) + 32u * (uint32_t)i;
+      a_fr[i] = A_LOAD == kLoadRDirect ? gemm_rdirect_frag_offset(BM, lane, row, 8u * mfma_ab_kvec(lane))
+                                       : gemm_lds_offset(row + mfma_ab_row(lane), mfma_ab_kvec(lane));
+    });
+    static_for<WNB>([&](auto j) {
+      const uint32_t row = wn * (WNB * 32u) + 32u * (uint32_t)j;
+      b_fr[j] = A_BYTES + (B_LOAD == kLoadRDirect ? gemm_rdirect_frag_offset(BN, lane, row, 8u * mfma_ab_kvec(lane))
+                                                  : gemm_lds_offset(row + mfma_ab_row(lane), mfma_ab_kvec(lane)));
+    });
+    auto read_fragments = [&](auto kk, auto buf) {
+      static_for<WMB>([&](auto i) {
+        if constexpr (A_LOAD == kLoadRDirect) af[buf][i] = lds_read_tr_16x8<BM>(lds + a_fr[i], kk);
+        else af[buf][i] = *reinterpret_cast<const u32x4*>(lds + (a_fr[i] ^ (32u * (uint32_t)kk)));
+      });
+      static_for<WNB>([&](auto j) {
+        if constexpr (B_LOAD == kLoadRDirect) bf[buf][j] = lds_read_tr_16x8<BN>(lds + b_fr[j], kk);
+        else bf[buf][j] = *reinterpret_cast<const u32x4*>(lds + (b_fr[j] ^ (32u * (uint32_t)kk)));
+      });
+    };
+    const uint32_t last = P.k_tiles - 1u;
+    la.fetch(0, P.a_k, 0u);
+    lb.fetch(0, P.b_k, A_BYTES);
+    la.fetch(last < 1u ? last : 1u, P.a_k, STAGE);
+    lb.fetch(last < 1u ? last : 1u, P.b_k, STAGE + A_BYTES);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's direct loads have landed in LDS
     __syncthreads();
-    if (more) read_fragments(nxt, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    constexpr int VM_LOADS = (BM + BN) / 32, MFMAS = WMB * WNB;
+    for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
+      static_for<KSTEPS - 1>([&](auto kk) {
+        constexpr int buf = kk % 2;
+        read_fragments(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, buf ^ 1>{});
+        multiply(std::integral_constant<int, buf>{});
+        // issue order: the LDS reads spread evenly between the MFMAs
+        static_for<MFMAS>([&](auto g) {
+          constexpr int reads = DS_READS * (g + 1) / MFMAS - DS_READS * g / MFMAS;
+          if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        });
+      });
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) before telling the others that the next stage is complete
+      __syncthreads();
+      const uint32_t kt2 = kt + 2u < last ? kt + 2u : last, stage_off = (kt & 1u) * STAGE;
+      la.fetch(kt2, P.a_k, stage_off);
+      lb.fetch(kt2, P.b_k, stage_off + A_BYTES);
+      static_for<WMB>([&](auto i) { a_fr[i] ^= STAGE; });
+      static_for<WNB>([&](auto j) { b_fr[j] ^= STAGE; });
+      read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+      multiply(std::integral_constant<int, (KSTEPS - 1) % 2>{});
+      // issue order: the direct loads and the LDS reads spread evenly between the MFMAs
+      static_for<MFMAS>([&](auto g) {
+        constexpr int loads = VM_LOADS * (g + 1) / MFMAS - VM_LOADS * g / MFMAS;
+        constexpr int reads = DS_READS * (g + 1) / MFMAS - DS_READS * g / MFMAS;
+        if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);
+        if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      });
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // the repeated loads of the last k tile end before the wavefront does
+  } else {
+    la.fetch(0, P.a_k, 0u);
+    lb.fetch(0, P.b_k, A_BYTES);
+    la.park(lds);
+    lb.park(lds + A_BYTES);
+    __syncthreads();
+
+    // The loads of k tile kt + 1 are issued before the MFMAs of k tile kt and parked after them; the fragments of k step
+    // kk + 1 are read from LDS while the MFMAs of step kk run.
+    const uint32_t a_row = wm * (WMB * 32u) + mfma_ab_row(lane), b_row = wn * (WNB * 32u) + mfma_ab_row(lane);
+    auto read_fragments = [&](const unsigned char* stage, auto kk, auto buf) {
+      const uint32_t kvec = 2u * (uint32_t)kk + mfma_ab_kvec(lane);
+      static_for<WMB>([&](auto i) { af[buf][i] = *reinterpret_cast<const u32x4*>(stage + gemm_lds_offset(a_row + 32u * (uint32_t)i, kvec)); });
+      static_for<WNB>([&](auto j) { bf[buf][j] = *reinterpret_cast<const u32x4*>(stage + A_BYTES + gemm_lds_offset(b_row + 32u * (uint32_t)j, kvec)); });
+    };
+    read_fragments(lds, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
+      const unsigned char* cur = lds + (kt & 1u) * STAGE;
+      unsigned char* nxt = lds + ((kt & 1u) ^ 1u) * STAGE;
+      const bool more = kt + 1 < P.k_tiles;
+      if (more) {
+        la.fetch(kt + 1, P.a_k, 0u);
+        lb.fetch(kt + 1, P.b_k, 0u);
+      }
+      static_for<KSTEPS>([&](auto kk) {
+        constexpr int buf = kk % 2;
+        if constexpr (kk + 1 < KSTEPS) read_fragments(cur, std::integral_constant<int, kk + 1>{}, std::integral_constant<int, buf ^ 1>{});
+        multiply(std::integral_constant<int, buf>{});
+        if constexpr (kk + 1 < KSTEPS) {
+          // issue order: one LDS read, then two MFMAs, repeated
+          static_for<WMB + WNB>([&](auto) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, (WMB * WNB) / (WMB + WNB), 0);
+          });
+        }
+      });
+      if (more) {
+        la.park(nxt);
+        lb.park(nxt + A_BYTES);
+      }
+      __syncthreads();
+      if (more) read_fragments(nxt, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    }
   }
 
   // C(m,n) += acc: a lane holds column n = lane % 32 of each fragment and 4 groups of 4 consecutive rows
@@ -290,23 +397,21 @@ static inline hipError_t launch_gemm_ab(const lc_gemm_plan& plan, const uint16_t
   return hipSuccess;
 }
 // vector loads are compiled per pair of modes; an operand that needs element loads takes the other one along.
-// A k-vector operand goes straight into LDS (kLoadKDirect) when the plan says it qualifies.
-template <bool BF16, int WB, int A_LOAD>
+// Operands that go straight into LDS do so as a pair (the planner marks both or neither).
+template <bool BF16, int WB, int A_LOAD, int FIRST, int SECOND>
 static inline hipError_t launch_gemm_a(const lc_gemm_plan& plan, int lb, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
-  if (lb == kLoadKDirect) return launch_gemm_ab<BF16, WB, A_LOAD, kLoadKDirect>(plan, a, b, c, s);
-  if (lb == kLoadKVec) return launch_gemm_ab<BF16, WB, A_LOAD, kLoadKVec>(plan, a, b, c, s);
-  if (lb == kLoadRVec) return launch_gemm_ab<BF16, WB, A_LOAD, kLoadRVec>(plan, a, b, c, s);
+  if (lb == FIRST) return launch_gemm_ab<BF16, WB, A_LOAD, FIRST>(plan, a, b, c, s);
+  if (lb == SECOND) return launch_gemm_ab<BF16, WB, A_LOAD, SECOND>(plan, a, b, c, s);
   return hipErrorInvalidValue;
 }
 template <bool BF16, int WB>
 static inline hipError_t launch_gemm(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
-  int la = plan.params.a_load, lb = plan.params.b_load;
+  const int la = gemm_effective_load(plan.params.a_load, plan.params.a_direct), lb = gemm_effective_load(plan.params.b_load, plan.params.b_direct);
   if (la == kLoadElem && lb == kLoadElem) return launch_gemm_ab<BF16, WB, kLoadElem, kLoadElem>(plan, a, b, c, s);
-  if (la == kLoadKVec && plan.params.a_direct) la = kLoadKDirect;
-  if (lb == kLoadKVec && plan.params.b_direct) lb = kLoadKDirect;
-  if (la == kLoadKDirect) return launch_gemm_a<BF16, WB, kLoadKDirect>(plan, lb, a, b, c, s);
-  if (la == kLoadKVec) return launch_gemm_a<BF16, WB, kLoadKVec>(plan, lb, a, b, c, s);
-  if (la == kLoadRVec) return launch_gemm_a<BF16, WB, kLoadRVec>(plan, lb, a, b, c, s);
+  if (la == kLoadKDirect) return launch_gemm_a<BF16, WB, kLoadKDirect, kLoadKDirect, kLoadRDirect>(plan, lb, a, b, c, s);
+  if (la == kLoadRDirect) return launch_gemm_a<BF16, WB, kLoadRDirect, kLoadKDirect, kLoadRDirect>(plan, lb, a, b, c, s);
+  if (la == kLoadKVec) return launch_gemm_a<BF16, WB, kLoadKVec, kLoadKVec, kLoadRVec>(plan, lb, a, b, c, s);
+  if (la == kLoadRVec) return launch_gemm_a<BF16, WB, kLoadRVec, kLoadKVec, kLoadRVec>(plan, lb, a, b, c, s);
   return hipErrorInvalidValue;
 }
 

@@ -18,7 +18,10 @@ enum GemmLoad : int32_t {
   kLoadElem = 2,   // element by element: any layout, any extent
   // kLoadKVec without the registers: 16-byte vectors along k sent by the memory pipeline straight into LDS.  Needs whole
   // k tiles (K a multiple of 64, each tile contiguous along k); chosen at launch, a plan still says kLoadKVec.
-  kLoadKDirect = 3
+  kLoadKDirect = 3,
+  // kLoadRVec without the registers: the tile goes into LDS as it lies in memory (k rows of BR contiguous elements) and the
+  // fragments are read with the LDS transpose load (ds_read_b64_tr_b16).  Same conditions; a plan still says kLoadRVec.
+  kLoadRDirect = 4
 };
 
 // One coalesced mode: integral coordinate -> offset in elements (all offsets of a GEMM operand fit 31 bits).
@@ -50,10 +53,16 @@ struct GemmParams {
   uint32_t M, N, K, L;
   uint32_t tiles_m, tiles_n, k_tiles;
   int32_t a_load, b_load;                  // GemmLoad
-  int32_t a_direct, b_direct;              // 1: the operand qualifies for kLoadKDirect
+  int32_t a_direct, b_direct;              // 1: the operand goes straight into LDS (kLoadKVec -> kLoadKDirect, kLoadRVec -> kLoadRDirect)
   int32_t c_vec;                           // 1: four consecutive m are contiguous and 16-byte aligned in C
   uint32_t group_m;                        // tile rows walked together before moving on along n
 };
+
+// the load the kernel runs for an operand the plan classified as `load`
+LC_HD int32_t gemm_effective_load(int32_t load, int32_t direct) {
+  if (!direct) return load;
+  return load == kLoadKVec ? (int32_t)kLoadKDirect : (load == kLoadRVec ? (int32_t)kLoadRDirect : load);
+}
 
 // ---------------------------------------------------------------------------------------------
 // Workgroup -> tile.  Workgroups are handed to the 8 XCDs round-robin and every XCD has its own L2,
@@ -99,13 +108,36 @@ LC_HD uint32_t gemm_lane_kvec(int32_t load, uint32_t lane) { return load == kLoa
 LC_HD uint32_t gemm_lane_row(int32_t load, uint32_t lane, uint32_t i) {
   return load == kLoadRVec ? ((lane & 7u) + 8u * (lane >> 6)) * 8u : (lane >> 3) + 32u * i;
 }
+// ---------------------------------------------------------------------------------------------
+// kLoadRDirect: the operand tile in LDS is k-major: row k holds the BR elements (BR / 8 slots of 16 bytes) of that k,
+// the 8-element group g of the row mode in slot g ^ 4 (k % 4).  A transpose load of 16 lanes reads 16 rows x 4 k
+// (4 k rows x 32 bytes); with this XOR layout (Sec. 2.3.2) the two lane groups that share a pass (rows 0..15 and
+// 16..31 of a fragment) and their 4 k rows touch 16 distinct 16-byte bank groups.
+// ---------------------------------------------------------------------------------------------
+LC_HD uint32_t gemm_rdirect_lds_offset(uint32_t BR, uint32_t k, uint32_t row) { return k * (BR * 2u) + ((((row >> 3) ^ (4u * (k & 3u)))) << 4) + (row & 7u) * 2u; }
+// Instruction i of wavefront w fills 1 KiB = 64 slots; lane l's slot is unit (w R + i) 64 + l of the tile: its k row and
+// the 8-row group it must ask memory for.
+LC_HD void gemm_rdirect_unit(uint32_t BR, uint32_t rows_per_lane, uint32_t tid, uint32_t i, uint32_t* k, uint32_t* row) {
+  const uint32_t unit = ((tid >> 6) * rows_per_lane + i) * 64u + (tid & 63u), slots = BR / 8u;
+  *k = unit / slots;
+  *row = ((unit % slots) ^ (4u * (*k & 3u))) * 8u;
+}
+// ds_read_b64_tr_b16 (checked on the GPU with an in-bounds probe): within each group of 16 lanes, result lane i element e
+// is element i % 4 of the 8 bytes that lane 4 e + i / 4 of the group points at.  Lane j of a group therefore points at
+// rows 4 (j % 4) .. + 3 of its group's 16 rows, at k step j / 4 of the 4: lane i then holds row i at k .. k + 3.
+// Byte offset (inside the operand's tile) for fragment rows row_base .. row_base + 31, k = k_base .. k_base + 3:
+LC_HD uint32_t gemm_rdirect_frag_offset(uint32_t BR, uint32_t lane, uint32_t row_base, uint32_t k_base) {
+  const uint32_t j = lane & 15u;
+  return gemm_rdirect_lds_offset(BR, k_base + (j >> 2), row_base + 16u * ((lane >> 4) & 1u) + 4u * (j & 3u));
+}
+
 // kLoadKDirect: instruction i of wavefront w fills the 1 KiB of LDS that holds rows 8 (w R + i) .. + 7 of the tile
 // (R = BR / 32 instructions per lane); lane l lands at byte 16 l of it, i.e. row + l / 8, slot l % 8, and therefore
 // asks for the k vector that lives in that slot: kv = slot ^ row ^ (row >> 3).
 LC_HD uint32_t gemm_direct_row(uint32_t rows_per_lane, uint32_t tid, uint32_t i) { return ((tid >> 6) * rows_per_lane + i) * 8u + ((tid & 63u) >> 3); }
 LC_HD uint32_t gemm_direct_kvec(uint32_t row, uint32_t tid) { return ((tid & 7u) ^ row ^ (row >> 3)) & 7u; }
 LC_HD uint32_t gemm_clamp_row(int32_t load, uint32_t row, uint32_t extent) {
-  const uint32_t last = load == kLoadRVec ? extent - 8u : extent - 1u;
+  const uint32_t last = load == kLoadRVec || load == kLoadRDirect ? extent - 8u : extent - 1u;
   return row < last ? row : last;
 }
 

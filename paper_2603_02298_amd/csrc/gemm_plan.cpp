@@ -154,9 +154,13 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   // element loads are compiled for both operands together: one operand that needs them takes the other along
   if (force == kLoadElem || P.a_load == kLoadElem || P.b_load == kLoadElem) P.a_load = P.b_load = kLoadElem;
   // straight into LDS: whole k tiles, each contiguous along k
-  auto direct_ok = [&](int load, const Modes& k) { return load == kLoadKVec && K % kGemmBK == 0 && k[0].extent % kGemmBK == 0; };
-  P.a_direct = direct_ok(P.a_load, a_k) && env_int("LC_TUNE_GEMM_DIRECT", 1) != 0 ? 1 : 0;
-  P.b_direct = direct_ok(P.b_load, b_k) && env_int("LC_TUNE_GEMM_DIRECT", 1) != 0 ? 1 : 0;
+  // (for row vectors: each of the tile's 64 k rows one even step of the k mode's first leaf from the tile's first);
+  // compiled for pairs of operands that both qualify
+  auto direct_ok = [&](int load, const Modes& k) { return load != kLoadElem && K % kGemmBK == 0 && k[0].extent % kGemmBK == 0; };
+  const int direct_env = env_int("LC_TUNE_GEMM_DIRECT", 3);   // bit 0: k vectors, bit 1: row vectors
+  auto direct_on = [&](int load) { return (direct_env & (load == kLoadKVec ? 1 : 2)) != 0; };
+  const bool direct = direct_ok(P.a_load, a_k) && direct_ok(P.b_load, b_k) && direct_on(P.a_load) && direct_on(P.b_load);
+  P.a_direct = P.b_direct = direct ? 1 : 0;
   P.c_vec = c_vec_ok(c_m, c_n) ? 1 : 0;
   if (env_int("LC_TUNE_GEMM_CVEC", 1) == 0) P.c_vec = 0;
   unsigned need_a = P.a_load == kLoadElem ? 2u : 16u, need_b = P.b_load == kLoadElem ? 2u : 16u;

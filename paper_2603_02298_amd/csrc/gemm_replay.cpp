@@ -52,6 +52,27 @@ struct Walker {
         }
       return;
     }
+    if (load == kLoadRDirect) {
+      // k-major tile: lane l of instruction i of wavefront w fills 16-byte unit (w R + i) 64 + l
+      const uint32_t rows_per_lane = BR / 32;
+      if (P.K % kGemmBK != 0) { ok = false; return; }
+      for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid)
+        for (uint32_t i = 0; i < rows_per_lane; ++i) {
+          uint32_t k, row;
+          gemm_rdirect_unit(BR, rows_per_lane, tid, i, &k, &row);
+          const int64_t off = (int64_t)gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + row, extent)) + (int64_t)k * kmode.lead_stride +
+                              gemm_mode_eval(kmode, kt * kGemmBK);
+          const uint32_t lds_at = ((tid >> 6) * rows_per_lane + i) * 1024u + (tid & 63u) * 16u;
+          // the k row's offset is what the k mode's layout function gives, and the slot is the one fragment reads expect
+          if (k >= (uint32_t)kGemmBK || row + 8 > BR || off % 8 != 0 || off + 8 > elems || lds_at != gemm_rdirect_lds_offset(BR, k, row) ||
+              (int64_t)k * kmode.lead_stride + gemm_mode_eval(kmode, kt * kGemmBK) != (int64_t)gemm_mode_eval(kmode, kt * kGemmBK + k)) {
+            ok = false;
+            return;
+          }
+          std::memcpy(tile + lds_at, base + off, 16);
+        }
+      return;
+    }
     for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
       const uint32_t kv = gemm_lane_kvec(load, tid), k0 = kt * kGemmBK + kv * 8u;
       if (load == kLoadRVec) {
@@ -96,6 +117,26 @@ struct Walker {
       }
     }
   }
+
+  // What a wavefront's lanes receive for one 32 x 16 fragment (rows row_base .. + 31 of the operand tile, k step kk):
+  // out[lane][v], v < 8.  Row-major tiles: one 16-byte read per lane.  k-major tiles: two LDS transpose loads
+  // (ds_read_b64_tr_b16), whose definition is applied here to the addresses the lanes present: within each group of
+  // 16 lanes, lane i's element e is element i % 4 of the 8 bytes lane 4 e + i / 4 points at.
+  void fragment(const unsigned char* tile, int32_t load, uint32_t BR, uint32_t row_base, uint32_t kk, uint16_t (*out)[8]) {
+    for (uint32_t lane = 0; lane < 64; ++lane) {
+      if (load != kLoadRDirect) {
+        std::memcpy(out[lane], tile + gemm_lds_offset(row_base + mfma_ab_row(lane), 2u * kk + mfma_ab_kvec(lane)), 16);
+        continue;
+      }
+      for (uint32_t h = 0; h < 2; ++h)
+        for (uint32_t e = 0; e < 4; ++e) {
+          const uint32_t src_lane = (lane & ~15u) + 4u * e + (lane & 15u) / 4u;
+          const uint32_t at = gemm_rdirect_frag_offset(BR, src_lane, row_base, 16u * kk + 8u * mfma_ab_kvec(src_lane) + 4u * h);
+          if (at % 8 != 0 || at + 8 > BR * 128u) { ok = false; return; }
+          std::memcpy(&out[lane][4 * h + e], tile + at + 2u * (lane & 3u), 2);
+        }
+    }
+  }
 };
 
 }  // namespace
@@ -118,6 +159,7 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
   std::vector<float> acc((size_t)BM * BN);
   std::vector<char> covered((size_t)P.tiles_m * P.tiles_n, 0);
   const uint32_t n_tiles = P.tiles_m * P.tiles_n;
+  const int32_t a_kind = gemm_effective_load(P.a_load, P.a_direct), b_kind = gemm_effective_load(P.b_load, P.b_direct);
   const uint16_t* const a_all = w.A;
   const uint16_t* const b_all = w.B;
   float* const c_all = c;
@@ -143,8 +185,8 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
     const uint32_t m0 = tm * BM, n0 = tn * BN;
     std::fill(acc.begin(), acc.end(), 0.f);
     for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
-      w.stage(w.A, w.a_elems, P.a_r, P.a_k, P.a_direct ? (int32_t)kLoadKDirect : P.a_load, m0, P.M, BM, kt, lds.data());
-      w.stage(w.B, w.b_elems, P.b_r, P.b_k, P.b_direct ? (int32_t)kLoadKDirect : P.b_load, n0, P.N, BN, kt, lds.data() + BM * 128u);
+      w.stage(w.A, w.a_elems, P.a_r, P.a_k, a_kind, m0, P.M, BM, kt, lds.data());
+      w.stage(w.B, w.b_elems, P.b_r, P.b_k, b_kind, n0, P.N, BN, kt, lds.data() + BM * 128u);
       if (!w.ok) return LC_ERR_INVALID_ARG;
       for (uint32_t wave = 0; wave < 4; ++wave) {
         const uint32_t wm = wave & 1u, wn = wave >> 1;
@@ -153,17 +195,16 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
             for (uint32_t j = 0; j < WNB; ++j) {
               // gather the two 32 x 16 fragments from the lanes' LDS reads, through the thread-value layouts
               float fa[32][16], fb[32][16];
-              for (uint32_t lane = 0; lane < 64; ++lane) {
-                const uint32_t kvec = 2u * kk + mfma_ab_kvec(lane);
-                uint16_t va[8], vb[8];
-                std::memcpy(va, lds.data() + gemm_lds_offset(wm * WMB * 32u + 32u * i + mfma_ab_row(lane), kvec), 16);
-                std::memcpy(vb, lds.data() + BM * 128u + gemm_lds_offset(wn * WNB * 32u + 32u * j + mfma_ab_row(lane), kvec), 16);
+              uint16_t va[64][8], vb[64][8];
+              w.fragment(lds.data(), a_kind, BM, wm * WMB * 32u + 32u * i, kk, va);
+              w.fragment(lds.data() + BM * 128u, b_kind, BN, wn * WNB * 32u + 32u * j, kk, vb);
+              if (!w.ok) return LC_ERR_INVALID_ARG;
+              for (uint32_t lane = 0; lane < 64; ++lane)
                 for (uint32_t v = 0; v < 8; ++v) {
                   const int64_t ca = tv_a((int64_t)lane + 64 * v), cb = tv_b((int64_t)lane + 64 * v);   // row + 32 k
-                  fa[ca % 32][ca / 32] = to_float(va[v]);
-                  fb[cb % 32][cb / 32] = to_float(vb[v]);
+                  fa[ca % 32][ca / 32] = to_float(va[lane][v]);
+                  fb[cb % 32][cb / 32] = to_float(vb[lane][v]);
                 }
-              }
               // D = A B^T + D, then back to the lanes' accumulators through the C fragment layout
               for (uint32_t lane = 0; lane < 64; ++lane)
                 for (uint32_t v = 0; v < 16; ++v) {

@@ -51,16 +51,25 @@ def test_walk_matches_oracle(oracle, name, mnk, expect, tile):
 
 
 def test_walk_direct_to_lds_loads(oracle):
-    # whole k tiles (K a multiple of 64, contiguous along k): k-vector operands go straight into LDS; the walk checks
-    # that every lane's 16 bytes land in the slot the fragment reads expect
-    for name, mnk, pieces in (("tn", (200, 136, 128), ["a_load=k-vectors(direct-to-LDS)", "b_load=k-vectors(direct-to-LDS)"]),
-                              ("nn_rowmajor_c", (72, 140, 64), ["a_load=k-vectors(direct-to-LDS)", "b_load=row-vectors+transpose"])):
+    # whole k tiles (K a multiple of 64, k tiles one leaf of the k mode): vector operands go straight into LDS, k-vector
+    # tiles row-major, row-vector tiles k-major and read back with the LDS transpose load; the walk checks that every
+    # lane's 16 bytes land in the slot the fragment reads expect, and applies the transpose load's definition
+    kd, rd = "k-vectors(direct-to-LDS)", "row-vectors+transpose(direct-to-LDS)"
+    for name, mnk, pieces in (("tn", (200, 136, 128), ["a_load=" + kd, "b_load=" + kd]),
+                              ("nt", (136, 264, 128), ["a_load=" + rd, "b_load=" + rd]),
+                              ("nn_rowmajor_c", (72, 140, 64), ["a_load=" + kd, "b_load=" + rd]),
+                              ("gett", (192, 100, 64), ["a_load=" + rd, "b_load=" + kd])):
         for tile in (128, 256):
             w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values="ints")
             _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile}, pieces)
     w = W.gemm_workload("tn", 200, 136, 128, ab_dtype="bf16", values="ints")
-    text = _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
-    assert "direct" not in text
+    assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
+    # the two kinds can be switched off separately (bit 0: k vectors, bit 1: row vectors); a pair goes direct together or not at all
+    w = W.gemm_workload("nt", 136, 264, 64, ab_dtype="f16", values="ints")
+    assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
+    assert "direct" in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 2})
+    w = W.gemm_workload("nn_rowmajor_c", 72, 140, 64, ab_dtype="bf16", values="ints")
+    assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
 
 
 def test_walk_f16_and_forced_element_loads(oracle):

@@ -82,14 +82,18 @@ def test_gemm_table_rows(oracle, name, mnk, tile, values):
 
 @pytest.mark.parametrize("values", ["ints", "normal"])
 def test_gemm_direct_to_lds_loads(oracle, values):
-    # K a multiple of 64 and contiguous k tiles: k-vector operands bypass the registers on their way into LDS
-    for name, mnk in (("tn", (520, 392, 256)), ("nn_rowmajor_c", (264, 300, 128))):
+    # K a multiple of 64 and k tiles inside one leaf of the k mode: vector operands bypass the registers on their way into
+    # LDS (row-vector tiles are stored k-major and read back with the LDS transpose load)
+    for name, mnk in (("tn", (520, 392, 256)), ("nt", (392, 520, 192)), ("nn_rowmajor_c", (264, 300, 128)), ("gett", (320, 200, 64))):
         for tile in (128, 256):
             w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values=values)
             assert "direct-to-LDS" in _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
     w = W.gemm_workload("tn", 200, 136, 192, ab_dtype="f16", values=values)
     assert "direct-to-LDS" in _parity(oracle, w)
     assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
+    w = W.gemm_workload("nt", 136, 200, 128, ab_dtype="f16", values=values)
+    assert "direct-to-LDS" in _parity(oracle, w)
+    assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
 
 
 def test_gemm_f16_and_element_loads(oracle):
