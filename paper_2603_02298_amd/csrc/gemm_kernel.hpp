@@ -87,6 +87,7 @@ struct OperandLoader {
   static constexpr bool DIRECT = LOAD == kLoadKDirect || LOAD == kLoadRDirect;
   static constexpr int NREG = LOAD == kLoadRVec ? 8 : (DIRECT ? 1 : ROWS);
   const uint16_t* base;
+  __amdgpu_buffer_rsrc_t rsrc;           // direct loads: the operand as a raw buffer (uniform base, 32-bit byte offsets)
   uint32_t K, kv, row_in_tile;           // row_in_tile: first row of the lane (block row for row-vector loads)
   uint32_t rowoff[LOAD == kLoadRVec ? 1 : ROWS];
   bool active, k_inside;
@@ -95,6 +96,8 @@ struct OperandLoader {
   __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, const GemmMode& kmode, uint32_t row0, uint32_t extent,
                                        uint32_t Ktot, uint32_t tid) {
     base = p;
+    // no range to enforce: every offset the lanes present is inside the operand by construction (rows are clamped, k tiles whole)
+    if constexpr (DIRECT) rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p), 0, 0xFFFFFFFFu, 0x00020000);
     K = Ktot;
     kv = gemm_lane_kvec(LOAD, tid);
     row_in_tile = gemm_lane_row(LOAD, tid, 0);
@@ -125,17 +128,24 @@ struct OperandLoader {
     }
   }
 
-  // stage_tile: LDS byte offset of this operand's tile in the stage the k tile goes to (used by kLoadKDirect only)
-  __device__ __forceinline__ void fetch(uint32_t kt, const GemmMode& kmode, uint32_t stage_tile) {
+  // Direct loads of one k tile: k_bytes is the tile's byte offset along the k mode (uniform), stage_tile the LDS byte offset
+  // of this operand's tile in the stage the k tile goes to.  Lane l's 16 bytes land at byte 16 l of the instruction's KiB.
+  template <int FIRST = 0, int END = ROWS>
+  __device__ __forceinline__ void fetch_direct(uint32_t k_bytes, uint32_t stage_tile) {
+    typedef __attribute__((address_space(3))) void lds_void;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
+    static_for<(END > FIRST ? END - FIRST : 0)>([&](auto d) {
+      constexpr int i = FIRST + d;
+      if constexpr (i >= 0 && i < ROWS)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(lds_bytes + stage_tile + (row_in_tile + (uint32_t)i) * 1024u), 16,
+                                                 (int)rowoff[i], (int)k_bytes, 0, 0);
+    });
+  }
+
+  __device__ __forceinline__ void fetch(uint32_t kt, const GemmMode& kmode) {
     const uint32_t k0 = kt * kGemmBK + kv * 8u;
     if constexpr (DIRECT) {
-      extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
-      // uniform base + 32-bit byte offset per lane (an operand is smaller than 2^31 elements); the LDS address is uniform
-      const unsigned char* p = reinterpret_cast<const unsigned char*>(base + gemm_mode_eval(kmode, kt * kGemmBK));
-#pragma unroll
-      for (int i = 0; i < ROWS; ++i)
-        __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(p + rowoff[i]),
-                                         reinterpret_cast<uint32_t*>(lds_bytes + stage_tile + (row_in_tile + (uint32_t)i) * 1024u), 16, 0, 0);
+      (void)kmode;
     } else if constexpr (LOAD == kLoadKVec) {
       k_inside = k0 < K;
       const uint16_t* p = base + gemm_mode_eval(kmode, k_inside ? k0 : 0u);
@@ -195,6 +205,27 @@ struct OperandLoader {
   }
 };
 
+// Byte offset of k tile t along an operand's k mode, for operands whose k tiles lie inside the mode's first leaf: stepping
+// to the next tile adds 64 strides of that leaf until the leaf is exhausted; only then is the layout function evaluated again.
+struct KTileOffset {
+  uint32_t bytes, step, left;   // left: k tiles from the current one to the end of the first leaf's run
+  __device__ __forceinline__ void seek(const GemmMode& k, uint32_t t) {
+    bytes = 2u * gemm_mode_eval(k, t * kGemmBK);
+    step = 2u * kGemmBK * k.lead_stride;
+    if (k.n == 1) {
+      left = 0xFFFFFFFFu;
+    } else {
+      uint32_t q, r;
+      fd_divmod(t * kGemmBK, k.div[0], &q, &r);
+      left = (k.div[0].div - r) / kGemmBK;
+    }
+  }
+  __device__ __forceinline__ void next(const GemmMode& k, uint32_t t) {
+    if (--left == 0) seek(k, t);
+    else bytes += step;
+  }
+};
+
 template <bool BF16, int WMB, int WNB, int A_LOAD, int B_LOAD>
 __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmParams P, const uint16_t* __restrict__ A,
                                                                           const uint16_t* __restrict__ B, float* __restrict__ C) {
@@ -241,7 +272,7 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     // Both tiles arrive by direct loads: no registers are held for them, so the loop is one basic block, software-pipelined
     // around a single barrier per k tile.  Stage kt % 2 holds k tile kt.  After the MFMAs of k step 2 are issued every
     // wavefront has read its last fragments of the stage; past the barrier the stage is free for k tile kt + 2, whose loads
-    // are issued at once, and k tile kt + 1 (loaded a whole tile earlier) is complete: its first fragments are read while
+    // start at once, and k tile kt + 1 (loaded since the barrier before) is complete: its first fragments are read while
     // the MFMAs of k step 3 run.  Past the last k tile the loads repeat it (in bounds, into a stage nobody reads again).
     static_assert((STAGE & (STAGE - 1)) == 0, "stages are told apart by one address bit");
     // per fragment: the lane's LDS address for the tile's first k step in the current stage.  Row-major tiles: k step kk
@@ -268,38 +299,59 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
       });
     };
     const uint32_t last = P.k_tiles - 1u;
-    la.fetch(0, P.a_k, 0u);
-    lb.fetch(0, P.b_k, A_BYTES);
-    la.fetch(last < 1u ? last : 1u, P.a_k, STAGE);
-    lb.fetch(last < 1u ? last : 1u, P.b_k, STAGE + A_BYTES);
+    KTileOffset ka, kb;
+    ka.seek(P.a_k, 0u);
+    kb.seek(P.b_k, 0u);
+    la.fetch_direct(ka.bytes, 0u);
+    lb.fetch_direct(kb.bytes, A_BYTES);
+    ka.seek(P.a_k, last < 1u ? last : 1u);
+    kb.seek(P.b_k, last < 1u ? last : 1u);
+    la.fetch_direct(ka.bytes, STAGE);
+    lb.fetch_direct(kb.bytes, STAGE + A_BYTES);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's direct loads have landed in LDS
     __syncthreads();
     read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    constexpr int VM_LOADS = (BM + BN) / 32, MFMAS = WMB * WNB;
+    constexpr int RA = BM / 32, RB = BN / 32, MFMAS = WMB * WNB;
+    // The RA + RB load instructions of a k tile (A's first) are issued in parts, one per k step, starting with the step
+    // after the barrier (k step 3): the vector memory path moves about 64 bytes per clock and CU, so a whole tile issued at
+    // once stalls the wavefronts (and with them the matrix cores) at issue.  Measured: A's loads in k step 3 and B's in
+    // k step 0 of the next iteration is the best split; loads issued later than that arrive after the barrier wants them.
+    constexpr int PART[5] = {0, RA, RA + RB, RA + RB, RA + RB};
+    auto issue_part = [&](auto part, uint32_t stage_off) {
+      la.template fetch_direct<PART[part], (PART[part + 1] < RA ? PART[part + 1] : RA)>(ka.bytes, stage_off);
+      lb.template fetch_direct<(PART[part] > RA ? PART[part] - RA : 0), PART[part + 1] - RA>(kb.bytes, stage_off + A_BYTES);
+    };
     for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
       static_for<KSTEPS - 1>([&](auto kk) {
         constexpr int buf = kk % 2;
+        constexpr int loads_here = PART[kk + 2] - PART[kk + 1];
+        issue_part(std::integral_constant<int, kk + 1>{}, ((kt & 1u) ^ 1u) * STAGE);   // the rest of k tile kt + 1
         read_fragments(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, buf ^ 1>{});
         multiply(std::integral_constant<int, buf>{});
-        // issue order: the LDS reads spread evenly between the MFMAs
+        // issue order: loads and LDS reads spread evenly between the MFMAs; the reads before the barrier over the first half
+        // of them, so that the last read has returned when the last MFMA is issued
+        constexpr int SPAN = kk + 2 == KSTEPS ? (MFMAS + 1) / 2 : MFMAS;
         static_for<MFMAS>([&](auto g) {
-          constexpr int reads = DS_READS * (g + 1) / MFMAS - DS_READS * g / MFMAS;
+          constexpr int loads = loads_here * (g + 1) / MFMAS - loads_here * g / MFMAS;
+          constexpr int reads = g < SPAN ? DS_READS * (g + 1) / SPAN - DS_READS * g / SPAN : 0;
+          if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);
           if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         });
       });
       __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) before telling the others that the next stage is complete
       __syncthreads();
-      const uint32_t kt2 = kt + 2u < last ? kt + 2u : last, stage_off = (kt & 1u) * STAGE;
-      la.fetch(kt2, P.a_k, stage_off);
-      lb.fetch(kt2, P.b_k, stage_off + A_BYTES);
+      if (kt + 2u <= last) {
+        ka.next(P.a_k, kt + 2u);
+        kb.next(P.b_k, kt + 2u);
+      }
+      issue_part(std::integral_constant<int, 0>{}, (kt & 1u) * STAGE);   // the first part of k tile kt + 2
       static_for<WMB>([&](auto i) { a_fr[i] ^= STAGE; });
       static_for<WNB>([&](auto j) { b_fr[j] ^= STAGE; });
       read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
       multiply(std::integral_constant<int, (KSTEPS - 1) % 2>{});
-      // issue order: the direct loads and the LDS reads spread evenly between the MFMAs
       static_for<MFMAS>([&](auto g) {
-        constexpr int loads = VM_LOADS * (g + 1) / MFMAS - VM_LOADS * g / MFMAS;
+        constexpr int loads = PART[1] * (g + 1) / MFMAS - PART[1] * g / MFMAS;
         constexpr int reads = DS_READS * (g + 1) / MFMAS - DS_READS * g / MFMAS;
         if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);
         if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
@@ -308,8 +360,8 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the repeated loads of the last k tile end before the wavefront does
   } else {
-    la.fetch(0, P.a_k, 0u);
-    lb.fetch(0, P.b_k, A_BYTES);
+    la.fetch(0, P.a_k);
+    lb.fetch(0, P.b_k);
     la.park(lds);
     lb.park(lds + A_BYTES);
     __syncthreads();
@@ -328,8 +380,8 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
       unsigned char* nxt = lds + ((kt & 1u) ^ 1u) * STAGE;
       const bool more = kt + 1 < P.k_tiles;
       if (more) {
-        la.fetch(kt + 1, P.a_k, 0u);
-        lb.fetch(kt + 1, P.b_k, 0u);
+        la.fetch(kt + 1, P.a_k);
+        lb.fetch(kt + 1, P.b_k);
       }
       static_for<KSTEPS>([&](auto kk) {
         constexpr int buf = kk % 2;

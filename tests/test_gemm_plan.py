@@ -64,6 +64,12 @@ def test_walk_direct_to_lds_loads(oracle):
             _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile}, pieces)
     w = W.gemm_workload("tn", 200, 136, 128, ab_dtype="bf16", values="ints")
     assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
+    # k modes of several leaves whose first leaf holds whole k tiles: the tile offset steps inside the leaf and is
+    # evaluated afresh at its end (A: two tiles per run, B: one)
+    M, N = 200, 136
+    w = W.GemmWorkload("folded_k_direct", "bf16", "(%d,(128,3)):(408,(1,136))" % M, "(%d,(64,6)):(1,(%d,%d))" % (N, N, 64 * N + 8),
+                       "(%d,%d):(1,%d)" % (M, N, M), (M - 1) * 408 + 127 + 2 * 136 + 1, N + 63 * N + 5 * (64 * N + 8), M * N, M, N, 384, "ints")
+    _walk_and_compare(oracle, w, None, ["a_load=" + kd, "b_load=" + rd])
     # the two kinds can be switched off separately (bit 0: k vectors, bit 1: row vectors); a pair goes direct together or not at all
     w = W.gemm_workload("nt", 136, 264, 64, ab_dtype="f16", values="ints")
     assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})

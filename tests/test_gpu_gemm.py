@@ -93,6 +93,13 @@ def test_gemm_direct_to_lds_loads(oracle, values):
     assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
     w = W.gemm_workload("nt", 136, 200, 128, ab_dtype="f16", values=values)
     assert "direct-to-LDS" in _parity(oracle, w)
+    # k modes of several leaves whose first leaf holds whole k tiles: the tile offset steps inside the leaf and is
+    # evaluated afresh at its end (A: two tiles per run, B: one)
+    M, N = 200, 136
+    w = W.GemmWorkload("folded_k_direct", "bf16", "(%d,(128,3)):(408,(1,136))" % M, "(%d,(64,6)):(1,(%d,%d))" % (N, N, 64 * N + 8),
+                       "(%d,%d):(1,%d)" % (M, N, M), (M - 1) * 408 + 127 + 2 * 136 + 1, N + 63 * N + 5 * (64 * N + 8), M * N, M, N, 384, values)
+    for tile in (128, 256):
+        assert _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile}).count("direct-to-LDS") == 2
     assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
 
 
