@@ -205,6 +205,12 @@ struct OperandLoader {
   }
 };
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() would also wait for every load in flight (the direct
+// loads count as global loads), which is exactly what the ring of tiles must not do; the caller states its own wait.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_s_barrier();
+}
+
 // Byte offset of k tile t along an operand's k mode, for operands whose k tiles lie inside the mode's first leaf: stepping
 // to the next tile adds 64 strides of that leaf until the leaf is exhausted; only then is the layout function evaluated again.
 struct KTileOffset {
@@ -270,13 +276,20 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
 
   if constexpr (A_DIRECT) {
     // Both tiles arrive by direct loads: no registers are held for them, so the loop is one basic block, software-pipelined
-    // around a single barrier per k tile.  Stage kt % 2 holds k tile kt.  After the MFMAs of k step 2 are issued every
-    // wavefront has read its last fragments of the stage; past the barrier the stage is free for k tile kt + 2, whose loads
-    // start at once, and k tile kt + 1 (loaded since the barrier before) is complete: its first fragments are read while
-    // the MFMAs of k step 3 run.  Past the last k tile the loads repeat it (in bounds, into a stage nobody reads again).
-    static_assert((STAGE & (STAGE - 1)) == 0, "stages are told apart by one address bit");
-    // per fragment: the lane's LDS address for the tile's first k step in the current stage.  Row-major tiles: k step kk
-    // flips slot bits (address ^ 32 kk); k-major tiles: k step kk is a constant offset.
+    // around a single barrier per k tile.  LDS is a ring of five slots of one operand tile each, filled in the order
+    // A(0), B(0), A(1), B(1), A(2), ...: A(t) sits in slot 2t mod 5, B(t) in slot (2t + 1) mod 5.  While k tile t is
+    // multiplied, two slots hold it, A(t + 1) is complete or landing, and B(t + 1) and A(t + 2) are being loaded: one
+    // quarter of a tile's load instructions per k step, because the vector memory path moves about 64 bytes per clock and
+    // CU and a tile issued at once stalls the wavefronts (and the matrix cores with them) at issue.
+    // The barrier sits between k steps 2 and 3: by then every wavefront has read its last fragments of tile t (two slots
+    // fall free: B(t + 2) and A(t + 3) go there), and tile t + 1 is complete: its first fragments are read while the MFMAs
+    // of k step 3 run.  Past the last k tile the loads repeat it (in bounds, into slots nobody reads again).
+    static_assert(BM == BN, "the ring's slots hold a tile of either operand");
+    static_assert(KSTEPS == 4, "the loop below spells out the four k steps");
+    constexpr uint32_t SLOT = A_BYTES;
+    constexpr int RA = BM / 32, RB = BN / 32, MFMAS = WMB * WNB;   // load instructions per lane and operand tile
+    // per fragment: the lane's LDS address for the tile's first k step in the slot being multiplied.  Row-major tiles: k step
+    // kk flips slot bits (address ^ 32 kk); k-major tiles: k step kk is a constant offset.
     uint32_t a_fr[WMB], b_fr[WNB];
     static_for<WMB>([&](auto i) {
       const uint32_t row = wm * (WMB * 32u) + 32u * (uint32_t)i;
@@ -285,8 +298,8 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     });
     static_for<WNB>([&](auto j) {
       const uint32_t row = wn * (WNB * 32u) + 32u * (uint32_t)j;
-      b_fr[j] = A_BYTES + (B_LOAD == kLoadRDirect ? gemm_rdirect_frag_offset(BN, lane, row, 8u * mfma_ab_kvec(lane))
-                                                  : gemm_lds_offset(row + mfma_ab_row(lane), mfma_ab_kvec(lane)));
+      b_fr[j] = SLOT + (B_LOAD == kLoadRDirect ? gemm_rdirect_frag_offset(BN, lane, row, 8u * mfma_ab_kvec(lane))
+                                               : gemm_lds_offset(row + mfma_ab_row(lane), mfma_ab_kvec(lane)));
     });
     auto read_fragments = [&](auto kk, auto buf) {
       static_for<WMB>([&](auto i) {
@@ -298,65 +311,73 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
         else bf[buf][j] = *reinterpret_cast<const u32x4*>(lds + (b_fr[j] ^ (32u * (uint32_t)kk)));
       });
     };
-    const uint32_t last = P.k_tiles - 1u;
-    KTileOffset ka, kb;
-    ka.seek(P.a_k, 0u);
-    kb.seek(P.b_k, 0u);
-    la.fetch_direct(ka.bytes, 0u);
-    lb.fetch_direct(kb.bytes, A_BYTES);
-    ka.seek(P.a_k, last < 1u ? last : 1u);
-    kb.seek(P.b_k, last < 1u ? last : 1u);
-    la.fetch_direct(ka.bytes, STAGE);
-    lb.fetch_direct(kb.bytes, STAGE + A_BYTES);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wavefront's direct loads have landed in LDS
-    __syncthreads();
-    read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    constexpr int RA = BM / 32, RB = BN / 32, MFMAS = WMB * WNB;
-    // The RA + RB load instructions of a k tile (A's first) are issued in parts, one per k step, starting with the step
-    // after the barrier (k step 3): the vector memory path moves about 64 bytes per clock and CU, so a whole tile issued at
-    // once stalls the wavefronts (and with them the matrix cores) at issue.  Measured: A's loads in k step 3 and B's in
-    // k step 0 of the next iteration is the best split; loads issued later than that arrive after the barrier wants them.
-    constexpr int PART[5] = {0, RA, RA + RB, RA + RB, RA + RB};
-    auto issue_part = [&](auto part, uint32_t stage_off) {
-      la.template fetch_direct<PART[part], (PART[part + 1] < RA ? PART[part + 1] : RA)>(ka.bytes, stage_off);
-      lb.template fetch_direct<(PART[part] > RA ? PART[part] - RA : 0), PART[part + 1] - RA>(kb.bytes, stage_off + A_BYTES);
-    };
-    for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
-      static_for<KSTEPS - 1>([&](auto kk) {
-        constexpr int buf = kk % 2;
-        constexpr int loads_here = PART[kk + 2] - PART[kk + 1];
-        issue_part(std::integral_constant<int, kk + 1>{}, ((kt & 1u) ^ 1u) * STAGE);   // the rest of k tile kt + 1
-        read_fragments(std::integral_constant<int, kk + 1>{}, std::integral_constant<int, buf ^ 1>{});
-        multiply(std::integral_constant<int, buf>{});
-        // issue order: loads and LDS reads spread evenly between the MFMAs; the reads before the barrier over the first half
-        // of them, so that the last read has returned when the last MFMA is issued
-        constexpr int SPAN = kk + 2 == KSTEPS ? (MFMAS + 1) / 2 : MFMAS;
-        static_for<MFMAS>([&](auto g) {
-          constexpr int loads = loads_here * (g + 1) / MFMAS - loads_here * g / MFMAS;
-          constexpr int reads = g < SPAN ? DS_READS * (g + 1) / SPAN - DS_READS * g / SPAN : 0;
-          if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);
-          if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        });
-      });
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) before telling the others that the next stage is complete
-      __syncthreads();
-      if (kt + 2u <= last) {
-        ka.next(P.a_k, kt + 2u);
-        kb.next(P.b_k, kt + 2u);
-      }
-      issue_part(std::integral_constant<int, 0>{}, (kt & 1u) * STAGE);   // the first part of k tile kt + 2
-      static_for<WMB>([&](auto i) { a_fr[i] ^= STAGE; });
-      static_for<WNB>([&](auto j) { b_fr[j] ^= STAGE; });
-      read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-      multiply(std::integral_constant<int, (KSTEPS - 1) % 2>{});
+    // issue order inside a k step: its loads and LDS reads spread evenly between the MFMAs (the reads over the first
+    // `span` of them)
+    auto issue_order = [&](auto loads_c, auto span_c) {
+      constexpr int LOADS = loads_c, SPAN = span_c;
       static_for<MFMAS>([&](auto g) {
-        constexpr int loads = PART[1] * (g + 1) / MFMAS - PART[1] * g / MFMAS;
-        constexpr int reads = DS_READS * (g + 1) / MFMAS - DS_READS * g / MFMAS;
+        constexpr int loads = LOADS * (g + 1) / MFMAS - LOADS * g / MFMAS;
+        constexpr int reads = g < SPAN ? DS_READS * (g + 1) / SPAN - DS_READS * g / SPAN : 0;
         if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);
         if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       });
+    };
+    auto next_slot = [](uint32_t slot) { return slot + 2u >= 5u ? slot + 2u - 5u : slot + 2u; };
+    // s_waitcnt vmcnt(n) lgkmcnt(0): all but the n youngest loads have landed, every LDS read has returned
+    auto wait_loads_but = [](auto n) {
+      constexpr int N = decltype(n)::value;
+      static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+      __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070);
+    };
+
+    const uint32_t last = P.k_tiles - 1u;
+    KTileOffset ka, kb;   // of the newest k tile requested for A and for B
+    ka.seek(P.a_k, 0u);
+    kb.seek(P.b_k, 0u);
+    la.fetch_direct(ka.bytes, 0u * SLOT);
+    lb.fetch_direct(kb.bytes, 1u * SLOT);
+    ka.seek(P.a_k, last < 1u ? last : 1u);
+    kb.seek(P.b_k, last < 1u ? last : 1u);
+    la.fetch_direct(ka.bytes, 2u * SLOT);
+    lb.fetch_direct(kb.bytes, 3u * SLOT);
+    ka.seek(P.a_k, last < 2u ? last : 2u);
+    la.fetch_direct(ka.bytes, 4u * SLOT);
+    wait_loads_but(std::integral_constant<int, 2 * RA + RB>{});   // k tile 0 has landed
+    lds_barrier();
+    read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    uint32_t sa = 0u, sb = 1u;   // slots of the k tile being multiplied
+    for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
+      const uint32_t s_b1 = next_slot(sb), s_a2 = next_slot(next_slot(sa));   // slots of B(kt + 1) and A(kt + 2)
+      // k step 0: second half of B(kt + 1); k steps 1 and 2: A(kt + 2)
+      lb.template fetch_direct<RB / 2, RB>(kb.bytes, s_b1 * SLOT);
+      read_fragments(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+      multiply(std::integral_constant<int, 0>{});
+      issue_order(std::integral_constant<int, RB - RB / 2>{}, std::integral_constant<int, MFMAS>{});
+      la.template fetch_direct<0, RA / 2>(ka.bytes, s_a2 * SLOT);
+      read_fragments(std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
+      multiply(std::integral_constant<int, 1>{});
+      issue_order(std::integral_constant<int, RA / 2>{}, std::integral_constant<int, MFMAS>{});
+      la.template fetch_direct<RA / 2, RA>(ka.bytes, s_a2 * SLOT);
+      read_fragments(std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{});
+      multiply(std::integral_constant<int, 0>{});
+      // the reads before the barrier over the first half of the MFMAs, so that the last one has returned when the last MFMA is issued
+      issue_order(std::integral_constant<int, RA - RA / 2>{}, std::integral_constant<int, (MFMAS + 1) / 2>{});
+      wait_loads_but(std::integral_constant<int, RA>{});   // k tile kt + 1 has landed; A(kt + 2) may still be on its way
+      lds_barrier();
+      if (kt + 2u <= last) kb.next(P.b_k, kt + 2u);
+      if (kt + 3u <= last) ka.next(P.a_k, kt + 3u);
+      // k step 3: first half of B(kt + 2), into the slot A(kt) leaves
+      lb.template fetch_direct<0, RB / 2>(kb.bytes, sa * SLOT);
+      const uint32_t sa_next = next_slot(sa), sb_next = next_slot(sb);
+      const uint32_t da = (sa_next - sa) * SLOT, db = (sb_next - sb) * SLOT;
+      static_for<WMB>([&](auto i) { a_fr[i] += da; });
+      static_for<WNB>([&](auto j) { b_fr[j] += db; });
+      sa = sa_next;
+      sb = sb_next;
+      read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+      multiply(std::integral_constant<int, 1>{});
+      issue_order(std::integral_constant<int, RB / 2>{}, std::integral_constant<int, MFMAS>{});
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // the repeated loads of the last k tile end before the wavefront does
   } else {

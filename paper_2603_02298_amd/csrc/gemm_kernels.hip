@@ -33,9 +33,12 @@ lc_status_t execute_gemm_plan(const lc_gemm_plan& plan, const void* a, const voi
   (void)hipGetLastError();
   hipError_t pre;
   const bool bf16 = plan.ab_dtype == LC_BF16;
-  if (plan.tile_m == 256 && plan.tile_n == 256 && plan.lds_bytes == 2u * 512u * 128u)
+  // LDS the kernels assume: two stages of an A and a B tile, or (direct loads, always as a pair) a ring of five tiles
+  if (plan.params.a_direct != plan.params.b_direct) return LC_ERR_INVALID_ARG;
+  const unsigned tiles_in_lds = plan.params.a_direct ? 5u : 4u;
+  if (plan.tile_m == 256 && plan.tile_n == 256 && plan.lds_bytes == tiles_in_lds * 256u * 128u)
     pre = bf16 ? launch_gemm_bf16_256(plan, ka, kb, kc, s) : launch_gemm_f16_256(plan, ka, kb, kc, s);
-  else if (plan.tile_m == 128 && plan.tile_n == 128 && plan.lds_bytes == 2u * 256u * 128u)
+  else if (plan.tile_m == 128 && plan.tile_n == 128 && plan.lds_bytes == tiles_in_lds * 128u * 128u)
     pre = bf16 ? launch_gemm_bf16_128(plan, ka, kb, kc, s) : launch_gemm_f16_128(plan, ka, kb, kc, s);
   else
     return LC_ERR_INVALID_ARG;

@@ -178,7 +178,8 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   P.k_tiles = (uint32_t)((K + kGemmBK - 1) / kGemmBK);
   if ((uint64_t)P.tiles_m * P.tiles_n >= (uint64_t(1) << 31)) return LC_ERR_TOO_LARGE;
   P.group_m = (uint32_t)std::max(1, env_int("LC_TUNE_GEMM_GROUP_M", 8));
-  plan.lds_bytes = 2u * (unsigned)(plan.tile_m + plan.tile_n) * 128u;   // two stages of (rows x 128 bytes) for A and B
+  // two stages of (rows x 128 bytes) for A and B; direct loads: a ring of five operand tiles
+  plan.lds_bytes = direct ? 5u * (unsigned)plan.tile_m * 128u : 2u * (unsigned)(plan.tile_m + plan.tile_n) * 128u;
   plan.a_text = mode_text(a_r) + " x " + mode_text(a_k);
   plan.b_text = mode_text(b_r) + " x " + mode_text(b_k);
   plan.c_text = mode_text(c_m) + " x " + mode_text(c_n);

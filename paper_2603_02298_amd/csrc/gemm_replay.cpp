@@ -149,13 +149,13 @@ lc_status_t gemm_replay_on_host(const lc_gemm_plan& plan, const uint16_t* a, int
   Walker w{plan, P, plan.exchanged ? b : a, plan.exchanged ? a : b, c, plan.exchanged ? b_elems : a_elems,
            plan.exchanged ? a_elems : b_elems, c_elems};
   const uint32_t BM = (uint32_t)plan.tile_m, BN = (uint32_t)plan.tile_n, WMB = BM / 64, WNB = BN / 64;
-  if (plan.lds_bytes != 2u * (BM + BN) * 128u) return LC_ERR_INVALID_ARG;
+  if (plan.lds_bytes != (P.a_direct ? 5u * BM * 128u : 2u * (BM + BN) * 128u) || (P.a_direct && BM != BN)) return LC_ERR_INVALID_ARG;
   Layout tv_a, tv_b, tv_c;
   mfma_fragment_layout(0, &tv_a);
   mfma_fragment_layout(1, &tv_b);
   mfma_fragment_layout(2, &tv_c);
   auto to_float = plan.ab_dtype == LC_BF16 ? bf16_to_float : f16_to_float;
-  std::vector<unsigned char> lds(plan.lds_bytes / 2);   // one stage is enough for a sequential walk
+  std::vector<unsigned char> lds((BM + BN) * 128u);   // one k tile of A and B is enough for a sequential walk
   std::vector<float> acc((size_t)BM * BN);
   std::vector<char> covered((size_t)P.tiles_m * P.tiles_n, 0);
   const uint32_t n_tiles = P.tiles_m * P.tiles_n;
