@@ -47,7 +47,7 @@ typedef enum {
   LC_ERR_NOT_SEGREGATED = 9,      /* composition: sublayouts of B without segregated images (Sec. 3.3.2) */
   LC_ERR_NOT_INJECTIVE = 10,      /* complement: a mode of the layout overlaps the span of smaller ones */
   LC_ERR_NOT_SURJECTIVE = 11,     /* logical divide: (B, B*) misses coordinates of A (Sec. 3.5.2) */
-  LC_ERR_DST_ALIASES = 12,        /* copy: two coordinates of dst share an offset (result would depend on order) */
+  LC_ERR_DST_ALIASES = 12,        /* copy: two coordinates of dst share an offset other than through stride-0 modes */
   LC_ERR_UNSUPPORTED_DTYPE = 13,
   LC_ERR_TOO_LARGE = 14,          /* size or cosize beyond 2^62, more than 64 leaf modes, or more work than the kernels index */
   LC_ERR_MISALIGNED = 15,         /* a device pointer is less aligned than the plan was created for */
@@ -188,7 +188,13 @@ lc_status_t lc_slayout_right_inverse(const lc_slayout_t* a, lc_layout_t** out);
 
 /* src_align_bytes / dst_align_bytes: alignment the caller guarantees for the device pointers that
  * will be passed to lc_plan_execute (a power of two; 256 for fresh allocations).  Errors: SIZE_MISMATCH,
- * DST_ALIASES (dst not injective; a single-element copy is exempt), UNSUPPORTED_DTYPE, TOO_LARGE. */
+ * DST_ALIASES (dst not injective; a single-element copy is exempt), UNSUPPORTED_DTYPE, TOO_LARGE.
+ * Destination modes of stride 0 do not count as aliasing: the loop of Sec. 2.6.1 runs i upwards, so the
+ * coordinate with those modes at their last position is the one written last, and the plan copies exactly
+ * that slice of the source (Sec. 2.5.1; lc_plan_describe reports overwritten_modes and src_offset).  Any
+ * other overlap in dst (strides that make distinct coordinates meet) is refused with DST_ALIASES; an injective
+ * dst of more than 2^22 elements whose strides are not nested (each at least the extent of the modes below it)
+ * is refused as well: its injectivity is not proved cheaply. */
 lc_status_t lc_plan_create(const lc_layout_t* src, const lc_layout_t* dst, lc_dtype_t dt,
                            unsigned src_align_bytes, unsigned dst_align_bytes, lc_plan_t** out);
 /* One-line description: kernel class, vector width, joint modes, tile, grid, LDS bytes, swizzle. */

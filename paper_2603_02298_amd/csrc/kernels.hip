@@ -492,6 +492,7 @@ static hipError_t launch_ragged(const lc_plan& plan, const void* src, void* dst,
 
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream) {
   if (!src || !dst) return LC_ERR_INVALID_ARG;
+  src = static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes;   // the slice that is written last
   if ((reinterpret_cast<uintptr_t>(src) % plan.src_align) != 0 || (reinterpret_cast<uintptr_t>(dst) % plan.dst_align) != 0)
     return LC_ERR_MISALIGNED;
   const int cus = device_cu_count();

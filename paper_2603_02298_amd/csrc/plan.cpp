@@ -532,6 +532,24 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
   return false;
 }
 
+// a3: refine both shapes to one shape F by composing each layout with the identity layout of F (Sec. 3.3.1); then every
+// mode of F has one stride on each side.  False when the shapes have no common refinement or a composition is not admissible.
+static bool joint_modes(const Modes& S, const Modes& D, std::vector<JointMode>* J) {
+  std::vector<int64_t> F;
+  if (!common_refinement(S, D, &F)) return false;
+  Modes ident;
+  int64_t run = 1;
+  for (int64_t e : F) { ident.push_back({e, run}); run *= e; }
+  Layout IF = Layout::flat(ident), Sr, Dr;
+  if (composition(Layout::flat(S), IF, &Sr) != LC_OK || composition(Layout::flat(D), IF, &Dr) != LC_OK ||
+      Sr.leaves.size() != F.size() || Dr.leaves.size() != F.size())
+    return false;
+  J->clear();
+  for (size_t k = 0; k < F.size(); ++k)
+    if (F[k] > 1) J->push_back({F[k], Sr.leaves[k].stride, Dr.leaves[k].stride});
+  return true;
+}
+
 lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src_align, unsigned dst_align,
                       const Tuning& tune, lc_plan* plan) {
   if (src.size() != dst.size()) return LC_ERR_SIZE_MISMATCH;             // @pre size(src) == size(dst)
@@ -547,8 +565,40 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
 
   // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
   Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
-  // a1: the destination must be injective, otherwise the result would depend on the iteration order
-  if (n > 1 && !layout_is_injective(D, n)) return LC_ERR_DST_ALIASES;
+  // a1: the destination must be injective, otherwise the result would depend on the iteration order -- except where
+  // the order of Sec. 2.6.1's loop (i ascending) decides it without a race: of the coordinates that differ only in
+  // destination modes of stride 0, the one with those modes at their last position is written last.  The copy is then
+  // the copy of that slice (Sec. 2.5.1): the modes fold into an offset of the source and leave both layouts.
+  if (n > 1 && !layout_is_injective(D, n)) {
+    std::vector<JointMode> J0;
+    if (!joint_modes(S, D, &J0)) return LC_ERR_DST_ALIASES;
+    Modes S2, D2;
+    int64_t offset = 0, n2 = 1;
+    int dropped = 0;
+    for (const JointMode& m : J0) {
+      if (m.b == 0) {
+        offset += (m.extent - 1) * m.a;
+        ++dropped;
+      } else {
+        S2.push_back({m.extent, m.a});
+        D2.push_back({m.extent, m.b});
+        n2 *= m.extent;
+      }
+    }
+    if (dropped == 0) return LC_ERR_DST_ALIASES;
+    if (S2.empty()) {
+      S2.push_back({1, 0});
+      D2.push_back({1, 0});
+    }
+    if (n2 > 1 && !layout_is_injective(coalesce_modes(D2), n2)) return LC_ERR_DST_ALIASES;   // overlaps of another kind stay refused
+    unsigned shifted_align = plan->src_align;
+    while (shifted_align > 1 && (offset * es) % shifted_align != 0) shifted_align /= 2;
+    lc_status_t st = make_plan(Layout::flat(S2), Layout::flat(D2), es, shifted_align, dst_align, tune, plan);
+    if (st != LC_OK) return st;
+    plan->src_offset_elems = offset;
+    plan->overwritten_modes = dropped;
+    return LC_OK;
+  }
 
   // a5 (the paper's route): K = stride-1 head of src o dst^ (Sec. 3.4.2); kept for reporting and
   // cross-checked against the joint modes below
@@ -753,6 +803,8 @@ std::string describe(const lc_plan& plan) {
   s += std::string("class=") + cls;
   s += " elem_bytes=" + std::to_string(plan.elem_bytes) + " n=" + std::to_string(plan.n_elems);
   s += " K=" + std::to_string(plan.common_vector) + " width_bytes=" + std::to_string(plan.width_bytes);
+  if (plan.overwritten_modes > 0)
+    s += " overwritten_modes=" + std::to_string(plan.overwritten_modes) + " src_offset=" + std::to_string(plan.src_offset_elems);
   s += " joint=[";
   for (size_t k = 0; k < plan.joint.size(); ++k) {
     if (k) s += " ";

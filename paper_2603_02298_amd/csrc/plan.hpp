@@ -38,6 +38,10 @@ struct lc_plan {
   lc::KernelClass cls = lc::KernelClass::Generic;
   int elem_bytes = 0;
   int64_t n_elems = 0;
+  // Destination modes of stride 0: the sequential loop's last write wins, so the copy is the slice at those modes'
+  // last coordinates: the source is read from src + src_offset_elems, the modes are gone from the plan.
+  int64_t src_offset_elems = 0;
+  int overwritten_modes = 0;
   int64_t common_vector = 1;               // K of Sec. 3.4.2 before hardware clamps
   std::vector<lc::JointMode> joint;        // after common refinement, destination-order sort, joint coalesce
   unsigned src_align = 0, dst_align = 0;   // alignment the access widths rely on

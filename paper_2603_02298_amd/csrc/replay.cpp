@@ -26,7 +26,9 @@ struct Buffers {
 lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_elems, void* dst, int64_t dst_elems,
                            int64_t* lds_conflicts) {
   const int es = plan.cls == KernelClass::Transpose ? plan.tile_elem_bytes : plan.elem_bytes;
-  Buffers B{static_cast<const unsigned char*>(src), static_cast<unsigned char*>(dst), src_elems * plan.elem_bytes, dst_elems * plan.elem_bytes};
+  if (plan.src_offset_elems < 0 || plan.src_offset_elems > src_elems) return LC_ERR_INVALID_ARG;
+  Buffers B{static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes, static_cast<unsigned char*>(dst),
+            (src_elems - plan.src_offset_elems) * plan.elem_bytes, dst_elems * plan.elem_bytes};
   if (lds_conflicts) *lds_conflicts = 0;
   if (plan.cls == KernelClass::Generic) {
     const GenericParams& P = plan.generic;

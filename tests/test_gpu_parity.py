@@ -58,12 +58,18 @@ def test_workloads_elementwise(oracle, name, scale):
 def test_copy_applications_table(oracle):
     for ln in golden_lines("copy_applications.txt"):
         name, s, d = [x.strip() for x in ln.split("|")]
-        if name == "Constant":
-            continue
-        for dt in ("f32", "bf16", "b8", "b64", "b128"):
-            if dt == "b128":
-                continue
+        for dt in ("f32", "bf16", "b8", "b64"):
             _parity(oracle, s, d, dt, tag=name)
+
+
+def test_destination_modes_of_stride_zero_keep_the_last_write(oracle):
+    # the sequential loop's last write wins; the library copies the slice that is written last
+    for s, d, dt in [("(4,2):(1,4)", "(4,2):(1,0)", "f32"), ("6:1", "(3,2):(1,0)", "f32"),
+                     ("(2,5,3,4):(60,1,5,15)", "(2,5,3,4):(0,1,0,5)", "b8"), ("(5,7):(7,1)", "(5,7):(0,0)", "f32"),
+                     ("(256,3,512):(1,131072,256)", "(256,3,512):(512,0,1)", "f32"),          # transposing class, several tiles
+                     ("(4096,5,64):(1,262144,4096)", "(4096,5,64):(1,0,4096)", "bf16"),       # direct class
+                     ("(1000,3,7):(21,7,1)", "(1000,3,7):(1,0,1000)", "b64")]:                # strided gather, offset of 14 elements
+        assert "overwritten_modes=" in _parity(oracle, s, d, dt, tag="stride-0 destination")
 
 
 def test_random_layout_pairs(oracle):

@@ -73,13 +73,10 @@ def test_copy_applications_table(oracle):
     from conftest import golden_lines
     for ln in golden_lines("copy_applications.txt"):
         name, s, d = [x.strip() for x in ln.split("|")]
-        if name == "Constant":   # destination aliases: refused by the GPU library
-            with pytest.raises(lc.LayoutCopyError) as e:
-                lc.Plan(s, d, "f32")
-            assert e.value.status_name == "DST_ALIASES"
-            continue
         for dt in ("f32", "bf16", "b8", "b64"):
-            _check(oracle, s, d, dt)
+            desc, _ = _check(oracle, s, d, dt)
+            # "Constant": every coordinate writes the one element; the loop's last write is what stays
+            assert ("overwritten_modes=1" in desc) == (name == "Constant"), desc
 
 
 def _random_pair(rng):
@@ -262,13 +259,29 @@ def test_plan_errors():
         lc.Plan("8:1", "9:1", "f32")
     assert e.value.status_name == "SIZE_MISMATCH"
     with pytest.raises(lc.LayoutCopyError) as e:
-        lc.Plan("(4,2):(1,0)", "(4,2):(1,0)", "f32")
+        lc.Plan("(4,4):(1,4)", "(4,4):(1,3)", "f32")      # overlapping rows
     assert e.value.status_name == "DST_ALIASES"
     with pytest.raises(lc.LayoutCopyError) as e:
-        lc.Plan("(4,4):(1,4)", "(4,4):(1,3)", "f32")      # overlapping rows
+        lc.Plan("(4,4,2):(1,4,16)", "(4,4,2):(1,3,0)", "f32")      # a stride-0 mode beside overlapping rows
     assert e.value.status_name == "DST_ALIASES"
     assert "class=" in lc.Plan("1:0", "1:0", "f32").describe()    # a single element never aliases
     assert "class=" in lc.Plan("(2,3):(3,2)", "(2,3):(3,2)", "f32").describe()   # injective though not nested
+
+
+def test_destination_modes_of_stride_zero_keep_the_last_write(oracle):
+    # Sec. 2.6.1's loop runs i upwards, so of the coordinates that differ only in destination modes of stride 0 the
+    # last one wins: the library copies that slice (the oracle runs the loop itself)
+    cases = [("(4,2):(1,4)", "(4,2):(1,0)", "f32", 1, 4),                       # the second column stays
+             ("6:1", "(3,2):(1,0)", "f32", 1, 3),                                 # shapes differ: refined first
+             ("(8,3,64):(1,8,24)", "(8,3,64):(64,0,1)", "bf16", 1, 16),           # a transposing copy around the dropped mode
+             ("(2,5,3,4):(60,1,5,15)", "(2,5,3,4):(0,1,0,5)", "b8", 2, 60 + 2 * 5),
+             ("(16,(4,2)):(1,(16,64))", "(16,(4,2)):(1,(0,16))", "b64", 1, 3 * 16),
+             ("(5,7):(7,1)", "(5,7):(0,0)", "f32", 2, 34),                         # everything into one element
+             ("(64,3,64):(1,4096,64)", "(64,3,64):(64,0,1)", "f32", 1, 8192)]
+    for s, d, dt, modes, offset in cases:
+        desc, _ = _check(oracle, s, d, dt)
+        assert "overwritten_modes=%d src_offset=%d" % (modes, offset) in desc, desc
+    assert "class=transpose" in _check(oracle, "(64,3,64):(1,4096,64)", "(64,3,64):(64,0,1)", "f32")[0]
 
 
 def test_alignment_limits_vector_width():
