@@ -5,9 +5,11 @@
 // (v_mfma_f32_32x32x16 bf16 / f16, fp32 accumulation).
 //
 // One workgroup of 4 wavefronts owns a BM x BN tile of C; wavefront (wm, wn) owns a (BM/2) x (BN/2)
-// quarter as WMB x WNB fragments of 32 x 32.  Per k tile of 64 the operand tiles pass through LDS,
-// double-buffered: the loads of k tile t+1 are issued before the MFMAs of k tile t and parked after
-// them.  How a tile is loaded depends on which mode of the operand is contiguous (GemmLoad).
+// quarter as WMB x WNB fragments of 32 x 32.  Per k tile of 64 the operand tiles pass through LDS.  How a
+// tile is loaded depends on which mode of the operand is contiguous (GemmLoad).  Pairs of operands that
+// qualify go straight from global memory into a ring of five LDS tiles (one barrier per k tile, loads a
+// quarter of a tile per k step); any other pair is loaded into registers before the MFMAs of k tile t and
+// parked in the other of two LDS stages after them.
 #pragma once
 #include <hip/hip_runtime.h>
 

@@ -153,3 +153,13 @@ def test_preconditions_and_refusals():
     p = lc.GemmPlan("(64,64):(64,1)", "(64,64):(64,1)", "(64,64):(1,64)", "bf16", a_align=16, b_align=16, c_align=4)
     assert "a_load=k-vectors" in p.describe() and "b_load=k-vectors" in p.describe() and "c_vec=0" in p.describe()
     assert p.flops == 2 * 64 ** 3
+    # execution checks the pointers against what the plan relies on before anything is launched (the addresses below
+    # are never dereferenced: both calls return at the check)
+    p = lc.GemmPlan("(64,64):(64,1)", "(64,64):(64,1)", "(64,64):(1,64)", "bf16")
+    for ptrs in ((0x10000 + 2, 0x20000, 0x30000), (0x10000, 0x20000 + 8, 0x30000), (0x10000, 0x20000, 0x30000 + 4)):
+        with pytest.raises(lc.LayoutCopyError) as e:
+            p.execute(*ptrs)
+        assert e.value.status_name == "MISALIGNED"
+    with pytest.raises(lc.LayoutCopyError) as e:
+        p.execute(0, 0x20000, 0x30000)
+    assert e.value.status_name == "INVALID_ARG"
