@@ -82,9 +82,32 @@ def time_workload(torch, lc, w, dev, steps, warmup, stream):
     plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
     ms_kernel = plan.time(sp, dp, warmup=min(warmup, 3), iters=steps, stream=stream)
     desc = plan.describe()
+    graph_ms = time_in_graph(torch, plan, sp, dp, steps) if ms_kernel < 0.05 else None
     del srcs, dsts
     torch.cuda.empty_cache()
-    return ms_step, ms_kernel, desc, n
+    return ms_step, ms_kernel, desc, n, graph_ms
+
+
+def time_in_graph(torch, plan, sp, dp, steps):
+    """ms per launch when the launches (one per buffer pair) are recorded once into a HIP graph and replayed: what a
+    launch-bound caller gets (short kernels: the eager step is mostly launch overhead)."""
+    side = torch.cuda.Stream()
+    n = len(sp)
+    with torch.cuda.stream(side):
+        plan.execute(sp[0], dp[0], side.cuda_stream)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for k in range(n):
+            plan.execute(sp[k], dp[k], torch.cuda.current_stream().cuda_stream)
+    reps = max(3, steps // n)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (reps * n)
 
 
 def cpu_baseline(w, budget_s=15.0):
@@ -217,7 +240,7 @@ def main():
         return
 
     w = W.workload(args.workload)
-    ms_step, ms_kernel, desc, n_pairs = time_workload(torch, lc, w, dev, args.steps, args.warmup, stream)
+    ms_step, ms_kernel, desc, n_pairs, graph_ms = time_workload(torch, lc, w, dev, args.steps, args.warmup, stream)
     value = w.algorithmic_bytes / (ms_step * 1e-3) / 1e9
     achieved = w.algorithmic_bytes / (ms_kernel * 1e-3) / 1e9
     dram_min = dram_minimum_bytes(w)
@@ -236,6 +259,7 @@ def main():
         "config": {"workload": w.name, "src_layout": w.src_layout, "dst_layout": w.dst_layout, "elements": w.n,
                    "algorithmic_bytes": w.algorithmic_bytes, "plan": desc},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "ms_per_step_in_hip_graph": None if graph_ms is None else round(graph_ms, 5),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel_ms": round(ms_kernel, 5), "dram_minimum_bytes": dram_min,
@@ -247,8 +271,9 @@ def main():
             if name == args.workload:
                 continue
             wk = W.workload(name)
-            st, kt, d, _ = time_workload(torch, lc, wk, dev, max(10, args.steps // 4), 3, stream)
+            st, kt, d, _, gms = time_workload(torch, lc, wk, dev, max(10, args.steps // 4), 3, stream)
             allw[wk.name] = {"ms_per_step": round(st, 5), "kernel_ms": round(kt, 5),
+                             "ms_per_step_in_hip_graph": None if gms is None else round(gms, 5),
                              "GBps_algorithmic": round(wk.algorithmic_bytes / (kt * 1e-3) / 1e9, 1),
                              "frac_of_peak_dram_minimum": round(dram_minimum_bytes(wk) / (kt * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                              "plan": d}
