@@ -203,7 +203,9 @@ lc_status_t lc_plan_describe(const lc_plan_t* plan, char* buf, size_t cap, size_
 lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream);
 void lc_plan_destroy(lc_plan_t* plan);
 
-/* lc_plan_create (alignment taken from the two pointers) + lc_plan_execute + lc_plan_destroy. */
+/* lc_plan_create (alignment taken from the two pointers) + lc_plan_execute + lc_plan_destroy.  The library keeps the
+ * plans of recent calls (up to 256, keyed by both layouts, dtype, the pointers' alignment and the LC_TUNE_* settings),
+ * so a repeated call only pays for the launch; thread-safe.  lc_gemm does the same. */
 lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, const lc_layout_t* dst_layout,
                     lc_dtype_t dt, void* hip_stream);
 

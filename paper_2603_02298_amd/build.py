@@ -11,7 +11,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["layout.cpp", "algebra.cpp", "semimodule.cpp", "plan.cpp", "replay.cpp", "gemm_plan.cpp", "gemm_replay.cpp", "capi.cpp",
            "gemm_capi.cpp", "kernels.hip", "gemm_kernels.hip", "gemm_inst_bf16_256.hip", "gemm_inst_bf16_128.hip",
            "gemm_inst_f16_256.hip", "gemm_inst_f16_128.hip"]
-HEADERS = ["layout.hpp", "algebra.hpp", "semimodule.hpp", "plan.hpp", "kernel_params.hpp", "gemm_plan.hpp", "gemm_params.hpp"]
+HEADERS = ["layout.hpp", "algebra.hpp", "semimodule.hpp", "plan.hpp", "kernel_params.hpp", "gemm_plan.hpp", "gemm_params.hpp", "plan_cache.hpp"]
 KERNEL_HEADERS = {"gemm_kernel.hpp": "gemm_inst_"}   # header -> prefix of the only sources that include it
 
 

@@ -5,9 +5,15 @@
 #include "algebra.hpp"
 #include "layoutcopy.h"
 #include "plan.hpp"
+#include "plan_cache.hpp"
 #include "semimodule.hpp"
 
 namespace {
+
+lc::PlanCache<lc_plan_t>& copy_plans() {
+  static lc::PlanCache<lc_plan_t> cache;
+  return cache;
+}
 
 lc_status_t put_string(const std::string& s, char* buf, size_t cap, size_t* needed) {
   if (needed) *needed = s.size() + 1;
@@ -217,10 +223,24 @@ lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, c
   if (es == 0) return LC_ERR_UNSUPPORTED_DTYPE;
   if (align_of(src) < (unsigned)es || align_of(dst) < (unsigned)es) return LC_ERR_MISALIGNED;
   try {
-    lc_plan_t plan;
-    lc_status_t st = lc::make_plan(src_layout->L, dst_layout->L, es, align_of(src), align_of(dst), lc::tuning_from_env(), &plan);
-    if (st != LC_OK) return st;
-    return lc::execute_plan(plan, src, dst, hip_stream);
+    // plans of recent calls are kept: planning is host work of some 10 us, several times a short kernel
+    const lc::Tuning tune = lc::tuning_from_env();
+    std::string key = src_layout->L.str() + "|" + dst_layout->L.str() + "|" + std::to_string(es) + "|" + std::to_string(align_of(src)) + "|" +
+                      std::to_string(align_of(dst));
+    for (int64_t v : {(int64_t)tune.micro_per_thread, (int64_t)tune.rest_order, (int64_t)tune.wgs_per_cu, (int64_t)tune.unroll,
+                      (int64_t)tune.swizzle_shift, (int64_t)tune.nontemporal, (int64_t)tune.blocked, tune.max_items, (int64_t)tune.force_class,
+                      (int64_t)tune.max_vec_bytes})
+      key += "," + std::to_string(v);
+    for (int64_t v : tune.tile) key += ";" + std::to_string(v);
+    std::shared_ptr<const lc_plan_t> plan = copy_plans().find(key);
+    if (!plan) {
+      auto fresh = std::make_shared<lc_plan_t>();
+      lc_status_t st = lc::make_plan(src_layout->L, dst_layout->L, es, align_of(src), align_of(dst), tune, fresh.get());
+      if (st != LC_OK) return st;
+      plan = fresh;
+      copy_plans().insert(key, plan);
+    }
+    return lc::execute_plan(*plan, src, dst, hip_stream);
   } catch (...) {
     return LC_ERR_INVALID_ARG;
   }

@@ -1,9 +1,12 @@
 // extern "C" boundary of the generic GEMM (include/layoutcopy.h): argument checks and marshalling only.
+#include <cstdlib>
 #include <cstring>
 #include <new>
+#include <string>
 
 #include "gemm_plan.hpp"
 #include "layoutcopy.h"
+#include "plan_cache.hpp"
 
 namespace {
 lc_status_t put_text(const std::string& s, char* buf, size_t cap, size_t* needed) {
@@ -55,11 +58,25 @@ lc_status_t lc_gemm(const void* a, const lc_layout_t* a_layout, const void* b, c
                     const lc_layout_t* c_layout, lc_dtype_t ab_dtype, void* hip_stream) {
   if (!a || !b || !c || !a_layout || !b_layout || !c_layout) return LC_ERR_INVALID_ARG;
   try {
-    lc_gemm_plan plan;
-    lc_status_t st = lc::make_gemm_plan(a_layout->L, b_layout->L, c_layout->L, (int)ab_dtype, pointer_alignment(a), pointer_alignment(b),
-                                        pointer_alignment(c), &plan);
-    if (st != LC_OK) return st;
-    return lc::execute_gemm_plan(plan, a, b, c, hip_stream);
+    // plans of recent calls are kept (see plan_cache.hpp); the planner's tuning knobs are part of the key
+    std::string key = a_layout->L.str() + "|" + b_layout->L.str() + "|" + c_layout->L.str() + "|" + std::to_string((int)ab_dtype) + "|" +
+                      std::to_string(pointer_alignment(a)) + "|" + std::to_string(pointer_alignment(b)) + "|" + std::to_string(pointer_alignment(c));
+    for (const char* knob : {"LC_TUNE_GEMM_LOAD", "LC_TUNE_GEMM_DIRECT", "LC_TUNE_GEMM_CVEC", "LC_TUNE_GEMM_TILE", "LC_TUNE_GEMM_GROUP_M",
+                             "LC_TUNE_GEMM_EXCHANGE"}) {
+      const char* v = std::getenv(knob);
+      key += std::string(",") + (v ? v : "");
+    }
+    static lc::PlanCache<lc_gemm_plan> plans;
+    std::shared_ptr<const lc_gemm_plan> plan = plans.find(key);
+    if (!plan) {
+      auto fresh = std::make_shared<lc_gemm_plan>();
+      lc_status_t st = lc::make_gemm_plan(a_layout->L, b_layout->L, c_layout->L, (int)ab_dtype, pointer_alignment(a), pointer_alignment(b),
+                                          pointer_alignment(c), fresh.get());
+      if (st != LC_OK) return st;
+      plan = fresh;
+      plans.insert(key, plan);
+    }
+    return lc::execute_gemm_plan(*plan, a, b, c, hip_stream);
   } catch (...) {
     return LC_ERR_INVALID_ARG;
   }
