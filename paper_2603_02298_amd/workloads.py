@@ -200,6 +200,24 @@ def batched_gemm_workload(name, M, N, K, L, ab_dtype="bf16", values="normal"):
     raise KeyError(name)
 
 
+def conv_gemm_workload(Nb, H, Wd, C, Kf, R, S, filters="kcrs", ab_dtype="bf16", values="normal"):
+    """The CONV row of Table gemm (Sec. 2.6.2): a convolution of an NHWC activation as one GEMM.  A (Kf,(C,R,S)) are
+    the filters, B ((Nb,P,Q),(C,R,S)) is the im2col view of the activation (no copy: P and R both step by an image row,
+    Q and S by a pixel, so the layout repeats strides and is not injective), C (Kf,(Nb,P,Q)) is the N,P,Q,K output.
+    filters: "kcrs" stores them K,C,R,S row-major (general strides along k: element loads), "krsc" K,R,S,C (channels
+    contiguous on both sides: vector loads)."""
+    P, Q = H - R + 1, Wd - S + 1
+    sN, sH, sW = H * Wd * C, Wd * C, C
+    if filters == "kcrs":
+        a = "(%d,(%d,%d,%d)):(%d,(%d,%d,1))" % (Kf, C, R, S, C * R * S, R * S, S)
+    else:
+        a = "(%d,(%d,%d,%d)):(%d,(1,%d,%d))" % (Kf, C, R, S, C * R * S, S * C, C)
+    b = "((%d,%d,%d),(%d,%d,%d)):((%d,%d,%d),(1,%d,%d))" % (Nb, P, Q, C, R, S, sN, sH, sW, sH, sW)
+    c = "(%d,(%d,%d,%d)):(1,(%d,%d,%d))" % (Kf, Nb, P, Q, Kf * P * Q, Kf * Q, Kf)
+    return GemmWorkload("gemm_conv_%s_%s" % (filters, ab_dtype), ab_dtype, a, b, c, Kf * C * R * S, Nb * H * Wd * C, Nb * P * Q * Kf,
+                        Kf, Nb * P * Q, C * R * S, values, "convolution as a GEMM over an im2col view")
+
+
 def _f16_bits(x32):
     return x32.astype(np.float16).view(np.uint16)
 

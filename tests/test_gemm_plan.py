@@ -78,6 +78,19 @@ def test_walk_direct_to_lds_loads(oracle):
     assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
 
 
+def test_walk_conv_row(oracle):
+    # the CONV row of Table gemm: B is the im2col view of the activation (repeated strides, not injective: fine for an
+    # operand that is only read).  Filters K,C,R,S: general strides along k, element loads; filters K,R,S,C with 64
+    # channels: both operands lead with whole k tiles of contiguous channels and go straight into LDS
+    w = W.conv_gemm_workload(2, 6, 5, 3, 4, 3, 2, "kcrs", values="ints")
+    _walk_and_compare(oracle, w, None, ["a_load=elements", "b_load=elements", "M=4 N=32 K=18"])
+    w = W.conv_gemm_workload(2, 7, 6, 8, 40, 3, 2, "krsc", values="ints")
+    _walk_and_compare(oracle, w, None, ["a_load=k-vectors", "b_load=k-vectors", "c_vec=1"])
+    w = W.conv_gemm_workload(1, 5, 9, 64, 72, 2, 3, "krsc", values="ints")
+    text = _walk_and_compare(oracle, w, None, ["a_load=k-vectors(direct-to-LDS)", "b_load=k-vectors(direct-to-LDS)"])
+    assert "K=384" in text
+
+
 def test_walk_f16_and_forced_element_loads(oracle):
     w = W.gemm_workload("tn", 130, 70, 40, ab_dtype="f16", values="ints")
     _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": 128}, ["ab=f16"])

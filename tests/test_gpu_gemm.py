@@ -112,6 +112,15 @@ def test_gemm_f16_and_element_loads(oracle):
         _parity(oracle, w)
 
 
+@pytest.mark.parametrize("values", ["ints", "normal"])
+def test_gemm_conv_row(oracle, values):
+    # the CONV row of Table gemm: a convolution as one GEMM over the im2col view of the activation
+    for args in ((2, 12, 10, 3, 20, 3, 2, "kcrs"), (2, 11, 9, 8, 40, 3, 2, "krsc"), (2, 14, 12, 64, 136, 3, 3, "krsc")):
+        w = W.conv_gemm_workload(*args, values=values)
+        desc = _parity(oracle, w)
+        assert ("direct-to-LDS" in desc) == (args[3] == 64), desc
+
+
 def test_gemm_degenerate_shapes(oracle):
     # a single row / column / k, and extents below one fragment
     for M, N, K in [(1, 1, 1), (1, 40, 8), (33, 1, 5), (8, 8, 8), (31, 33, 17)]:
