@@ -135,6 +135,10 @@ struct OperandLoader {
   template <int FIRST = 0, int END = ROWS>
   __device__ __forceinline__ void fetch_direct(uint32_t k_bytes, uint32_t stage_tile) {
     typedef __attribute__((address_space(3))) void lds_void;
+    // The same dynamic LDS as the kernel's `lds`, under a name of its own on purpose: the compiler then sees no alias
+    // between these writes and the fragment reads and adds no waits of its own (it would make every LDS read wait for
+    // all loads in flight).  Ordering is stated by hand where it is needed: s_waitcnt vmcnt(n) before the k tile's
+    // barrier, and the barrier itself.
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
     static_for<(END > FIRST ? END - FIRST : 0)>([&](auto d) {
       constexpr int i = FIRST + d;

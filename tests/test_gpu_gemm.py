@@ -93,6 +93,10 @@ def test_gemm_direct_to_lds_loads(oracle, values):
     assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 0})
     w = W.gemm_workload("nt", 136, 200, 128, ab_dtype="f16", values=values)
     assert "direct-to-LDS" in _parity(oracle, w)
+    for name in ("tn", "nt", "nn_rowmajor_c"):   # fp16 on the 256-tile kernels
+        w = W.gemm_workload(name, 392, 520, 192, ab_dtype="f16", values=values)
+        desc = _parity(oracle, w, {"LC_TUNE_GEMM_TILE": 256})
+        assert desc.count("direct-to-LDS") == 2 and "tile=256x256" in desc
     # k modes of several leaves whose first leaf holds whole k tiles: the tile offset steps inside the leaf and is
     # evaluated afresh at its end (A: two tiles per run, B: one)
     M, N = 200, 136
