@@ -175,10 +175,14 @@ def time_gemm(torch, lc, name, dev, steps, warmup, stream, size=8192):
 
 def gemm_record(w, ms_step, ms_kernel, desc):
     tf_kernel = w.flops / (ms_kernel * 1e-3) / 1e12
+    traffic = None   # HBM bytes per launch from the committed counter runs (profiles/), when this workload has one
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(w.name)
     return {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "a_layout": w.a_layout, "b_layout": w.b_layout, "c_layout": w.c_layout,
             "flops": w.flops, "ms_per_step": round(ms_step, 5), "TFLOPs_whole_call": round(w.flops / (ms_step * 1e-3) / 1e12, 1),
             "roofline": {"bound": "mfma", "achieved": round(tf_kernel, 1), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": None, "kernel_ms": round(ms_kernel, 5)},
+                         "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": traffic, "kernel_ms": round(ms_kernel, 5)},
             "plan": desc}
 
 
