@@ -78,6 +78,14 @@ def test_walk_direct_to_lds_loads(oracle):
     assert "direct" not in _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
 
 
+def test_walk_batched_direct_loads(oracle):
+    # rank-3 layouts on the direct path: the batch offset is folded into the base the buffer loads start from
+    for name, mnkl in (("strided_batch", (136, 72, 128, 3)), ("shared_b", (128, 140, 64, 2))):
+        w = W.batched_gemm_workload(name, *mnkl, values="ints")
+        text = _walk_and_compare(oracle, w)
+        assert text.count("direct-to-LDS") == 2 and "L=%d" % w.L in text, text
+
+
 def test_walk_conv_row(oracle):
     # the CONV row of Table gemm: B is the im2col view of the activation (repeated strides, not injective: fine for an
     # operand that is only read).  Filters K,C,R,S: general strides along k, element loads; filters K,R,S,C with 64

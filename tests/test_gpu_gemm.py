@@ -162,7 +162,8 @@ def test_gemm_hierarchical_k_broadcast_and_accumulate(oracle):
 
 @pytest.mark.parametrize("values", ["ints", "normal"])
 @pytest.mark.parametrize("name,mnkl", [("strided_batch", (264, 136, 72, 5)), ("shared_b", (128, 300, 40, 4)),
-                                       ("folded_batch", (70, 45, 33, 6))])
+                                       ("folded_batch", (70, 45, 33, 6)),
+                                       ("strided_batch", (264, 136, 192, 3)), ("shared_b", (128, 300, 64, 4))])   # direct loads
 def test_batched_gemm(oracle, name, mnkl, values):
     # the batched form of Sec. 1 (rank-3 layouts): strided batch, a shared (stride-0) operand, a folded batch mode
     w = W.batched_gemm_workload(name, *mnkl, values=values)
