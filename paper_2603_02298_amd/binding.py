@@ -99,6 +99,8 @@ def lib():
     L.lc_gemm_plan_time.argtypes = [P, P, P, P, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
     L.lc_mfma_fragment_layout.argtypes = [ctypes.c_int, PP]
     L.lc_debug_gemm_replay_on_host.argtypes = [P, P, i64, P, i64, P, i64]
+    L.lc_debug_gemm_lds_address.argtypes = [ctypes.c_int, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32]
+    L.lc_debug_gemm_lds_address.restype = i64
     _lib = L
     return L
 

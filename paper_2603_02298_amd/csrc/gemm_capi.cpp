@@ -110,4 +110,15 @@ lc_status_t lc_debug_gemm_replay_on_host(const lc_gemm_plan_t* plan, const uint1
   }
 }
 
+// Test instrumentation: the kernels' LDS address functions (gemm_params.hpp), so that tests can compare them with
+// XOR-stride layouts (Sec. 2.3.2) and model the banks.  what = 0: byte offset of k vector `b` of row `a` in a row-major
+// tile; 1: of element (k = a, row = b) in a k-major tile of `rows` rows; 2: the address lane `lane` presents to the
+// transpose load of fragment rows a .. a + 31, k = b .. b + 3.  Not in the public header.
+int64_t lc_debug_gemm_lds_address(int what, uint32_t rows, uint32_t lane, uint32_t a, uint32_t b) {
+  if (what == 0) return lc::gemm_lds_offset(a, b);
+  if (what == 1) return lc::gemm_rdirect_lds_offset(rows, a, b);
+  if (what == 2) return lc::gemm_rdirect_frag_offset(rows, lane, a, b);
+  return -1;
+}
+
 }  // extern "C"

@@ -184,3 +184,52 @@ def test_preconditions_and_refusals():
     with pytest.raises(lc.LayoutCopyError) as e:
         p.execute(0, 0x20000, 0x30000)
     assert e.value.status_name == "INVALID_ARG"
+
+
+def test_lds_arrangements_are_xor_layouts_without_bank_conflicts(oracle):
+    # Both LDS tile arrangements of the GEMM kernels are layouts with XOR strides (Sec. 2.3.2) over the bits of their
+    # coordinates, in units of 16 bytes; and under the bank model (64 banks of 4 bytes, 256 bytes per pass) the fragment
+    # reads of either arrangement touch every bank once per pass.
+    from paper_2603_02298_amd.binding import lib
+    addr = lib().lc_debug_gemm_lds_address
+    # row-major tile: unit = 8 row + ((kv ^ row ^ (row >> 3)) & 7), coordinate (kv, row), 256 rows
+    text = "((2,2,2),(2,2,2,2,2,2,2,2)):((f1,f2,f4),(f9,f18,f36,f65,f130,f260,f512,f1024))"
+    for S in (oracle.SLayout, lc.SLayout):
+        L = S(text)
+        for row in range(256):
+            for kv in range(8):
+                assert 16 * L(kv + 8 * row) == addr(0, 256, 0, row, kv), (row, kv)
+    # k-major tile of 256 rows (32 groups of 8 rows per k): unit = 32 k + (group ^ 4 (k mod 4)), coordinate (group, k)
+    text = "((2,2,2,2,2),(2,2,2,2,2,2)):((f1,f2,f4,f8,f16),(f36,f72,f128,f256,f512,f1024))"
+    for S in (oracle.SLayout, lc.SLayout):
+        L = S(text)
+        for k in range(64):
+            for group in range(32):
+                assert 16 * L(group + 32 * k) == addr(1, 256, 0, k, 8 * group), (k, group)
+    # ... and of 128 rows (16 groups): the XOR reaches the top two bits of the group
+    L = lc.SLayout("((2,2,2,2),(2,2,2,2,2,2)):((f1,f2,f4,f8),(f20,f40,f64,f128,f256,f512))")
+    for k in range(64):
+        for group in range(16):
+            assert 16 * L(group + 16 * k) == addr(1, 128, 0, k, 8 * group), (k, group)
+
+    def banks(byte_ranges):
+        hit = []
+        for lo, n in byte_ranges:
+            assert lo % 4 == 0
+            hit += [(lo // 4 + d) % 64 for d in range(n // 4)]
+        return hit
+
+    # one 16-byte read per lane, 16 lanes per pass: 16 consecutive fragment rows, one k vector
+    for row0 in range(0, 256, 16):
+        for kv in range(8):
+            assert sorted(banks([(addr(0, 256, 0, row0 + r, kv), 16) for r in range(16)])) == list(range(64))
+    # the direct loads fill 1 KiB contiguously: nothing to check.  Staged k-vector parks: lanes 0..15 = 2 rows x 8 vectors
+    for row0 in range(0, 256, 2):
+        assert sorted(banks([(addr(0, 256, 0, row0 + l // 8, l % 8), 16) for l in range(16)])) == list(range(64))
+    # transpose loads: 8 bytes per lane, 32 lanes per pass (either half of the wavefront)
+    for rows in (128, 256):
+        for row_base in range(0, rows, 32):
+            for k_base in range(0, 64, 4):
+                for half in (0, 32):
+                    got = banks([(addr(2, rows, half + l, row_base, k_base), 8) for l in range(32)])
+                    assert sorted(got) == list(range(64)), (rows, row_base, k_base, half)
