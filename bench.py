@@ -217,7 +217,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; the path has no multi-GPU part (see DESIGN.md, sharding note)", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; the path has no multi-GPU part (how it would shard is described in the design notes)", file=sys.stderr)
         sys.exit(2)
 
     import torch

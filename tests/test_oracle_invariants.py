@@ -24,7 +24,7 @@ def test_bruteforce_universe(bruteforce_binary):
     """Every layout of rank <= 3 with extents <= 4 (all mode orders, one stride zeroed, one boundary
     padded, every regrouping) and every stride in 0..6; all ordered pairs of the rank <= 2 subset and
     20000 seeded random pairs.  The rank-4 / extent-8 universe of the first workload runs with
-    `oracle/bruteforce --rank 4 --extent 8` (hours); a rank-4 / extent-4 run is recorded in the design doc."""
+    `oracle/bruteforce --rank 4 --extent 8` (hours); a rank-4 / extent-4 run is recorded in the design notes."""
     r = subprocess.run([bruteforce_binary], capture_output=True, text=True, timeout=900)
     assert r.returncode == 0, r.stdout[-3000:]
     assert "ALL POST-CONDITIONS HOLD" in r.stdout
