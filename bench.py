@@ -169,15 +169,18 @@ def time_gemm(torch, lc, name, dev, steps, warmup, stream, size=8192):
     ms_kernel = plan.time(a.data_ptr(), b.data_ptr(), c.data_ptr(), min(warmup, 3), steps, stream)
     desc = plan.describe()
     vendor = None
-    if name == "tn":
+    if name in ("tn", "nt"):
         # for scale only: the vendor library behind torch.matmul on the same operands (bf16 result, no read of C)
-        am, bm = a.view(size, size), b.view(size, size)
+        if name == "tn":     # A (M,K) and B (N,K) row-major: C = A B^T
+            am, bm = a.view(size, size), b.view(size, size).t()
+        else:                # A (M,K):(1,M) is a (K,M) row-major matrix transposed, B (N,K):(1,N) likewise
+            am, bm = a.view(size, size).t(), b.view(size, size)
         for _ in range(3):
-            torch.matmul(am, bm.t())
+            torch.matmul(am, bm)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            torch.matmul(am, bm.t())
+            torch.matmul(am, bm)
         torch.cuda.synchronize()
         vendor = (time.perf_counter() - t0) * 1e3 / steps
     del a, b, c
@@ -301,7 +304,7 @@ def main():
             gemm[gw.name] = gemm_record(gw, st, kt, d)
             if vendor_ms:
                 gemm[gw.name]["vendor_library_for_scale"] = {
-                    "what": "torch.matmul on the same operands: C = A B^T in bf16, no accumulation into an fp32 C",
+                    "what": "torch.matmul on the same operands in the same memory layouts: C = A B^T in bf16, no accumulation into an fp32 C",
                     "ms_per_step": round(vendor_ms, 5), "TFLOPs": round(gw.flops / (vendor_ms * 1e-3) / 1e12, 1)}
         out["gemm"] = gemm
     if not args.no_cpu_baseline:
