@@ -343,6 +343,7 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     kb.seek(P.b_k, 0u);
     la.fetch_direct(ka.bytes, 0u * SLOT);
     lb.fetch_direct(kb.bytes, 1u * SLOT);
+    __builtin_amdgcn_sched_barrier(0x038F);   // k tile 0's loads stay the oldest: the first wait below counts from the youngest
     ka.seek(P.a_k, last < 1u ? last : 1u);
     kb.seek(P.b_k, last < 1u ? last : 1u);
     la.fetch_direct(ka.bytes, 2u * SLOT);
@@ -360,6 +361,10 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
       read_fragments(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
       multiply(std::integral_constant<int, 0>{});
       issue_order(std::integral_constant<int, RB - RB / 2>{}, std::integral_constant<int, MFMAS>{});
+      // The wait before the barrier counts loads: all but the RA youngest must have landed, and those must be A(kt + 2)'s.
+      // So no load of B may be scheduled behind a load of A: nothing but vector memory instructions is held back here
+      // (mask: ALU, VALU, SALU, MFMA and LDS instructions may cross).
+      __builtin_amdgcn_sched_barrier(0x038F);
       la.template fetch_direct<0, RA / 2>(ka.bytes, s_a2 * SLOT);
       read_fragments(std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
       multiply(std::integral_constant<int, 1>{});
