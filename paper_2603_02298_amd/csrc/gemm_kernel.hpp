@@ -214,7 +214,10 @@ struct OperandLoader {
 // Workgroup barrier that orders LDS accesses only.  __syncthreads() would also wait for every load in flight (the direct
 // loads count as global loads), which is exactly what the ring of tiles must not do; the caller states its own wait.
 __device__ __forceinline__ void lds_barrier() {
+  // the empty statements are compiler-only fences: no memory access is moved across the barrier, nothing is emitted
+  asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 }
 
 // Byte offset of k tile t along an operand's k mode, for operands whose k tiles lie inside the mode's first leaf: stepping
