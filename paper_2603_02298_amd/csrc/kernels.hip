@@ -6,7 +6,10 @@
 
 #include <algorithm>
 #include <atomic>
+#include <map>
+#include <mutex>
 #include <string>
+#include <utility>
 
 #include "kernel_params.hpp"
 #include "plan.hpp"
@@ -147,13 +150,26 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 
   }
 }
 
+// Tile queues: pairs of counters (tiles handed out, workgroups done) in device memory that belongs to the library's code
+// object: nothing is allocated.  Launches on one stream run one after the other, so a stream keeps one pair for good;
+// the host hands out kTileQueues pairs and launches on further streams, or under graph capture, use the fixed order.
+constexpr int kTileQueues = 64;
+__device__ unsigned int g_tile_queues[kTileQueues][2];
+__device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
+  if (atomicAdd(&queue[1], 1u) == gridDim.x - 1u) {   // the last workgroup out: nobody asks any more
+    queue[0] = 0u;
+    queue[1] = 0u;
+    __threadfence();
+  }
+}
+
 // FULL: every lane owns MT micro-tiles and MT*V picks (n_micro == MT * kBlock), so the tile loop has
 // no per-lane predicates.  Its body is straight-line code on purpose: the loads of the next tile are
 // issued before the stores of the current one, and with no branch between them the wait before
 // parking can count the stores out (memory operations retire in issue order) instead of draining them.
 template <int ES, int V, int MT, int NT, bool FULL>
 __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
-                                                          unsigned char* __restrict__ dst) {
+                                                          unsigned char* __restrict__ dst, unsigned int* queue, uint32_t tile_bytes) {
   constexpr int DW = V * ES / 4;                 // dwords per vector
   constexpr int SLOT = V * ES;                   // bytes per vector
   typedef typename Word<SLOT>::type Vec;
@@ -242,7 +258,18 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     tile_step = 1;
     tile_end = min(P.n_tiles, tile + per_wg);
   }
-  if (tile >= tile_end) return;
+  // queue != nullptr (never with `blocked`): tiles past the first gridDim.x are handed out in the order the workgroups ask
+  // for them: queue[0] counts the tiles handed out.  Lane 0 asks one tile ahead and passes the answer on through a word
+  // of LDS behind the tile, at a barrier the loop has anyway.  queue[1] counts the workgroups that are done; the last one
+  // puts both counters back to zero for the next launch that is given this pair.
+  const bool dynamic = queue != nullptr;
+  volatile uint32_t* handed_out = reinterpret_cast<volatile uint32_t*>(lds + tile_bytes);
+  uint32_t asked = 0;
+  if (tile >= tile_end) {
+    if (dynamic && threadIdx.x == 0) leave_tile_queue(queue);
+    return;
+  }
+  if (dynamic && threadIdx.x == 0) asked = atomicAdd(&queue[0], 1u);
   int64_t so, dof;
   tile_origin(P, tile, &so, &dof);
   load_tile(so);
@@ -261,26 +288,31 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     }
   }
   park_tile();
+  if (dynamic && threadIdx.x == 0) *handed_out = gridDim.x + asked;
   __syncthreads();
+  uint32_t next = dynamic ? *handed_out : tile + tile_step;
   // invariant at the top: the current tile is parked in LDS, no load is in flight
   for (;;) {
-    const uint32_t next = tile + tile_step;
     if (next >= tile_end) {
       store_tile(dof);
       break;
     }
+    if (dynamic && threadIdx.x == 0) asked = atomicAdd(&queue[0], 1u);
     int64_t dof_next;
     tile_origin(P, next, &so, &dof_next);
     load_tile(so);
     __builtin_amdgcn_sched_barrier(0);   // keep every load ahead of every store in program order
     store_tile(dof);
     __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();   // every pick is done: LDS may be overwritten
+    __syncthreads();   // every pick is done: LDS may be overwritten (and every lane has read the word behind the tile)
     park_tile();
+    if (dynamic && threadIdx.x == 0) *handed_out = gridDim.x + asked;
     __syncthreads();
     tile = next;
     dof = dof_next;
+    next = dynamic ? *handed_out : tile + tile_step;
   }
+  if (dynamic && threadIdx.x == 0) leave_tile_queue(queue);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -423,6 +455,36 @@ static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsig
   }
 }
 
+// The pair of queue counters a launch on stream `s` may use, or nullptr: the stream is being captured into a graph (a
+// replay may run beside anything), or all pairs belong to other streams already.  One pair per stream and device:
+// launches on a stream do not overlap, which is what the counters' reset by the last workgroup relies on.
+static hipError_t tile_queue_of_stream(hipStream_t s, unsigned int** out) {
+  *out = nullptr;
+  hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  hipError_t e = hipStreamIsCapturing(s, &capturing);
+  if (e != hipSuccess) return e;
+  if (capturing != hipStreamCaptureStatusNone) return hipSuccess;
+  int dev = 0;
+  if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  static std::mutex lock;
+  static std::map<std::pair<int, hipStream_t>, int> slot_of;      // (device, stream) -> pair
+  static std::map<int, std::pair<unsigned int*, int>> per_device;   // device -> (address of the array, pairs handed out)
+  std::lock_guard<std::mutex> hold(lock);
+  auto dv = per_device.find(dev);
+  if (dv == per_device.end()) {
+    void* base = nullptr;
+    if ((e = hipGetSymbolAddress(&base, HIP_SYMBOL(g_tile_queues))) != hipSuccess) return e;
+    dv = per_device.emplace(dev, std::make_pair(static_cast<unsigned int*>(base), 0)).first;
+  }
+  auto it = slot_of.find({dev, s});
+  if (it == slot_of.end()) {
+    if (dv->second.second >= kTileQueues) return hipSuccess;   // no pair left: fixed order
+    it = slot_of.emplace(std::make_pair(dev, s), dv->second.second++).first;
+  }
+  *out = dv->second.first + 2 * it->second;
+  return hipSuccess;
+}
+
 template <int ES, int V, int MT, int NT, bool FULL>
 static hipError_t launch_transpose_f(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   const unsigned char* sp = static_cast<const unsigned char*>(src);
@@ -436,7 +498,15 @@ static hipError_t launch_transpose_f(const lc_plan& plan, const void* src, void*
       raised.store(true, std::memory_order_release);
     }
   }
-  hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
+  unsigned int* queue = nullptr;
+  unsigned lds_bytes = plan.lds_bytes;
+  if (plan.tile_queue && grid < plan.transpose.n_tiles) {
+    hipError_t e = tile_queue_of_stream(s, &queue);
+    if (e != hipSuccess) return e;
+    if (queue) lds_bytes += 16;   // the word that carries the next tile to the other lanes
+  }
+  hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), lds_bytes, s, plan.transpose, sp, dp, queue,
+                     plan.lds_bytes);
   return hipSuccess;
 }
 template <int ES, int V, int MT, int NT>

@@ -198,3 +198,42 @@ def test_plan_reuse_and_streams(oracle):
     torch.cuda.synchronize()
     for dst in outs:
         assert (dst.cpu().numpy() == want).all()
+
+
+def test_tile_queue(oracle, monkeypatch):
+    # tiles handed out on request (a pair of counters in device memory, reset by the last workgroup): forced on for
+    # sizes the oracle can check in full; twice in a row on one stream (the second launch finds the counters at zero)
+    monkeypatch.setenv("LC_TUNE_TILE_QUEUE", "1")
+    for name, scale in (("c5", 64), ("c2", 4), ("c3", 16), ("c1", 1)):
+        w = W.workload(name, scale)
+        for rep in range(2):
+            desc = _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag=w.name + " queue")
+        assert "tile_queue=1" in desc, desc
+    # one workgroup per CU, so that the grid is shorter than the list of tiles and every workgroup asks several times
+    monkeypatch.setenv("LC_TUNE_WGS_PER_CU", "1")
+    for name, scale in (("c5", 64), ("c2", 4), ("c3", 16), ("c1", 1)):
+        w = W.workload(name, scale)
+        assert "tile_queue=1" in _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag=w.name + " queue, 1 per CU")
+
+
+def test_tile_queue_on_several_streams(oracle, monkeypatch):
+    # every stream keeps a pair of counters of its own: copies that run side by side do not share one
+    monkeypatch.setenv("LC_TUNE_TILE_QUEUE", "1")
+    monkeypatch.setenv("LC_TUNE_WGS_PER_CU", "1")
+    w = W.workload("c5", 64)
+    src_bits = W.source_bits(w)
+    want = np.zeros(w.dst_elems, dtype=src_bits.dtype)
+    oracle.copy(src_bits, oracle.Layout(w.src_layout), want, oracle.Layout(w.dst_layout))
+    dev = torch.device("cuda:0")
+    plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
+    assert "tile_queue=1" in plan.describe()
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    src_t = torch.from_numpy(src_bits.view(np.int32)).to(dev)
+    dsts = [torch.zeros(w.dst_elems, dtype=torch.int32, device=dev) for _ in streams]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for st, d in zip(streams, dsts):
+            plan.execute(src_t.data_ptr(), d.data_ptr(), st.cuda_stream)
+    torch.cuda.synchronize()
+    for d in dsts:
+        assert (d.cpu().numpy().view(src_bits.dtype) == want).all()
