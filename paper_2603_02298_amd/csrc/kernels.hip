@@ -169,7 +169,7 @@ __device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
 // parking can count the stores out (memory operations retire in issue order) instead of draining them.
 template <int ES, int V, int MT, int NT, bool FULL>
 __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
-                                                          unsigned char* __restrict__ dst, unsigned int* queue, uint32_t tile_bytes) {
+                                                          unsigned char* __restrict__ dst, unsigned int* queue, uint32_t tile_bytes, uint32_t grab) {
   constexpr int DW = V * ES / 4;                 // dwords per vector
   constexpr int SLOT = V * ES;                   // bytes per vector
   typedef typename Word<SLOT>::type Vec;
@@ -259,8 +259,9 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     tile_end = min(P.n_tiles, tile + per_wg);
   }
   // queue != nullptr (never with `blocked`): tiles past the first gridDim.x are handed out in the order the workgroups ask
-  // for them: queue[0] counts the tiles handed out.  Lane 0 asks one tile ahead and passes the answer on through a word
-  // of LDS behind the tile, at a barrier the loop has anyway.  queue[1] counts the workgroups that are done; the last one
+  // for them, `grab` consecutive tiles per request: queue[0] counts the tiles handed out.  Lane 0 asks one request ahead
+  // (while the first tile of a batch is loaded it asks for the batch after the next) and passes the answer on through a
+  // word of LDS behind the tile, at a barrier the loop has anyway.  queue[1] counts the workgroups that are done; the last one
   // puts both counters back to zero for the next launch that is given this pair.
   const bool dynamic = queue != nullptr;
   volatile uint32_t* handed_out = reinterpret_cast<volatile uint32_t*>(lds + tile_bytes);
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     if (dynamic && threadIdx.x == 0) leave_tile_queue(queue);
     return;
   }
-  if (dynamic && threadIdx.x == 0) asked = atomicAdd(&queue[0], 1u);
+  if (dynamic && threadIdx.x == 0) asked = atomicAdd(&queue[0], grab);
   int64_t so, dof;
   tile_origin(P, tile, &so, &dof);
   load_tile(so);
@@ -290,14 +291,17 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
   park_tile();
   if (dynamic && threadIdx.x == 0) *handed_out = gridDim.x + asked;
   __syncthreads();
-  uint32_t next = dynamic ? *handed_out : tile + tile_step;
+  // dynamic: `left` tiles of the current batch follow the current tile; next_batch is where the batch after it starts
+  uint32_t left = 0, next_batch = dynamic ? *handed_out : 0u;
+  uint32_t next = dynamic ? next_batch : tile + tile_step;
   // invariant at the top: the current tile is parked in LDS, no load is in flight
   for (;;) {
     if (next >= tile_end) {
       store_tile(dof);
       break;
     }
-    if (dynamic && threadIdx.x == 0) asked = atomicAdd(&queue[0], 1u);
+    const bool new_batch = dynamic && left == 0;   // `next` is the first tile of a batch: ask for the batch after it
+    if (new_batch && threadIdx.x == 0) asked = atomicAdd(&queue[0], grab);
     int64_t dof_next;
     tile_origin(P, next, &so, &dof_next);
     load_tile(so);
@@ -306,11 +310,20 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();   // every pick is done: LDS may be overwritten (and every lane has read the word behind the tile)
     park_tile();
-    if (dynamic && threadIdx.x == 0) *handed_out = gridDim.x + asked;
+    if (new_batch && threadIdx.x == 0) *handed_out = gridDim.x + asked;
     __syncthreads();
     tile = next;
     dof = dof_next;
-    next = dynamic ? *handed_out : tile + tile_step;
+    if (!dynamic) {
+      next = tile + tile_step;
+    } else if (new_batch) {
+      left = grab - 1u;
+      next_batch = *handed_out;
+      next = left > 0 ? tile + 1u : next_batch;
+    } else {
+      --left;
+      next = left > 0 ? tile + 1u : next_batch;
+    }
   }
   if (dynamic && threadIdx.x == 0) leave_tile_queue(queue);
 }
@@ -506,7 +519,7 @@ static hipError_t launch_transpose_f(const lc_plan& plan, const void* src, void*
     if (queue) lds_bytes += 16;   // the word that carries the next tile to the other lanes
   }
   hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), lds_bytes, s, plan.transpose, sp, dp, queue,
-                     plan.lds_bytes);
+                     plan.lds_bytes, (uint32_t)std::max(1, plan.tile_queue));
   return hipSuccess;
 }
 template <int ES, int V, int MT, int NT>

@@ -527,13 +527,15 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     if (P.n_ragged > 0 || (V == 1 && es != 16)) want = 8;
     plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : std::max(1, std::min(std::min(8, fit), want));
     // Long grids of large tiles: workgroups drift apart over hundreds of tiles, and asking a device-side queue for the
-    // next tile (one tile ahead) evens that out (measured: +10 % on the NCHW -> NHWC workload); with small tiles or few
-    // tiles per workgroup the answer arrives later than the loads it waits beside, and the fixed order is faster.
-    // 16 bytes of LDS behind the tile carry the answer to the other lanes.
+    // next tiles (one request ahead) evens that out.  Measured on MI355X: one request per 64 KiB of tile data is best
+    // (64 KiB tiles one at a time: 71 -> 79 % of the HBM peak; 32 KiB tiles two at a time: 73 -> 81 %, one at a time 65 %:
+    // too many requests for one counter); with few tiles per workgroup the fixed order is faster (2048 tiles: 69 -> 45 %).
+    // 16 bytes of LDS behind the tile carry the answer to the other lanes.  tile_queue = tiles per request, 0 = fixed order.
     const bool queue_fits = (uint64_t)(plan->lds_bytes + 16u) * (unsigned)plan->wgs_per_cu <= 160u * 1024u && !P.blocked &&
                             P.n_ragged == 0 && !(V == 1 && es != 16);   // the kernel without predicates only
-    const bool queue_pays = plan->lds_bytes >= 64u * 1024u && P.n_tiles >= 4096u;
-    plan->tile_queue = queue_fits && (tune.tile_queue >= 0 ? tune.tile_queue != 0 : queue_pays) ? 1 : 0;
+    const bool queue_pays = plan->lds_bytes >= 32u * 1024u && P.n_tiles >= 4096u;
+    const int per_request = (int)std::max(1u, 65536u / std::max(1u, plan->lds_bytes));
+    plan->tile_queue = queue_fits ? (tune.tile_queue >= 0 ? tune.tile_queue : (queue_pays ? per_request : 0)) : 0;
     plan->src_align = (unsigned)(V * es);
     plan->dst_align = (unsigned)(V * es);
     return true;
@@ -837,7 +839,7 @@ std::string describe(const lc_plan& plan) {
     s += " unroll=" + std::to_string(plan.unroll);
   }
   s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal);
-  if (plan.tile_queue) s += " tile_queue=1";
+  if (plan.tile_queue) s += " tile_queue=" + std::to_string(plan.tile_queue);
   s += " blocked=" + std::to_string(plan.cls == KernelClass::Transpose ? plan.transpose.blocked : plan.cls == KernelClass::Direct ? plan.direct.blocked : 0u);
   if (!plan.note.empty()) s += " note=\"" + plan.note + "\"";
   return s;

@@ -29,7 +29,7 @@ struct Tuning {
   std::vector<int64_t> tile;   // transpose: tile extents per joint mode (overrides the planner's choice)
   int force_class = -1;        // 0 generic, 1 direct, 2 transpose (falls back when not applicable)
   int max_vec_bytes = -1;      // cap on the access width
-  int tile_queue = -1;         // transpose: 1 / 0 = hand tiles out through a device-side queue / in a fixed order
+  int tile_queue = -1;         // transpose: n > 0 = hand tiles out through a device-side queue, n per request; 0 = in a fixed order
 };
 Tuning tuning_from_env();
 
@@ -69,7 +69,7 @@ struct lc_plan {
   lc::GenericParams generic{};
 
   int wgs_per_cu = 0;
-  int tile_queue = 0;                      // transposing class: tiles past the first grid-full are handed out on request
+  int tile_queue = 0;                      // transposing class: tiles past the first grid-full are handed out on request, this many at a time
   int nontemporal = 0;                     // bit 0: loads, bit 1: stores
   std::string note;                        // why a faster class was not taken
 };

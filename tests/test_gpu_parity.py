@@ -209,11 +209,15 @@ def test_tile_queue(oracle, monkeypatch):
         for rep in range(2):
             desc = _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag=w.name + " queue")
         assert "tile_queue=1" in desc, desc
-    # one workgroup per CU, so that the grid is shorter than the list of tiles and every workgroup asks several times
+    # one workgroup per CU, so that the grid is shorter than the list of tiles and every workgroup asks several times;
+    # one, three and eight tiles per request (the last batch straddles the end of the list)
     monkeypatch.setenv("LC_TUNE_WGS_PER_CU", "1")
-    for name, scale in (("c5", 64), ("c2", 4), ("c3", 16), ("c1", 1)):
-        w = W.workload(name, scale)
-        assert "tile_queue=1" in _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag=w.name + " queue, 1 per CU")
+    for grab in (1, 3, 8):
+        monkeypatch.setenv("LC_TUNE_TILE_QUEUE", str(grab))
+        for name, scale in (("c5", 64), ("c2", 4), ("c3", 16), ("c1", 1)):
+            w = W.workload(name, scale)
+            desc = _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="%s queue %d, 1 per CU" % (w.name, grab))
+            assert "tile_queue=%d" % grab in desc, desc
 
 
 def test_tile_queue_on_several_streams(oracle, monkeypatch):
