@@ -199,7 +199,13 @@ lc_status_t lc_plan_create(const lc_layout_t* src, const lc_layout_t* dst, lc_dt
                            unsigned src_align_bytes, unsigned dst_align_bytes, lc_plan_t** out);
 /* One-line description: kernel class, vector width, joint modes, tile, grid, LDS bytes, swizzle. */
 lc_status_t lc_plan_describe(const lc_plan_t* plan, char* buf, size_t cap, size_t* needed);
-/* Enqueue the copy on `hip_stream`.  Asynchronous.  Errors: MISALIGNED, HIP. */
+/* Enqueue the copy on `hip_stream`.  Asynchronous; allocates nothing, copies nothing, synchronises nothing (it may be
+ * recorded into a HIP graph).  Errors: MISALIGNED, HIP.
+ * Long transposing copies hand their tiles out through a pair of counters in device memory of the library's own code
+ * object, one pair per stream (the library's launches on a stream run in stream order, which is what keeps a pair to one
+ * kernel at a time); launches on more than 64 streams of a device, and launches under graph capture, use a fixed tile
+ * order instead.  A stream that is destroyed with such a copy still queued, and whose handle value the runtime then
+ * gives to a new stream, would share its pair with it: synchronise before destroying the stream. */
 lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream);
 void lc_plan_destroy(lc_plan_t* plan);
 
