@@ -344,6 +344,32 @@ def copy(src, src_layout, dst, dst_layout, begin=0, end=None, spans_checked=Fals
     return dst
 
 
+def copy_parallel(src, src_layout, dst, dst_layout, threads, begin=0, end=None, spans_checked=False):
+    """The same element loop with the integral coordinates [begin, end) cut into `threads` consecutive ranges, one host
+    thread per range (ctypes releases the interpreter lock during the call).  Every range runs the oracle's own
+    copy_range.  Only for an injective destination: then no two coordinates write the same offset and the order of
+    Sec. 2.6.1's loop cannot matter; the caller vouches for that (the five benchmark workloads are injective)."""
+    from concurrent.futures import ThreadPoolExecutor
+    sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
+    end = dl.size if end is None else end
+    n = end - begin
+    threads = max(1, min(int(threads), n))
+    if not spans_checked:
+        assert sl.cosize <= src.size and dl.cosize <= dst.size, "buffer smaller than the layout's cosize"
+    cuts = [begin + n * k // threads for k in range(threads + 1)]
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        list(pool.map(lambda k: copy(src, sl, dst, dl, cuts[k], cuts[k + 1], spans_checked=True), range(threads)))
+    return dst
+
+
+def host_threads(limit=16):
+    """Host cores this process may use (its affinity mask), at most `limit`."""
+    try:
+        return max(1, min(limit, len(os.sched_getaffinity(0))))
+    except AttributeError:
+        return max(1, min(limit, os.cpu_count() or 1))
+
+
 def gemm_sizes(a_layout, b_layout, c_layout):
     """(M, N, K) — (M, N, K, L) for rank-3 layouts — when the three layouts meet the preconditions of the generic
     (batched) GEMM, else OracleError."""

@@ -246,7 +246,7 @@ lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, c
   }
 }
 
-int64_t lc_plan_algorithmic_bytes(const lc_plan_t* plan) { return plan ? 2 * plan->n_elems * plan->elem_bytes : -1; }
+int64_t lc_plan_algorithmic_bytes(const lc_plan_t* plan) { return plan ? (plan->distinct_reads + plan->n_elems) * plan->elem_bytes : -1; }
 
 lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup, int iters,
                          void* hip_stream, float* ms_per_iter) {

@@ -468,17 +468,28 @@ static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsig
   }
 }
 
-// The pair of queue counters a launch on stream `s` may use, or nullptr: the stream is being captured into a graph (a
-// replay may run beside anything), or all pairs belong to other streams already.  One pair per stream and device:
-// launches on a stream do not overlap, which is what the counters' reset by the last workgroup relies on.
-static hipError_t tile_queue_of_stream(hipStream_t s, unsigned int** out) {
+// The pair of queue counters a launch on stream `s` may use, or nullptr (fixed tile order) when no pair can be promised to
+// this launch alone: the stream is being captured into a graph (a replay may run beside anything), the handle is
+// hipStreamPerThread (one value, a different stream in every host thread), the stream belongs to another device than the
+// current one, or all pairs belong to other streams already.  One pair per stream and device: launches on a stream do not
+// overlap, which is what the counters' reset by the last workgroup relies on.  `failed` names the call behind an error.
+static hipError_t tile_queue_of_stream(hipStream_t s, unsigned int** out, const char** failed) {
   *out = nullptr;
+  if (s == hipStreamPerThread) return hipSuccess;
   hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+  *failed = "hipStreamIsCapturing";
   hipError_t e = hipStreamIsCapturing(s, &capturing);
   if (e != hipSuccess) return e;
   if (capturing != hipStreamCaptureStatusNone) return hipSuccess;
   int dev = 0;
+  *failed = "hipGetDevice";
   if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+  if (s != nullptr) {   // the null stream is the current device's
+    hipDevice_t owner = 0;
+    *failed = "hipStreamGetDevice";
+    if ((e = hipStreamGetDevice(s, &owner)) != hipSuccess) return e;
+    if ((int)owner != dev) return hipSuccess;
+  }
   static std::mutex lock;
   static std::map<std::pair<int, hipStream_t>, int> slot_of;      // (device, stream) -> pair
   static std::map<int, std::pair<unsigned int*, int>> per_device;   // device -> (address of the array, pairs handed out)
@@ -486,6 +497,7 @@ static hipError_t tile_queue_of_stream(hipStream_t s, unsigned int** out) {
   auto dv = per_device.find(dev);
   if (dv == per_device.end()) {
     void* base = nullptr;
+    *failed = "hipGetSymbolAddress";
     if ((e = hipGetSymbolAddress(&base, HIP_SYMBOL(g_tile_queues))) != hipSuccess) return e;
     dv = per_device.emplace(dev, std::make_pair(static_cast<unsigned int*>(base), 0)).first;
   }
@@ -498,37 +510,45 @@ static hipError_t tile_queue_of_stream(hipStream_t s, unsigned int** out) {
   return hipSuccess;
 }
 
+// what a launcher reports back: the HIP status of whatever it called before the launch, and that call's name
+struct PreLaunch {
+  hipError_t status = hipSuccess;
+  const char* call = "";
+};
+
 template <int ES, int V, int MT, int NT, bool FULL>
-static hipError_t launch_transpose_f(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static PreLaunch launch_transpose_f(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   const unsigned char* sp = static_cast<const unsigned char*>(src);
   unsigned char* dp = static_cast<unsigned char*>(dst);
-  if (plan.lds_bytes > 64 * 1024) {
-    static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
-    if (!raised.load(std::memory_order_acquire)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT, FULL>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-      if (e != hipSuccess) return e;
-      raised.store(true, std::memory_order_release);
-    }
-  }
+  PreLaunch pre;
   unsigned int* queue = nullptr;
   unsigned lds_bytes = plan.lds_bytes;
   if (plan.tile_queue && grid < plan.transpose.n_tiles) {
-    hipError_t e = tile_queue_of_stream(s, &queue);
-    if (e != hipSuccess) return e;
+    pre.status = tile_queue_of_stream(s, &queue, &pre.call);
+    if (pre.status != hipSuccess) return pre;
     if (queue) lds_bytes += 16;   // the word that carries the next tile to the other lanes
+  }
+  if (lds_bytes > 64 * 1024) {   // what this launch asks for, the queue's word included
+    static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
+    if (!raised.load(std::memory_order_acquire)) {
+      pre.call = "hipFuncSetAttribute";
+      pre.status = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT, FULL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (pre.status != hipSuccess) return pre;
+      raised.store(true, std::memory_order_release);
+    }
   }
   hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), lds_bytes, s, plan.transpose, sp, dp, queue,
                      plan.lds_bytes, (uint32_t)std::max(1, plan.tile_queue));
-  return hipSuccess;
+  return pre;
 }
 template <int ES, int V, int MT, int NT>
-static hipError_t launch_transpose_n(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static PreLaunch launch_transpose_n(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   if (plan.transpose.n_micro == (uint32_t)MT * kBlock) return launch_transpose_f<ES, V, MT, NT, true>(plan, src, dst, grid, s);
   return launch_transpose_f<ES, V, MT, NT, false>(plan, src, dst, grid, s);
 }
 template <int ES, int V, int MT>
-static hipError_t launch_transpose_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static PreLaunch launch_transpose_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   switch (plan.nontemporal) {
     case 0: return launch_transpose_n<ES, V, MT, 0>(plan, src, dst, grid, s);
     case 1: return launch_transpose_n<ES, V, MT, 1>(plan, src, dst, grid, s);
@@ -537,7 +557,7 @@ static hipError_t launch_transpose_m(const lc_plan& plan, const void* src, void*
   }
 }
 template <int ES, int V>
-static hipError_t launch_transpose(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static PreLaunch launch_transpose(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   switch (plan.micro_per_thread) {
     case 1: return launch_transpose_m<ES, V, 1>(plan, src, dst, grid, s);
     case 2: return launch_transpose_m<ES, V, 2>(plan, src, dst, grid, s);
@@ -546,22 +566,22 @@ static hipError_t launch_transpose(const lc_plan& plan, const void* src, void* d
       if constexpr (V == 1) return launch_transpose_m<ES, V, 8>(plan, src, dst, grid, s);
       break;
   }
-  return hipErrorInvalidValue;
+  return PreLaunch{hipErrorInvalidValue, "kernel selection (micro-tiles per lane)"};
 }
 
 template <int ES, int V, int MT>
-static hipError_t launch_ragged_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static PreLaunch launch_ragged_m(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   const unsigned char* sp = static_cast<const unsigned char*>(src);
   unsigned char* dp = static_cast<unsigned char*>(dst);
   if (plan.nontemporal & 1)
     hipLaunchKernelGGL((ragged_transpose_kernel<ES, V, MT, 1>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
   else
     hipLaunchKernelGGL((ragged_transpose_kernel<ES, V, MT, 0>), dim3(grid), dim3(kBlock), plan.lds_bytes, s, plan.transpose, sp, dp);
-  return hipSuccess;
+  return PreLaunch{};
 }
 template <int ES, int V>
-static hipError_t launch_ragged(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
-  if (plan.lds_bytes > 64 * 1024) return hipErrorInvalidValue;   // the planner keeps ragged tiles within the default LDS limit
+static PreLaunch launch_ragged(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  if (plan.lds_bytes > 64 * 1024) return PreLaunch{hipErrorInvalidValue, "ragged tile larger than the default LDS limit"};   // the planner keeps them within it
   switch (plan.micro_per_thread) {
     case 1: return launch_ragged_m<ES, V, 1>(plan, src, dst, grid, s);
     case 2: return launch_ragged_m<ES, V, 2>(plan, src, dst, grid, s);
@@ -570,7 +590,7 @@ static hipError_t launch_ragged(const lc_plan& plan, const void* src, void* dst,
       if constexpr (V == 1) return launch_ragged_m<ES, V, 8>(plan, src, dst, grid, s);
       break;
   }
-  return hipErrorInvalidValue;
+  return PreLaunch{hipErrorInvalidValue, "kernel selection (micro-tiles per lane)"};
 }
 
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream) {
@@ -582,7 +602,7 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
   if (cus <= 0) return LC_ERR_HIP;
   hipStream_t s = static_cast<hipStream_t>(stream);
   (void)hipGetLastError();
-  hipError_t pre = hipSuccess;
+  PreLaunch pre;
   if (plan.cls == KernelClass::Generic) {
     uint64_t want = ((uint64_t)plan.generic.n + kBlock - 1) / kBlock;
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, (uint64_t)cus * 16));
@@ -637,7 +657,7 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
       default: return LC_ERR_UNSUPPORTED_DTYPE;
     }
   }
-  if (hip_failed(pre, "hipFuncSetAttribute") || hip_failed(hipGetLastError(), "kernel launch")) return LC_ERR_HIP;
+  if (hip_failed(pre.status, pre.call) || hip_failed(hipGetLastError(), "kernel launch")) return LC_ERR_HIP;
   return LC_OK;
 }
 

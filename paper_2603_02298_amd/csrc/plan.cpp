@@ -518,7 +518,6 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     plan->dst_run_bytes = run_length(J, dst_order, t, false) * es;
     // nontemporal stores only when every store instruction covers whole 128-byte lines
     if (tune.nontemporal < 0 && plan->dst_run_bytes % 128 == 0) plan->nontemporal |= 2;
-    // nontemporal stores only when every store instruction covers whole 128-byte lines
     // Measured on MI355X: HBM efficiency is best with ONE resident workgroup per CU (its next tile's
     // loads overlap its current tile's stores); short grids need more workgroups to fill the chip.
     int fit = (int)(160 * 1024 / std::max(1u, plan->lds_bytes));
@@ -576,6 +575,9 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
 
   // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
   Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
+  plan->distinct_reads = 1;
+  for (const Mode& m : S)
+    if (m.stride != 0) plan->distinct_reads *= m.extent;
   // a1: the destination must be injective, otherwise the result would depend on the iteration order -- except where
   // the order of Sec. 2.6.1's loop (i ascending) decides it without a race: of the coordinates that differ only in
   // destination modes of stride 0, the one with those modes at their last position is written last.  The copy is then
@@ -611,10 +613,12 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     return LC_OK;
   }
 
-  // a5 (the paper's route): K = stride-1 head of src o dst^ (Sec. 3.4.2); kept for reporting and
-  // cross-checked against the joint modes below
+  // a5 (the paper's route): K = stride-1 head of src o dst^ (Sec. 3.4.2), reported by describe().  The width the
+  // kernels use is derived from the joint modes below and clamped by element width and alignment; when both exist
+  // it never exceeds K (asserted where the direct class picks its vector).
   int64_t K = 1;
-  if (max_common_vector(src, dst, &K) != LC_OK) K = 1;
+  const bool K_known = max_common_vector(src, dst, &K) == LC_OK;
+  if (!K_known) K = 1;
   plan->common_vector = K;
 
   // a3: refine both shapes to one shape F by composing each layout with the identity layout of F
@@ -708,6 +712,8 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     for (int k = 0; k < nj; ++k)
       if (k != q) { need.push_back(J[(size_t)k].a); need.push_back(J[(size_t)k].b); }
     VEC = common_pow2(cap, need);
+    // the two routes to the vector agree: a run that both sides keep contiguous is a prefix of the algebraic K
+    if (K_known && VEC > K) VEC = common_pow2((int)std::min<int64_t>(cap, K), need);
   }
 
   // ---- Transpose class on 16-byte words ---------------------------------------------------------

@@ -39,6 +39,7 @@ struct lc_plan {
   lc::KernelClass cls = lc::KernelClass::Generic;
   int elem_bytes = 0;
   int64_t n_elems = 0;
+  int64_t distinct_reads = 0;              // source elements read when modes of stride 0 (re-reads of one element) count once
   // Destination modes of stride 0: the sequential loop's last write wins, so the copy is the slice at those modes'
   // last coordinates: the source is read from src + src_offset_elems, the modes are gone from the plan.
   int64_t src_offset_elems = 0;

@@ -14,11 +14,17 @@ SEED_BASE = 2603022980
 
 
 class Workload:
-    def __init__(self, name, dtype, src_layout, dst_layout, src_elems, dst_elems, n, values, note=""):
+    def __init__(self, name, dtype, src_layout, dst_layout, src_elems, dst_elems, n, values, note="", distinct_reads=None,
+                 dram_read_elems=None):
         self.name, self.dtype = name, dtype
         self.src_layout, self.dst_layout = src_layout, dst_layout
         self.src_elems, self.dst_elems, self.n = src_elems, dst_elems, n
         self.values, self.note = values, note
+        # plain numbers stated per workload (no layout arithmetic here; the tests check them against the oracle):
+        # distinct source elements the copy reads (a stride-0 mode re-reads the same ones), and source elements whose
+        # 32-byte sectors DRAM has to deliver (a strided gather drags its neighbours along)
+        self.distinct_reads = n if distinct_reads is None else distinct_reads
+        self.dram_read_elems = self.distinct_reads if dram_read_elems is None else dram_read_elems
 
     @property
     def elem_bytes(self):
@@ -26,7 +32,13 @@ class Workload:
 
     @property
     def algorithmic_bytes(self):
-        return 2 * self.n * self.elem_bytes
+        """Element reads + element writes the method performs, re-reads through a stride-0 mode counted once."""
+        return (self.distinct_reads + self.n) * self.elem_bytes
+
+    @property
+    def dram_minimum_bytes(self):
+        """Bytes HBM cannot avoid moving: every 32-byte sector of the source that holds a read element, every written byte."""
+        return (self.dram_read_elems + self.n) * self.elem_bytes
 
 
 def _c1(scale=1):
@@ -69,13 +81,14 @@ def _c3(scale=1):
 def _c4a(scale=1):
     n = (1 << 26) // scale
     return Workload("c4a_strided_gather_f32", "f32", "%d:3" % n, "%d:1" % n, (1 << 28) // scale, n, n, "int_valued",
-                    "gather with stride 3 into a contiguous destination")
+                    "gather with stride 3 into a contiguous destination",
+                    dram_read_elems=3 * n)   # every 32-byte sector of the 3n-element span holds a read element
 
 
 def _c4b(scale=1):
     m = (1 << 20) // scale
     return Workload("c4b_broadcast_f32", "f32", "(%d,16):(1,0)" % m, "(%d,16):(1,%d)" % (m, m), m, 16 * m, 16 * m,
-                    "int_valued", "stride-0 broadcast of a vector into 16 rows")
+                    "int_valued", "stride-0 broadcast of a vector into 16 rows", distinct_reads=m)
 
 
 def _c5(scale=1):

@@ -118,3 +118,17 @@ def test_aliasing_destination_last_write_wins(oracle):
     dst = np.zeros(3, np.uint32)
     oracle.copy(src, "6:1", dst, "(3,2):(1,0)")
     assert list(dst) == [13, 14, 15]
+
+
+def test_ranges_on_host_threads_equal_the_single_loop(oracle):
+    """The loop cut into ranges (one per host thread) against the loop as Sec. 2.6.1 writes it and against numpy:
+    for an injective destination the order of the coordinates cannot matter."""
+    N, C, H, W = 3, 5, 7, 11
+    sl = "(%d,%d,%d,%d):(%d,%d,%d,1)" % (N, C, H, W, C * H * W, H * W, W)
+    dl = "(%d,%d,%d,%d):(%d,1,%d,%d)" % (N, C, H, W, H * W * C, W * C, C)
+    src = _rand(N * C * H * W, np.uint32, 21)
+    whole = oracle.copy(src, sl, np.zeros_like(src), dl)
+    for threads in (1, 2, 3, 8, 5000):
+        cut = oracle.copy_parallel(src, sl, np.zeros_like(src), dl, threads)
+        assert (cut == whole).all()
+    assert (whole.reshape(N, H, W, C) == src.reshape(N, C, H, W).transpose(0, 2, 3, 1)).all()
