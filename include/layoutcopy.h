@@ -47,11 +47,13 @@ typedef enum {
   LC_ERR_NOT_SEGREGATED = 9,      /* composition: sublayouts of B without segregated images (Sec. 3.3.2) */
   LC_ERR_NOT_INJECTIVE = 10,      /* complement: a mode of the layout overlaps the span of smaller ones */
   LC_ERR_NOT_SURJECTIVE = 11,     /* logical divide: (B, B*) misses coordinates of A (Sec. 3.5.2) */
-  LC_ERR_DST_ALIASES = 12,        /* copy: two coordinates of dst share an offset other than through stride-0 modes */
+  LC_ERR_DST_ALIASES = 12,        /* GEMM: two coordinates of C share an offset (copies with such a destination plan as "last-writer") */
   LC_ERR_UNSUPPORTED_DTYPE = 13,
   LC_ERR_TOO_LARGE = 14,          /* size or cosize beyond 2^62, more than 64 leaf modes, or more work than the kernels index */
   LC_ERR_MISALIGNED = 15,         /* a device pointer is less aligned than the plan was created for */
-  LC_ERR_HIP = 16                 /* a HIP runtime call failed (no device, launch failure, ...) */
+  LC_ERR_HIP = 16,                /* a HIP runtime call failed (no device, launch failure, ...) */
+  LC_ERR_NEEDS_WORKSPACE = 17,    /* the plan needs scratch device memory: use lc_plan_execute_workspace */
+  LC_ERR_WORKSPACE_TOO_SMALL = 18 /* the workspace is NULL, misaligned or smaller than lc_plan_workspace_bytes */
 } lc_status_t;
 
 /* Element types.  The copy moves bit patterns; the dtype only fixes the element width. */
@@ -188,13 +190,13 @@ lc_status_t lc_slayout_right_inverse(const lc_slayout_t* a, lc_layout_t** out);
 
 /* src_align_bytes / dst_align_bytes: alignment the caller guarantees for the device pointers that
  * will be passed to lc_plan_execute (a power of two; 256 for fresh allocations).  Errors: SIZE_MISMATCH,
- * DST_ALIASES (dst not injective; a single-element copy is exempt), UNSUPPORTED_DTYPE, TOO_LARGE.
+ * UNSUPPORTED_DTYPE, TOO_LARGE.
  * Destination modes of stride 0 do not count as aliasing: the loop of Sec. 2.6.1 runs i upwards, so the
  * coordinate with those modes at their last position is the one written last, and the plan copies exactly
  * that slice of the source (Sec. 2.5.1; lc_plan_describe reports overwritten_modes and src_offset).  Any
- * other overlap in dst (strides that make distinct coordinates meet) is refused with DST_ALIASES; an injective
- * dst of more than 2^22 elements whose strides are not nested (each at least the extent of the modes below it)
- * is refused as well: its injectivity is not proved cheaply. */
+ * other overlap in dst (strides that make distinct coordinates meet), and a dst of more than 2^22 elements whose
+ * strides are not nested (each at least the extent of the modes below it; its injectivity is not proved cheaply),
+ * gives a plan of class "last-writer", which needs a workspace: see lc_plan_execute_workspace. */
 lc_status_t lc_plan_create(const lc_layout_t* src, const lc_layout_t* dst, lc_dtype_t dt,
                            unsigned src_align_bytes, unsigned dst_align_bytes, lc_plan_t** out);
 /* One-line description: kernel class, vector width, joint modes, tile, grid, LDS bytes, swizzle. */
@@ -208,6 +210,19 @@ lc_status_t lc_plan_describe(const lc_plan_t* plan, char* buf, size_t cap, size_
  * launches on a stream of another device than the current one use a fixed tile order instead.  A stream that is destroyed with such a copy still queued, and whose handle value the runtime then
  * gives to a new stream, would share its pair with it: synchronise before destroying the stream. */
 lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream);
+/* Scatter with repeated destination offsets (Table copy, Sec. 2.6.1): the loop runs i upwards, so an offset that several
+ * integral coordinates reach keeps the value of the largest of them.  A destination that aliases in another way than
+ * through modes of stride 0, or whose distinctness cannot be shown on the host (more than 2^22 elements with strides that
+ * do not nest), plans as class "last-writer": a first pass records, per destination offset, the largest coordinate that
+ * reaches it (atomic maximum into one 32-bit word per element of cosize(dst)), a second pass lets only those coordinates
+ * write.  Such a plan needs lc_plan_workspace_bytes(plan) bytes of scratch device memory (0 for every other plan), which
+ * the caller owns and passes to lc_plan_execute_workspace (4-byte aligned; contents before and after the call are
+ * meaningless; two executions that overlap in time need two workspaces).  lc_plan_execute and lc_copy return
+ * NEEDS_WORKSPACE for such a plan; lc_plan_execute_workspace runs every other plan as lc_plan_execute does and ignores the
+ * workspace.  Errors: WORKSPACE_TOO_SMALL (NULL, misaligned or short), MISALIGNED, HIP. */
+int64_t lc_plan_workspace_bytes(const lc_plan_t* plan);
+lc_status_t lc_plan_execute_workspace(const lc_plan_t* plan, const void* src, void* dst, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream);
 void lc_plan_destroy(lc_plan_t* plan);
 
 /* lc_plan_create (alignment taken from the two pointers) + lc_plan_execute + lc_plan_destroy.  The library keeps the

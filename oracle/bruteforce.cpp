@@ -9,7 +9,7 @@
 // above one mode scaled by 2 or 3 (padding); every regrouping of the modes into contiguous groups.
 // A second universe takes every stride in 0..Dmax for rank <= 3, extents <= 4.
 //
-// usage: bruteforce [--rank R] [--extent E] [--pair-rank r] [--pair-extent e] [--random N] [--seed S]
+// usage: bruteforce [--rank R] [--extent E] [--pair-rank r] [--pair-extent e] [--random N] [--seed S] [--product-budget C]
 // Exit status 0 iff no post-condition failed.
 #include <algorithm>
 #include <atomic>
@@ -249,6 +249,12 @@ void check_unary(const Layout& A) {
 }
 
 // ---- pair checks ------------------------------------------------------------------------------------
+// The product checks walk size(A) * size(B) coordinates.  Pairs drawn from a large universe can exceed what is
+// affordable: above this many coordinates the defining equation of the logical product is checked on an evenly
+// spaced lattice of about that many coordinates (both ends included) and the tile-disjointness and
+// blocked / raked rearrangement checks, which need the whole image, are left to the smaller pairs.  0 = no limit.
+int64_t g_product_budget = 0;
+
 void check_pair(const Layout& A, const Layout& B) {
   const std::string name = to_string(A) + " , " + to_string(B);
   {  // composition, Sec. 3.3: B <= R (compatible) and R(c) = A(B(c)) for every coordinate of B
@@ -295,9 +301,19 @@ void check_pair(const Layout& A, const Layout& B) {
       bool good = complement(A, 0, &Astar) == OK && rank(R.shape) == 2 && to_string(sublayout(R, 0)) == to_string(A) &&
                   compatible(B.shape, sublayout(R, 1).shape);
       const int64_t na = size(A), nb = size(B);
-      for (int64_t b = 0; good && b < nb; ++b)
-        for (int64_t a = 0; good && a < na; ++a) good = eval(R, a + na * b) == eval(A, a) + eval(Astar, eval(B, b));
-      if (good && is_injective(A) && is_injective(B)) {
+      const bool sampled = g_product_budget > 0 && na * nb > g_product_budget;
+      int64_t step_a = 1, step_b = 1;
+      if (sampled) {
+        tally("logical_product_sampled").cases++;
+        int64_t side = 1;
+        while ((side + 1) * (side + 1) <= g_product_budget) ++side;
+        step_a = std::max<int64_t>(1, (na + side - 1) / side);
+        step_b = std::max<int64_t>(1, (nb + side - 1) / side);
+      }
+      for (int64_t b = 0; good && b < nb; b = (b + step_b < nb || b == nb - 1) ? b + step_b : nb - 1)
+        for (int64_t a = 0; good && a < na; a = (a + step_a < na || a == na - 1) ? a + step_a : na - 1)
+          good = eval(R, a + na * b) == eval(A, a) + eval(Astar, eval(B, b));
+      if (good && !sampled && is_injective(A) && is_injective(B)) {
         // the complement is disjoint from A on its whole extended domain, so distinct grid points give disjoint tiles
         std::vector<int64_t> all = image_of(R, na * nb);
         std::sort(all.begin(), all.end());
@@ -313,7 +329,7 @@ void check_pair(const Layout& A, const Layout& B) {
       }
       if (good) t.ok++; else t.failed("logical_product " + name + " -> " + to_string(R));
     }
-    if (rank(A.shape) == rank(B.shape) && !A.shape.is_int) {
+    if (rank(A.shape) == rank(B.shape) && !A.shape.is_int && !(g_product_budget > 0 && size(A) * size(B) > g_product_budget)) {
       Tally& tb = tally("blocked_raked_product");
       tb.cases++;
       Layout P, Bp, Rp;
@@ -434,12 +450,13 @@ int main(int argc, char** argv) {
     else if (!strcmp(argv[i], "--max-stride")) Dmax = atoi(argv[i + 1]);
     else if (!strcmp(argv[i], "--random")) nrandom = atol(argv[i + 1]);
     else if (!strcmp(argv[i], "--seed")) seed = strtoull(argv[i + 1], nullptr, 10);
+    else if (!strcmp(argv[i], "--product-budget")) g_product_budget = atoll(argv[i + 1]);
     else { fprintf(stderr, "unknown option %s\n", argv[i]); return 2; }
   }
   rng_state = seed;
   for (const char* n : {"coalesce", "coalesce_bymode", "right_inverse", "right_inverse_size_bound",
                         "right_inverse_maximal_when_injective", "complement", "composition", "composition_refused",
-                        "max_common_vector", "logical_divide", "zipped_divide", "left_inverse", "logical_product",
+                        "max_common_vector", "logical_divide", "zipped_divide", "left_inverse", "logical_product", "logical_product_sampled",
                         "blocked_raked_product"})
     tally(n);
 

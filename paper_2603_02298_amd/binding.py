@@ -80,6 +80,9 @@ def lib():
     L.lc_plan_create.argtypes = [P, P, ctypes.c_int, ctypes.c_uint, ctypes.c_uint, PP]
     L.lc_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
     L.lc_plan_execute.argtypes = [P, P, P, P]
+    L.lc_plan_workspace_bytes.argtypes = [P]
+    L.lc_plan_workspace_bytes.restype = i64
+    L.lc_plan_execute_workspace.argtypes = [P, P, P, P, sz, P]
     L.lc_plan_destroy.argtypes = [P]
     L.lc_plan_destroy.restype = None
     L.lc_copy.argtypes = [P, P, P, P, ctypes.c_int, P]
@@ -294,6 +297,15 @@ class Plan:
     def execute(self, src_ptr, dst_ptr, stream=0):
         """src_ptr / dst_ptr: device addresses (e.g. tensor.data_ptr()); stream: hipStream_t as int."""
         _check(lib().lc_plan_execute(self._h, src_ptr, dst_ptr, stream), "lc_plan_execute")
+
+    @property
+    def workspace_bytes(self):
+        return lib().lc_plan_workspace_bytes(self._h)
+
+    def execute_workspace(self, src_ptr, dst_ptr, workspace_ptr, workspace_bytes, stream=0):
+        """The same with scratch device memory (a device address and its size) for plans of class last-writer."""
+        _check(lib().lc_plan_execute_workspace(self._h, src_ptr, dst_ptr, workspace_ptr, workspace_bytes, stream),
+               "lc_plan_execute_workspace")
 
     def time(self, src_ptrs, dst_ptrs, warmup, iters, stream=0):
         n = len(src_ptrs)

@@ -67,6 +67,8 @@ const char* lc_status_string(lc_status_t s) {
     case LC_ERR_TOO_LARGE: return "TOO_LARGE";
     case LC_ERR_MISALIGNED: return "MISALIGNED";
     case LC_ERR_HIP: return "HIP";
+    case LC_ERR_NEEDS_WORKSPACE: return "NEEDS_WORKSPACE";
+    case LC_ERR_WORKSPACE_TOO_SMALL: return "WORKSPACE_TOO_SMALL";
   }
   return "UNKNOWN";
 }
@@ -208,6 +210,12 @@ lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, v
   if (!plan) return LC_ERR_INVALID_ARG;
   return lc::execute_plan(*plan, src, dst, hip_stream);
 }
+int64_t lc_plan_workspace_bytes(const lc_plan_t* plan) { return plan ? plan->workspace_bytes : -1; }
+lc_status_t lc_plan_execute_workspace(const lc_plan_t* plan, const void* src, void* dst, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::execute_plan_workspace(*plan, src, dst, workspace, workspace_bytes, hip_stream);
+}
 void lc_plan_destroy(lc_plan_t* plan) { delete plan; }
 
 lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, const lc_layout_t* dst_layout, lc_dtype_t dt,
@@ -229,7 +237,8 @@ lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, c
                       std::to_string(align_of(dst));
     for (int64_t v : {(int64_t)tune.micro_per_thread, (int64_t)tune.rest_order, (int64_t)tune.wgs_per_cu, (int64_t)tune.unroll,
                       (int64_t)tune.swizzle_shift, (int64_t)tune.nontemporal, (int64_t)tune.blocked, tune.max_items, (int64_t)tune.force_class,
-                      (int64_t)tune.max_vec_bytes, (int64_t)tune.tile_queue})
+                      (int64_t)tune.max_vec_bytes, (int64_t)tune.tile_queue, (int64_t)tune.queue_rounds, (int64_t)tune.queue_counters,
+                      (int64_t)tune.leftover_lead, (int64_t)tune.grid})
       key += "," + std::to_string(v);
     for (int64_t v : tune.tile) key += ";" + std::to_string(v);
     std::shared_ptr<const lc_plan_t> plan = copy_plans().find(key);

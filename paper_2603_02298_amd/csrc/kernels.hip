@@ -67,6 +67,32 @@ __global__ __launch_bounds__(kBlock) void generic_kernel(GenericParams P, const 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Last writer: a destination that maps several integral coordinates to one offset keeps what Sec. 2.6.1's loop (i ascending)
+// writes there last, the value of the largest such coordinate.  Pass 1 records that coordinate per offset (atomic maximum
+// into a zeroed word per destination offset), pass 2 lets exactly the recorded coordinates write.  Coordinate 0 needs no
+// record of its own: an offset only it reaches keeps the zero the scratch memory starts with.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void zero_words_kernel(uint32_t* __restrict__ words, uint64_t n) {
+  const uint64_t step = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += step) words[i] = 0u;
+}
+__global__ __launch_bounds__(kBlock) void last_writer_mark_kernel(GenericParams P, uint32_t* __restrict__ last) {
+  touch_kernel_arguments<(int)sizeof(GenericParams)>();
+  const uint32_t step = gridDim.x * kBlock;
+  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < P.n; i += step) atomicMax(last + flat_eval(P.dst, i), i);
+}
+template <int ES>
+__global__ __launch_bounds__(kBlock) void last_writer_move_kernel(GenericParams P, const typename Word<ES>::type* __restrict__ src,
+                                                                 typename Word<ES>::type* __restrict__ dst, const uint32_t* __restrict__ last) {
+  touch_kernel_arguments<(int)sizeof(GenericParams)>();
+  const uint32_t step = gridDim.x * kBlock;
+  for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < P.n; i += step) {
+    const int64_t off = flat_eval(P.dst, i);
+    if (last[off] == i) dst[off] = src[flat_eval(P.src, i)];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Direct: one W-byte access per item and side; lanes are consecutive along the destination order.
 // U items are in flight per lane; an optional looped mode re-uses a loaded value when its source
 // stride is zero (broadcast).
@@ -150,15 +176,21 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 
   }
 }
 
-// Tile queues: pairs of counters (tiles handed out, workgroups done) in device memory that belongs to the library's code
-// object: nothing is allocated.  Launches on one stream run one after the other, so a stream keeps one pair for good;
-// the host hands out kTileQueues pairs and launches on further streams, or under graph capture, use the fixed order.
+// Tile queues: blocks of counters in device memory that belongs to the library's code object: nothing is allocated.
+// A block is kQueueLines lines of 128 bytes with one counter at the start of each, so that no two counters share a cache
+// line: line 0 counts the workgroups that are done, lines 1.. count the tiles handed out (a launch spreads its requests
+// over up to kQueueLines - 1 of them, workgroup w asking counter w mod n).  Launches on one stream run one after the
+// other, so a stream keeps one block for good; the host hands out kTileQueues blocks and launches on further streams, or
+// under graph capture, use the fixed order.
 constexpr int kTileQueues = 64;
-__device__ unsigned int g_tile_queues[kTileQueues][2];
+constexpr int kQueueLines = 16;
+constexpr int kQueueLineWords = 32;   // 128 bytes
+constexpr int kQueueBlockWords = kQueueLines * kQueueLineWords;
+__device__ __attribute__((aligned(256))) unsigned int g_tile_queues[kTileQueues * kQueueBlockWords];
 __device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
-  if (atomicAdd(&queue[1], 1u) == gridDim.x - 1u) {   // the last workgroup out: nobody asks any more
-    queue[0] = 0u;
-    queue[1] = 0u;
+  if (atomicAdd(&queue[0], 1u) == gridDim.x - 1u) {   // the last workgroup out: nobody asks any more
+#pragma unroll
+    for (int c = 0; c < kQueueLines; ++c) queue[c * kQueueLineWords] = 0u;
     __threadfence();
   }
 }
@@ -169,7 +201,8 @@ __device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
 // parking can count the stores out (memory operations retire in issue order) instead of draining them.
 template <int ES, int V, int MT, int NT, bool FULL>
 __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
-                                                          unsigned char* __restrict__ dst, unsigned int* queue, uint32_t tile_bytes, uint32_t grab) {
+                                                          unsigned char* __restrict__ dst, unsigned int* queue, uint32_t tile_bytes, uint32_t grab,
+                                                          uint32_t static_rounds, uint32_t n_counters, uint32_t leftover_lead) {
   constexpr int DW = V * ES / 4;                 // dwords per vector
   constexpr int SLOT = V * ES;                   // bytes per vector
   typedef typename Word<SLOT>::type Vec;
@@ -258,19 +291,41 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     tile_step = 1;
     tile_end = min(P.n_tiles, tile + per_wg);
   }
-  // queue != nullptr (never with `blocked`): tiles past the first gridDim.x are handed out in the order the workgroups ask
-  // for them, `grab` consecutive tiles per request: queue[0] counts the tiles handed out.  Lane 0 asks one request ahead
-  // (while the first tile of a batch is loaded it asks for the batch after the next) and passes the answer on through a
-  // word of LDS behind the tile, at a barrier the loop has anyway.  queue[1] counts the workgroups that are done; the last one
-  // puts both counters back to zero for the next launch that is given this pair.
+  // queue != nullptr (never with `blocked`): the first static_rounds * gridDim.x tiles go by workgroup index, the tiles
+  // past them are handed out in the order the workgroups ask for them, `grab` consecutive tiles per request, by n_counters
+  // counters (workgroup w asks counter w mod n_counters, which hands out every n_counters-th batch).  Lane 0 asks one tile
+  // ahead: when the loads of a workgroup's last tile by index begin it asks for its first batch, and when the loads of a
+  // batch's first tile begin it asks for the batch after.  The request is issued before those loads and so returns before
+  // them; the answer reaches the other lanes through a word of LDS behind the tile, at a barrier the loop has anyway.
+  // queue[0] counts the workgroups that are done; the last one puts every counter back to zero for the next launch that is
+  // given this block.
+  // leftover_lead > 0 (fixed order only): the tiles that are left after the last whole round of the grid go to the first
+  // leftover_lead workgroups alone, round after round (the workgroups a CU is given first run ahead of the later ones).
   const bool dynamic = queue != nullptr;
+  const uint32_t G = gridDim.x;
   volatile uint32_t* handed_out = reinterpret_cast<volatile uint32_t*>(lds + tile_bytes);
   uint32_t asked = 0;
+  uint32_t static_end = tile_end, batch_base = 0, batch_stride = 1;
+  unsigned int* counter = queue;
+  if (dynamic) {
+    const uint32_t c = blockIdx.x % n_counters;
+    static_end = static_rounds * G;
+    counter = queue + (1u + c) * kQueueLineWords;
+    batch_base = static_end + c * grab;   // an answer a (a multiple of grab) stands for the batch that starts at tile
+    batch_stride = n_counters;            // batch_base + a * batch_stride
+  }
+  const uint32_t whole_rounds_end = (!dynamic && !P.blocked && leftover_lead > 0) ? (tile_end / G) * G : tile_end;
+  auto fixed_next = [&](uint32_t t) -> uint32_t {   // the tile after t in the fixed order
+    if (t + tile_step < whole_rounds_end || whole_rounds_end == tile_end) return t + tile_step;
+    if (t < whole_rounds_end) return blockIdx.x < leftover_lead ? whole_rounds_end + blockIdx.x : tile_end;
+    return t + leftover_lead;
+  };
   if (tile >= tile_end) {
     if (dynamic && threadIdx.x == 0) leave_tile_queue(queue);
     return;
   }
-  if (dynamic && threadIdx.x == 0) asked = atomicAdd(&queue[0], grab);
+  bool ask = dynamic && tile + G >= static_end;   // the first tile is this workgroup's last tile by index
+  if (ask && threadIdx.x == 0) asked = atomicAdd(counter, grab);
   int64_t so, dof;
   tile_origin(P, tile, &so, &dof);
   load_tile(so);
@@ -289,19 +344,21 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     }
   }
   park_tile();
-  if (dynamic && threadIdx.x == 0) *handed_out = gridDim.x + asked;
+  if (ask && threadIdx.x == 0) *handed_out = batch_base + asked * batch_stride;
   __syncthreads();
   // dynamic: `left` tiles of the current batch follow the current tile; next_batch is where the batch after it starts
-  uint32_t left = 0, next_batch = dynamic ? *handed_out : 0u;
-  uint32_t next = dynamic ? next_batch : tile + tile_step;
+  uint32_t left = 0, next_batch = ask ? *handed_out : 0u;
+  uint32_t next = !dynamic ? fixed_next(tile) : (ask ? next_batch : tile + G);
   // invariant at the top: the current tile is parked in LDS, no load is in flight
   for (;;) {
     if (next >= tile_end) {
       store_tile(dof);
       break;
     }
-    const bool new_batch = dynamic && left == 0;   // `next` is the first tile of a batch: ask for the batch after it
-    if (new_batch && threadIdx.x == 0) asked = atomicAdd(&queue[0], grab);
+    // a request goes out with the loads of `next` when that is the last tile by index or the first tile of a batch
+    const bool by_index = dynamic && next < static_end;
+    ask = dynamic && (by_index ? next + G >= static_end : left == 0);
+    if (ask && threadIdx.x == 0) asked = atomicAdd(counter, grab);
     int64_t dof_next;
     tile_origin(P, next, &so, &dof_next);
     load_tile(so);
@@ -310,13 +367,16 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();   // every pick is done: LDS may be overwritten (and every lane has read the word behind the tile)
     park_tile();
-    if (new_batch && threadIdx.x == 0) *handed_out = gridDim.x + asked;
+    if (ask && threadIdx.x == 0) *handed_out = batch_base + asked * batch_stride;
     __syncthreads();
     tile = next;
     dof = dof_next;
     if (!dynamic) {
-      next = tile + tile_step;
-    } else if (new_batch) {
+      next = fixed_next(tile);
+    } else if (by_index) {
+      next = ask ? *handed_out : tile + G;
+      left = 0;
+    } else if (ask) {
       left = grab - 1u;
       next_batch = *handed_out;
       next = left > 0 ? tile + 1u : next_batch;
@@ -506,7 +566,7 @@ static hipError_t tile_queue_of_stream(hipStream_t s, unsigned int** out, const 
     if (dv->second.second >= kTileQueues) return hipSuccess;   // no pair left: fixed order
     it = slot_of.emplace(std::make_pair(dev, s), dv->second.second++).first;
   }
-  *out = dv->second.first + 2 * it->second;
+  *out = dv->second.first + (size_t)kQueueBlockWords * it->second;
   return hipSuccess;
 }
 
@@ -538,8 +598,12 @@ static PreLaunch launch_transpose_f(const lc_plan& plan, const void* src, void* 
       raised.store(true, std::memory_order_release);
     }
   }
+  const uint32_t counters = (uint32_t)std::max(1, std::min(plan.queue_counters, kQueueLines - 1));
+  // whole rounds of the grid that go by index before the queue takes over (at least one, never past the last whole round)
+  const uint32_t rounds = (uint32_t)std::max<int64_t>(1, std::min<int64_t>(plan.queue_static_rounds, plan.transpose.n_tiles / grid));
   hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), lds_bytes, s, plan.transpose, sp, dp, queue,
-                     plan.lds_bytes, (uint32_t)std::max(1, plan.tile_queue));
+                     plan.lds_bytes, (uint32_t)std::max(1, plan.tile_queue), rounds, counters,
+                     (uint32_t)std::min<int64_t>(std::max(0, plan.leftover_lead), grid));
   return pre;
 }
 template <int ES, int V, int MT, int NT>
@@ -593,7 +657,27 @@ static PreLaunch launch_ragged(const lc_plan& plan, const void* src, void* dst, 
   return PreLaunch{hipErrorInvalidValue, "kernel selection (micro-tiles per lane)"};
 }
 
+template <int ES>
+static void launch_last_writer_move(const lc_plan& plan, const void* src, void* dst, const uint32_t* last, unsigned grid, hipStream_t s) {
+  typedef typename Word<ES>::type T;
+  hipLaunchKernelGGL(last_writer_move_kernel<ES>, dim3(grid), dim3(kBlock), 0, s, plan.generic, static_cast<const T*>(src), static_cast<T*>(dst), last);
+}
+
+static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t workspace_bytes, void* stream);
+
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream) {
+  if (plan.cls == KernelClass::LastWriter) return LC_ERR_NEEDS_WORKSPACE;
+  return execute_with(plan, src, dst, nullptr, 0, stream);
+}
+
+lc_status_t execute_plan_workspace(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t workspace_bytes, void* stream) {
+  if (plan.workspace_bytes > 0 &&
+      (!workspace || (int64_t)workspace_bytes < plan.workspace_bytes || reinterpret_cast<uintptr_t>(workspace) % 4 != 0))
+    return LC_ERR_WORKSPACE_TOO_SMALL;
+  return execute_with(plan, src, dst, workspace, workspace_bytes, stream);
+}
+
+static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t, void* stream) {
   if (!src || !dst) return LC_ERR_INVALID_ARG;
   src = static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes;   // the slice that is written last
   if ((reinterpret_cast<uintptr_t>(src) % plan.src_align) != 0 || (reinterpret_cast<uintptr_t>(dst) % plan.dst_align) != 0)
@@ -603,7 +687,23 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   (void)hipGetLastError();
   PreLaunch pre;
-  if (plan.cls == KernelClass::Generic) {
+  if (plan.cls == KernelClass::LastWriter) {
+    // three launches in stream order: clear the records, record the last coordinate per offset, move
+    uint32_t* last = static_cast<uint32_t*>(workspace);
+    const uint64_t words = (uint64_t)plan.workspace_bytes / 4;
+    const unsigned zgrid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>((words + kBlock - 1) / kBlock, (uint64_t)cus * 16));
+    const unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(((uint64_t)plan.generic.n + kBlock - 1) / kBlock, (uint64_t)cus * 16));
+    hipLaunchKernelGGL(zero_words_kernel, dim3(zgrid), dim3(kBlock), 0, s, last, words);
+    hipLaunchKernelGGL(last_writer_mark_kernel, dim3(grid), dim3(kBlock), 0, s, plan.generic, last);
+    switch (plan.elem_bytes) {
+      case 1: launch_last_writer_move<1>(plan, src, dst, last, grid, s); break;
+      case 2: launch_last_writer_move<2>(plan, src, dst, last, grid, s); break;
+      case 4: launch_last_writer_move<4>(plan, src, dst, last, grid, s); break;
+      case 8: launch_last_writer_move<8>(plan, src, dst, last, grid, s); break;
+      case 16: launch_last_writer_move<16>(plan, src, dst, last, grid, s); break;
+      default: return LC_ERR_UNSUPPORTED_DTYPE;
+    }
+  } else if (plan.cls == KernelClass::Generic) {
     uint64_t want = ((uint64_t)plan.generic.n + kBlock - 1) / kBlock;
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, (uint64_t)cus * 16));
     switch (plan.elem_bytes) {
@@ -616,7 +716,7 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
     }
   } else if (plan.cls == KernelClass::Direct) {
     uint64_t want = ((uint64_t)plan.direct.n_items + (uint64_t)kBlock * plan.unroll - 1) / ((uint64_t)kBlock * plan.unroll);
-    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, (uint64_t)cus * plan.wgs_per_cu));
+    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, plan.grid_override > 0 ? (uint64_t)plan.grid_override : (uint64_t)cus * plan.wgs_per_cu));
     for (int64_t j = 0; j < plan.n_launches; ++j) {
       const void* sj = static_cast<const unsigned char*>(src) + j * plan.launch_src_step * plan.elem_bytes;
       void* dj = static_cast<unsigned char*>(dst) + j * plan.launch_dst_step * plan.elem_bytes;
@@ -630,7 +730,7 @@ lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* 
       }
     }
   } else {
-    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(plan.transpose.n_tiles, (uint64_t)cus * plan.wgs_per_cu));
+    unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(plan.transpose.n_tiles, plan.grid_override > 0 ? (uint64_t)plan.grid_override : (uint64_t)cus * plan.wgs_per_cu));
     const int key = plan.tile_elem_bytes * 100 + plan.V;
     if (plan.transpose.n_ragged > 0 || (plan.V == 1 && plan.tile_elem_bytes != 16)) {
       switch (key) {

@@ -23,6 +23,10 @@ Tuning tuning_from_env() {
   t.max_vec_bytes = env_int("LC_TUNE_MAX_VEC_BYTES", t.max_vec_bytes);
   t.blocked = env_int("LC_TUNE_BLOCKED", t.blocked);
   t.tile_queue = env_int("LC_TUNE_TILE_QUEUE", t.tile_queue);
+  t.queue_rounds = env_int("LC_TUNE_QUEUE_ROUNDS", t.queue_rounds);
+  t.queue_counters = env_int("LC_TUNE_QUEUE_COUNTERS", t.queue_counters);
+  t.leftover_lead = env_int("LC_TUNE_LEFTOVER_LEAD", t.leftover_lead);
+  t.grid = env_int("LC_TUNE_GRID", t.grid);
   t.max_items = env_int("LC_TUNE_MAX_ITEMS", (int)t.max_items);
   if (const char* v = std::getenv("LC_TUNE_TILE")) {
     for (const char* p = v; *p;) {
@@ -204,6 +208,19 @@ static lc_status_t plan_generic(const Modes& S, const Modes& D, int64_t n, lc_pl
   plan->generic.n = (uint32_t)n;
   plan->width_bytes = plan->elem_bytes;
   plan->note = why;
+  return LC_OK;
+}
+
+// Destinations that alias (Table copy, "Scatter" with repeated offsets; Sec. 2.6.1: the loop's last write stays).
+static lc_status_t plan_last_writer(const Modes& S, const Modes& D, int64_t n, lc_plan* plan, const std::string& why) {
+  int64_t span = 1;   // cosize of the destination: largest offset + 1
+  for (const Mode& m : D) span += (m.extent - 1) * m.stride;
+  lc_status_t st = plan_generic(S, D, n, plan, why);
+  if (st != LC_OK) return st;
+  if (span >= (1ll << 40)) return LC_ERR_TOO_LARGE;
+  plan->cls = KernelClass::LastWriter;
+  plan->workspace_bytes = span * 4;
+  plan->wgs_per_cu = 16;
   return LC_OK;
 }
 
@@ -535,6 +552,9 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     const bool queue_pays = plan->lds_bytes >= 32u * 1024u && P.n_tiles >= 4096u;
     const int per_request = (int)std::max(1u, 65536u / std::max(1u, plan->lds_bytes));
     plan->tile_queue = queue_fits ? (tune.tile_queue >= 0 ? tune.tile_queue : (queue_pays ? per_request : 0)) : 0;
+    plan->queue_static_rounds = tune.queue_rounds >= 1 ? tune.queue_rounds : 1;
+    plan->queue_counters = tune.queue_counters >= 1 ? tune.queue_counters : 1;
+    plan->leftover_lead = tune.leftover_lead >= 0 ? tune.leftover_lead : 0;
     plan->src_align = (unsigned)(V * es);
     plan->dst_align = (unsigned)(V * es);
     return true;
@@ -572,6 +592,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   plan->src_align = std::min(src_align, 256u);
   plan->dst_align = std::min(dst_align, 256u);
   plan->nontemporal = tune.nontemporal >= 0 ? (tune.nontemporal & 3) : 1;   // stores: decided per class below
+  plan->grid_override = tune.grid > 0 ? tune.grid : 0;
 
   // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
   Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
@@ -584,32 +605,36 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   // the copy of that slice (Sec. 2.5.1): the modes fold into an offset of the source and leave both layouts.
   if (n > 1 && !layout_is_injective(D, n)) {
     std::vector<JointMode> J0;
-    if (!joint_modes(S, D, &J0)) return LC_ERR_DST_ALIASES;
     Modes S2, D2;
     int64_t offset = 0, n2 = 1;
     int dropped = 0;
-    for (const JointMode& m : J0) {
-      if (m.b == 0) {
-        offset += (m.extent - 1) * m.a;
-        ++dropped;
-      } else {
-        S2.push_back({m.extent, m.a});
-        D2.push_back({m.extent, m.b});
-        n2 *= m.extent;
+    if (joint_modes(S, D, &J0)) {
+      for (const JointMode& m : J0) {
+        if (m.b == 0) {
+          offset += (m.extent - 1) * m.a;
+          ++dropped;
+        } else {
+          S2.push_back({m.extent, m.a});
+          D2.push_back({m.extent, m.b});
+          n2 *= m.extent;
+        }
       }
     }
-    if (dropped == 0) return LC_ERR_DST_ALIASES;
+    // any other overlap (or a destination too large to enumerate whose strides do not nest): decided per offset on the device
+    if (dropped == 0) return plan_last_writer(S, D, n, plan, "destination offsets repeat (or could not be shown distinct)");
     if (S2.empty()) {
       S2.push_back({1, 0});
       D2.push_back({1, 0});
     }
-    if (n2 > 1 && !layout_is_injective(coalesce_modes(D2), n2)) return LC_ERR_DST_ALIASES;   // overlaps of another kind stay refused
     unsigned shifted_align = plan->src_align;
     while (shifted_align > 1 && (offset * es) % shifted_align != 0) shifted_align /= 2;
-    lc_status_t st = make_plan(Layout::flat(S2), Layout::flat(D2), es, shifted_align, dst_align, tune, plan);
+    lc_status_t st = make_plan(Layout::flat(S2), Layout::flat(D2), es, shifted_align, dst_align, tune, plan);   // may itself be last-writer
     if (st != LC_OK) return st;
     plan->src_offset_elems = offset;
     plan->overwritten_modes = dropped;
+    plan->distinct_reads = 1;
+    for (const Mode& m : S)
+      if (m.stride != 0) plan->distinct_reads *= m.extent;
     return LC_OK;
   }
 
@@ -816,7 +841,8 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
 
 std::string describe(const lc_plan& plan) {
   std::string s;
-  const char* cls = plan.cls == KernelClass::Generic ? "generic" : plan.cls == KernelClass::Direct ? "direct" : "transpose";
+  const char* cls = plan.cls == KernelClass::Generic ? "generic" : plan.cls == KernelClass::Direct ? "direct" :
+                    plan.cls == KernelClass::LastWriter ? "last-writer" : "transpose";
   s += std::string("class=") + cls;
   s += " elem_bytes=" + std::to_string(plan.elem_bytes) + " n=" + std::to_string(plan.n_elems);
   s += " K=" + std::to_string(plan.common_vector) + " width_bytes=" + std::to_string(plan.width_bytes);
@@ -844,8 +870,12 @@ std::string describe(const lc_plan& plan) {
     s += " launches=" + std::to_string(plan.n_launches);
     s += " unroll=" + std::to_string(plan.unroll);
   }
+  if (plan.cls == KernelClass::LastWriter) s += " workspace_bytes=" + std::to_string(plan.workspace_bytes);
   s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal);
-  if (plan.tile_queue) s += " tile_queue=" + std::to_string(plan.tile_queue);
+  if (plan.tile_queue)
+    s += " tile_queue=" + std::to_string(plan.tile_queue) + " queue_rounds=" + std::to_string(plan.queue_static_rounds) +
+         " queue_counters=" + std::to_string(plan.queue_counters);
+  if (plan.leftover_lead) s += " leftover_lead=" + std::to_string(plan.leftover_lead);
   s += " blocked=" + std::to_string(plan.cls == KernelClass::Transpose ? plan.transpose.blocked : plan.cls == KernelClass::Direct ? plan.direct.blocked : 0u);
   if (!plan.note.empty()) s += " note=\"" + plan.note + "\"";
   return s;

@@ -13,7 +13,7 @@ struct JointMode {
   int64_t extent, a, b;   // extent, source stride, destination stride (elements)
 };
 
-enum class KernelClass { Generic, Direct, Transpose };
+enum class KernelClass { Generic, Direct, Transpose, LastWriter };
 
 // Knobs the planner normally chooses itself; values < 0 mean "planner's choice".  Read from the
 // environment (LC_TUNE_*) once per plan so that tile shapes can be swept without rebuilding.
@@ -30,6 +30,10 @@ struct Tuning {
   int force_class = -1;        // 0 generic, 1 direct, 2 transpose (falls back when not applicable)
   int max_vec_bytes = -1;      // cap on the access width
   int tile_queue = -1;         // transpose: n > 0 = hand tiles out through a device-side queue, n per request; 0 = in a fixed order
+  int queue_rounds = -1;       // transpose: whole rounds of the grid handed out by index before the queue takes over (>= 1)
+  int queue_counters = -1;     // transpose: counters the requests are spread over (1..15)
+  int grid = -1;               // workgroups of the launch (overrides CUs * wgs_per_cu)
+  int leftover_lead = -1;      // transpose, fixed order: the tiles left after the last whole round go to this many leading workgroups
 };
 Tuning tuning_from_env();
 
@@ -66,11 +70,20 @@ struct lc_plan {
   unsigned lds_bytes = 0;
   int64_t src_run_bytes = 0, dst_run_bytes = 0;
 
-  // Generic
+  // Generic and LastWriter (both evaluate the two coalesced layouts per element)
   lc::GenericParams generic{};
+  // LastWriter: the destination maps several coordinates to one offset (or could not be shown not to).  Sec. 2.6.1's loop
+  // leaves the value of the LARGEST integral coordinate that reaches an offset.  A first pass records that coordinate per
+  // offset in scratch memory (one 32-bit word per element of the destination's span), a second pass lets only the recorded
+  // coordinates write: the result does not depend on the order in which lanes run.
+  int64_t workspace_bytes = 0;
 
   int wgs_per_cu = 0;
-  int tile_queue = 0;                      // transposing class: tiles past the first grid-full are handed out on request, this many at a time
+  int grid_override = 0;                   // > 0: workgroups of the launch, whatever the CU count
+  int tile_queue = 0;                      // transposing class: tiles past the first rounds of the grid are handed out on request, this many at a time
+  int queue_static_rounds = 1;             // ... whole rounds of the grid that go by workgroup index first
+  int queue_counters = 1;                  // ... counters (one cache line each) the requests are spread over
+  int leftover_lead = 0;                   // fixed order: leading workgroups that share the tiles left after the last whole round (0: all)
   int nontemporal = 0;                     // bit 0: loads, bit 1: stores
   std::string note;                        // why a faster class was not taken
 };
@@ -94,6 +107,8 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
 const char* last_hip_error();
 void set_last_hip_error(const std::string& text);
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream);
+// the same with scratch device memory for the plans that need it (workspace_bytes > 0); others ignore it
+lc_status_t execute_plan_workspace(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t workspace_bytes, void* stream);
 lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
                       int iters, void* stream, float* ms_per_iter);
 

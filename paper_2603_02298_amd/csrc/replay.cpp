@@ -33,6 +33,19 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
   if (plan.cls == KernelClass::Generic) {
     const GenericParams& P = plan.generic;
     for (uint32_t i = 0; i < P.n; ++i) B.move(flat_eval(P.src, i) * es, flat_eval(P.dst, i) * es, es);
+  } else if (plan.cls == KernelClass::LastWriter) {
+    // the two passes of the device path, both walked BACKWARDS here: the result may not depend on the order
+    const GenericParams& P = plan.generic;
+    std::vector<uint32_t> winner((size_t)(plan.workspace_bytes / 4), 0u);
+    for (uint32_t i = P.n; i-- > 0;) {
+      const int64_t off = flat_eval(P.dst, i);
+      if (off < 0 || off >= (int64_t)winner.size()) { B.ok = false; break; }
+      if (winner[(size_t)off] < i) winner[(size_t)off] = i;
+    }
+    for (uint32_t i = P.n; B.ok && i-- > 0;) {
+      const int64_t off = flat_eval(P.dst, i);
+      if (winner[(size_t)off] == i) B.move(flat_eval(P.src, i) * es, off * es, es);
+    }
   } else if (plan.cls == KernelClass::Direct) {
     const DirectParams& P = plan.direct;
     const int W = plan.width_bytes;

@@ -220,6 +220,73 @@ def test_tile_queue(oracle, monkeypatch):
             assert "tile_queue=%d" % grab in desc, desc
 
 
+def test_tile_queue_after_whole_rounds_and_over_several_counters(oracle, monkeypatch):
+    # the queue taking over after two (or, capped, all) whole rounds of the grid, requests spread over 8 and 15 counters;
+    # and, in the fixed order, the tiles left after the last whole round going to the leading workgroups only
+    for name, scale in (("c2", 4), ("c5", 64), ("c3", 16)):
+        w = W.workload(name, scale)
+        bits = W.source_bits(w)
+        for env in ({"LC_TUNE_TILE_QUEUE": "1", "LC_TUNE_QUEUE_ROUNDS": "2", "LC_TUNE_QUEUE_COUNTERS": "8", "LC_TUNE_GRID": "100"},
+                    {"LC_TUNE_TILE_QUEUE": "2", "LC_TUNE_QUEUE_ROUNDS": "1", "LC_TUNE_QUEUE_COUNTERS": "15", "LC_TUNE_GRID": "37"},
+                    {"LC_TUNE_TILE_QUEUE": "1", "LC_TUNE_QUEUE_ROUNDS": "1000", "LC_TUNE_QUEUE_COUNTERS": "3", "LC_TUNE_GRID": "48"},
+                    {"LC_TUNE_TILE_QUEUE": "3", "LC_TUNE_QUEUE_ROUNDS": "2", "LC_TUNE_QUEUE_COUNTERS": "8"},
+                    {"LC_TUNE_TILE_QUEUE": "0", "LC_TUNE_LEFTOVER_LEAD": "7", "LC_TUNE_GRID": "100"},
+                    {"LC_TUNE_TILE_QUEUE": "0", "LC_TUNE_LEFTOVER_LEAD": "1", "LC_TUNE_GRID": "61"},
+                    {"LC_TUNE_TILE_QUEUE": "0", "LC_TUNE_LEFTOVER_LEAD": "5000", "LC_TUNE_GRID": "96"}):
+            for k, v in env.items():
+                monkeypatch.setenv(k, v)
+            for rep in range(2):   # twice: the second launch must find every counter at zero
+                _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=bits, tag="%s %s" % (w.name, env))
+            for k in env:
+                monkeypatch.delenv(k)
+
+
+def test_aliasing_destinations_keep_the_last_write(oracle):
+    # Scatter with repeated offsets (Table copy): the loop's last write to an offset stays.  Class last-writer, with a
+    # workspace of one word per destination offset; the same workspace is used again without clearing (the plan clears it)
+    dev = torch.device("cuda:0")
+    cases = [("(4,4):(1,4)", "(4,4):(1,3)", "f32"), ("(4,4,2):(1,4,16)", "(4,4,2):(1,3,0)", "f32"),
+             ("(7,5):(1,7)", "(7,5):(2,3)", "bf16"), ("(16,16):(16,1)", "(16,16):(1,1)", "b8"),
+             ("(6,10):(10,1)", "(4,15):(3,2)", "b64"), ("(3,(2,5)):(1,(3,6))", "(3,(2,5)):(5,(7,1))", "b16"),
+             ("(1000,300):(1,1000)", "(1000,300):(3,7)", "f32"),                    # 300000 coordinates onto 5097 offsets
+             ("(4096,2048):(1,4096)", "(4096,2048):(3,4097)", "f32"),               # injective, but too large to show on the host
+             ("(512,512,8):(1,512,262144)", "(512,512,8):(512,1,1000)", "bf16")]    # 2^21 coordinates, overlapping slabs
+    ws = torch.full((64 << 20,), -1, dtype=torch.int32, device=dev)                 # stale contents on purpose
+    for s, d, dt in cases:
+        es = lc.DTYPE_BYTES[dt]
+        sl, dl = oracle.Layout(s), oracle.Layout(d)
+        print("case last-writer", s, "->", d, dt, flush=True)
+        rng = np.random.default_rng(len(s))
+        src_bits = rng.integers(0, 255, size=sl.cosize * es, dtype=np.uint8).view(_np_int(es))
+        want = np.full(dl.cosize * es, 0x5A, np.uint8).view(_np_int(es))
+        oracle.copy(src_bits, sl, want, dl)
+        plan = lc.Plan(s, d, dt)
+        assert "class=last-writer" in plan.describe() and 0 < plan.workspace_bytes <= ws.numel() * 4, plan.describe()
+        src_t = torch.from_numpy(src_bits).to(dev)
+        for rep in range(2):
+            dst_t = torch.from_numpy(np.full(dl.cosize * es, 0x5A, np.uint8).view(_np_int(es))).to(dev)
+            plan.execute_workspace(src_t.data_ptr(), dst_t.data_ptr(), ws.data_ptr(), ws.numel() * 4, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert (dst_t.cpu().numpy() == want).all(), plan.describe()
+        with pytest.raises(lc.LayoutCopyError) as e:
+            plan.execute(src_t.data_ptr(), dst_t.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        assert e.value.status_name == "NEEDS_WORKSPACE"
+        with pytest.raises(lc.LayoutCopyError) as e:
+            plan.execute_workspace(src_t.data_ptr(), dst_t.data_ptr(), ws.data_ptr(), plan.workspace_bytes - 4, 0)
+        assert e.value.status_name == "WORKSPACE_TOO_SMALL"
+    # a plan that needs no workspace runs through the same call
+    w = W.workload("c1", 16)
+    bits = W.source_bits(w)
+    want = np.zeros(w.dst_elems, dtype=bits.dtype)
+    oracle.copy(bits, w.src_layout, want, w.dst_layout)
+    plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
+    src_t = torch.from_numpy(bits.view(np.int32)).to(dev)
+    dst_t = torch.zeros(w.dst_elems, dtype=torch.int32, device=dev)
+    plan.execute_workspace(src_t.data_ptr(), dst_t.data_ptr(), 0, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert (dst_t.cpu().numpy().view(bits.dtype) == want).all()
+
+
 def test_tile_queue_on_several_streams(oracle, monkeypatch):
     # every stream keeps a pair of counters of its own: copies that run side by side do not share one
     monkeypatch.setenv("LC_TUNE_TILE_QUEUE", "1")

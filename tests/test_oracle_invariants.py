@@ -23,16 +23,51 @@ def bruteforce_binary():
 def test_bruteforce_universe(bruteforce_binary):
     """Every layout of rank <= 3 with extents <= 4 (all mode orders, one stride zeroed, one boundary
     padded, every regrouping) and every stride in 0..6; all ordered pairs of the rank <= 2 subset and
-    20000 seeded random pairs.  The rank-4 / extent-8 universe of the first workload runs with
-    `oracle/bruteforce --rank 4 --extent 8` (hours); a rank-4 / extent-4 run is recorded in the design notes."""
+    20000 seeded random pairs.  The rank-4 / extent-8 universe of the first workload is the slow test below."""
     r = subprocess.run([bruteforce_binary], capture_output=True, text=True, timeout=900)
     assert r.returncode == 0, r.stdout[-3000:]
     assert "ALL POST-CONDITIONS HOLD" in r.stdout
     # the sweep must actually have exercised successful results of every operation
     for line in r.stdout.splitlines():
         f = line.split()
-        if len(f) >= 6 and f[1] == "cases" and f[0] not in ("composition_refused",):
+        if len(f) >= 6 and f[1] == "cases" and f[0] not in ("composition_refused", "logical_product_sampled"):
             assert int(f[4]) > 1000, line
+
+
+def _tally_lines(text):
+    return sorted(ln.split() for ln in text.splitlines() if " cases " in ln)
+
+
+def test_rank4_extent8_universe_tally_is_committed():
+    """BASELINE config 1's universe (every layout with at most 4 modes and extents at most 8): the tally that
+    tests/golden/make_bruteforce_tally.py wrote is in the repository, covers every operation and reports no failure."""
+    path = os.path.join(ROOT, "tests", "golden", "bruteforce_rank4_extent8.txt")
+    text = open(path).read()
+    assert "--rank 4 --extent 8" in text.splitlines()[0]
+    assert "ALL POST-CONDITIONS HOLD" in text and "exit status 0" in text
+    names = set()
+    for f in _tally_lines(text):
+        names.add(f[0])
+        assert f[-1] == "0" and f[-2] == "failed", f
+        if f[0] in ("coalesce", "coalesce_bymode", "right_inverse", "complement"):
+            assert int(f[2]) > 4000000, f            # the whole unary universe, every regrouping
+        if f[0] in ("composition", "logical_divide"):
+            assert int(f[2]) > 300000000 and int(f[4]) > 100000000, f
+    assert {"coalesce", "complement", "right_inverse", "left_inverse", "composition", "logical_divide", "zipped_divide",
+            "logical_product", "blocked_raked_product", "max_common_vector"} <= names
+
+
+@pytest.mark.slow
+@pytest.mark.skipif(os.environ.get("RUN_SLOW_UNIVERSE") != "1", reason="about an hour on 8 cores: set RUN_SLOW_UNIVERSE=1")
+def test_rank4_extent8_universe_rerun():
+    """Runs the universe again and compares its tally with the committed one."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_tally", os.path.join(ROOT, "tests", "golden", "make_bruteforce_tally.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    rc, text = mod.run()
+    assert rc == 0, text[-3000:]
+    assert _tally_lines(text) == _tally_lines(open(mod.OUT).read())
 
 
 def _flat_layouts(max_rank, max_extent):
