@@ -53,7 +53,8 @@ typedef enum {
   LC_ERR_MISALIGNED = 15,         /* a device pointer is less aligned than the plan was created for */
   LC_ERR_HIP = 16,                /* a HIP runtime call failed (no device, launch failure, ...) */
   LC_ERR_NEEDS_WORKSPACE = 17,    /* the plan needs scratch device memory: use lc_plan_execute_workspace */
-  LC_ERR_WORKSPACE_TOO_SMALL = 18 /* the workspace is NULL, misaligned or smaller than lc_plan_workspace_bytes */
+  LC_ERR_WORKSPACE_TOO_SMALL = 18,/* the workspace is NULL, misaligned or smaller than lc_plan_workspace_bytes */
+  LC_ERR_SCRATCH_LIMIT = 19       /* lc_plan_execute_static: the plan needs more scratch than the library's static array holds */
 } lc_status_t;
 
 /* Element types.  The copy moves bit patterns; the dtype only fixes the element width. */
@@ -223,6 +224,18 @@ lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, v
 int64_t lc_plan_workspace_bytes(const lc_plan_t* plan);
 lc_status_t lc_plan_execute_workspace(const lc_plan_t* plan, const void* src, void* dst, void* workspace, size_t workspace_bytes,
                                       void* hip_stream);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it): lc_plan_execute_workspace with the scratch memory taken from a static array in device memory of the
+ * library's own code object, LC_STATIC_SCRATCH_BYTES (8 MiB) per GPU, which every GPU the library runs on holds until the
+ * process ends.  Calls nothing that allocates.  A plan that needs more (lc_plan_workspace_bytes(plan) >
+ * lc_static_scratch_bytes()) is refused with SCRATCH_LIMIT; a plan that needs no scratch runs as lc_plan_execute does.
+ * All calls on a GPU share that GPU's array, whatever the stream, and the array keeps what the last call left in it
+ * (each call clears the part it uses with a kernel of its own, so stale contents do no harm): two calls that overlap in
+ * time on one GPU race on it; calls on one stream, or ordered by events, do not.  The array used is the current
+ * device's (hipGetDevice), which must be the device of `hip_stream`. */
+#define LC_STATIC_SCRATCH_BYTES (8u << 20)
+size_t lc_static_scratch_bytes(void);
+lc_status_t lc_plan_execute_static(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream);
 void lc_plan_destroy(lc_plan_t* plan);
 
 /* lc_plan_create (alignment taken from the two pointers) + lc_plan_execute + lc_plan_destroy.  The library keeps the

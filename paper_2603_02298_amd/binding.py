@@ -83,6 +83,8 @@ def lib():
     L.lc_plan_workspace_bytes.argtypes = [P]
     L.lc_plan_workspace_bytes.restype = i64
     L.lc_plan_execute_workspace.argtypes = [P, P, P, P, sz, P]
+    L.lc_plan_execute_static.argtypes = [P, P, P, P]
+    L.lc_static_scratch_bytes.restype = sz
     L.lc_plan_destroy.argtypes = [P]
     L.lc_plan_destroy.restype = None
     L.lc_copy.argtypes = [P, P, P, P, ctypes.c_int, P]
@@ -297,6 +299,10 @@ class Plan:
     def execute(self, src_ptr, dst_ptr, stream=0):
         """src_ptr / dst_ptr: device addresses (e.g. tensor.data_ptr()); stream: hipStream_t as int."""
         _check(lib().lc_plan_execute(self._h, src_ptr, dst_ptr, stream), "lc_plan_execute")
+
+    def execute_static(self, src_ptr, dst_ptr, stream=0):
+        """The same with the library's static scratch array on the current GPU: allocates nothing."""
+        _check(lib().lc_plan_execute_static(self._h, src_ptr, dst_ptr, stream), "lc_plan_execute_static")
 
     @property
     def workspace_bytes(self):

@@ -69,6 +69,7 @@ const char* lc_status_string(lc_status_t s) {
     case LC_ERR_HIP: return "HIP";
     case LC_ERR_NEEDS_WORKSPACE: return "NEEDS_WORKSPACE";
     case LC_ERR_WORKSPACE_TOO_SMALL: return "WORKSPACE_TOO_SMALL";
+    case LC_ERR_SCRATCH_LIMIT: return "SCRATCH_LIMIT";
   }
   return "UNKNOWN";
 }
@@ -215,6 +216,11 @@ lc_status_t lc_plan_execute_workspace(const lc_plan_t* plan, const void* src, vo
                                       void* hip_stream) {
   if (!plan) return LC_ERR_INVALID_ARG;
   return lc::execute_plan_workspace(*plan, src, dst, workspace, workspace_bytes, hip_stream);
+}
+size_t lc_static_scratch_bytes(void) { return lc::static_scratch_bytes(); }
+lc_status_t lc_plan_execute_static(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::execute_plan_static(*plan, src, dst, hip_stream);
 }
 void lc_plan_destroy(lc_plan_t* plan) { delete plan; }
 

@@ -677,6 +677,37 @@ lc_status_t execute_plan_workspace(const lc_plan& plan, const void* src, void* d
   return execute_with(plan, src, dst, workspace, workspace_bytes, stream);
 }
 
+// Scratch memory for callers that cannot allocate: one array per GPU in the device memory of this code object.  Its name is
+// a host-side stand-in; the address on a device comes from hipGetSymbolAddress, asked once per device with that device
+// current, and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[LC_STATIC_SCRATCH_BYTES];
+size_t static_scratch_bytes() { return LC_STATIC_SCRATCH_BYTES; }
+
+lc_status_t execute_plan_static(const lc_plan& plan, const void* src, void* dst, void* stream) {
+  if (plan.workspace_bytes == 0) return execute_with(plan, src, dst, nullptr, 0, stream);   // no scratch needed, nothing allocated either
+  if (plan.workspace_bytes > (int64_t)LC_STATIC_SCRATCH_BYTES) {
+    set_last_hip_error("the plan needs " + std::to_string(plan.workspace_bytes) + " bytes of scratch, the static array holds " +
+                       std::to_string((size_t)LC_STATIC_SCRATCH_BYTES));
+    return LC_ERR_SCRATCH_LIMIT;
+  }
+  int dev = 0;
+  if (hip_failed(hipGetDevice(&dev), "hipGetDevice")) return LC_ERR_HIP;
+  static std::mutex lock;
+  static std::map<int, void*> address_on;   // device -> address of its copy of the array
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> hold(lock);
+    auto it = address_on.find(dev);
+    if (it == address_on.end()) {
+      void* found = nullptr;
+      if (hip_failed(hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)), "hipGetSymbolAddress") || !found) return LC_ERR_HIP;
+      it = address_on.emplace(dev, found).first;
+    }
+    ptr = it->second;
+  }
+  return execute_with(plan, src, dst, ptr, LC_STATIC_SCRATCH_BYTES, stream);
+}
+
 static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t, void* stream) {
   if (!src || !dst) return LC_ERR_INVALID_ARG;
   src = static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes;   // the slice that is written last

@@ -108,6 +108,9 @@ const char* last_hip_error();
 void set_last_hip_error(const std::string& text);
 lc_status_t execute_plan(const lc_plan& plan, const void* src, void* dst, void* stream);
 // the same with scratch device memory for the plans that need it (workspace_bytes > 0); others ignore it
+// the same with the library's static scratch array of the current device; allocates nothing
+size_t static_scratch_bytes();
+lc_status_t execute_plan_static(const lc_plan& plan, const void* src, void* dst, void* stream);
 lc_status_t execute_plan_workspace(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t workspace_bytes, void* stream);
 lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
                       int iters, void* stream, float* ms_per_iter);

@@ -26,7 +26,7 @@ def test_status_strings_and_dtypes():
     import paper_2603_02298_amd as lc
     L = lc.lib()
     seen = set()
-    for code in range(19):
+    for code in range(20):
         s = L.lc_status_string(code).decode()
         assert s != "UNKNOWN" and s not in seen
         seen.add(s)
