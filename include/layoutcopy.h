@@ -134,6 +134,13 @@ lc_status_t lc_right_inverse(const lc_layout_t* a, lc_layout_t** out);
  * injective.  Stride-0 modes of `a` are not inverted.  Errors: NOT_INJECTIVE (moving modes overlap),
  * STRIDE_DIVISIBILITY (a stride does not divide the next larger one: no layout inverts that). */
 lc_status_t lc_left_inverse(const lc_layout_t* a, lc_layout_t** out);
+/* Application of the left-inverse (Sec. 3.4.3): does the data layout `a` hold every offset the instruction layout `t`
+ * accesses, i.e. is there for every i < |t| a coordinate c of `a` with t(i) = a(c)?  Decided as the paper does, by
+ * a(a^†(t(i))) = t(i) with a^†(t(i)) inside a's domain.  *yes receives 1 or 0.  `where` (optional): on yes, *where
+ * receives the layout a^† o t, which maps instruction coordinates to coordinates of `a` (NULL when that composition is
+ * not admissible by Sec. 3.3.2's conditions; the answer in *yes stands either way); on no, NULL.
+ * Errors: those of lc_left_inverse (`a` must have a left-inverse layout); TOO_LARGE (|t| > 2^26). */
+lc_status_t lc_admissible(const lc_layout_t* a, const lc_layout_t* t, int* yes, lc_layout_t** where);
 
 /* Logical product A (x) B = (A, A* o B) (Sec. 3.5.1): mode 0 is the tile A, mode 1 repeats it over the
  * grid B.  Errors of lc_complement and lc_composition. */

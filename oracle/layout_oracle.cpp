@@ -529,6 +529,20 @@ Status left_inverse(const Layout& A, Layout* R) {
 }
 
 // ===========================================================================
+// Application of the left-inverse (Sec. 3.4.3): every offset T(i) of an instruction layout exists in the
+// image of the data layout A.  Written out as the statement reads: the image of A is enumerated, then
+// every T(i) is looked up in it.
+// ===========================================================================
+bool admissible(const Layout& A, const Layout& T) {
+  std::vector<int64_t> image;
+  for (int64_t c = 0; c < size(A); ++c) image.push_back(eval(A, c));
+  std::sort(image.begin(), image.end());
+  for (int64_t i = 0; i < size(T); ++i)
+    if (!std::binary_search(image.begin(), image.end(), eval(T, i))) return false;
+  return true;
+}
+
+// ===========================================================================
 // Logical product and its rearrangements (Sec. 3.5.1)
 // ===========================================================================
 Status logical_product(const Layout& A, const Layout& B, Layout* R) {

@@ -100,6 +100,9 @@ Status composition_bymode(const Layout& A, const Layout& tiler, Layout* R); // S
 Status complement(const Layout& A, int64_t cotarget, Layout* R);        // Sec. 3.5; cotarget 0 = cosize(A)
 Layout right_inverse(const Layout& A);                      // Sec. 3.4.1
 Status left_inverse(const Layout& A, Layout* R);            // Sec. 3.4.3: A(R(A(k))) = A(k)
+// Sec. 3.4.3, application: does the image of the data layout A hold every offset the instruction layout T produces?
+// The statement itself, "for all i in Z_|T| there is c in Z(A) with T(i) = A(c)", by enumeration of both.
+bool admissible(const Layout& A, const Layout& T);
 Status logical_product(const Layout& A, const Layout& B, Layout* R);    // Sec. 3.5.1: (A, A* o B)
 Status blocked_product(const Layout& A, const Layout& B, Layout* R);    // Sec. 3.5.1 "Related products": ((A_0,B'_0),(A_1,B'_1),...)
 Status raked_product(const Layout& A, const Layout& B, Layout* R);      // Sec. 3.5.1 "Related products": ((B'_0,A_0),(B'_1,A_1),...)

@@ -155,6 +155,7 @@ int oracle_left_inverse(const Layout* a, Layout** out) {
   *out = new Layout(r);
   return oracle::OK;
 }
+int oracle_admissible(const Layout* a, const Layout* t) { return oracle::admissible(*a, *t) ? 1 : 0; }
 int oracle_complement(const Layout* a, int64_t cotarget, Layout** out) {
   Layout r;
   oracle::Status st = oracle::complement(*a, cotarget, &r);

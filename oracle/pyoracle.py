@@ -78,6 +78,7 @@ def lib():
                      "logical_product", "blocked_product", "raked_product"):
             getattr(L, "oracle_" + name).argtypes = [P, P, PP]
         L.oracle_complement.argtypes = [P, i64, PP]
+        L.oracle_admissible.argtypes = [P, P]
         L.oracle_layout_slice.argtypes = [P, ctypes.c_char_p, ctypes.POINTER(i64), PP]
         L.oracle_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
         L.oracle_max_common_vector_def.argtypes = [P, P, ctypes.POINTER(i64)]
@@ -275,6 +276,12 @@ def coalesce(a): return _unary("coalesce", a)
 def coalesce_bymode(a): return _unary("coalesce_bymode", a)
 def right_inverse(a): return _unary("right_inverse", a)
 def left_inverse(a): return _unary("left_inverse", a)
+def admissible(a, t):
+    """Sec. 3.4.3, application: every offset of the instruction layout t is in the image of the data layout a."""
+    a, t = _as_layout(a), _as_layout(t)
+    return lib().oracle_admissible(a._h, t._h) == 1
+
+
 def logical_product(a, b): return _binary("logical_product", a, b)
 def blocked_product(a, b): return _binary("blocked_product", a, b)
 def raked_product(a, b): return _binary("raked_product", a, b)

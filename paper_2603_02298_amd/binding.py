@@ -77,6 +77,7 @@ def lib():
     L.lc_slayout_coalesce.argtypes = [P, PP]
     L.lc_slayout_right_inverse.argtypes = [P, PP]
     L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
+    L.lc_admissible.argtypes = [P, P, ctypes.POINTER(ctypes.c_int), PP]
     L.lc_plan_create.argtypes = [P, P, ctypes.c_int, ctypes.c_uint, ctypes.c_uint, PP]
     L.lc_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
     L.lc_plan_execute.argtypes = [P, P, P, P]
@@ -260,6 +261,16 @@ def lc_complement(a, cotarget=0):
     h = ctypes.c_void_p()
     _check(lib().lc_complement(a._h, cotarget, ctypes.byref(h)), "lc_complement(%s, %d)" % (a, cotarget))
     return Layout(_handle=h)
+
+
+def lc_admissible(a, t):
+    """(yes, where): Sec. 3.4.3's check that the data layout a holds every offset of the instruction layout t, and the
+    layout a^† o t of their locations (None when not admissible, or when that composition does not exist)."""
+    a, t = _as_layout(a), _as_layout(t)
+    yes = ctypes.c_int()
+    h = ctypes.c_void_p()
+    _check(lib().lc_admissible(a._h, t._h, ctypes.byref(yes), ctypes.byref(h)), "lc_admissible(%s, %s)" % (a, t))
+    return bool(yes.value), (Layout(_handle=h) if h.value else None)
 
 
 def lc_max_common_vector(a, b):

@@ -229,6 +229,27 @@ lc_status_t left_inverse(const Layout& a, Layout* out) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Application of the left-inverse (Sec. 3.4.3): which offsets of an instruction layout T exist in a data layout A, and
+// where.  The left-inverse turns an offset into the only coordinate that could produce it; the offset exists in A exactly
+// when that coordinate is inside A's domain and A maps it back to the offset.
+// ---------------------------------------------------------------------------------------------
+lc_status_t admissible(const Layout& a, const Layout& t, bool* yes, Layout* where, bool* has_where) {
+  Layout inv;
+  lc_status_t st = left_inverse(a, &inv);
+  if (st != LC_OK) return st;
+  const int64_t na = a.size(), nt = t.size();
+  if (nt > (1ll << 26)) return LC_ERR_TOO_LARGE;
+  *yes = true;
+  for (int64_t i = 0; i < nt && *yes; ++i) {
+    const int64_t off = t(i), c = inv(off);
+    if (c < 0 || c >= na || a(c) != off) *yes = false;
+  }
+  *has_where = false;
+  if (*yes && composition(inv, t, where) == LC_OK) *has_where = true;
+  return LC_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Products (Sec. 3.5.1): A (x) B = (A, A* o B); the blocked / raked products pair up like modes.
 // ---------------------------------------------------------------------------------------------
 lc_status_t logical_product(const Layout& a, const Layout& b, Layout* out) {

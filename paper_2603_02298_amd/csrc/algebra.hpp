@@ -16,6 +16,10 @@ lc_status_t composition_bymode(const Layout& a, const Layout& tiler, Layout* out
 lc_status_t complement(const Layout& a, int64_t cotarget, Layout* out);                 // Sec. 3.5
 Layout right_inverse(const Layout& a);                                                  // Sec. 3.4.1
 lc_status_t left_inverse(const Layout& a, Layout* out);                                 // Sec. 3.4.3
+// Sec. 3.4.3, application: is every offset T(i) in the image of A?  Decided the paper's way, A(A^†(T(i))) = T(i) with
+// A^†(T(i)) inside A's domain; *where = A^† o T (instruction coordinate -> data coordinate) when that composition exists,
+// else a layout of size 0 modes ("1:0") and *has_where = false.
+lc_status_t admissible(const Layout& a, const Layout& t, bool* yes, Layout* where, bool* has_where);
 lc_status_t logical_product(const Layout& a, const Layout& b, Layout* out);             // Sec. 3.5.1
 lc_status_t blocked_product(const Layout& a, const Layout& b, Layout* out);             // Sec. 3.5.1
 lc_status_t raked_product(const Layout& a, const Layout& b, Layout* out);               // Sec. 3.5.1

@@ -168,6 +168,23 @@ lc_status_t lc_left_inverse(const lc_layout_t* a, lc_layout_t** out) {
   lc_status_t st = lc::left_inverse(a->L, &r);
   return st == LC_OK ? give(r, out) : st;
 }
+lc_status_t lc_admissible(const lc_layout_t* a, const lc_layout_t* t, int* yes, lc_layout_t** where) {
+  if (!a || !t || !yes) return LC_ERR_INVALID_ARG;
+  try {
+    bool ok = false, has_where = false;
+    lc::Layout w;
+    lc_status_t st = lc::admissible(a->L, t->L, &ok, &w, &has_where);
+    if (st != LC_OK) return st;
+    *yes = ok ? 1 : 0;
+    if (where) {
+      *where = nullptr;
+      if (has_where) return give(w, where);
+    }
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
 lc_status_t lc_logical_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::logical_product, a, b, out); }
 lc_status_t lc_blocked_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::blocked_product, a, b, out); }
 lc_status_t lc_raked_product(const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) { return binary(lc::raked_product, a, b, out); }

@@ -211,3 +211,48 @@ def test_complement_cotargets_match_oracle(oracle):
         for m in (0, 1, 7, 24, 1000):
             a, b = _both(oracle, "complement_under", [A, str(m)]) if m else _both(oracle, "complement", [A])
             assert a == b, (A, m)
+
+
+def test_admissibility_of_instruction_layouts(oracle):
+    """Sec. 3.4.3's application: the library decides by the left-inverse (a(a^†(t(i))) = t(i)), the oracle by the
+    statement itself (every t(i) looked up in the enumerated image of a); both against hand-checked cases and each other."""
+    import paper_2603_02298_amd as lc
+    from conftest import golden_lines
+    for ln in golden_lines("admissibility.txt"):
+        a, t, want, _why = [x.strip() for x in ln.split("|")]
+        assert oracle.admissible(a, t) == (want == "yes"), ln
+        yes, where = lc.lc_admissible(a, t)
+        assert yes == (want == "yes"), ln
+        if where is not None:   # instruction coordinate -> coordinate of the data layout: a(where(i)) = t(i)
+            A, T = oracle.Layout(a), oracle.Layout(t)
+            assert str(where) == str(oracle.composition(oracle.left_inverse(a), t)), ln
+            W = oracle.Layout(str(where))
+            assert all(A(W(i)) == T(i) for i in range(T.size)), ln
+        else:
+            assert want == "no" or a == "4:0", ln
+    assert lc.lc_admissible("(128,256):(16384,1)", "(1,128):(1,16384)")[1] is not None
+    # brute force: nested data layouts in random mode order against random instruction layouts
+    rng = np.random.default_rng(5)
+    agree = {True: 0, False: 0}
+    for _ in range(600):
+        r = int(rng.integers(1, 4))
+        ext = [int(x) for x in rng.integers(1, 6, r)]
+        order = rng.permutation(r)
+        d, run = [0] * r, int(rng.choice([1, 1, 2, 3]))
+        for m in order:
+            d[m] = run
+            run *= ext[m] * int(rng.choice([1, 1, 2]))
+        a = "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, d)))
+        rt = int(rng.integers(1, 3))
+        t = "(%s):(%s)" % (",".join(str(int(x)) for x in rng.integers(1, 5, rt)), ",".join(str(int(x)) for x in rng.integers(0, 7, rt)))
+        try:
+            yes, where = lc.lc_admissible(a, t)
+        except lc.LayoutCopyError as e:
+            assert e.status_name in ("STRIDE_DIVISIBILITY", "NOT_INJECTIVE"), (a, t, e.status_name)
+            continue
+        assert yes == oracle.admissible(a, t), (a, t)
+        agree[yes] += 1
+        if where is not None:
+            A, T, W = oracle.Layout(a), oracle.Layout(t), oracle.Layout(str(where))
+            assert all(A(W(i)) == T(i) for i in range(T.size)), (a, t, str(where))
+    assert agree[True] > 50 and agree[False] > 50, agree
