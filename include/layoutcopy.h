@@ -8,12 +8,14 @@
  *   - COPY moves dst(i) = src(i) for every integral coordinate i (Sec. 2.6.1).
  *
  * Conventions that hold for every entry point
- *   - Strides and offsets are counted in ELEMENTS of the copy's dtype, never in bytes.
+ *   - Strides and offsets are counted in ELEMENTS of the copy's dtype, never in bytes.  Strides are integers of either
+ *     sign (Sec. 2.3.2: Z is an integer-semimodule): the layout function, coalesce, slicing and COPY take negative
+ *     strides; the operations whose statements are written for strides in N return NEGATIVE_STRIDE for them.
  *   - Layout and plan handles are host objects, immutable after creation, owned by the caller and
  *     released with the matching destroy call.  Handles may be shared between threads.
  *   - `const void* src` / `void* dst` of the copy calls are DEVICE pointers to offset 0 of the
- *     respective layout; the caller owns that memory and guarantees cosize(layout) elements are
- *     addressable.  The library allocates no device memory, never synchronises the device and
+ *     respective layout; the caller owns that memory and guarantees that the offsets
+ *     [min_offset(layout), cosize(layout)) around it are addressable.  The library allocates no device memory, never synchronises the device and
  *     launches only on the stream it is given (`hip_stream` is a hipStream_t passed as void*;
  *     NULL = the default stream).
  *   - Every call returns an lc_status_t; on error `*out` is left untouched.  No C++ exception
@@ -40,7 +42,7 @@ typedef enum {
   LC_ERR_PARSE = 2,               /* text is not "S:D" in the paper's notation */
   LC_ERR_NOT_CONGRUENT = 3,       /* shape and stride have different profiles (Sec. 2.3: S ~ D) */
   LC_ERR_BAD_EXTENT = 4,          /* an extent < 1 (a shape is an HTuple of positive integers, Sec. 2.2) */
-  LC_ERR_NEGATIVE_STRIDE = 5,     /* only strides in N are supported */
+  LC_ERR_NEGATIVE_STRIDE = 5,     /* an operation stated for strides in N (composition, complement, inverses, divides, products, GEMM) was given a negative stride */
   LC_ERR_SIZE_MISMATCH = 6,       /* COPY precondition size(src) == size(dst) violated (Sec. 2.6.1) */
   LC_ERR_STRIDE_DIVISIBILITY = 7, /* composition: stride divisibility condition (Eq. divis_stride) */
   LC_ERR_SHAPE_DIVISIBILITY = 8,  /* composition: shape divisibility condition (Eq. divis_shape) */
@@ -74,7 +76,7 @@ int lc_dtype_bytes(lc_dtype_t dt); /* element width in bytes, 0 for an unknown d
  * ------------------------------------------------------------------------------------------- */
 
 /* Parse the paper's printed form, e.g. "((8,512),(8,1024)):((1,8),(4096,32768))" or "24:3"
- * (Sec. 2.4.1).  Whitespace is ignored.  Errors: PARSE, NOT_CONGRUENT, BAD_EXTENT, NEGATIVE_STRIDE. */
+ * (Sec. 2.4.1).  Whitespace is ignored; strides may be negative.  Errors: PARSE, NOT_CONGRUENT, BAD_EXTENT, TOO_LARGE. */
 lc_status_t lc_layout_parse(const char* text, lc_layout_t** out);
 
 /* Build from a pre-order encoding of the shape tree: an entry -k (k >= 1) opens a tuple of k children,
@@ -90,6 +92,7 @@ lc_status_t lc_layout_to_string(const lc_layout_t* layout, char* buf, size_t cap
 
 int64_t lc_layout_size(const lc_layout_t* layout);   /* |L|: product of the extents (Sec. 2.4.1) */
 int64_t lc_layout_cosize(const lc_layout_t* layout); /* largest offset of the image + 1 (Sec. 2.4.1) */
+int64_t lc_layout_min_offset(const lc_layout_t* layout); /* smallest offset of the image: 0 unless a stride is negative */
 int lc_layout_rank(const lc_layout_t* layout);       /* Sec. 2.1 */
 int lc_layout_depth(const lc_layout_t* layout);      /* Sec. 2.1 */
 

@@ -198,7 +198,9 @@ Status parse_layout(const std::string& text, Layout* out) {
 Status validate(const Layout& L) {
   if (!congruent(L.shape, L.stride)) return ERR_NOT_CONGRUENT;  // Sec. 2.3: S ~ D
   for (int64_t s : leaves(L.shape)) if (s < 1) return ERR_BAD_EXTENT;          // shape is an HTuple(Z+)
-  for (int64_t d : leaves(L.stride)) if (d < 0) return ERR_NEGATIVE_STRIDE;    // integer strides in N only
+  // strides are integers of either sign (Sec. 2.3.2: Z is an integer-semimodule).  The layout function, coalesce and
+  // COPY take them as they are; the algebra whose statements are written for strides in N (composition's divisibility
+  // conditions, complement's ordering, the inverses) refuses them: see has_negative_stride().
   return OK;
 }
 
@@ -237,11 +239,25 @@ Layout concat(const std::vector<Layout>& parts) {
 int64_t size(const Layout& L) { return size(L.shape); }
 
 int64_t cosize(const Layout& L) {
-  // Largest offset is reached at the largest coordinate of every mode (strides are >= 0).
+  // The largest offset is reached with every mode of positive stride at its last coordinate and every mode of negative
+  // stride at coordinate 0.
   std::vector<int64_t> s = leaves(L.shape), d = leaves(L.stride);
   int64_t m = 0;
-  for (size_t k = 0; k < s.size(); ++k) m += (s[k] - 1) * d[k];
+  for (size_t k = 0; k < s.size(); ++k) if (d[k] > 0) m += (s[k] - 1) * d[k];
   return m + 1;
+}
+
+int64_t min_offset(const Layout& L) {
+  // The smallest offset: every mode of negative stride at its last coordinate (0 when no stride is negative).
+  std::vector<int64_t> s = leaves(L.shape), d = leaves(L.stride);
+  int64_t m = 0;
+  for (size_t k = 0; k < s.size(); ++k) if (d[k] < 0) m += (s[k] - 1) * d[k];
+  return m;
+}
+
+bool has_negative_stride(const Layout& L) {
+  for (int64_t d : leaves(L.stride)) if (d < 0) return true;
+  return false;
 }
 
 // L(i) = inner_product(idx2crd_S(i), D), idx2crd applied again inside every mode

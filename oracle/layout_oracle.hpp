@@ -80,6 +80,8 @@ Layout sublayout(const Layout& L, int i);                   // L_i = S_i : D_i (
 Layout concat(const std::vector<Layout>& parts);            // (L_0, L_1, ...) (Eq. concat)
 int64_t size(const Layout& L);
 int64_t cosize(const Layout& L);                            // max of the image + 1 (Sec. 2.4.1, image)
+int64_t min_offset(const Layout& L);                        // min of the image: 0 unless a stride is negative
+bool has_negative_stride(const Layout& L);
 
 // L(c) for an integral coordinate; every integer is accepted (extended domain,
 // Sec. 2.4.1): only the last mode at each level stays unreduced.

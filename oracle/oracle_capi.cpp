@@ -68,6 +68,7 @@ int oracle_layout_to_string(const Layout* L, char* buf, size_t cap, size_t* need
 }
 int64_t oracle_layout_size(const Layout* L) { return oracle::size(*L); }
 int64_t oracle_layout_cosize(const Layout* L) { return oracle::cosize(*L); }
+int64_t oracle_layout_min_offset(const Layout* L) { return oracle::min_offset(*L); }
 int oracle_layout_rank(const Layout* L) { return oracle::rank(L->shape); }
 int oracle_layout_depth(const Layout* L) { return oracle::depth(L->shape); }
 int64_t oracle_layout_eval(const Layout* L, int64_t i) { return oracle::eval(*L, i); }
@@ -128,10 +129,18 @@ int oracle_layout_slice(const Layout* L, const char* coord, int64_t* offset, Lay
 }
 int oracle_coalesce(const Layout* a, Layout** out) { *out = new Layout(oracle::coalesce(*a)); return oracle::OK; }
 int oracle_coalesce_bymode(const Layout* a, Layout** out) { *out = new Layout(oracle::coalesce_bymode(*a)); return oracle::OK; }
-int oracle_right_inverse(const Layout* a, Layout** out) { *out = new Layout(oracle::right_inverse(*a)); return oracle::OK; }
+// The statements of these operations are written for strides in N: negative strides are refused here, at the boundary.
+#define REFUSE_NEGATIVE(L) do { if (oracle::has_negative_stride(*(L))) return oracle::ERR_NEGATIVE_STRIDE; } while (0)
+int oracle_right_inverse(const Layout* a, Layout** out) {
+  REFUSE_NEGATIVE(a);
+  *out = new Layout(oracle::right_inverse(*a));
+  return oracle::OK;
+}
 
 #define ORACLE_BINARY(name)                                             \
   int oracle_##name(const Layout* a, const Layout* b, Layout** out) {   \
+    REFUSE_NEGATIVE(a);                                                 \
+    REFUSE_NEGATIVE(b);                                                 \
     Layout r;                                                           \
     oracle::Status st = oracle::name(*a, *b, &r);                       \
     if (st != oracle::OK) return st;                                    \
@@ -149,14 +158,16 @@ ORACLE_BINARY(zipped_divide)
 #undef ORACLE_BINARY
 
 int oracle_left_inverse(const Layout* a, Layout** out) {
+  REFUSE_NEGATIVE(a);
   Layout r;
   oracle::Status st = oracle::left_inverse(*a, &r);
   if (st != oracle::OK) return st;
   *out = new Layout(r);
   return oracle::OK;
 }
-int oracle_admissible(const Layout* a, const Layout* t) { return oracle::admissible(*a, *t) ? 1 : 0; }
+int oracle_admissible(const Layout* a, const Layout* t) { return oracle::admissible(*a, *t) ? 1 : 0; }   // the statement holds for any integers
 int oracle_complement(const Layout* a, int64_t cotarget, Layout** out) {
+  REFUSE_NEGATIVE(a);
   Layout r;
   oracle::Status st = oracle::complement(*a, cotarget, &r);
   if (st != oracle::OK) return st;
@@ -164,10 +175,14 @@ int oracle_complement(const Layout* a, int64_t cotarget, Layout** out) {
   return oracle::OK;
 }
 int oracle_max_common_vector_def(const Layout* a, const Layout* b, int64_t* K) {
+  REFUSE_NEGATIVE(a);
+  REFUSE_NEGATIVE(b);
   *K = oracle::max_common_vector_def(*a, *b);
   return oracle::OK;
 }
 int oracle_max_common_vector(const Layout* a, const Layout* b, int64_t* K) {
+  REFUSE_NEGATIVE(a);
+  REFUSE_NEGATIVE(b);
   return oracle::max_common_vector_alg(*a, *b, K);
 }
 

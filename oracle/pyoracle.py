@@ -54,7 +54,7 @@ def lib():
         L.oracle_layout_destroy.argtypes = [P]
         L.oracle_layout_destroy.restype = None
         L.oracle_layout_to_string.argtypes = [P, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
-        for name in ("size", "cosize"):
+        for name in ("size", "cosize", "min_offset"):
             f = getattr(L, "oracle_layout_" + name)
             f.argtypes = [P]
             f.restype = i64
@@ -137,6 +137,11 @@ class Layout:
     @property
     def cosize(self):
         return lib().oracle_layout_cosize(self._h)
+
+    @property
+    def min_offset(self):
+        """Smallest offset of the image: 0 unless a stride is negative."""
+        return lib().oracle_layout_min_offset(self._h)
 
     @property
     def rank(self):
@@ -333,20 +338,22 @@ def congruent(p, s): return lib().oracle_congruent(p.encode(), s.encode()) == 1
 def weakly_congruent(p, s): return lib().oracle_weakly_congruent(p.encode(), s.encode()) == 1
 
 
-def copy(src, src_layout, dst, dst_layout, begin=0, end=None, spans_checked=False):
+def copy(src, src_layout, dst, dst_layout, begin=0, end=None, spans_checked=False, src_origin=0, dst_origin=0):
     """dst(i) = src(i) over numpy arrays (1-D, same itemsize), element by element, in order.
     With a range [begin, end) the caller may pass buffers that only cover the offsets that range
-    reaches and vouch for it with spans_checked=True."""
+    reaches and vouch for it with spans_checked=True.  src_origin / dst_origin: the element of the array that offset 0
+    of the layout refers to (the accessor's pointer, Sec. 2.5); needed when strides are negative."""
     sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
     assert src.dtype.itemsize == dst.dtype.itemsize and src.flags.c_contiguous and dst.flags.c_contiguous
     if not spans_checked:
-        assert sl.cosize <= src.size and dl.cosize <= dst.size, "buffer smaller than the layout's cosize"
+        assert src_origin + sl.min_offset >= 0 and src_origin + sl.cosize <= src.size, "source buffer does not cover the layout's image"
+        assert dst_origin + dl.min_offset >= 0 and dst_origin + dl.cosize <= dst.size, "destination buffer does not cover the layout's image"
+    sp = ctypes.c_void_p(src.ctypes.data + src_origin * src.dtype.itemsize)
+    dp = ctypes.c_void_p(dst.ctypes.data + dst_origin * dst.dtype.itemsize)
     if end is None:
-        st = lib().oracle_copy(src.ctypes.data_as(ctypes.c_void_p), sl._h, dst.ctypes.data_as(ctypes.c_void_p), dl._h,
-                               src.dtype.itemsize)
+        st = lib().oracle_copy(sp, sl._h, dp, dl._h, src.dtype.itemsize)
     else:
-        st = lib().oracle_copy_range(src.ctypes.data_as(ctypes.c_void_p), sl._h, dst.ctypes.data_as(ctypes.c_void_p),
-                                     dl._h, src.dtype.itemsize, begin, end)
+        st = lib().oracle_copy_range(sp, sl._h, dp, dl._h, src.dtype.itemsize, begin, end)
     _check(st, "copy")
     return dst
 

@@ -76,6 +76,8 @@ def lib():
     L.lc_slayout_composition.argtypes = [P, P, PP]
     L.lc_slayout_coalesce.argtypes = [P, PP]
     L.lc_slayout_right_inverse.argtypes = [P, PP]
+    L.lc_layout_min_offset.argtypes = [P]
+    L.lc_layout_min_offset.restype = i64
     L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
     L.lc_admissible.argtypes = [P, P, ctypes.POINTER(ctypes.c_int), PP]
     L.lc_plan_create.argtypes = [P, P, ctypes.c_int, ctypes.c_uint, ctypes.c_uint, PP]
@@ -93,6 +95,7 @@ def lib():
     L.lc_plan_algorithmic_bytes.restype = i64
     L.lc_plan_time.argtypes = [P, PP, PP, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
     L.lc_debug_replay_on_host.argtypes = [P, P, i64, P, i64, ctypes.POINTER(i64)]
+    L.lc_debug_replay_on_host_at.argtypes = [P, P, i64, i64, P, i64, i64, ctypes.POINTER(i64)]
     u = ctypes.c_uint
     L.lc_gemm_plan_create.argtypes = [P, P, P, ctypes.c_int, u, u, u, PP]
     L.lc_gemm_plan_describe.argtypes = [P, ctypes.c_char_p, sz, ctypes.POINTER(sz)]
@@ -147,6 +150,7 @@ class Layout:
     __repr__ = __str__
     size = property(lambda self: lib().lc_layout_size(self._h))
     cosize = property(lambda self: lib().lc_layout_cosize(self._h))
+    min_offset = property(lambda self: lib().lc_layout_min_offset(self._h))
     rank = property(lambda self: lib().lc_layout_rank(self._h))
     depth = property(lambda self: lib().lc_layout_depth(self._h))
 
@@ -332,12 +336,13 @@ class Plan:
         _check(lib().lc_plan_time(self._h, a, b, n, warmup, iters, stream, ctypes.byref(ms)), "lc_plan_time")
         return ms.value
 
-    def debug_replay_on_host(self, src, dst):
+    def debug_replay_on_host(self, src, dst, src_origin=0, dst_origin=0):
         """Test instrumentation: walk the plan's index arithmetic over numpy arrays on the host
-        (bounds-checked); returns the modelled LDS bank-conflict cycles of one tile."""
+        (bounds-checked); returns the modelled LDS bank-conflict cycles of one tile.  src_origin / dst_origin: the
+        element of each array that offset 0 of its layout refers to (layouts with negative strides reach below it)."""
         c = ctypes.c_int64()
-        _check(lib().lc_debug_replay_on_host(self._h, src.ctypes.data_as(ctypes.c_void_p), src.size,
-                                             dst.ctypes.data_as(ctypes.c_void_p), dst.size, ctypes.byref(c)),
+        _check(lib().lc_debug_replay_on_host_at(self._h, src.ctypes.data_as(ctypes.c_void_p), src.size, src_origin,
+                                                dst.ctypes.data_as(ctypes.c_void_p), dst.size, dst_origin, ctypes.byref(c)),
                "lc_debug_replay_on_host")
         return c.value
 
@@ -348,17 +353,19 @@ def lc_copy(src_ptr, src_layout, dst_ptr, dst_layout, dtype, stream=0):
     _check(lib().lc_copy(src_ptr, sl._h, dst_ptr, dl._h, DTYPES[dtype], stream), "lc_copy(%s -> %s)" % (sl, dl))
 
 
-def copy_tensor(src, src_layout, dst, dst_layout, dtype=None):
-    """Convenience for torch tensors on the GPU: takes data pointers and torch's current stream."""
+def copy_tensor(src, src_layout, dst, dst_layout, dtype=None, src_origin=0, dst_origin=0):
+    """Convenience for torch tensors on the GPU: takes data pointers and torch's current stream.  src_origin / dst_origin:
+    the element of each tensor that offset 0 of its layout refers to (layouts with negative strides reach below it)."""
     import torch
     if not (src.is_cuda and dst.is_cuda):
         raise RuntimeError("copy_tensor needs GPU tensors: the copy only runs in the HIP kernels")
     if dtype is None:
         dtype = {4: "b32", 2: "b16", 1: "b8", 8: "b64"}[src.element_size()]
     sl, dl = _as_layout(src_layout), _as_layout(dst_layout)
-    if sl.cosize > src.numel() or dl.cosize > dst.numel():
-        raise ValueError("tensor smaller than the layout's cosize")
-    lc_copy(src.data_ptr(), sl, dst.data_ptr(), dl, dtype, torch.cuda.current_stream().cuda_stream)
+    if src_origin + sl.min_offset < 0 or src_origin + sl.cosize > src.numel() or dst_origin + dl.min_offset < 0 or dst_origin + dl.cosize > dst.numel():
+        raise ValueError("tensor does not cover the offsets the layout reaches")
+    lc_copy(src.data_ptr() + src_origin * src.element_size(), sl, dst.data_ptr() + dst_origin * dst.element_size(), dl, dtype,
+            torch.cuda.current_stream().cuda_stream)
 
 
 class GemmPlan:

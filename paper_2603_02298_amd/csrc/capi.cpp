@@ -33,8 +33,13 @@ lc_status_t give(const lc::Layout& L, lc_layout_t** out) {
 }
 
 typedef lc_status_t (*binary_op)(const lc::Layout&, const lc::Layout&, lc::Layout*);
+// composition's divisibility conditions, complement's ordering and the inverses are stated for strides in N (Sec. 3)
+#define LC_REFUSE_NEGATIVE(h) do { if ((h)->L.has_negative_stride()) return LC_ERR_NEGATIVE_STRIDE; } while (0)
+
 lc_status_t binary(binary_op op, const lc_layout_t* a, const lc_layout_t* b, lc_layout_t** out) {
   if (!a || !b || !out) return LC_ERR_INVALID_ARG;
+  LC_REFUSE_NEGATIVE(a);
+  LC_REFUSE_NEGATIVE(b);
   try {
     lc::Layout r;
     lc_status_t st = op(a->L, b->L, &r);
@@ -131,6 +136,7 @@ lc_status_t lc_layout_to_string(const lc_layout_t* layout, char* buf, size_t cap
 }
 int64_t lc_layout_size(const lc_layout_t* layout) { return layout ? layout->L.size() : -1; }
 int64_t lc_layout_cosize(const lc_layout_t* layout) { return layout ? layout->L.cosize() : -1; }
+int64_t lc_layout_min_offset(const lc_layout_t* layout) { return layout ? layout->L.min_offset() : 1; }
 int lc_layout_rank(const lc_layout_t* layout) { return layout ? layout->L.rank() : -1; }
 int lc_layout_depth(const lc_layout_t* layout) { return layout ? layout->L.depth() : -1; }
 int64_t lc_layout_eval(const lc_layout_t* layout, int64_t i) { return (layout && i >= 0) ? layout->L(i) : -1; }
@@ -160,16 +166,20 @@ lc_status_t lc_coalesce_bymode(const lc_layout_t* a, lc_layout_t** out) {
 }
 lc_status_t lc_right_inverse(const lc_layout_t* a, lc_layout_t** out) {
   if (!a || !out) return LC_ERR_INVALID_ARG;
+  LC_REFUSE_NEGATIVE(a);
   return give(lc::right_inverse(a->L), out);
 }
 lc_status_t lc_left_inverse(const lc_layout_t* a, lc_layout_t** out) {
   if (!a || !out) return LC_ERR_INVALID_ARG;
+  LC_REFUSE_NEGATIVE(a);
   lc::Layout r;
   lc_status_t st = lc::left_inverse(a->L, &r);
   return st == LC_OK ? give(r, out) : st;
 }
 lc_status_t lc_admissible(const lc_layout_t* a, const lc_layout_t* t, int* yes, lc_layout_t** where) {
   if (!a || !t || !yes) return LC_ERR_INVALID_ARG;
+  LC_REFUSE_NEGATIVE(a);
+  LC_REFUSE_NEGATIVE(t);
   try {
     bool ok = false, has_where = false;
     lc::Layout w;
@@ -196,12 +206,15 @@ lc_status_t lc_zipped_divide(const lc_layout_t* a, const lc_layout_t* t, lc_layo
 
 lc_status_t lc_complement(const lc_layout_t* a, int64_t cotarget, lc_layout_t** out) {
   if (!a || !out) return LC_ERR_INVALID_ARG;
+  LC_REFUSE_NEGATIVE(a);
   lc::Layout r;
   lc_status_t st = lc::complement(a->L, cotarget, &r);
   return st == LC_OK ? give(r, out) : st;
 }
 lc_status_t lc_max_common_vector(const lc_layout_t* a, const lc_layout_t* b, int64_t* K) {
   if (!a || !b || !K) return LC_ERR_INVALID_ARG;
+  LC_REFUSE_NEGATIVE(a);
+  LC_REFUSE_NEGATIVE(b);
   return lc::max_common_vector(a->L, b->L, K);
 }
 
@@ -291,7 +304,16 @@ lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* c
 lc_status_t lc_debug_replay_on_host(const lc_plan_t* plan, const void* src_host, int64_t src_elems, void* dst_host,
                                     int64_t dst_elems, int64_t* lds_conflicts) {
   if (!plan || !src_host || !dst_host) return LC_ERR_INVALID_ARG;
-  return lc::replay_on_host(*plan, src_host, src_elems, dst_host, dst_elems, lds_conflicts);
+  return lc::replay_on_host(*plan, src_host, 0, src_elems, dst_host, 0, dst_elems, lds_conflicts);
+}
+// The same for layouts with negative strides: the buffers start src_origin / dst_origin elements before offset 0.
+lc_status_t lc_debug_replay_on_host_at(const lc_plan_t* plan, const void* src_buffer, int64_t src_elems, int64_t src_origin, void* dst_buffer,
+                                       int64_t dst_elems, int64_t dst_origin, int64_t* lds_conflicts) {
+  if (!plan || !src_buffer || !dst_buffer || src_origin < 0 || dst_origin < 0 || src_origin >= src_elems || dst_origin >= dst_elems)
+    return LC_ERR_INVALID_ARG;
+  const int eb = plan->elem_bytes;
+  return lc::replay_on_host(*plan, static_cast<const unsigned char*>(src_buffer) + src_origin * eb, -src_origin, src_elems - src_origin,
+                            static_cast<unsigned char*>(dst_buffer) + dst_origin * eb, -dst_origin, dst_elems - dst_origin, lds_conflicts);
 }
 
 

@@ -31,6 +31,7 @@ extern "C" {
 lc_status_t lc_gemm_plan_create(const lc_layout_t* a, const lc_layout_t* b, const lc_layout_t* c, lc_dtype_t ab_dtype, unsigned a_align_bytes,
                                 unsigned b_align_bytes, unsigned c_align_bytes, lc_gemm_plan_t** out) {
   if (!a || !b || !c || !out) return LC_ERR_INVALID_ARG;
+  if (a->L.has_negative_stride() || b->L.has_negative_stride() || c->L.has_negative_stride()) return LC_ERR_NEGATIVE_STRIDE;   // the GEMM planner's buffer loads take offsets >= 0
   try {
     lc_gemm_plan* p = new lc_gemm_plan;
     lc_status_t st = lc::make_gemm_plan(a->L, b->L, c->L, (int)ab_dtype, a_align_bytes, b_align_bytes, c_align_bytes, p);

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(kBlock) void zero_words_kernel(uint32_t* __restrict
   const uint64_t step = (uint64_t)gridDim.x * kBlock;
   for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += step) words[i] = 0u;
 }
+// `last` points at the record of destination offset 0 (offsets below 0 exist with negative strides: the records start lower)
 __global__ __launch_bounds__(kBlock) void last_writer_mark_kernel(GenericParams P, uint32_t* __restrict__ last) {
   touch_kernel_arguments<(int)sizeof(GenericParams)>();
   const uint32_t step = gridDim.x * kBlock;
@@ -710,7 +711,9 @@ lc_status_t execute_plan_static(const lc_plan& plan, const void* src, void* dst,
 
 static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t, void* stream) {
   if (!src || !dst) return LC_ERR_INVALID_ARG;
-  src = static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes;   // the slice that is written last
+  // offsets the planner folded into the accessors: the slice that is written last, the last elements of modes walked backwards
+  src = static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes;
+  dst = static_cast<unsigned char*>(dst) + plan.dst_offset_elems * plan.elem_bytes;
   if ((reinterpret_cast<uintptr_t>(src) % plan.src_align) != 0 || (reinterpret_cast<uintptr_t>(dst) % plan.dst_align) != 0)
     return LC_ERR_MISALIGNED;
   const int cus = device_cu_count();
@@ -720,11 +723,12 @@ static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst,
   PreLaunch pre;
   if (plan.cls == KernelClass::LastWriter) {
     // three launches in stream order: clear the records, record the last coordinate per offset, move
-    uint32_t* last = static_cast<uint32_t*>(workspace);
+    uint32_t* records = static_cast<uint32_t*>(workspace);
+    uint32_t* last = records + plan.workspace_bias;   // the record of destination offset 0
     const uint64_t words = (uint64_t)plan.workspace_bytes / 4;
     const unsigned zgrid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>((words + kBlock - 1) / kBlock, (uint64_t)cus * 16));
     const unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(((uint64_t)plan.generic.n + kBlock - 1) / kBlock, (uint64_t)cus * 16));
-    hipLaunchKernelGGL(zero_words_kernel, dim3(zgrid), dim3(kBlock), 0, s, last, words);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(zgrid), dim3(kBlock), 0, s, records, words);
     hipLaunchKernelGGL(last_writer_mark_kernel, dim3(grid), dim3(kBlock), 0, s, plan.generic, last);
     switch (plan.elem_bytes) {
       case 1: launch_last_writer_move<1>(plan, src, dst, last, grid, s); break;

@@ -55,8 +55,19 @@ int64_t Layout::size() const {
 
 int64_t Layout::cosize() const {
   int64_t top = 0;
-  for (const Mode& m : leaves) top += (m.extent - 1) * m.stride;
+  for (const Mode& m : leaves) if (m.stride > 0) top += (m.extent - 1) * m.stride;
   return top + 1;
+}
+
+int64_t Layout::min_offset() const {
+  int64_t low = 0;
+  for (const Mode& m : leaves) if (m.stride < 0) low += (m.extent - 1) * m.stride;
+  return low;
+}
+
+bool Layout::has_negative_stride() const {
+  for (const Mode& m : leaves) if (m.stride < 0) return true;
+  return false;
 }
 
 Layout Layout::mode(int i) const {
@@ -182,9 +193,9 @@ lc_status_t validate(const Layout& L) {
   long double size = 1.0L, top = 0.0L;
   for (const Mode& m : L.leaves) {
     if (m.extent < 1) return LC_ERR_BAD_EXTENT;
-    if (m.stride < 0) return LC_ERR_NEGATIVE_STRIDE;
+    // strides of either sign (Sec. 2.3.2: Z is an integer-semimodule); the operations stated for strides in N refuse them
     size *= (long double)m.extent;
-    top += (long double)(m.extent - 1) * (long double)m.stride;
+    top += (long double)(m.extent - 1) * (long double)(m.stride < 0 ? -m.stride : m.stride);
     if (size > limit || top > limit) return LC_ERR_TOO_LARGE;
   }
   if (L.leaves.size() > 64 || L.profile.size() > 256) return LC_ERR_TOO_LARGE;

@@ -33,7 +33,9 @@ struct Layout {
   int rank() const { return profile[0] == 0 ? 1 : profile[0]; }
   int depth() const;
   int64_t size() const;
-  int64_t cosize() const;
+  int64_t cosize() const;                   // largest offset + 1
+  int64_t min_offset() const;               // smallest offset: 0 unless a stride is negative
+  bool has_negative_stride() const;
   Layout mode(int i) const;                 // L_i = S_i : D_i (a leaf is its own mode 0)
   std::string str() const;
   int64_t operator()(int64_t i) const;      // integral coordinate, extended domain

@@ -178,7 +178,7 @@ static int64_t run_length(const std::vector<JointMode>& J, const std::vector<int
   int64_t run = 1, expect = 1;
   for (int k : order) {
     int64_t st = src_side ? J[(size_t)k].a : J[(size_t)k].b;
-    if (st == 0) continue;
+    if (st <= 0) continue;   // a broadcast or a reversed mode is no part of a contiguous run
     if (st != expect) break;
     run *= t[(size_t)k];
     if (t[(size_t)k] < J[(size_t)k].extent) break;
@@ -213,13 +213,17 @@ static lc_status_t plan_generic(const Modes& S, const Modes& D, int64_t n, lc_pl
 
 // Destinations that alias (Table copy, "Scatter" with repeated offsets; Sec. 2.6.1: the loop's last write stays).
 static lc_status_t plan_last_writer(const Modes& S, const Modes& D, int64_t n, lc_plan* plan, const std::string& why) {
-  int64_t span = 1;   // cosize of the destination: largest offset + 1
-  for (const Mode& m : D) span += (m.extent - 1) * m.stride;
+  int64_t span = 1, lowest = 0;   // offsets the destination reaches: lowest .. lowest + span - 1
+  for (const Mode& m : D) {
+    span += (m.extent - 1) * std::abs(m.stride);
+    if (m.stride < 0) lowest += (m.extent - 1) * m.stride;
+  }
   lc_status_t st = plan_generic(S, D, n, plan, why);
   if (st != LC_OK) return st;
   if (span >= (1ll << 40)) return LC_ERR_TOO_LARGE;
   plan->cls = KernelClass::LastWriter;
   plan->workspace_bytes = span * 4;
+  plan->workspace_bias = -lowest;
   plan->wgs_per_cu = 16;
   return LC_OK;
 }
@@ -261,7 +265,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
   // offsets inside a tile are 32-bit in the kernel: a growth step must keep both spans below 2^30 elements
   auto spans_fit = [&](const std::vector<int64_t>& tt) {
     int64_t ss = 0, sd = 0;
-    for (int k = 0; k < nj; ++k) { ss += (tt[(size_t)k] - 1) * J[(size_t)k].a; sd += (tt[(size_t)k] - 1) * J[(size_t)k].b; }
+    for (int k = 0; k < nj; ++k) { ss += (tt[(size_t)k] - 1) * std::abs(J[(size_t)k].a); sd += (tt[(size_t)k] - 1) * J[(size_t)k].b; }
     return ss < (1ll << 30) && sd < (1ll << 30);
   };
   auto micro_of = [&](const std::vector<int64_t>& tt) {
@@ -394,7 +398,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
       if (ext > 1) mm.push_back({ext, ta * scale, tb * scale, k == p, k == q, coord_weight(k, scale)});
     }
     int64_t span_s = 0, span_d = 0;
-    for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * J[(size_t)k].a; span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
+    for (int k = 0; k < nj; ++k) { span_s += (t[(size_t)k] - 1) * std::abs(J[(size_t)k].a); span_d += (t[(size_t)k] - 1) * J[(size_t)k].b; }
     if (span_s >= (1ll << 30) || span_d >= (1ll << 30) || mm.size() >= (size_t)kMaxModes) ok = false;
     if (ok) {
       // destination order of the tile's vectors: the micro modes and the position ip along p
@@ -462,7 +466,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
       P.n_vec = run;
       P.n_micro = run / (uint32_t)V;
       P.a_q = (int32_t)J[(size_t)q].a;
-      if (J[(size_t)q].a * (V - 1) >= (1ll << 30) || J[(size_t)p].b * (V - 1) >= (1ll << 30)) ok = false;
+      if (std::abs(J[(size_t)q].a) * (V - 1) >= (1ll << 30) || J[(size_t)p].b * (V - 1) >= (1ll << 30)) ok = false;
     }
   }
   if (ok) {
@@ -570,14 +574,38 @@ static bool joint_modes(const Modes& S, const Modes& D, std::vector<JointMode>* 
   Modes ident;
   int64_t run = 1;
   for (int64_t e : F) { ident.push_back({e, run}); run *= e; }
-  Layout IF = Layout::flat(ident), Sr, Dr;
-  if (composition(Layout::flat(S), IF, &Sr) != LC_OK || composition(Layout::flat(D), IF, &Dr) != LC_OK ||
-      Sr.leaves.size() != F.size() || Dr.leaves.size() != F.size())
-    return false;
+  // Composition is stated for strides in N; a mode of negative stride refines like its mirror image (the same extents,
+  // every stride of the refinement with the mode's sign), so the magnitudes are composed and the signs put back.
+  auto refine = [&](const Modes& M, std::vector<int64_t>* strides) {
+    Modes mag = M;
+    for (Mode& m : mag) m.stride = m.stride < 0 ? -m.stride : m.stride;
+    Layout R;
+    if (composition(Layout::flat(mag), Layout::flat(ident), &R) != LC_OK || R.leaves.size() != F.size()) return false;
+    size_t parent = 0;
+    int64_t left = M[0].extent;
+    for (size_t k = 0; k < F.size(); ++k) {
+      while (left == 1 && parent + 1 < M.size()) left = M[++parent].extent;
+      strides->push_back(M[parent].stride < 0 ? -R.leaves[k].stride : R.leaves[k].stride);
+      left /= F[k];
+    }
+    return true;
+  };
+  std::vector<int64_t> sa, sb;
+  if (!refine(S, &sa) || !refine(D, &sb)) return false;
   J->clear();
   for (size_t k = 0; k < F.size(); ++k)
-    if (F[k] > 1) J->push_back({F[k], Sr.leaves[k].stride, Dr.leaves[k].stride});
+    if (F[k] > 1) J->push_back({F[k], sa[k], sb[k]});
   return true;
+}
+
+static Modes magnitudes(const Modes& M) {
+  Modes out = M;
+  for (Mode& m : out) m.stride = m.stride < 0 ? -m.stride : m.stride;
+  return out;
+}
+static bool any_negative(const Modes& M) {
+  for (const Mode& m : M) if (m.stride < 0) return true;
+  return false;
 }
 
 lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src_align, unsigned dst_align,
@@ -603,7 +631,9 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   // the order of Sec. 2.6.1's loop (i ascending) decides it without a race: of the coordinates that differ only in
   // destination modes of stride 0, the one with those modes at their last position is written last.  The copy is then
   // the copy of that slice (Sec. 2.5.1): the modes fold into an offset of the source and leave both layouts.
-  if (n > 1 && !layout_is_injective(D, n)) {
+  // (mirroring a mode, c -> extent - 1 - c, turns a negative stride into its magnitude and shifts every offset by the same
+  // constant: injectivity is that of the magnitudes)
+  if (n > 1 && !layout_is_injective(coalesce_modes(magnitudes(D)), n)) {
     std::vector<JointMode> J0;
     Modes S2, D2;
     int64_t offset = 0, n2 = 1;
@@ -630,11 +660,47 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
     while (shifted_align > 1 && (offset * es) % shifted_align != 0) shifted_align /= 2;
     lc_status_t st = make_plan(Layout::flat(S2), Layout::flat(D2), es, shifted_align, dst_align, tune, plan);   // may itself be last-writer
     if (st != LC_OK) return st;
-    plan->src_offset_elems = offset;
-    plan->overwritten_modes = dropped;
+    plan->src_offset_elems += offset;
+    plan->overwritten_modes += dropped;
     plan->distinct_reads = 1;
     for (const Mode& m : S)
       if (m.stride != 0) plan->distinct_reads *= m.extent;
+    return LC_OK;
+  }
+
+  // Negative destination strides: COPY may visit its coordinates in any order as long as both sides take the same one
+  // (Sec. 3.4.2), so every joint mode whose destination stride is negative is walked backwards, c -> extent - 1 - c.  Both
+  // of its strides change sign and the mode's last element becomes its first: (extent - 1) * stride goes into each
+  // pointer.  What is left has destination strides >= 0 and is planned as usual; source strides that are still negative
+  // are true reversals of source against destination and stay (the kernels' index arithmetic is signed).
+  if (any_negative(D)) {
+    std::vector<JointMode> J0;
+    if (!joint_modes(S, D, &J0)) return plan_generic(S, D, n, plan, "shapes have no common refinement");   // signed strides as they are
+    Modes S2, D2;
+    int64_t src_shift = 0, dst_shift = 0;
+    for (const JointMode& m : J0) {
+      if (m.b < 0) {
+        src_shift += (m.extent - 1) * m.a;
+        dst_shift += (m.extent - 1) * m.b;
+        S2.push_back({m.extent, -m.a});
+        D2.push_back({m.extent, -m.b});
+      } else {
+        S2.push_back({m.extent, m.a});
+        D2.push_back({m.extent, m.b});
+      }
+    }
+    if (S2.empty()) { S2.push_back({1, 0}); D2.push_back({1, 0}); }
+    auto shifted = [&](unsigned align, int64_t shift) {
+      while (align > 1 && (shift * es) % (int64_t)align != 0) align /= 2;
+      return align;
+    };
+    const int64_t reads = plan->distinct_reads;
+    lc_status_t st = make_plan(Layout::flat(S2), Layout::flat(D2), es, shifted(plan->src_align, src_shift), shifted(plan->dst_align, dst_shift), tune, plan);
+    if (st != LC_OK) return st;
+    plan->src_offset_elems += src_shift;
+    plan->dst_offset_elems += dst_shift;
+    plan->reflected_modes += 1;
+    plan->distinct_reads = reads;
     return LC_OK;
   }
 
@@ -642,26 +708,18 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   // kernels use is derived from the joint modes below and clamped by element width and alignment; when both exist
   // it never exceeds K (asserted where the direct class picks its vector).
   int64_t K = 1;
-  const bool K_known = max_common_vector(src, dst, &K) == LC_OK;
+  const bool K_known = !any_negative(S) && max_common_vector(src, dst, &K) == LC_OK;
   if (!K_known) K = 1;
   plan->common_vector = K;
 
   // a3: refine both shapes to one shape F by composing each layout with the identity layout of F
   // (Sec. 3.3.1); then every mode of F has one stride on each side.
-  std::vector<int64_t> F;
-  if (!common_refinement(S, D, &F)) return plan_generic(S, D, n, plan, "shapes have no common refinement");
-  Modes ident;
-  {
-    int64_t run = 1;
-    for (int64_t e : F) { ident.push_back({e, run}); run *= e; }
-  }
-  Layout IF = Layout::flat(ident), Sr, Dr;
-  if (composition(Layout::flat(S), IF, &Sr) != LC_OK || composition(Layout::flat(D), IF, &Dr) != LC_OK ||
-      Sr.leaves.size() != F.size() || Dr.leaves.size() != F.size())
-    return plan_generic(S, D, n, plan, "refinement by composition was not admissible");
   std::vector<JointMode> J;
-  for (size_t k = 0; k < F.size(); ++k)
-    if (F[k] > 1) J.push_back({F[k], Sr.leaves[k].stride, Dr.leaves[k].stride});
+  {
+    std::vector<int64_t> F;
+    if (!common_refinement(S, D, &F)) return plan_generic(S, D, n, plan, "shapes have no common refinement");
+    if (!joint_modes(S, D, &J)) return plan_generic(S, D, n, plan, "refinement by composition was not admissible");
+  }
   if (J.empty()) J.push_back({1, 0, 0});
 
   // a4: the same permutation on both sides leaves COPY unchanged (Sec. 3.4.2): order by destination
@@ -848,6 +906,8 @@ std::string describe(const lc_plan& plan) {
   s += " K=" + std::to_string(plan.common_vector) + " width_bytes=" + std::to_string(plan.width_bytes);
   if (plan.overwritten_modes > 0)
     s += " overwritten_modes=" + std::to_string(plan.overwritten_modes) + " src_offset=" + std::to_string(plan.src_offset_elems);
+  if (plan.reflected_modes > 0)
+    s += " reflected=1 src_offset=" + std::to_string(plan.src_offset_elems) + " dst_offset=" + std::to_string(plan.dst_offset_elems);
   s += " joint=[";
   for (size_t k = 0; k < plan.joint.size(); ++k) {
     if (k) s += " ";

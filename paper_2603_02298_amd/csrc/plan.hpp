@@ -48,6 +48,10 @@ struct lc_plan {
   // last coordinates: the source is read from src + src_offset_elems, the modes are gone from the plan.
   int64_t src_offset_elems = 0;
   int overwritten_modes = 0;
+  // Joint modes of negative destination stride are walked backwards (the same order on both sides, Sec. 3.4.2): their
+  // last elements become the origins, folded into both pointers.
+  int64_t dst_offset_elems = 0;
+  int reflected_modes = 0;
   int64_t common_vector = 1;               // K of Sec. 3.4.2 before hardware clamps
   std::vector<lc::JointMode> joint;        // after common refinement, destination-order sort, joint coalesce
   unsigned src_align = 0, dst_align = 0;   // alignment the access widths rely on
@@ -77,6 +81,7 @@ struct lc_plan {
   // offset in scratch memory (one 32-bit word per element of the destination's span), a second pass lets only the recorded
   // coordinates write: the result does not depend on the order in which lanes run.
   int64_t workspace_bytes = 0;
+  int64_t workspace_bias = 0;              // the record of destination offset o is word o + workspace_bias (negative strides reach below 0)
 
   int wgs_per_cu = 0;
   int grid_override = 0;                   // > 0: workgroups of the launch, whatever the CU count
@@ -100,8 +105,10 @@ bool layout_is_injective(const Modes& coalesced, int64_t n);
 // Walks the plan on the host exactly along the kernels' index arithmetic and moves the bytes in
 // host memory.  It exists to prove the routing of a plan (and that every access stays inside the
 // two buffers) without a GPU; it is not a way to execute a copy and nothing in the copy path calls it.
-lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_elems, void* dst, int64_t dst_elems,
-                           int64_t* lds_conflicts);
+// src / dst point at offset 0 of the layouts; [src_lo, src_hi) and [dst_lo, dst_hi) are the element offsets around them
+// that belong to the buffers (lo <= 0 < hi).
+lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo, int64_t src_hi, void* dst, int64_t dst_lo,
+                           int64_t dst_hi, int64_t* lds_conflicts);
 
 // Defined with the kernels: enqueue the plan's kernel on a HIP stream / time repeated executions.
 const char* last_hip_error();

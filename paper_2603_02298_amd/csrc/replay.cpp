@@ -12,23 +12,26 @@ int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes,
 
 namespace {
 struct Buffers {
-  const unsigned char* src;
+  const unsigned char* src;   // the plan's effective source / destination pointers (offsets folded in)
   unsigned char* dst;
-  int64_t src_bytes, dst_bytes;
+  int64_t src_lo, src_hi, dst_lo, dst_hi;   // byte offsets around them that belong to the buffers
   bool ok = true;
   void move(int64_t so, int64_t dof, int bytes) {
-    if (so < 0 || dof < 0 || so + bytes > src_bytes || dof + bytes > dst_bytes) { ok = false; return; }
+    if (so < src_lo || dof < dst_lo || so + bytes > src_hi || dof + bytes > dst_hi) { ok = false; return; }
     std::memcpy(dst + dof, src + so, (size_t)bytes);
   }
 };
 }  // namespace
 
-lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_elems, void* dst, int64_t dst_elems,
-                           int64_t* lds_conflicts) {
+lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo, int64_t src_hi, void* dst, int64_t dst_lo,
+                           int64_t dst_hi, int64_t* lds_conflicts) {
   const int es = plan.cls == KernelClass::Transpose ? plan.tile_elem_bytes : plan.elem_bytes;
-  if (plan.src_offset_elems < 0 || plan.src_offset_elems > src_elems) return LC_ERR_INVALID_ARG;
-  Buffers B{static_cast<const unsigned char*>(src) + plan.src_offset_elems * plan.elem_bytes, static_cast<unsigned char*>(dst),
-            (src_elems - plan.src_offset_elems) * plan.elem_bytes, dst_elems * plan.elem_bytes};
+  const int eb = plan.elem_bytes;
+  if (plan.src_offset_elems < src_lo || plan.src_offset_elems >= src_hi || plan.dst_offset_elems < dst_lo || plan.dst_offset_elems >= dst_hi)
+    return LC_ERR_INVALID_ARG;
+  Buffers B{static_cast<const unsigned char*>(src) + plan.src_offset_elems * eb, static_cast<unsigned char*>(dst) + plan.dst_offset_elems * eb,
+            (src_lo - plan.src_offset_elems) * eb, (src_hi - plan.src_offset_elems) * eb,
+            (dst_lo - plan.dst_offset_elems) * eb, (dst_hi - plan.dst_offset_elems) * eb};
   if (lds_conflicts) *lds_conflicts = 0;
   if (plan.cls == KernelClass::Generic) {
     const GenericParams& P = plan.generic;
@@ -38,13 +41,13 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
     const GenericParams& P = plan.generic;
     std::vector<uint32_t> winner((size_t)(plan.workspace_bytes / 4), 0u);
     for (uint32_t i = P.n; i-- > 0;) {
-      const int64_t off = flat_eval(P.dst, i);
-      if (off < 0 || off >= (int64_t)winner.size()) { B.ok = false; break; }
-      if (winner[(size_t)off] < i) winner[(size_t)off] = i;
+      const int64_t off = flat_eval(P.dst, i), word = off + plan.workspace_bias;
+      if (word < 0 || word >= (int64_t)winner.size()) { B.ok = false; break; }
+      if (winner[(size_t)word] < i) winner[(size_t)word] = i;
     }
     for (uint32_t i = P.n; B.ok && i-- > 0;) {
       const int64_t off = flat_eval(P.dst, i);
-      if (winner[(size_t)off] == i) B.move(flat_eval(P.src, i) * es, off * es, es);
+      if (winner[(size_t)(off + plan.workspace_bias)] == i) B.move(flat_eval(P.src, i) * es, off * es, es);
     }
   } else if (plan.cls == KernelClass::Direct) {
     const DirectParams& P = plan.direct;
@@ -85,7 +88,7 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
         }
         for (int iq = 0; iq < V; ++iq) {
           int64_t off = (sbase + so + (int64_t)iq * P.a_q) * es;
-          if (off < 0 || off + slot > B.src_bytes) { B.ok = false; break; }
+          if (off < B.src_lo || off + slot > B.src_hi) { B.ok = false; break; }
           for (int ip = 0; ip < V; ++ip) {
             size_t l = (size_t)lds_slot(P, g0 + (uint32_t)ip * P.gpos_pv) * (size_t)slot + (size_t)iq * (size_t)es;
             if (l + (size_t)es > lds.size()) { B.ok = false; break; }
@@ -106,7 +109,7 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_ele
         }
         int64_t off = (dbase + din) * es;
         size_t l = (size_t)lds_slot(P, g) * (size_t)slot;
-        if (off < 0 || off + slot > B.dst_bytes || l + (size_t)slot > lds.size()) { B.ok = false; break; }
+        if (off < B.dst_lo || off + slot > B.dst_hi || l + (size_t)slot > lds.size()) { B.ok = false; break; }
         std::memcpy(B.dst + off, &lds[l], (size_t)slot);
       }
       if (lds_conflicts && tile == 0) {

@@ -287,6 +287,43 @@ def test_aliasing_destinations_keep_the_last_write(oracle):
     assert (dst_t.cpu().numpy().view(bits.dtype) == want).all()
 
 
+def test_negative_strides(oracle):
+    # modes of negative destination stride are walked backwards on both sides; negative source strides stay as reversals
+    dev = torch.device("cuda:0")
+    cases = [("4096:1", "4096:-1", "f32"), ("4096:-1", "4096:-1", "f32"), ("100000:-1", "100000:1", "bf16"), ("13:-3", "13:1", "b8"),
+             ("(64,48):(1,64)", "(64,48):(-48,1)", "f32"), ("(64,48):(1,-64)", "(64,48):(48,1)", "f32"),
+             ("(256,64,3):(1,256,-16384)", "(256,64,3):(64,1,16384)", "bf16"), ("(256,64,3):(1,256,16384)", "(256,64,3):(64,1,-16384)", "bf16"),
+             ("(512,512,4):(1,512,-262144)", "(512,512,4):(512,1,262144)", "f32"),        # several tiles, batches reversed
+             ("(1024,1024):(1,1024)", "(1024,1024):(1024,-1)", "f32"),                    # transpose onto flipped columns
+             ("(6,10):(10,-1)", "(4,15):(-15,1)", "b64"), ("(4,2,3):(1,4,8)", "(4,2,3):(1,0,-4)", "f32")]
+    rng = np.random.default_rng(9)
+    for i in range(60):
+        r = int(rng.integers(1, 4))
+        ext = [int(x) for x in rng.integers(1, 40, r)]
+        def strides():
+            order = rng.permutation(r)
+            d, run = [0] * r, 1
+            for m in order:
+                d[m] = run * int(rng.choice([1, -1]))
+                run *= ext[m] * int(rng.choice([1, 1, 2]))
+            return d
+        cases.append(("(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, strides()))),
+                      "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, strides()))), ["f32", "bf16", "b8", "b64"][i % 4]))
+    for s, d, dt in cases:
+        es = lc.DTYPE_BYTES[dt]
+        sl, dl = oracle.Layout(s), oracle.Layout(d)
+        so, do = -sl.min_offset, -dl.min_offset
+        print("case signed", s, "->", d, dt, flush=True)
+        src_bits = np.random.default_rng(len(s) + len(d)).integers(0, 255, size=(so + sl.cosize) * es, dtype=np.uint8).view(_np_int(es))
+        want = np.full((do + dl.cosize) * es, 0x5A, np.uint8).view(_np_int(es))
+        oracle.copy(src_bits, sl, want, dl, src_origin=so, dst_origin=do)
+        src_t = torch.from_numpy(src_bits).to(dev)
+        dst_t = torch.from_numpy(np.full((do + dl.cosize) * es, 0x5A, np.uint8).view(_np_int(es))).to(dev)
+        lc.copy_tensor(src_t, s, dst_t, d, dt, src_origin=so, dst_origin=do)
+        torch.cuda.synchronize()
+        assert (dst_t.cpu().numpy() == want).all(), lc.Plan(s, d, dt).describe()
+
+
 def test_tile_queue_on_several_streams(oracle, monkeypatch):
     # every stream keeps a pair of counters of its own: copies that run side by side do not share one
     monkeypatch.setenv("LC_TUNE_TILE_QUEUE", "1")

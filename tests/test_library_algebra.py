@@ -112,7 +112,7 @@ def test_from_tree_equals_parse():
 
 @pytest.mark.parametrize("text,status", [
     ("(4,8):(1,4", "PARSE"), ("4,8:1,4", "PARSE"), ("(4,8):(1,(2,3))", "NOT_CONGRUENT"), ("(4,0):(1,4)", "BAD_EXTENT"),
-    ("(4,8):(1,-4)", "NEGATIVE_STRIDE"), ("", "PARSE"), ("(4,8)", "PARSE"), ("(4,8):(1,4) x", "PARSE")])
+    ("(4,8):(1,-)", "PARSE"), ("", "PARSE"), ("(4,8)", "PARSE"), ("(4,8):(1,4) x", "PARSE")])
 def test_parse_errors(oracle, text, status):
     with pytest.raises(lc.LayoutCopyError) as e:
         lc.Layout(text)
@@ -120,6 +120,30 @@ def test_parse_errors(oracle, text, status):
     with pytest.raises(oracle.OracleError) as e2:
         oracle.Layout(text)
     assert e2.value.status_name == status
+
+
+def test_negative_strides_evaluate_but_the_algebra_for_strides_in_N_refuses_them(oracle):
+    # Sec. 2.3.2: Z is an integer-semimodule, so a stride may be negative; the layout function, coalesce and slicing take
+    # them, the operations stated for strides in N say so
+    for text in ["8:-1", "(4,8):(1,-4)", "((2,3),4):((-1,2),-6)"]:
+        a, o = lc.Layout(text), oracle.Layout(text)
+        assert str(a) == str(o) == text
+        assert (a.size, a.cosize, a.min_offset) == (o.size, o.cosize, o.min_offset)
+        offs = o.offsets()
+        assert [a(i) for i in range(a.size)] == list(offs)
+        assert a.min_offset == offs.min() and a.cosize == offs.max() + 1
+        assert [lc.lc_coalesce(a)(i) for i in range(a.size)] == list(offs)
+        assert [oracle.coalesce(o)(i) for i in range(a.size)] == list(offs)
+        for op in (lc.lc_right_inverse, lc.lc_left_inverse, lambda x: lc.lc_complement(x, 64), lambda x: lc.lc_composition(x, "4:1"),
+                   lambda x: lc.lc_composition("64:1", x), lambda x: lc.lc_logical_divide(x, "2:1"), lambda x: lc.lc_max_common_vector(x, x)):
+            with pytest.raises(lc.LayoutCopyError) as e:
+                op(a)
+            assert e.value.status_name == "NEGATIVE_STRIDE"
+        for op in (oracle.right_inverse, oracle.left_inverse, lambda x: oracle.complement(x, 64), lambda x: oracle.composition(x, "4:1")):
+            with pytest.raises(oracle.OracleError) as e2:
+                op(o)
+            assert e2.value.status_name == "NEGATIVE_STRIDE"
+    assert str(lc.lc_coalesce("(4,8):(-1,-4)")) == str(oracle.coalesce("(4,8):(-1,-4)")) == "32:-1"
 
 
 def test_absurd_sizes_are_refused():

@@ -132,3 +132,43 @@ def test_ranges_on_host_threads_equal_the_single_loop(oracle):
         cut = oracle.copy_parallel(src, sl, np.zeros_like(src), dl, threads)
         assert (cut == whole).all()
     assert (whole.reshape(N, H, W, C) == src.reshape(N, C, H, W).transpose(0, 2, 3, 1)).all()
+
+
+def test_negative_strides_are_numpy_negative_steps(oracle):
+    """Sec. 2.3.2 allows strides from Z; the accessor's pointer (Sec. 2.5) then sits inside the buffer.  The loop against
+    numpy's negative-step slicing and flips: reversal, reversed gather, flipped matrix, flipped transpose."""
+    src = _rand(40, np.uint32, 31)
+    # reversed copy: dst[i] = src[39 - i]
+    dst = np.zeros(40, np.uint32)
+    oracle.copy(src, "40:-1", dst, "40:1", src_origin=39)
+    assert (dst == src[::-1]).all()
+    # the destination runs backwards instead
+    dst = np.zeros(40, np.uint32)
+    oracle.copy(src, "40:1", dst, "40:-1", dst_origin=39)
+    assert (dst == src[::-1]).all()
+    # both backwards: a plain copy again
+    dst = np.zeros(40, np.uint32)
+    oracle.copy(src, "40:-1", dst, "40:-1", src_origin=39, dst_origin=39)
+    assert (dst == src).all()
+    # gather every third element from the top down
+    dst = np.zeros(13, np.uint32)
+    oracle.copy(src, "13:-3", dst, "13:1", src_origin=38)
+    assert (dst == src[38::-3]).all()
+    # a 5 x 8 row-major matrix flipped upside down, left-right, and both, into a column-major destination
+    M, N = 5, 8
+    a = src.reshape(M, N)
+    for flip_rows, flip_cols in [(True, False), (False, True), (True, True)]:
+        sl = "(%d,%d):(%d,%d)" % (M, N, -N if flip_rows else N, -1 if flip_cols else 1)
+        origin = (M - 1) * N * flip_rows + (N - 1) * flip_cols
+        dst = np.zeros(M * N, np.uint32)
+        oracle.copy(src, sl, dst, "(%d,%d):(1,%d)" % (M, N, M), src_origin=origin)
+        want = a[::-1] if flip_rows else a
+        want = want[:, ::-1] if flip_cols else want
+        assert (dst.reshape(N, M).T == want).all(), sl
+    # numpy's own strided view with a negative stride as the destination
+    dst = np.zeros(40, np.uint32)
+    oracle.copy(src, "(5,8):(8,1)", dst, "(5,8):(-1,5)", dst_origin=4)
+    view = np.lib.stride_tricks.as_strided(dst[4:], shape=(5, 8), strides=(-4, 20))
+    assert (view == a).all()
+    lo = oracle.Layout("(5,8):(-1,5)")
+    assert (lo.min_offset, lo.cosize) == (-4, 36)

@@ -307,6 +307,58 @@ def test_aliasing_destinations_keep_the_last_write(oracle):
     assert lc.Plan("(4,4):(1,4)", "(4,4):(4,1)", "f32").workspace_bytes == 0
 
 
+def _check_signed(oracle, src_layout, dst_layout, dtype, seed=0):
+    """_check for layouts with negative strides: both buffers extend below offset 0."""
+    es = lc.DTYPE_BYTES[dtype]
+    sl, dl = oracle.Layout(src_layout), oracle.Layout(dst_layout)
+    so, do = -sl.min_offset, -dl.min_offset
+    rng = np.random.default_rng(seed)
+    src = rng.integers(0, 255, size=(so + sl.cosize) * es, dtype=np.uint8).view(_np_dtype(es))
+    want = np.full(do + dl.cosize, 0xA5A5A5A5A5A5A5A5 & ((1 << (8 * es)) - 1), dtype=_np_dtype(es))
+    got = want.copy()
+    oracle.copy(src, sl, want, dl, src_origin=so, dst_origin=do)
+    plan = lc.Plan(src_layout, dst_layout, dtype)
+    plan.debug_replay_on_host(src, got, so, do)
+    assert (got == want).all(), plan.describe()
+    return plan.describe()
+
+
+def test_negative_strides_are_planned_by_walking_modes_backwards(oracle):
+    # a joint mode of negative destination stride is walked backwards on both sides (Sec. 3.4.2: any order, the same on
+    # both sides): what is left has destination strides >= 0; negative source strides stay as true reversals
+    d = _check_signed(oracle, "4096:1", "4096:-1", "f32")
+    assert "reflected=1" in d and "dst_offset=-4095" in d and "class=direct" in d, d
+    d = _check_signed(oracle, "4096:-1", "4096:-1", "f32")                      # both reversed: a plain copy again, but of the
+    assert "reflected=1" in d and "joint=[(4096,1,1)]" in d and "width_bytes=4" in d, d   # memory BELOW two aligned pointers: its start is not aligned
+    d = _check_signed(oracle, "4096:-1", "4096:1", "bf16")                      # a true reversal: element by element
+    assert "reflected" not in d and "width_bytes=2" in d, d
+    d = _check_signed(oracle, "(64,48):(1,64)", "(64,48):(-48,1)", "f32")       # transpose with flipped rows: walking the rows
+    assert "reflected=1" in d and "(64,-1,48)" in d, d                          # backwards reverses the source's contiguous mode
+    d = _check_signed(oracle, "(64,48):(1,-64)", "(64,48):(48,1)", "f32")       # transpose reading the columns backwards
+    assert "class=transpose" in d, d
+    d = _check_signed(oracle, "(256,64,3):(1,256,-16384)", "(256,64,3):(64,1,16384)", "bf16")   # batch of transposes, batches reversed
+    assert "class=transpose" in d, d
+    d = _check_signed(oracle, "(256,64,3):(1,256,16384)", "(256,64,3):(64,1,-16384)", "bf16")   # the same seen from the destination
+    assert "class=transpose" in d and "reflected=1" in d, d
+    _check_signed(oracle, "(6,10):(10,-1)", "(4,15):(-15,1)", "f32")             # no common refinement: element-wise, signed
+    _check_signed(oracle, "(4,2,3):(1,4,8)", "(4,2,3):(1,0,-4)", "f32")          # an overwritten mode and a reversed one
+    _check_signed(oracle, "(4,4):(1,4)", "(4,4):(-1,3)", "b16")                  # aliasing with a negative stride: last writer
+    rng = np.random.default_rng(9)
+    for i in range(300):
+        r = int(rng.integers(1, 4))
+        ext = [int(x) for x in rng.integers(1, 9, r)]
+        def strides():
+            order = rng.permutation(r)
+            d, run = [0] * r, 1
+            for m in order:
+                d[m] = run * int(rng.choice([1, -1]))
+                run *= ext[m] * int(rng.choice([1, 1, 2]))
+            return d
+        s = "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, strides())))
+        t = "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, strides())))
+        _check_signed(oracle, s, t, ["f32", "bf16", "b8", "b64"][i % 4], seed=i)
+
+
 def test_alignment_limits_vector_width():
     wide = lc.Plan("4096:1", "4096:1", "f32").describe()
     narrow = lc.Plan("4096:1", "4096:1", "f32", src_align=4, dst_align=256).describe()
