@@ -306,6 +306,13 @@ lc_status_t lc_debug_replay_on_host(const lc_plan_t* plan, const void* src_host,
   if (!plan || !src_host || !dst_host) return LC_ERR_INVALID_ARG;
   return lc::replay_on_host(*plan, src_host, 0, src_elems, dst_host, 0, dst_elems, lds_conflicts);
 }
+// The LDS bank model the planner checks its slot layouts with (test instrumentation): extra cycles of one wavefront
+// instruction whose lane l accesses `access_bytes` bytes at byte_addr[l].
+int lc_debug_lds_conflicts(const uint32_t* byte_addr_64, int access_bytes, int is_write) {
+  bool active[64];
+  for (int l = 0; l < 64; ++l) active[l] = true;
+  return lc::lds_pass_conflicts(byte_addr_64, active, 64, access_bytes, is_write != 0);
+}
 // The same for layouts with negative strides: the buffers start src_origin / dst_origin elements before offset 0.
 lc_status_t lc_debug_replay_on_host_at(const lc_plan_t* plan, const void* src_buffer, int64_t src_elems, int64_t src_origin, void* dst_buffer,
                                        int64_t dst_elems, int64_t dst_origin, int64_t* lds_conflicts) {

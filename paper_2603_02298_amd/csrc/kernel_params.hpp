@@ -135,8 +135,10 @@ struct TransposeParams {
   uint32_t n_micro;                // micro-tiles per tile
   uint32_t n_vec;                  // vectors per tile = n_micro * V
   int32_t a_q;                     // source stride of one step along q (elements)
-  // LDS holds the tile's vectors at slot(g) = g ^ ((g >> swz_shift) & swz_mask), g = destination-order index
-  uint32_t swz_shift, swz_mask;
+  // LDS holds the tile's vectors at slot(g) = g ^ ((g >> swz_shift) & swz_mask) ^ ((g >> swz_shift2) & swz_mask2),
+  // g = destination-order index: an XOR layout over the bits of g (Sec. 2.3.2), bit b carrying f_(2^b), or
+  // f_(2^b + 2^(b - shift)) when a term's mask picks it up.  An unused term has mask 0.
+  uint32_t swz_shift, swz_mask, swz_shift2, swz_mask2;
   // tiles: the rest modes of zipped_divide; the tile id is their colexicographic index
   int32_t n_rest;
   FastDiv rdiv[kMaxModes];
@@ -155,7 +157,9 @@ struct TransposeParams {
   uint32_t cw_s[kMaxModes];        // coordinate step (packed) of one step of source-order micro mode k
   uint32_t cw_d[kMaxModes + 1];    // the same for the destination-order modes
 };
-LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t g) { return g ^ ((g >> P.swz_shift) & P.swz_mask); }
+LC_HD uint32_t lds_slot(const TransposeParams& P, uint32_t g) {
+  return g ^ ((g >> P.swz_shift) & P.swz_mask) ^ ((g >> P.swz_shift2) & P.swz_mask2);
+}
 // A loop over modes with a run-time trip count reads its parameters with one dependent scalar load
 // per trip, and every index decode costs three quarter-rate integer multiplies per mode and lane;
 // a chain of those ahead of the first global load costs microseconds per launch.  Hence the lane /

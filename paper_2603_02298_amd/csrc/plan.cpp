@@ -97,31 +97,49 @@ static int common_pow2(int cap, const std::vector<int64_t>& must_divide) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// LDS bank model used to pick the swizzle (and reported by the host replay): 64 banks of 4 bytes;
-// a wavefront access of b bytes per lane is served in passes of 256/b consecutive lanes; inside a
-// pass a bank serves one distinct dword address per cycle.  Cost = extra cycles.
+// LDS bank model (checks the swizzle; reported by the host replay).  Measured on gfx950 with SQ_LDS_BANK_CONFLICT on
+// address patterns made for the purpose (one wavefront, per instruction):
+//   width   write: lanes per pass, banks repeat every    read: lanes per pass, banks repeat every
+//   16 B    8 consecutive lanes,   128 bytes             16 lanes (*),          256 bytes
+//    8 B    16 consecutive lanes,  128 bytes             32 consecutive lanes,  256 bytes
+//    4 B    32 consecutive lanes,  128 bytes             32 consecutive lanes,  128 bytes
+//   (*) in each half of the wavefront the 4-lane groups 0,3,5,6 go together and so do 1,2,4,7 (equal parity of the
+//       group index's bits): lanes 0-3,12-15,20-27 and 4-11,16-19,28-31.
+// A pass takes as many cycles as the most loaded bank has distinct dwords; cost = cycles beyond one per pass.
 // ---------------------------------------------------------------------------------------------
-int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes) {
-  int per_pass = 256 / access_bytes;
-  if (per_pass > 64) per_pass = 64;
+static int lds_pass_of_lane(int lane, int access_bytes, bool is_write) {
+  if (is_write) return lane / (128 / std::max(4, std::min(16, access_bytes)));
+  if (access_bytes >= 16) {
+    const int group = (lane / 4) % 8;
+    const int parity = (group ^ (group >> 1) ^ (group >> 2)) & 1;
+    return (lane / 32) * 2 + parity;
+  }
+  return lane / 32;
+}
+int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes, bool is_write) {
   const int words = access_bytes >= 4 ? access_bytes / 4 : 1;
+  const uint32_t banks = (is_write || access_bytes <= 4) ? 32u : 64u;
   int cost = 0;
-  for (int base = 0; base < lanes; base += per_pass) {
+  for (int pass = 0; pass < 8; ++pass) {
     uint8_t cnt[64];
-    uint32_t first[64];
+    uint32_t seen[64][8];
     std::memset(cnt, 0, sizeof(cnt));
-    for (int l = base; l < base + per_pass && l < lanes; ++l) {
-      if (!active[l]) continue;
+    bool any = false;
+    for (int l = 0; l < lanes; ++l) {
+      if (!active[l] || lds_pass_of_lane(l, access_bytes, is_write) != pass) continue;
+      any = true;
       for (int w = 0; w < words; ++w) {
-        uint32_t dword = byte_addr[l] / 4 + (uint32_t)w;
-        int bank = (int)(dword & 63u);
-        if (cnt[bank] && first[bank] == dword) continue;   // same dword again: served by the same access
-        if (!cnt[bank]) first[bank] = dword;
+        const uint32_t dword = byte_addr[l] / 4 + (uint32_t)w, bank = dword % banks;
+        bool again = false;
+        for (int k = 0; k < cnt[bank] && k < 8; ++k) if (seen[bank][k] == dword) again = true;   // the same dword: one access
+        if (again) continue;
+        if (cnt[bank] < 8) seen[bank][cnt[bank]] = dword;
         cnt[bank]++;
       }
     }
+    if (!any) continue;
     int worst = 1;
-    for (int b = 0; b < 64; ++b) worst = std::max<int>(worst, cnt[b]);
+    for (uint32_t b = 0; b < banks; ++b) worst = std::max<int>(worst, cnt[b]);
     cost += worst - 1;
   }
   return cost;
@@ -145,7 +163,7 @@ int transpose_swizzle_cost(const TransposeParams& P, int V, int es, uint32_t max
     for (int ip = 0; ip < V && ip < max_ip; ++ip) {
       uint32_t wa[64];
       for (int l = 0; l < 64; ++l) wa[l] = lds_slot(P, g0[l] + (uint32_t)ip * P.gpos_pv) * (uint32_t)slot_bytes;
-      cost += lds_pass_conflicts(wa, act, lanes, slot_bytes);
+      cost += lds_pass_conflicts(wa, act, lanes, slot_bytes, true);
     }
   }
   uint32_t pick_waves = std::min<uint32_t>((P.n_vec + 63) / 64, max_waves);
@@ -157,7 +175,7 @@ int transpose_swizzle_cost(const TransposeParams& P, int V, int es, uint32_t max
       act[l] = g < P.n_vec;
       ra[l] = lds_slot(P, g) * (uint32_t)slot_bytes;
     }
-    cost += lds_pass_conflicts(ra, act, lanes, slot_bytes);
+    cost += lds_pass_conflicts(ra, act, lanes, slot_bytes, false);
   }
   return cost;
 }
@@ -507,23 +525,84 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     }
   }
   if (ok) {
-    // swizzle: XOR four higher bits of the slot index into its low four bits; pick the source bits
-    // that minimise the modelled bank conflicts of the parking writes (picks stay contiguous)
-    // (the search looks at the first wavefront only; describe() reports the model over the whole tile)
-    int best_shift = -1, best_cost = 0;
-    P.swz_shift = 0; P.swz_mask = 0;
-    best_cost = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
-    if (tune.swizzle_shift == -2) {
-      for (int sh = 4; best_cost > 0 && sh <= 12 && (P.n_vec >> sh) > 0; ++sh) {
-        P.swz_shift = (uint32_t)sh; P.swz_mask = 15;
-        int c = transpose_swizzle_cost(P, V, es, 1, 2, std::min(64, 2 * 256 / (V * es)));
-        if (c < best_cost) { best_cost = c; best_shift = sh; }
+    // a10: where the tile's vectors lie in LDS.  Vector g (destination order) goes to slot g ^ swz(g): an XOR layout over
+    // the bits of g (Sec. 2.3.2).  Picks read consecutive g and are conflict-free for any swz that only folds higher bits
+    // into the low ones.  Parks: a write pass is nb = log2(128 / slot bytes) consecutive lanes (128 bytes of banks), so the
+    // slots' low nb bits have to take every value over the lanes' low nb bits.  With power-of-two extents the park
+    // layout lane -> g moves lane bit i to one bit pi(i) of g: a bit that lands below nb already selects a bank bit; every
+    // other one is folded onto a bank bit that is still free, i.e. bit pi(i) of g gets the stride f_(2^pi(i) + 2^k) in
+    // place of f_(2^pi(i)).  Folds with the same distance pi(i) - k make one shift-and-mask term; the kernels evaluate two.
+    // Other shapes (or more terms) fall back to a search over single shifts against the bank model, which in every case
+    // has the last word: the derived layout is kept only if the model finds no conflict.
+    const int slot_bytes = V * es;
+    int nb = 0;
+    while ((128 >> (nb + 1)) >= std::max(4, std::min(16, slot_bytes))) ++nb;   // lanes per write pass = 2^nb
+    P.swz_shift = P.swz_mask = P.swz_shift2 = P.swz_mask2 = 0;
+    bool derived = false;
+    if (tune.swizzle_shift == -2 && P.n_micro >= (1u << nb)) {
+      uint32_t free_bits = (1u << nb) - 1u;
+      int fold_from[8], n_fold = 0;
+      bool linear = true;
+      for (int i = 0; i < nb && linear; ++i) {
+        int32_t so;
+        uint32_t g = 0, g_zero = 0;
+        micro_from_src_order(P, 1u << i, &so, &g);
+        micro_from_src_order(P, 0, &so, &g_zero);
+        g -= g_zero;
+        if (g == 0 || (g & (g - 1)) != 0) { linear = false; break; }   // the lane bit does not move exactly one bit of g
+        int b = 0;
+        while ((1u << b) != g) ++b;
+        if (b < nb) free_bits &= ~(1u << b);
+        else fold_from[n_fold++] = b;
       }
-    } else if (tune.swizzle_shift >= 4) {
-      best_shift = tune.swizzle_shift;
+      // and the lanes of a pass really are those bits' span: lane = sum of its bits without carries (power-of-two extents)
+      for (int i = 0; i < nb && linear; ++i)
+        for (int j = i + 1; j < nb && linear; ++j) {
+          int32_t so;
+          uint32_t gi = 0, gj = 0, gij = 0;
+          micro_from_src_order(P, 1u << i, &so, &gi);
+          micro_from_src_order(P, 1u << j, &so, &gj);
+          micro_from_src_order(P, (1u << i) | (1u << j), &so, &gij);
+          if (gij != gi + gj) linear = false;
+        }
+      if (linear) {
+        uint32_t shift_of[2] = {0, 0}, mask_of[2] = {0, 0};
+        int terms = 0;
+        bool fits = true;
+        for (int f = 0; f < n_fold && fits; ++f) {
+          int k = 0;
+          while (!(free_bits & (1u << k))) ++k;                          // lowest bank bit still free
+          free_bits &= ~(1u << k);
+          const uint32_t dist = (uint32_t)(fold_from[f] - k);
+          int t = 0;
+          while (t < terms && shift_of[t] != dist) ++t;
+          if (t == terms) { if (terms == 2) { fits = false; break; } shift_of[terms++] = dist; }
+          mask_of[t] |= 1u << k;
+        }
+        if (fits) {
+          P.swz_shift = shift_of[0]; P.swz_mask = mask_of[0];
+          P.swz_shift2 = shift_of[1]; P.swz_mask2 = mask_of[1];
+          derived = transpose_swizzle_cost(P, V, es, 1u << 20, 64) == 0;
+          if (!derived) P.swz_shift = P.swz_mask = P.swz_shift2 = P.swz_mask2 = 0;
+        }
+      }
     }
-    if (best_shift >= 4) { P.swz_shift = (uint32_t)best_shift; P.swz_mask = 15; }
-    else { P.swz_shift = 0; P.swz_mask = 0; }
+    if (!derived) {
+      int best_shift = -1;
+      int best_cost = transpose_swizzle_cost(P, V, es, 4, 64);
+      if (tune.swizzle_shift == -2) {
+        for (int sh = 3; best_cost > 0 && sh <= 12 && (P.n_vec >> sh) > 0; ++sh) {
+          P.swz_shift = (uint32_t)sh; P.swz_mask = 15;
+          int c = transpose_swizzle_cost(P, V, es, 4, 64);
+          if (c < best_cost) { best_cost = c; best_shift = sh; }
+        }
+      } else if (tune.swizzle_shift >= 3) {
+        best_shift = tune.swizzle_shift;
+      }
+      if (best_shift >= 3) { P.swz_shift = (uint32_t)best_shift; P.swz_mask = 15; }
+      else { P.swz_shift = 0; P.swz_mask = 0; }
+    }
+    plan->swizzle_derived = derived;
     plan->cls = KernelClass::Transpose;
     plan->V = V;
     plan->width_bytes = V * es;
@@ -921,6 +1000,22 @@ std::string describe(const lc_plan& plan) {
     s += " micro_tiles=" + std::to_string(plan.transpose.n_micro) + " per_lane=" + std::to_string(plan.micro_per_thread);
     s += " tiles=" + std::to_string(plan.transpose.n_tiles) + " lds_bytes=" + std::to_string(plan.lds_bytes);
     s += " swizzle_shift=" + std::to_string(plan.transpose.swz_mask ? (int)plan.transpose.swz_shift : -1);
+    s += std::string(" swizzle=") + (plan.swizzle_derived ? "derived" : plan.transpose.swz_mask ? "searched" : "none");
+    {
+      // the slot function as a layout with XOR strides over the bits of g (Sec. 2.3.2)
+      int bits = 0;
+      while ((1u << bits) < plan.transpose.n_vec) ++bits;
+      std::string shape, stride;
+      const TransposeParams& T = plan.transpose;
+      for (int b = 0; b < std::max(bits, 1); ++b) {
+        uint32_t d = 1u << b;
+        if (b >= (int)T.swz_shift && ((T.swz_mask >> (b - (int)T.swz_shift)) & 1u)) d ^= 1u << (b - (int)T.swz_shift);
+        if (b >= (int)T.swz_shift2 && ((T.swz_mask2 >> (b - (int)T.swz_shift2)) & 1u)) d ^= 1u << (b - (int)T.swz_shift2);
+        shape += (b ? ",2" : "2");
+        stride += (b ? ",f" : "f") + std::to_string(d);
+      }
+      s += " lds_layout=(" + shape + "):(" + stride + ")";
+    }
     s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.tile_elem_bytes, 1u << 20, 64));
     s += " lane_split=" + std::to_string(plan.transpose.src_split) + "/" + std::to_string(plan.transpose.dst_split);
     s += " ragged_modes=" + std::to_string(plan.transpose.n_ragged);

@@ -72,6 +72,7 @@ struct lc_plan {
   int p_mode = -1, q_mode = -1;
   lc::TransposeParams transpose{};
   unsigned lds_bytes = 0;
+  bool swizzle_derived = false;            // the LDS slot layout came out of the park layout's bits (else: searched against the bank model)
   int64_t src_run_bytes = 0, dst_run_bytes = 0;
 
   // Generic and LastWriter (both evaluate the two coalesced layouts per element)
@@ -109,6 +110,9 @@ bool layout_is_injective(const Modes& coalesced, int64_t n);
 // that belong to the buffers (lo <= 0 < hi).
 lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo, int64_t src_hi, void* dst, int64_t dst_lo,
                            int64_t dst_hi, int64_t* lds_conflicts);
+
+// The LDS bank model (plan.cpp): extra cycles of one wavefront instruction whose active lane l accesses access_bytes at byte_addr[l].
+int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes, bool is_write);
 
 // Defined with the kernels: enqueue the plan's kernel on a HIP stream / time repeated executions.
 const char* last_hip_error();

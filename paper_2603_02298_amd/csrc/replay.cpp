@@ -8,7 +8,6 @@
 
 namespace lc {
 
-int lds_pass_conflicts(const uint32_t* byte_addr, const bool* active, int lanes, int access_bytes);
 
 namespace {
 struct Buffers {
@@ -126,7 +125,7 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo,
           for (int ip = 0; ip < V; ++ip) {
             uint32_t wa[64];
             for (int l = 0; l < 64; ++l) wa[l] = lds_slot(P, g0[l] + (uint32_t)ip * P.gpos_pv) * (uint32_t)slot;
-            *lds_conflicts += lds_pass_conflicts(wa, act, 64, slot);
+            *lds_conflicts += lds_pass_conflicts(wa, act, 64, slot, true);
           }
         }
         for (uint32_t wave = 0; wave * 64 < lanes * (uint32_t)V; ++wave) {
@@ -137,7 +136,7 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo,
             act[l] = g < P.n_vec;
             ra[l] = lds_slot(P, g) * (uint32_t)slot;
           }
-          *lds_conflicts += lds_pass_conflicts(ra, act, 64, slot);
+          *lds_conflicts += lds_pass_conflicts(ra, act, 64, slot, false);
         }
       }
     }
