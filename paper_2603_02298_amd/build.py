@@ -19,10 +19,15 @@ def _hipcc():
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
+# kernels.hip: the leading scalar kernel arguments (up to 14 dwords) are preloaded into scalar registers at wavefront
+# start where the firmware supports it; the compiler keeps a prologue that loads them for firmware that does not
+EXTRA_FLAGS = {"kernels.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
+
+
 def compile_command(source):
     return [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
             # packed-FP32 instruction selection is switched off for all device code
-            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + EXTRA_FLAGS.get(source, []) + [
             "-c", os.path.join(CSRC, source), "-o", os.path.join(OBJ_DIR, source + ".o")]
 
 

@@ -270,6 +270,37 @@ LC_HD int32_t vector_lane_part(const TransposeParams& P, uint32_t lane) {
   }
   return d;
 }
+// What the first loads of a launch need, in fourteen dwords.  They travel as the kernel's leading scalar arguments (the
+// source pointer and the twelve dwords below), which the hardware can place in scalar registers when a wavefront starts
+// (kernel-argument preload); a wavefront then issues the loads of its first tile before the rest of the argument block has
+// arrived from memory, about half a microsecond earlier per launch.  Covers plans whose lanes own one micro-tile, whose
+// lane index decodes by shifts (the lane / trip split above) over at most four modes, and whose grid of tiles has at most
+// two modes; every other plan leaves `ctl` at 0 and starts through the argument block.
+struct TransposeHead {
+  uint32_t ctl;        // bit 0: valid; bits 1..16: four 4-bit counts, the bits of the lane index each source-order mode takes
+                       // (the last mode in use takes 8: all that is left); bits 17..21: shift of the division below;
+                       // bits 22..30: micro-tiles per tile (lanes at or past it load nothing)
+  int32_t a_q;         // source stride of one step along q (elements)
+  int32_t sa[4];       // source strides of the lane's modes (elements)
+  uint32_t r0_mul, r0_div;   // the first rest mode's extent as a multiply-shift division
+  int64_t ra0, ra1;    // source strides of the two rest modes (elements)
+};
+constexpr int kHeadMaxGrid = 8192;   // largest grid whose first tiles the planner has compared with the argument block's decode
+LC_HD int32_t head_lane_offset(const TransposeHead& H, uint32_t lane) {
+  int32_t s = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t bits = (H.ctl >> (1 + 4 * k)) & 15u;
+    s += (int32_t)(lane & ((1u << bits) - 1u)) * H.sa[k];
+    lane >>= bits;
+  }
+  return s;
+}
+LC_HD uint32_t head_n_micro(const TransposeHead& H) { return (H.ctl >> 22) & 511u; }
+LC_HD int64_t head_tile_origin(const TransposeHead& H, uint32_t tile) {
+  const uint32_t q = (mulhi_u32(tile, H.r0_mul) + tile) >> ((H.ctl >> 17) & 31u);
+  return (int64_t)(tile - q * H.r0_div) * H.ra0 + (int64_t)q * H.ra1;
+}
 // tile id -> offsets of the tile's origin (slicing the rest mode: the coordinate is folded into the accessor, Sec. 2.5.1)
 LC_HD void tile_origin(const TransposeParams& P, uint32_t tile, int64_t* so, int64_t* dof) {
   int64_t s = 0, d = 0;

@@ -200,15 +200,43 @@ __device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
 // no per-lane predicates.  Its body is straight-line code on purpose: the loads of the next tile are
 // issued before the stores of the current one, and with no branch between them the wait before
 // parking can count the stores out (memory operations retire in issue order) instead of draining them.
-template <int ES, int V, int MT, int NT, bool FULL>
-__global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, const unsigned char* __restrict__ src,
+//
+// The leading scalar arguments (the source pointer and the twelve dwords of a TransposeHead) are all the first loads need;
+// they are the arguments the hardware may preload into scalar registers at wavefront start.  With h_ctl's valid bit set a
+// workgroup issues the loads of its first tile (tile id = workgroup index) from them alone, before the argument block is
+// touched; the lane state from the block is worked out while those loads are in flight.
+// DYN: tiles past the first rounds come from the queue (FULL tiles only); without it the queue's code is not in the kernel.
+template <int ES, int V, int MT, int NT, bool FULL, bool DYN>
+__global__ __launch_bounds__(kBlock) void transpose_kernel(const unsigned char* __restrict__ src, uint32_t h_ctl, int32_t h_aq, int32_t h_sa0,
+                                                          int32_t h_sa1, int32_t h_sa2, int32_t h_sa3, uint32_t h_mul, uint32_t h_div,
+                                                          int64_t h_ra0, int64_t h_ra1, TransposeParams P,
                                                           unsigned char* __restrict__ dst, unsigned int* queue, uint32_t tile_bytes, uint32_t grab,
                                                           uint32_t static_rounds, uint32_t n_counters, uint32_t leftover_lead) {
   constexpr int DW = V * ES / 4;                 // dwords per vector
   constexpr int SLOT = V * ES;                   // bytes per vector
   typedef typename Word<SLOT>::type Vec;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  touch_kernel_arguments<(int)sizeof(TransposeParams)>();
+  uint32_t r[MT][V][DW];
+  bool early = false;
+  if constexpr (MT == 1) {
+    if (h_ctl & 1u) {
+      early = true;
+      const TransposeHead H{h_ctl, h_aq, {h_sa0, h_sa1, h_sa2, h_sa3}, h_mul, h_div, h_ra0, h_ra1};
+      const int64_t in_tile = head_lane_offset(H, threadIdx.x);
+      const unsigned char* base = src + (head_tile_origin(H, blockIdx.x) + in_tile) * ES;
+      if (FULL || threadIdx.x < head_n_micro(H)) {
+#pragma unroll
+        for (int iq = 0; iq < V; ++iq) {
+          Vec v = gload<NT>(reinterpret_cast<const Vec*>(base + (int64_t)iq * h_aq * ES));
+          const uint32_t* w = reinterpret_cast<const uint32_t*>(&v);
+#pragma unroll
+          for (int k = 0; k < DW; ++k) r[0][iq][k] = w[k];
+        }
+      }
+      asm volatile("" ::: "memory");   // counts as a possible store: the loads stay ahead of everything below
+    }
+  }
+  touch_kernel_arguments<(int)sizeof(TransposeParams) + 64>();
 
   // tile-invariant lane state (wavefront-level index arithmetic done once):
   // per owned micro-tile its source offset and LDS base index; per picked vector its destination offset
@@ -236,7 +264,6 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
     for (int m = 0; m < MT; ++m)
       if (act[m]) micro_from_src_order(P, threadIdx.x + (uint32_t)m * kBlock, &src_in[m], &park_g[m]);
   }
-  uint32_t r[MT][V][DW];
   // global -> registers: V vectors along p per micro-tile, one per step along q
   auto load_tile = [&](int64_t so) {
     const unsigned char* base = src + so * ES;
@@ -302,7 +329,7 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
   // given this block.
   // leftover_lead > 0 (fixed order only): the tiles that are left after the last whole round of the grid go to the first
   // leftover_lead workgroups alone, round after round (the workgroups a CU is given first run ahead of the later ones).
-  const bool dynamic = queue != nullptr;
+  constexpr bool dynamic = DYN;
   const uint32_t G = gridDim.x;
   volatile uint32_t* handed_out = reinterpret_cast<volatile uint32_t*>(lds + tile_bytes);
   uint32_t asked = 0;
@@ -329,7 +356,7 @@ __global__ __launch_bounds__(kBlock) void transpose_kernel(TransposeParams P, co
   if (ask && threadIdx.x == 0) asked = atomicAdd(counter, grab);
   int64_t so, dof;
   tile_origin(P, tile, &so, &dof);
-  load_tile(so);
+  if (!early) load_tile(so);
   // The destination side of the lane state is worked out while the first loads are in flight.  The
   // empty statement below counts as a possible store, so the compiler cannot sink the loads past it.
   asm volatile("" ::: "memory");
@@ -584,7 +611,7 @@ static PreLaunch launch_transpose_f(const lc_plan& plan, const void* src, void* 
   PreLaunch pre;
   unsigned int* queue = nullptr;
   unsigned lds_bytes = plan.lds_bytes;
-  if (plan.tile_queue && grid < plan.transpose.n_tiles) {
+  if (FULL && plan.tile_queue && grid < plan.transpose.n_tiles) {
     pre.status = tile_queue_of_stream(s, &queue, &pre.call);
     if (pre.status != hipSuccess) return pre;
     if (queue) lds_bytes += 16;   // the word that carries the next tile to the other lanes
@@ -593,8 +620,11 @@ static PreLaunch launch_transpose_f(const lc_plan& plan, const void* src, void* 
     static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
     if (!raised.load(std::memory_order_acquire)) {
       pre.call = "hipFuncSetAttribute";
-      pre.status = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT, FULL>),
+      pre.status = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT, FULL, false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (pre.status == hipSuccess && FULL)
+        pre.status = hipFuncSetAttribute(reinterpret_cast<const void*>(&transpose_kernel<ES, V, MT, NT, FULL, FULL>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (pre.status != hipSuccess) return pre;
       raised.store(true, std::memory_order_release);
     }
@@ -602,9 +632,17 @@ static PreLaunch launch_transpose_f(const lc_plan& plan, const void* src, void* 
   const uint32_t counters = (uint32_t)std::max(1, std::min(plan.queue_counters, kQueueLines - 1));
   // whole rounds of the grid that go by index before the queue takes over (at least one, never past the last whole round)
   const uint32_t rounds = (uint32_t)std::max<int64_t>(1, std::min<int64_t>(plan.queue_static_rounds, plan.transpose.n_tiles / grid));
-  hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL>), dim3(grid), dim3(kBlock), lds_bytes, s, plan.transpose, sp, dp, queue,
-                     plan.lds_bytes, (uint32_t)std::max(1, plan.tile_queue), rounds, counters,
-                     (uint32_t)std::min<int64_t>(std::max(0, plan.leftover_lead), grid));
+  // the head serves launches in the fixed tile order, where a workgroup's first tile is its index (a request to the queue
+  // would have to go out ahead of the first loads), on grids whose first tiles the planner has checked
+  TransposeHead h = plan.head;
+  if (queue || MT != 1 || grid > (unsigned)kHeadMaxGrid || grid > plan.transpose.n_tiles) h.ctl = 0;
+  const uint32_t grab = (uint32_t)std::max(1, plan.tile_queue), lead = (uint32_t)std::min<int64_t>(std::max(0, plan.leftover_lead), grid);
+  if (FULL && queue)
+    hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL, FULL>), dim3(grid), dim3(kBlock), lds_bytes, s, sp, h.ctl, h.a_q, h.sa[0], h.sa[1],
+                       h.sa[2], h.sa[3], h.r0_mul, h.r0_div, h.ra0, h.ra1, plan.transpose, dp, queue, plan.lds_bytes, grab, rounds, counters, lead);
+  else
+    hipLaunchKernelGGL((transpose_kernel<ES, V, MT, NT, FULL, false>), dim3(grid), dim3(kBlock), lds_bytes, s, sp, h.ctl, h.a_q, h.sa[0], h.sa[1],
+                       h.sa[2], h.sa[3], h.r0_mul, h.r0_div, h.ra0, h.ra1, plan.transpose, dp, queue, plan.lds_bytes, grab, rounds, counters, lead);
   return pre;
 }
 template <int ES, int V, int MT, int NT>

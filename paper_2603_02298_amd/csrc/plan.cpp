@@ -27,6 +27,7 @@ Tuning tuning_from_env() {
   t.queue_counters = env_int("LC_TUNE_QUEUE_COUNTERS", t.queue_counters);
   t.leftover_lead = env_int("LC_TUNE_LEFTOVER_LEAD", t.leftover_lead);
   t.grid = env_int("LC_TUNE_GRID", t.grid);
+  t.early_loads = env_int("LC_TUNE_EARLY_LOADS", t.early_loads);
   t.max_items = env_int("LC_TUNE_MAX_ITEMS", (int)t.max_items);
   if (const char* v = std::getenv("LC_TUNE_TILE")) {
     for (const char* p = v; *p;) {
@@ -252,6 +253,50 @@ static bool transpose_instantiated(int es, int V) {
 // the ragged kernel also moves single elements (V = 1) of any width
 static bool ragged_instantiated(int es, int V) {
   return transpose_instantiated(es, V) || (V == 1 && (es == 1 || es == 2 || es == 4 || es == 8 || es == 16));
+}
+
+// The fourteen dwords the first loads of a launch can be computed from (TransposeHead), when the plan fits them.
+static void fill_transpose_head(const TransposeParams& P, int micro_per_thread, TransposeHead* H) {
+  std::memset(H, 0, sizeof(*H));
+  if (micro_per_thread != 1 || P.n_ragged != 0 || P.blocked || P.src_split < 1 || P.src_split > 4 || P.n_rest > 2 || P.n_micro > (uint32_t)kBlock)
+    return;
+  uint32_t ctl = 1u, taken = 0;
+  for (int k = 0; k < P.src_split; ++k) {
+    // modes below the last one the lane reaches have extents that divide kBlock (powers of two); the last takes what is left
+    uint32_t bits = 8;
+    if (k + 1 < P.src_split) {
+      bits = 0;
+      while ((1u << bits) < P.ext_s[k].div) ++bits;
+      if ((1u << bits) != P.ext_s[k].div) return;
+    }
+    ctl |= bits << (1 + 4 * k);
+    taken += bits;
+    H->sa[k] = P.sa_s[k];
+  }
+  if (taken < 8) return;
+  // tile id -> (r, q) by the first rest mode; a grid of one mode (or a single tile) divides by more than any tile id
+  const FastDiv d = P.n_rest == 2 ? P.rdiv[0] : make_fastdiv(0x7fffffffu);
+  H->r0_mul = d.mul;
+  H->r0_div = d.div;
+  ctl |= (d.shift & 31u) << 17;
+  ctl |= P.n_micro << 22;
+  H->ra0 = P.n_rest >= 1 ? P.ra[0] : 0;
+  H->ra1 = P.n_rest == 2 ? P.ra[1] : 0;
+  H->a_q = P.a_q;
+  H->ctl = ctl;
+  // the head must say what the argument block says: every lane's offset and every tile's origin
+  for (uint32_t lane = 0; lane < (uint32_t)kBlock; ++lane) {
+    int32_t so;
+    uint32_t g0;
+    micro_lane_part(P, lane, &so, &g0);
+    if (lane < P.n_micro && head_lane_offset(*H, lane) != so + P.src_trip_off[0]) { H->ctl = 0; return; }
+  }
+  // (a workgroup's first tile is its index in the grid: the launcher uses the head only for grids within kHeadMaxGrid)
+  for (uint32_t t = 0; t < std::min<uint32_t>(P.n_tiles, (uint32_t)kHeadMaxGrid); ++t) {
+    int64_t so, dof;
+    tile_origin(P, t, &so, &dof);
+    if (head_tile_origin(*H, t) != so) { H->ctl = 0; return; }
+  }
 }
 
 // Tiles a copy over joint modes J (extents and strides in units of `es` bytes) for the transposing
@@ -640,6 +685,7 @@ static bool plan_tiled(const std::vector<JointMode>& J, int es, int V, int p, in
     plan->leftover_lead = tune.leftover_lead >= 0 ? tune.leftover_lead : 0;
     plan->src_align = (unsigned)(V * es);
     plan->dst_align = (unsigned)(V * es);
+    if (tune.early_loads != 0) fill_transpose_head(P, plan->micro_per_thread, &plan->head);
     return true;
   }
   return false;
@@ -1019,6 +1065,7 @@ std::string describe(const lc_plan& plan) {
     s += " modelled_lds_conflicts=" + std::to_string(transpose_swizzle_cost(plan.transpose, plan.V, plan.tile_elem_bytes, 1u << 20, 64));
     s += " lane_split=" + std::to_string(plan.transpose.src_split) + "/" + std::to_string(plan.transpose.dst_split);
     s += " ragged_modes=" + std::to_string(plan.transpose.n_ragged);
+    s += " early_loads=" + std::to_string(plan.head.ctl & 1u);
     s += " src_run_bytes=" + std::to_string(plan.src_run_bytes) + " dst_run_bytes=" + std::to_string(plan.dst_run_bytes);
   } else if (plan.cls == KernelClass::Direct) {
     s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);

@@ -34,6 +34,7 @@ struct Tuning {
   int queue_counters = -1;     // transpose: counters the requests are spread over (1..15)
   int grid = -1;               // workgroups of the launch (overrides CUs * wgs_per_cu)
   int leftover_lead = -1;      // transpose, fixed order: the tiles left after the last whole round go to this many leading workgroups
+  int early_loads = -1;        // transpose: 0 = the first loads wait for the whole argument block (no TransposeHead)
 };
 Tuning tuning_from_env();
 
@@ -71,6 +72,7 @@ struct lc_plan {
   std::vector<int64_t> tile_extent;        // per joint mode
   int p_mode = -1, q_mode = -1;
   lc::TransposeParams transpose{};
+  lc::TransposeHead head{};                // what the first loads need, for the kernel's leading arguments (ctl = 0: not in use)
   unsigned lds_bytes = 0;
   bool swizzle_derived = false;            // the LDS slot layout came out of the park layout's bits (else: searched against the bank model)
   int64_t src_run_bytes = 0, dst_run_bytes = 0;

@@ -1,6 +1,7 @@
 // Host replay of a plan: the same index arithmetic as the kernels (kernel_params.hpp), executed
 // lane by lane on host memory, with every access checked against the buffer sizes.  A checking
 // device for plans; never part of executing a copy.
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
@@ -63,6 +64,22 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo,
     const int V = plan.V, slot = V * es;
     std::vector<unsigned char> lds((size_t)plan.lds_bytes);
     const uint32_t lanes = (uint32_t)kBlock * (uint32_t)plan.micro_per_thread;
+    if (plan.head.ctl & 1u) {
+      // the first loads of a workgroup are addressed from the head alone: it has to agree with the argument block for every
+      // lane and for every tile id a workgroup can start on
+      if (plan.micro_per_thread != 1 || head_n_micro(plan.head) != P.n_micro || plan.head.a_q != P.a_q || P.src_split < 1) return LC_ERR_INVALID_ARG;
+      for (uint32_t lane = 0; lane < P.n_micro; ++lane) {
+        int32_t so;
+        uint32_t g0;
+        micro_lane_part(P, lane, &so, &g0);
+        if (head_lane_offset(plan.head, lane) != so + P.src_trip_off[0]) return LC_ERR_INVALID_ARG;
+      }
+      for (uint32_t tile = 0; tile < std::min<uint32_t>(P.n_tiles, (uint32_t)kHeadMaxGrid); ++tile) {
+        int64_t so, dof;
+        tile_origin(P, tile, &so, &dof);
+        if (head_tile_origin(plan.head, tile) != so) return LC_ERR_INVALID_ARG;
+      }
+    }
     for (uint32_t tile = 0; tile < P.n_tiles && B.ok; ++tile) {
       int64_t sbase, dbase;
       uint32_t rem0 = 0x10000u, rem1 = 0x10000u;
