@@ -98,21 +98,22 @@ __global__ __launch_bounds__(kBlock) void last_writer_move_kernel(GenericParams 
 // U items are in flight per lane; an optional looped mode re-uses a loaded value when its source
 // stride is zero (broadcast).
 // ---------------------------------------------------------------------------------------------
-template <int W, int U, int NT>
-__global__ __launch_bounds__(kBlock) void direct_kernel(DirectParams P, const typename Word<W>::type* __restrict__ src,
-                                                       typename Word<W>::type* __restrict__ dst) {
+// item -> offsets through `offsets(item, &so, &dof)`; everything else by value
+template <int W, int U, int NT, class Offsets>
+__device__ __forceinline__ void direct_body(const typename Word<W>::type* __restrict__ src, typename Word<W>::type* __restrict__ dst,
+                                            uint32_t n_items, bool blocked, uint32_t loop_extent, int64_t loop_sa, int64_t loop_sb,
+                                            Offsets offsets) {
   typedef typename Word<W>::type T;
-  touch_kernel_arguments<(int)sizeof(DirectParams)>();
   // strided: lane items are `step` apart and the whole grid sweeps memory together;
   // blocked: a workgroup owns the contiguous range [first, last) and sweeps it kBlock items at a time
-  uint32_t step = gridDim.x * kBlock, first = blockIdx.x * kBlock, last = P.n_items;
-  if (P.blocked) {
-    uint32_t chunk = (P.n_items + gridDim.x - 1) / gridDim.x;
+  uint32_t step = gridDim.x * kBlock, first = blockIdx.x * kBlock, last = n_items;
+  if (blocked) {
+    uint32_t chunk = (n_items + gridDim.x - 1) / gridDim.x;
     chunk = (chunk + kBlock * U - 1) / (kBlock * U) * (kBlock * U);
     step = kBlock;
     first = blockIdx.x * chunk;
-    last = min(P.n_items, first + chunk);
-    if (blockIdx.x * (uint64_t)chunk >= P.n_items) return;
+    last = min(n_items, first + chunk);
+    if (blockIdx.x * (uint64_t)chunk >= n_items) return;
   }
   for (uint32_t base = first + threadIdx.x; base < last; base += step * U) {
     int64_t so[U], dof[U];
@@ -123,29 +124,47 @@ __global__ __launch_bounds__(kBlock) void direct_kernel(DirectParams P, const ty
       uint32_t it = base + (uint32_t)j * step;
       ok[j] = it < last;
       so[j] = dof[j] = 0;
-      if (ok[j]) direct_offsets(P, it, &so[j], &dof[j]);
+      if (ok[j]) offsets(it, &so[j], &dof[j]);
     }
-    if (P.loop_extent == 1) {
+    if (loop_extent == 1) {
 #pragma unroll
       for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j]);
 #pragma unroll
       for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j], v[j]);
-    } else if (P.loop_sa == 0) {
+    } else if (loop_sa == 0) {
 #pragma unroll
       for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j]);
-      for (uint32_t r = 0; r < P.loop_extent; ++r) {
+      for (uint32_t r = 0; r < loop_extent; ++r) {
 #pragma unroll
-        for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j] + (int64_t)r * P.loop_sb, v[j]);
+        for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j] + (int64_t)r * loop_sb, v[j]);
       }
     } else {
-      for (uint32_t r = 0; r < P.loop_extent; ++r) {
+      for (uint32_t r = 0; r < loop_extent; ++r) {
 #pragma unroll
-        for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j] + (int64_t)r * P.loop_sa);
+        for (int j = 0; j < U; ++j) if (ok[j]) v[j] = gload<NT>(src + so[j] + (int64_t)r * loop_sa);
 #pragma unroll
-        for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j] + (int64_t)r * P.loop_sb, v[j]);
+        for (int j = 0; j < U; ++j) if (ok[j]) gstore<NT>(dst + dof[j] + (int64_t)r * loop_sb, v[j]);
       }
     }
   }
+}
+
+// The leading scalar arguments (fourteen dwords, preloaded into scalar registers where the hardware does it) describe a
+// copy over ONE joint mode completely (a plain copy, a strided gather or scatter, a broadcast): with h_ctl's bit 0 set the
+// kernel never reads the argument block and its first loads wait for no memory.  h_ctl: bit 0 valid, bit 1 blocked,
+// bits 2.. the looped mode's extent.
+template <int W, int U, int NT>
+__global__ __launch_bounds__(kBlock) void direct_kernel(const typename Word<W>::type* __restrict__ src, typename Word<W>::type* __restrict__ dst,
+                                                       uint32_t h_ctl, uint32_t h_items, int64_t h_sa, int64_t h_sb, int64_t h_loop_sa,
+                                                       int64_t h_loop_sb, DirectParams P) {
+  if (h_ctl & 1u) {
+    direct_body<W, U, NT>(src, dst, h_items, (h_ctl & 2u) != 0, h_ctl >> 2, h_loop_sa, h_loop_sb,
+                          [&](uint32_t item, int64_t* so, int64_t* dof) { *so = (int64_t)item * h_sa; *dof = (int64_t)item * h_sb; });
+    return;
+  }
+  touch_kernel_arguments<(int)sizeof(DirectParams) + 64>();
+  direct_body<W, U, NT>(src, dst, P.n_items, P.blocked != 0, P.loop_extent, P.loop_sa, P.loop_sb,
+                        [&](uint32_t item, int64_t* so, int64_t* dof) { direct_offsets(P, item, so, dof); });
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -539,11 +558,17 @@ static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, uns
   typedef typename Word<W>::type T;
   const T* sp = static_cast<const T*>(src);
   T* dp = static_cast<T*>(dst);
+  // a copy over one joint mode travels whole in the leading arguments (see direct_kernel)
+  const DirectParams& P = plan.direct;
+  uint32_t ctl = 0;
+  if (plan.early_loads && P.n_modes == 1 && P.loop_extent < (1u << 30)) ctl = 1u | (P.blocked ? 2u : 0u) | (P.loop_extent << 2);
+  const uint32_t items = P.n_items;
+  const int64_t sa = P.sa[0], sb = P.sb[0], lsa = P.loop_sa, lsb = P.loop_sb;
   switch (plan.nontemporal) {
-    case 0: hipLaunchKernelGGL((direct_kernel<W, U, 0>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
-    case 1: hipLaunchKernelGGL((direct_kernel<W, U, 1>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
-    case 2: hipLaunchKernelGGL((direct_kernel<W, U, 2>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
-    default: hipLaunchKernelGGL((direct_kernel<W, U, 3>), dim3(grid), dim3(kBlock), 0, s, plan.direct, sp, dp); break;
+    case 0: hipLaunchKernelGGL((direct_kernel<W, U, 0>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
+    case 1: hipLaunchKernelGGL((direct_kernel<W, U, 1>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
+    case 2: hipLaunchKernelGGL((direct_kernel<W, U, 2>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
+    default: hipLaunchKernelGGL((direct_kernel<W, U, 3>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
   }
 }
 template <int W>

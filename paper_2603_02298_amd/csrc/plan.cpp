@@ -746,6 +746,7 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   plan->dst_align = std::min(dst_align, 256u);
   plan->nontemporal = tune.nontemporal >= 0 ? (tune.nontemporal & 3) : 1;   // stores: decided per class below
   plan->grid_override = tune.grid > 0 ? tune.grid : 0;
+  plan->early_loads = tune.early_loads != 0;
 
   // a2: both layouts as functions of the integral coordinate (Sec. 3.2)
   Modes S = coalesce_modes(src.leaves), D = coalesce_modes(dst.leaves);
@@ -1071,6 +1072,7 @@ std::string describe(const lc_plan& plan) {
     s += " items=" + std::to_string(plan.direct.n_items) + " loop=" + std::to_string(plan.direct.loop_extent);
     s += " launches=" + std::to_string(plan.n_launches);
     s += " unroll=" + std::to_string(plan.unroll);
+    s += " early_loads=" + std::to_string(plan.early_loads && plan.direct.n_modes == 1 && plan.direct.loop_extent < (1u << 30) ? 1 : 0);
   }
   if (plan.cls == KernelClass::LastWriter) s += " workspace_bytes=" + std::to_string(plan.workspace_bytes);
   s += " wgs_per_cu=" + std::to_string(plan.wgs_per_cu) + " nt=" + std::to_string(plan.nontemporal);

@@ -93,6 +93,7 @@ struct lc_plan {
   int queue_counters = 1;                  // ... counters (one cache line each) the requests are spread over
   int leftover_lead = 0;                   // fixed order: leading workgroups that share the tiles left after the last whole round (0: all)
   int nontemporal = 0;                     // bit 0: loads, bit 1: stores
+  bool early_loads = true;                 // kernels may start from their leading scalar arguments alone (tuning can switch it off)
   std::string note;                        // why a faster class was not taken
 };
 
