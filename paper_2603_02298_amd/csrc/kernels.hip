@@ -168,6 +168,82 @@ __global__ __launch_bounds__(kBlock) void direct_kernel(const typename Word<W>::
 }
 
 // ---------------------------------------------------------------------------------------------
+// Gather with a small source stride: the destination-contiguous mode is read with stride GS elements (GS * ES < 32 bytes:
+// every 16-byte word of the source span holds an element that is wanted).  A work item is one 16-byte vector of the
+// destination; the lane loads the GS consecutive 16-byte words that hold its 16 / ES source elements (word GS * o on for
+// vector o: always aligned), keeps every GS-th element and stores one vector.  A wavefront so reads GS KiB of contiguous
+// source and writes 1 KiB.  The last vector along the mode would read up to 16 / ES - 1 elements past the last element the
+// layout reaches, which the caller has not promised to be addressable: it loads element by element.
+// Offsets are in units of 16 bytes, from the direct class's argument block; mode 0 is the gathered mode.
+// ---------------------------------------------------------------------------------------------
+template <int ES, int GS>
+__device__ __forceinline__ u32x4 keep_every(const u32x4 (&t)[GS]) {
+  uint32_t f[4 * GS];
+#pragma unroll
+  for (int k = 0; k < GS; ++k)
+#pragma unroll
+    for (int d = 0; d < 4; ++d) f[4 * k + d] = t[k][d];
+  u32x4 o;
+  if constexpr (ES == 4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = f[e * GS];
+  } else if constexpr (ES == 8) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) { o[2 * e] = f[2 * e * GS]; o[2 * e + 1] = f[2 * e * GS + 1]; }
+  } else {   // ES == 2: element h is half h % 2 of dword h / 2
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      constexpr int dummy = 0; (void)dummy;
+      const int h0 = 2 * j * GS, h1 = (2 * j + 1) * GS;
+      const uint32_t lo = (f[h0 / 2] >> (16 * (h0 % 2))) & 0xffffu, hi = (f[h1 / 2] >> (16 * (h1 % 2))) & 0xffffu;
+      o[j] = lo | (hi << 16);
+    }
+  }
+  return o;
+}
+template <int ES, int GS, int U>
+__global__ __launch_bounds__(kBlock) void gather_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, DirectParams P) {
+  typedef typename Word<ES>::type E;
+  touch_kernel_arguments<(int)sizeof(DirectParams) + 16>();
+  const uint32_t step = gridDim.x * kBlock;
+  const uint32_t ext0 = P.n_modes > 1 ? P.div[0].div : P.n_items;   // vectors along the gathered mode
+  for (uint32_t base = blockIdx.x * kBlock + threadIdx.x; base < P.n_items; base += step * U) {
+    int64_t so[U], dof[U];
+    bool ok[U], last[U];
+    u32x4 v[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const uint32_t it = base + (uint32_t)j * step;
+      ok[j] = it < P.n_items;
+      so[j] = dof[j] = 0;
+      last[j] = false;
+      if (ok[j]) {
+        direct_offsets(P, it, &so[j], &dof[j]);
+        const uint32_t o = P.n_modes > 1 ? it - fd_div(it, P.div[0]) * ext0 : it;
+        last[j] = o == ext0 - 1u;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+      if (ok[j]) {
+        if (!last[j]) {
+          u32x4 t[GS];
+#pragma unroll
+          for (int k = 0; k < GS; ++k) t[k] = gload<1>(src + so[j] + k);
+          v[j] = keep_every<ES, GS>(t);
+        } else {
+          const E* e = reinterpret_cast<const E*>(src + so[j]);
+          E* w = reinterpret_cast<E*>(&v[j]);
+#pragma unroll
+          for (int k = 0; k < 16 / ES; ++k) w[k] = e[k * GS];
+        }
+      }
+#pragma unroll
+    for (int j = 0; j < U; ++j) if (ok[j]) gstore<2>(dst + dof[j], v[j]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Transpose through LDS.  Persistent workgroups walk the grid of tiles (the rest mode of
 // zipped_divide, Sec. 3.5.2); per tile each lane owns MT micro-tiles of V x V elements.
 //   load : V global loads of V*ES bytes along the source-contiguous mode p (one per step along q)
@@ -571,6 +647,25 @@ static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, uns
     default: hipLaunchKernelGGL((direct_kernel<W, U, 3>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
   }
 }
+template <int ES, int GS>
+static void launch_gather_s(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  const u32x4* sp = static_cast<const u32x4*>(src);
+  u32x4* dp = static_cast<u32x4*>(dst);
+  if (plan.unroll >= 2) hipLaunchKernelGGL((gather_kernel<ES, GS, 2>), dim3(grid), dim3(kBlock), 0, s, sp, dp, plan.direct);
+  else hipLaunchKernelGGL((gather_kernel<ES, GS, 1>), dim3(grid), dim3(kBlock), 0, s, sp, dp, plan.direct);
+}
+template <int ES>
+static bool launch_gather(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+  switch (plan.gather_stride) {
+    case 2: launch_gather_s<ES, 2>(plan, src, dst, grid, s); return true;
+    case 3: launch_gather_s<ES, 3>(plan, src, dst, grid, s); return true;
+    case 4: if constexpr (ES < 8) { launch_gather_s<ES, 4>(plan, src, dst, grid, s); return true; } break;
+    case 5: if constexpr (ES < 8) { launch_gather_s<ES, 5>(plan, src, dst, grid, s); return true; } break;
+    case 6: if constexpr (ES < 8) { launch_gather_s<ES, 6>(plan, src, dst, grid, s); return true; } break;
+    case 7: if constexpr (ES < 8) { launch_gather_s<ES, 7>(plan, src, dst, grid, s); return true; } break;
+  }
+  return false;
+}
 template <int W>
 static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
   switch (plan.unroll) {
@@ -818,6 +913,16 @@ static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst,
     for (int64_t j = 0; j < plan.n_launches; ++j) {
       const void* sj = static_cast<const unsigned char*>(src) + j * plan.launch_src_step * plan.elem_bytes;
       void* dj = static_cast<unsigned char*>(dst) + j * plan.launch_dst_step * plan.elem_bytes;
+      if (plan.gather_stride > 0) {
+        bool launched = false;
+        switch (plan.elem_bytes) {
+          case 2: launched = launch_gather<2>(plan, sj, dj, grid, s); break;
+          case 4: launched = launch_gather<4>(plan, sj, dj, grid, s); break;
+          case 8: launched = launch_gather<8>(plan, sj, dj, grid, s); break;
+        }
+        if (!launched) return LC_ERR_UNSUPPORTED_DTYPE;
+        continue;
+      }
       switch (plan.width_bytes) {
         case 1: launch_direct<1>(plan, sj, dj, grid, s); break;
         case 2: launch_direct<2>(plan, sj, dj, grid, s); break;

@@ -52,6 +52,22 @@ lc_status_t replay_on_host(const lc_plan& plan, const void* src, int64_t src_lo,
   } else if (plan.cls == KernelClass::Direct) {
     const DirectParams& P = plan.direct;
     const int W = plan.width_bytes;
+    if (plan.gather_stride > 0) {
+      // gather_kernel: vector `item` of the destination keeps every S-th element of S consecutive source words; all but the
+      // last vector along mode 0 load those words whole
+      const int S = plan.gather_stride, VE = 16 / eb;
+      const uint32_t ext0 = P.n_modes > 1 ? P.div[0].div : P.n_items;
+      if (W != 16) return LC_ERR_INVALID_ARG;
+      for (int64_t j = 0; j < plan.n_launches; ++j)
+        for (uint32_t item = 0; item < P.n_items; ++item) {
+          int64_t so, dof;
+          direct_offsets(P, item, &so, &dof);
+          const int64_t sbyte = so * 16 + j * plan.launch_src_step * eb, dbyte = dof * 16 + j * plan.launch_dst_step * eb;
+          const uint32_t o = P.n_modes > 1 ? item % ext0 : item;
+          if (o != ext0 - 1u && (sbyte < B.src_lo || sbyte + (int64_t)S * 16 > B.src_hi)) B.ok = false;
+          for (int e = 0; e < VE; ++e) B.move(sbyte + (int64_t)e * S * eb, dbyte + (int64_t)e * eb, eb);
+        }
+    } else
     for (int64_t j = 0; j < plan.n_launches; ++j)
       for (uint32_t item = 0; item < P.n_items; ++item) {
         int64_t so, dof;

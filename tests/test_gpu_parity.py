@@ -145,6 +145,25 @@ def test_tuning_variants_stay_exact(oracle, monkeypatch):
         _parity(oracle, w.src_layout, w.dst_layout, w.dtype, src_bits=W.source_bits(w), tag="unroll" + u)
 
 
+def test_gathers_with_small_source_stride(oracle, monkeypatch):
+    """16-byte words on both sides of a gather whose source stride is a few elements (gather_kernel): every stride the
+    kernel is built for, the three element widths, outer modes, a single vector per row, sizes that span many
+    workgroups with a ragged last trip; buffers exactly as long as the layouts reach."""
+    monkeypatch.setenv("LC_TUNE_GATHER", "1")
+    cases = [("%d:%d" % (n, s), "%d:1" % n, dt) for dt, strides in (("f32", (2, 3, 4, 5, 6, 7)), ("bf16", (2, 3, 4, 5, 6, 7)), ("b64", (2, 3)))
+             for s in strides for n in (16, 1000 * 8, (1 << 20) + 136)]
+    cases += [("(64,30):(3,200)", "(64,30):(1,64)", "f32"), ("(32,5,7):(6,192,1920)", "(32,5,7):(1,64,320)", "bf16"),
+              ("(8,3001):(5,40)", "(8,3001):(1,8)", "bf16")]
+    for s, d, dt in cases:
+        desc = _parity(oracle, s, d, dt, seed=21, tag="gather")
+        assert "gather_stride=" in desc, desc
+    monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
+    desc = _parity(oracle, "%d:3" % (1 << 16), "%d:1" % (1 << 16), "f32", seed=22, tag="gather sliced")
+    assert "gather_stride=3 " in desc and "launches=1 " not in desc, desc
+    monkeypatch.setenv("LC_TUNE_UNROLL", "1")
+    _parity(oracle, "%d:3" % (1 << 16), "%d:1" % (1 << 16), "bf16", seed=23, tag="gather one item per lane")
+
+
 def test_sliced_launches(oracle, monkeypatch):
     # the slicing used beyond 2^31 work items, forced at a small size
     monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
@@ -295,7 +314,8 @@ def test_negative_strides(oracle):
              ("(256,64,3):(1,256,-16384)", "(256,64,3):(64,1,16384)", "bf16"), ("(256,64,3):(1,256,16384)", "(256,64,3):(64,1,-16384)", "bf16"),
              ("(512,512,4):(1,512,-262144)", "(512,512,4):(512,1,262144)", "f32"),        # several tiles, batches reversed
              ("(1024,1024):(1,1024)", "(1024,1024):(1024,-1)", "f32"),                    # transpose onto flipped columns
-             ("(6,10):(10,-1)", "(4,15):(-15,1)", "b64"), ("(4,2,3):(1,4,8)", "(4,2,3):(1,0,-4)", "f32")]
+             ("(6,10):(10,-1)", "(4,15):(-15,1)", "b64"), ("(4,2,3):(1,4,8)", "(4,2,3):(1,0,-4)", "f32"),
+             ("(64,9):(3,-192)", "(64,9):(1,64)", "f32")]                                  # a gather with its rows backwards
     rng = np.random.default_rng(9)
     for i in range(60):
         r = int(rng.integers(1, 4))

@@ -65,7 +65,8 @@ def test_rank4_extent8_universe_rerun():
     spec = importlib.util.spec_from_file_location("make_tally", os.path.join(ROOT, "tests", "golden", "make_bruteforce_tally.py"))
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
-    rc, text = mod.run()
+    import tempfile
+    rc, text = mod.run(parts_dir=tempfile.mkdtemp(), fresh=True)
     assert rc == 0, text[-3000:]
     assert _tally_lines(text) == _tally_lines(open(mod.OUT).read())
 

@@ -366,3 +366,36 @@ def test_alignment_limits_vector_width():
     # padded rows whose pitch is not a multiple of the vector: width drops to what divides it
     assert "width_bytes=8" in lc.Plan("(64,32):(1,66)", "(64,32):(1,64)", "f32").describe()
     assert "width_bytes=4" in lc.Plan("(64,32):(1,65)", "(64,32):(1,64)", "f32").describe()
+
+
+def test_gather_with_small_source_stride_moves_whole_words(oracle, monkeypatch):
+    """A destination-contiguous mode read with stride S (S * element < 32 bytes): 16-byte words on both sides, the lane
+    keeps every S-th element of S consecutive source words.  Buffers are exactly as long as the layouts reach: the last
+    vector along the mode must not read past the last element (it loads element by element).  On request only: element by
+    element is faster on MI355X."""
+    monkeypatch.setenv("LC_TUNE_GATHER", "1")
+    cases = [("4096:3", "4096:1", "f32", 3), ("4096:2", "4096:1", "f32", 2), ("1024:7", "1024:1", "f32", 7),
+             ("4096:3", "4096:1", "bf16", 3), ("2048:5", "2048:1", "bf16", 5), ("1024:7", "1024:1", "f16", 7),
+             ("512:3", "512:1", "b64", 3), ("512:2", "512:1", "b64", 2),
+             ("(64,30):(3,200)", "(64,30):(1,64)", "f32", 3),                 # rows of a padded matrix, every third column
+             ("(32,5,7):(6,192,1920)", "(32,5,7):(1,64,320)", "bf16", 6)]     # outer strides in whole words on both sides
+    for s, d, dt, stride in cases:
+        desc, _ = _check(oracle, s, d, dt, "direct")
+        assert "gather_stride=%d " % stride in desc and "width_bytes=16 " in desc, desc
+    desc = _check_signed(oracle, "(64,9):(3,-192)", "(64,9):(1,64)", "f32")  # rows walked backwards on the source side
+    assert "gather_stride=3 " in desc, desc
+    # not this path: stride too long for the element width, a ragged extent, an outer stride that splits a word, a
+    # broadcast mode, pointers that are not 16-byte aligned
+    for s, d, dt in [("4096:8", "4096:1", "f32"), ("1024:4", "1024:1", "b64"), ("4094:3", "4094:1", "f32"),
+                     ("(64,30):(3,201)", "(64,30):(1,64)", "f32"), ("(64,4):(3,0)", "(64,4):(1,64)", "f32")]:
+        desc, _ = _check(oracle, s, d, dt)
+        assert "gather_stride" not in desc, desc
+    assert "gather_stride" not in lc.Plan("4096:3", "4096:1", "f32", src_align=4).describe()
+    # sliced into launches along the gathered mode itself
+    monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "100")
+    desc, _ = _check(oracle, "4096:3", "4096:1", "f32", "direct")
+    assert "gather_stride=3 " in desc and "launches=16 " in desc, desc
+    monkeypatch.delenv("LC_TUNE_MAX_ITEMS")
+    monkeypatch.delenv("LC_TUNE_GATHER")
+    desc, _ = _check(oracle, "4096:3", "4096:1", "f32", "direct")
+    assert "gather_stride" not in desc and "width_bytes=4 " in desc, desc
