@@ -6,7 +6,7 @@ call of a workload plans on the host (validate, coalesce, refine, sort, vector w
 that plan in the library's plan cache, so a timed step is plan look-up + launch + kernel.  Buffers rotate so that a
 step never finds its data in the last-level cache.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c1|c2|c3|c4a|c4b|copy|gemm_tn|gemm_nt] [--no-all]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c1|c2|c3|c4a|c4b|copy|gemm_tn|gemm_nt|calibrate] [--no-all]
 
 Prints ONE JSON line.  The headline (`value`, `config`, `roofline`, `cpu_baseline`) is the largest single-GPU
 configuration, workload 5 (NCHW -> NHWC, 2^30 fp32 elements, 8 GiB moved); `workloads` carries the same record for
@@ -256,6 +256,23 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream().cuda_stream
+
+    if args.workload == "calibrate":
+        # For the counter runs only: two library kernels with traffic on ONE side that is known independently of this
+        # library -- a sum over 2^28 int32 (reads 2^30 bytes, writes next to nothing) and a fill of 2^28 int32 (writes
+        # 2^30 bytes, reads nothing).  rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this run gives the counters' scale.
+        x = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        y = torch.empty(1 << 28, dtype=torch.int32, device=dev)
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            x.sum()
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            y.fill_(7)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": {"read_only": "torch.sum over 2^28 int32: 2^30 bytes read per call, %d calls" % args.steps,
+                                          "write_only": "torch.Tensor.fill_ of 2^28 int32: 2^30 bytes written per call, %d calls" % args.steps}}))
+        return
 
     if args.workload.startswith("gemm_"):
         # the second workload as the headline of this run (used for its profiles)
