@@ -10,9 +10,13 @@ template __global__ void gemm_kernel<true, 2, 2, 0, 1>(GemmParams, const uint16_
 template __global__ void gemm_kernel<true, 2, 2, 1, 0>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<true, 2, 2, 1, 1>(GemmParams, const uint16_t*, const uint16_t*, float*);
 template __global__ void gemm_kernel<true, 2, 2, 3, 3>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<true, 2, 2, 3, 3, true>(GemmParams, const uint16_t*, const uint16_t*, float*);   // K with a short last k tile
 template __global__ void gemm_kernel<true, 2, 2, 3, 4>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<true, 2, 2, 3, 4, true>(GemmParams, const uint16_t*, const uint16_t*, float*);   // K with a short last k tile
 template __global__ void gemm_kernel<true, 2, 2, 4, 3>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<true, 2, 2, 4, 3, true>(GemmParams, const uint16_t*, const uint16_t*, float*);   // K with a short last k tile
 template __global__ void gemm_kernel<true, 2, 2, 4, 4>(GemmParams, const uint16_t*, const uint16_t*, float*);
+template __global__ void gemm_kernel<true, 2, 2, 4, 4, true>(GemmParams, const uint16_t*, const uint16_t*, float*);   // K with a short last k tile
 template __global__ void gemm_kernel<true, 2, 2, 2, 2>(GemmParams, const uint16_t*, const uint16_t*, float*);
 
 hipError_t launch_gemm_bf16_128(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {

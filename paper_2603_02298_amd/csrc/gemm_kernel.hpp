@@ -83,7 +83,9 @@ __device__ __forceinline__ u32x4 select_or_zero(bool keep, u32x4 v) {
 // One operand (A or B) of one workgroup: issues the global loads of a k tile into registers, parks them in LDS.
 // Loads are unconditional from clamped coordinates (always inside the tensor); what lies past K is zeroed
 // in registers afterwards, so the loop carries no divergent branch.
-template <int BR, int LOAD>
+// KTAIL (direct loads): K is not a multiple of the k tile; the lanes whose piece of the last k tile lies at or past K
+// present an offset outside the buffer there, which the memory pipeline answers with zeros (no access is made).
+template <int BR, int LOAD, bool KTAIL = false>
 struct OperandLoader {
   static constexpr int ROWS = BR / 32;                                    // rows per lane for k-vector / element loads
   static constexpr bool DIRECT = LOAD == kLoadKDirect || LOAD == kLoadRDirect;
@@ -92,15 +94,19 @@ struct OperandLoader {
   __amdgpu_buffer_rsrc_t rsrc;           // direct loads: the operand as a raw buffer (uniform base, 32-bit byte offsets)
   uint32_t K, kv, row_in_tile;           // row_in_tile: first row of the lane (block row for row-vector loads)
   uint32_t rowoff[LOAD == kLoadRVec ? 1 : ROWS];
+  uint32_t tail_mask;                    // KTAIL: bit i = instruction i of this lane asks for k below K in the last k tile
   bool active, k_inside;
   u32x4 regs[NREG];
 
   __device__ __forceinline__ void init(const uint16_t* p, const GemmMode& rmode, const GemmMode& kmode, uint32_t row0, uint32_t extent,
                                        uint32_t Ktot, uint32_t tid) {
     base = p;
-    // no range to enforce: every offset the lanes present is inside the operand by construction (rows are clamped, k tiles whole)
+    // every offset the lanes present is inside the operand by construction (rows are clamped, k tiles whole), except the
+    // offset 0xFFFFFFFF that stands for "past K" in a short last k tile: it is out of the buffer's range whatever the range
     if constexpr (DIRECT) rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p), 0, 0xFFFFFFFFu, 0x00020000);
     K = Ktot;
+    tail_mask = 0u;
+    const uint32_t k_rem = Ktot - (Ktot - 1u) / kGemmBK * kGemmBK;   // k present in the last k tile (1 .. 64)
     kv = gemm_lane_kvec(LOAD, tid);
     row_in_tile = gemm_lane_row(LOAD, tid, 0);
     active = LOAD != kLoadRVec || BR >= kBlock || tid < (uint32_t)BR;   // whole wavefronts: lanes 128.. of a 128-row tile
@@ -112,6 +118,7 @@ struct OperandLoader {
       for (int i = 0; i < ROWS; ++i) {
         const uint32_t row = gemm_direct_row(ROWS, tid, (uint32_t)i);
         rowoff[i] = 2u * (gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + row, extent)) + 8u * gemm_direct_kvec(row, tid));   // bytes
+        tail_mask |= (8u * gemm_direct_kvec(row, tid) < k_rem ? 1u : 0u) << i;
       }
       row_in_tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6)) * ROWS;   // the wavefront's first KiB of the tile (uniform)
     } else if constexpr (LOAD == kLoadRDirect) {
@@ -122,6 +129,7 @@ struct OperandLoader {
         uint32_t k, row;
         gemm_rdirect_unit(BR, ROWS, tid, (uint32_t)i, &k, &row);
         rowoff[i] = 2u * (gemm_mode_eval(rmode, gemm_clamp_row(LOAD, row0 + row, extent)) + k * kmode.lead_stride);   // bytes
+        tail_mask |= (k < k_rem ? 1u : 0u) << i;
       }
       row_in_tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid >> 6)) * ROWS;   // the wavefront's first KiB of the tile (uniform)
     } else {
@@ -132,8 +140,9 @@ struct OperandLoader {
 
   // Direct loads of one k tile: k_bytes is the tile's byte offset along the k mode (uniform), stage_tile the LDS byte offset
   // of this operand's tile in the stage the k tile goes to.  Lane l's 16 bytes land at byte 16 l of the instruction's KiB.
+  // tail (uniform): the k tile is the short last one
   template <int FIRST = 0, int END = ROWS>
-  __device__ __forceinline__ void fetch_direct(uint32_t k_bytes, uint32_t stage_tile) {
+  __device__ __forceinline__ void fetch_direct(uint32_t k_bytes, uint32_t stage_tile, bool tail = false) {
     typedef __attribute__((address_space(3))) void lds_void;
     // The same dynamic LDS as the kernel's `lds`, under a name of its own on purpose: the compiler then sees no alias
     // between these writes and the fragment reads and adds no waits of its own (it would make every LDS read wait for
@@ -142,9 +151,12 @@ struct OperandLoader {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
     static_for<(END > FIRST ? END - FIRST : 0)>([&](auto d) {
       constexpr int i = FIRST + d;
-      if constexpr (i >= 0 && i < ROWS)
+      if constexpr (i >= 0 && i < ROWS) {
+        uint32_t voff = rowoff[i];
+        if constexpr (KTAIL) voff = (tail && ((tail_mask >> i) & 1u) == 0u) ? 0xFFFFFFFFu : voff;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(lds_bytes + stage_tile + (row_in_tile + (uint32_t)i) * 1024u), 16,
-                                                 (int)rowoff[i], (int)k_bytes, 0, 0);
+                                                 (int)voff, (int)k_bytes, 0, 0);
+      }
     });
   }
 
@@ -241,7 +253,7 @@ struct KTileOffset {
   }
 };
 
-template <bool BF16, int WMB, int WNB, int A_LOAD, int B_LOAD>
+template <bool BF16, int WMB, int WNB, int A_LOAD, int B_LOAD, bool KTAIL = false>
 __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmParams P, const uint16_t* __restrict__ A,
                                                                           const uint16_t* __restrict__ B, float* __restrict__ C) {
   constexpr int BM = 64 * WMB, BN = 64 * WNB;
@@ -258,8 +270,8 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
   B += gemm_mode_eval(P.b_l, blockIdx.y);
   C += gemm_mode_eval(P.c_l, blockIdx.y);
 
-  OperandLoader<BM, A_LOAD> la;
-  OperandLoader<BN, B_LOAD> lb;
+  OperandLoader<BM, A_LOAD, KTAIL> la;
+  OperandLoader<BN, B_LOAD, KTAIL> lb;
   la.init(A, P.a_r, P.a_k, m0, P.M, P.K, tid);
   lb.init(B, P.b_r, P.b_k, n0, P.N, P.K, tid);
 
@@ -344,15 +356,16 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     KTileOffset ka, kb;   // of the newest k tile requested for A and for B
     ka.seek(P.a_k, 0u);
     kb.seek(P.b_k, 0u);
-    la.fetch_direct(ka.bytes, 0u * SLOT);
-    lb.fetch_direct(kb.bytes, 1u * SLOT);
+    // (the last argument of a fetch: the k tile it asks for is the last one, which KTAIL kernels load short)
+    la.fetch_direct(ka.bytes, 0u * SLOT, last == 0u);
+    lb.fetch_direct(kb.bytes, 1u * SLOT, last == 0u);
     __builtin_amdgcn_sched_barrier(0x038F);   // k tile 0's loads stay the oldest: the first wait below counts from the youngest
     ka.seek(P.a_k, last < 1u ? last : 1u);
     kb.seek(P.b_k, last < 1u ? last : 1u);
-    la.fetch_direct(ka.bytes, 2u * SLOT);
-    lb.fetch_direct(kb.bytes, 3u * SLOT);
+    la.fetch_direct(ka.bytes, 2u * SLOT, last <= 1u);
+    lb.fetch_direct(kb.bytes, 3u * SLOT, last <= 1u);
     ka.seek(P.a_k, last < 2u ? last : 2u);
-    la.fetch_direct(ka.bytes, 4u * SLOT);
+    la.fetch_direct(ka.bytes, 4u * SLOT, last <= 2u);
     wait_loads_but(std::integral_constant<int, 2 * RA + RB>{});   // k tile 0 has landed
     lds_barrier();
     read_fragments(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
@@ -360,7 +373,8 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     for (uint32_t kt = 0; kt < P.k_tiles; ++kt) {
       const uint32_t s_b1 = next_slot(sb), s_a2 = next_slot(next_slot(sa));   // slots of B(kt + 1) and A(kt + 2)
       // k step 0: second half of B(kt + 1); k steps 1 and 2: A(kt + 2)
-      lb.template fetch_direct<RB / 2, RB>(kb.bytes, s_b1 * SLOT);
+      const bool b1_last = kt + 1u >= last, a2_last = kt + 2u >= last;   // B(kt + 1) / A(kt + 2) and B(kt + 2) are the last k tile
+      lb.template fetch_direct<RB / 2, RB>(kb.bytes, s_b1 * SLOT, b1_last);
       read_fragments(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
       multiply(std::integral_constant<int, 0>{});
       issue_order(std::integral_constant<int, RB - RB / 2>{}, std::integral_constant<int, MFMAS>{});
@@ -368,11 +382,11 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
       // So no load of B may be scheduled behind a load of A: nothing but vector memory instructions is held back here
       // (mask: ALU, VALU, SALU, MFMA and LDS instructions may cross).
       __builtin_amdgcn_sched_barrier(0x038F);
-      la.template fetch_direct<0, RA / 2>(ka.bytes, s_a2 * SLOT);
+      la.template fetch_direct<0, RA / 2>(ka.bytes, s_a2 * SLOT, a2_last);
       read_fragments(std::integral_constant<int, 2>{}, std::integral_constant<int, 0>{});
       multiply(std::integral_constant<int, 1>{});
       issue_order(std::integral_constant<int, RA / 2>{}, std::integral_constant<int, MFMAS>{});
-      la.template fetch_direct<RA / 2, RA>(ka.bytes, s_a2 * SLOT);
+      la.template fetch_direct<RA / 2, RA>(ka.bytes, s_a2 * SLOT, a2_last);
       read_fragments(std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{});
       multiply(std::integral_constant<int, 0>{});
       // the reads before the barrier over the first half of the MFMAs, so that the last one has returned when the last MFMA is issued
@@ -382,7 +396,7 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
       if (kt + 2u <= last) kb.next(P.b_k, kt + 2u);
       if (kt + 3u <= last) ka.next(P.a_k, kt + 3u);
       // k step 3: first half of B(kt + 2), into the slot A(kt) leaves
-      lb.template fetch_direct<0, RB / 2>(kb.bytes, sa * SLOT);
+      lb.template fetch_direct<0, RB / 2>(kb.bytes, sa * SLOT, a2_last);
       const uint32_t sa_next = next_slot(sa), sb_next = next_slot(sb);
       const uint32_t da = (sa_next - sa) * SLOT, db = (sb_next - sb) * SLOT;
       static_for<WMB>([&](auto i) { a_fr[i] += da; });
@@ -468,20 +482,27 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
 // Launchers
 // ---------------------------------------------------------------------------------------------
 
-template <bool BF16, int WB, int A_LOAD, int B_LOAD>
-static inline hipError_t launch_gemm_ab(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
+template <bool BF16, int WB, int A_LOAD, int B_LOAD, bool KTAIL>
+static inline hipError_t launch_gemm_abk(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
   if (plan.lds_bytes > 64 * 1024) {
     static std::atomic<bool> raised{false};   // one flag per instantiation: the attribute belongs to the kernel function
     if (!raised.load(std::memory_order_acquire)) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD, KTAIL>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e != hipSuccess) return e;
       raised.store(true, std::memory_order_release);
     }
   }
   const unsigned grid = plan.params.tiles_m * plan.params.tiles_n;
-  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD>), dim3(grid, plan.params.L), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
+  hipLaunchKernelGGL((gemm_kernel<BF16, WB, WB, A_LOAD, B_LOAD, KTAIL>), dim3(grid, plan.params.L), dim3(kBlock), plan.lds_bytes, s, plan.params, a, b, c);
   return hipSuccess;
+}
+template <bool BF16, int WB, int A_LOAD, int B_LOAD>
+static inline hipError_t launch_gemm_ab(const lc_gemm_plan& plan, const uint16_t* a, const uint16_t* b, float* c, hipStream_t s) {
+  // a short last k tile: direct loads only (the staged loads zero what lies past K in registers)
+  if constexpr (A_LOAD == kLoadKDirect || A_LOAD == kLoadRDirect)
+    if (plan.params.K % kGemmBK != 0) return launch_gemm_abk<BF16, WB, A_LOAD, B_LOAD, true>(plan, a, b, c, s);
+  return launch_gemm_abk<BF16, WB, A_LOAD, B_LOAD, false>(plan, a, b, c, s);
 }
 // vector loads are compiled per pair of modes; an operand that needs element loads takes the other one along.
 // Operands that go straight into LDS do so as a pair (the planner marks both or neither).

@@ -16,8 +16,9 @@ enum GemmLoad : int32_t {
   kLoadKVec = 0,   // 16-byte vectors along k (k-mode leads with a stride-1 leaf): straight into place
   kLoadRVec = 1,   // 16-byte vectors along the row mode (m or n): 8x8 blocks transposed in registers
   kLoadElem = 2,   // element by element: any layout, any extent
-  // kLoadKVec without the registers: 16-byte vectors along k sent by the memory pipeline straight into LDS.  Needs whole
-  // k tiles (K a multiple of 64, each tile contiguous along k); chosen at launch, a plan still says kLoadKVec.
+  // kLoadKVec without the registers: 16-byte vectors along k sent by the memory pipeline straight into LDS.  Needs k tiles
+  // that are contiguous along k (whole tiles inside the k mode's first leaf; a k mode of one leaf may end in a short tile,
+  // whose lanes past K are answered with zeros); chosen at launch, a plan still says kLoadKVec.
   kLoadKDirect = 3,
   // kLoadRVec without the registers: the tile goes into LDS as it lies in memory (k rows of BR contiguous elements) and the
   // fragments are read with the LDS transpose load (ds_read_b64_tr_b16).  Same conditions; a plan still says kLoadRVec.

@@ -153,10 +153,16 @@ lc_status_t make_gemm_plan(const Layout& A_in, const Layout& B_in, const Layout&
   const int force = env_int("LC_TUNE_GEMM_LOAD", -1);   // tests: force the element-wise loads
   // element loads are compiled for both operands together: one operand that needs them takes the other along
   if (force == kLoadElem || P.a_load == kLoadElem || P.b_load == kLoadElem) P.a_load = P.b_load = kLoadElem;
-  // straight into LDS: whole k tiles, each contiguous along k
+  // straight into LDS: k tiles that are contiguous along k
   // (for row vectors: each of the tile's 64 k rows one even step of the k mode's first leaf from the tile's first);
   // compiled for pairs of operands that both qualify
-  auto direct_ok = [&](int load, const Modes& k) { return load != kLoadElem && K % kGemmBK == 0 && k[0].extent % kGemmBK == 0; };
+  // A k mode of a single leaf may end in a short k tile: the lanes whose piece lies past K are answered with zeros
+  // (k vectors: K a multiple of 8, so that no vector straddles K).
+  auto direct_ok = [&](int load, const Modes& k) {
+    if (load == kLoadElem) return false;
+    if (K % kGemmBK == 0 && k[0].extent % kGemmBK == 0) return true;
+    return k.size() == 1 && (load == kLoadRVec || K % 8 == 0) && env_int("LC_TUNE_GEMM_KTAIL", 1) != 0;
+  };
   const int direct_env = env_int("LC_TUNE_GEMM_DIRECT", 3);   // bit 0: k vectors, bit 1: row vectors
   auto direct_on = [&](int load) { return (direct_env & (load == kLoadKVec ? 1 : 2)) != 0; };
   const bool direct = direct_ok(P.a_load, a_k) && direct_ok(P.b_load, b_k) && direct_on(P.a_load) && direct_on(P.b_load);

@@ -47,7 +47,12 @@ struct Walker {
           const uint32_t row = gemm_direct_row(rows_per_lane, tid, i), kv = gemm_direct_kvec(row, tid);
           const int64_t off = (int64_t)gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + row, extent)) + 8u * kv + gemm_mode_eval(kmode, kt * kGemmBK);
           const uint32_t lds_at = ((tid >> 6) * rows_per_lane + i) * 1024u + (tid & 63u) * 16u;
-          if (off % 8 != 0 || off + 8 > elems || lds_at != gemm_lds_offset(row, kv) || kt * kGemmBK + 8u * kv + 8u > P.K) { ok = false; return; }
+          if (lds_at != gemm_lds_offset(row, kv)) { ok = false; return; }
+          if (kt * kGemmBK + 8u * kv >= P.K) {   // past K in a short last k tile: the lane's offset is out of range, zeros arrive
+            std::memset(tile + lds_at, 0, 16);
+            continue;
+          }
+          if (off % 8 != 0 || off + 8 > elems || kt * kGemmBK + 8u * kv + 8u > P.K) { ok = false; return; }
           std::memcpy(tile + lds_at, base + off, 16);
         }
       return;
@@ -55,7 +60,6 @@ struct Walker {
     if (load == kLoadRDirect) {
       // k-major tile: lane l of instruction i of wavefront w fills 16-byte unit (w R + i) 64 + l
       const uint32_t rows_per_lane = BR / 32;
-      if (P.K % kGemmBK != 0) { ok = false; return; }
       for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid)
         for (uint32_t i = 0; i < rows_per_lane; ++i) {
           uint32_t k, row;
@@ -63,8 +67,13 @@ struct Walker {
           const int64_t off = (int64_t)gemm_mode_eval(rmode, gemm_clamp_row(load, row0 + row, extent)) + (int64_t)k * kmode.lead_stride +
                               gemm_mode_eval(kmode, kt * kGemmBK);
           const uint32_t lds_at = ((tid >> 6) * rows_per_lane + i) * 1024u + (tid & 63u) * 16u;
+          if (k >= (uint32_t)kGemmBK || row + 8 > BR || lds_at != gemm_rdirect_lds_offset(BR, k, row)) { ok = false; return; }
+          if (kt * kGemmBK + k >= P.K) {   // past K in a short last k tile: zeros arrive
+            std::memset(tile + lds_at, 0, 16);
+            continue;
+          }
           // the k row's offset is what the k mode's layout function gives, and the slot is the one fragment reads expect
-          if (k >= (uint32_t)kGemmBK || row + 8 > BR || off % 8 != 0 || off + 8 > elems || lds_at != gemm_rdirect_lds_offset(BR, k, row) ||
+          if (off % 8 != 0 || off + 8 > elems ||
               (int64_t)k * kmode.lead_stride + gemm_mode_eval(kmode, kt * kGemmBK) != (int64_t)gemm_mode_eval(kmode, kt * kGemmBK + k)) {
             ok = false;
             return;

@@ -45,9 +45,26 @@ CASES = [
 
 @pytest.mark.parametrize("name,mnk,expect", CASES)
 @pytest.mark.parametrize("tile", [128, 256])
-def test_walk_matches_oracle(oracle, name, mnk, expect, tile):
+@pytest.mark.parametrize("ktail", [0, 1])
+def test_walk_matches_oracle(oracle, name, mnk, expect, tile, ktail):
+    # K is no multiple of the k tile in any of these.  ktail = 0: tiles pass through registers, what lies past K is zeroed
+    # there; ktail = 1 (the default): vector operands still go straight into LDS, the lanes past K are answered with zeros
     w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values="ints")
-    _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile}, expect + ["tile=%dx%d" % (tile, tile)])
+    text = _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile, "LC_TUNE_GEMM_KTAIL": ktail}, expect + ["tile=%dx%d" % (tile, tile)])
+    assert ("direct-to-LDS" in text) == (ktail == 1 and name != "blis"), text
+
+
+def test_walk_short_last_k_tiles_on_the_direct_path(oracle):
+    # K from a single vector to several tiles plus a remainder; K a multiple of 8 (no k vector may straddle K; row vectors
+    # come in blocks of 8 k)
+    for name, Ks in (("tn", (8, 24, 72, 200)), ("nt", (8, 40, 72, 136, 200)), ("nn_rowmajor_c", (40, 136)), ("gett", (16, 88))):
+        for K in Ks:
+            for tile in (128, 256):
+                w = W.gemm_workload(name, 200, 136, K, ab_dtype="bf16", values="ints")
+                text = _walk_and_compare(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
+                assert text.count("direct-to-LDS") == 2 and "k_tiles=%d " % ((K + 63) // 64) in text, text
+    w = W.gemm_workload("tn", 200, 136, 100, ab_dtype="bf16", values="ints")     # 100 = 8 * 12 + 4: a k vector would straddle K
+    assert "direct" not in _walk_and_compare(oracle, w, None)
 
 
 def test_walk_direct_to_lds_loads(oracle):

@@ -73,11 +73,29 @@ CASES = [
 
 @pytest.mark.parametrize("values", ["ints", "normal"])
 @pytest.mark.parametrize("tile", [128, 256])
+@pytest.mark.parametrize("ktail", [0, 1])
 @pytest.mark.parametrize("name,mnk", CASES)
-def test_gemm_table_rows(oracle, name, mnk, tile, values):
+def test_gemm_table_rows(oracle, name, mnk, tile, values, ktail):
+    # K is no multiple of the k tile in any of these: ktail = 0 takes the tiles through registers (what lies past K is zeroed
+    # there), ktail = 1 (the default) sends vector operands straight into LDS with zeros for the lanes past K
     w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values=values)
-    desc = _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
+    desc = _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile, "LC_TUNE_GEMM_KTAIL": ktail})
     assert "tile=%dx%d" % (tile, tile) in desc
+    assert ("direct-to-LDS" in desc) == (ktail == 1 and name != "blis"), desc
+
+
+@pytest.mark.parametrize("name,Ks", [("tn", (8, 24, 72, 200, 1000)), ("nt", (8, 40, 72, 136, 200, 1000)), ("nn_rowmajor_c", (40, 136)), ("gett", (16, 88))])
+def test_gemm_short_last_k_tiles_on_the_direct_path(oracle, name, Ks):
+    # the ring of LDS tiles with a last k tile that is short (from a single k on): the lanes past K present an offset out
+    # of the buffer's range and zeros arrive in their slots
+    for K in Ks:
+        for tile in (128, 256):
+            for values in ("ints", "normal"):
+                w = W.gemm_workload(name, 304, 264, K, ab_dtype="bf16", values=values)
+                desc = _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
+                assert desc.count("direct-to-LDS") == 2 and "k_tiles=%d " % ((K + 63) // 64) in desc, desc
+    w = W.gemm_workload(name, 136, 200, Ks[-1], ab_dtype="f16", values="ints")
+    assert "direct-to-LDS" in _parity(oracle, w)
 
 
 @pytest.mark.parametrize("values", ["ints", "normal"])
@@ -105,6 +123,19 @@ def test_gemm_direct_to_lds_loads(oracle, values):
     for tile in (128, 256):
         assert _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile}).count("direct-to-LDS") == 2
     assert "direct-to-LDS" not in _parity(oracle, w, {"LC_TUNE_GEMM_DIRECT": 1})
+
+
+@pytest.mark.parametrize("K", [64, 128, 192, 256, 320])
+@pytest.mark.parametrize("name", ["tn", "nt", "nn_rowmajor_c"])
+def test_gemm_ring_of_tiles_with_few_k_tiles(oracle, name, K):
+    # 1 to 5 k tiles through the ring of five LDS slots: the prologue requests k tiles 0, 1 and A(2) whatever K is (past
+    # the last tile it repeats it), the loop's first passes run on slots the prologue filled, and with 5 tiles the
+    # slots come round once.  Both tile sizes, integer values (exact) and N(0,1).
+    for tile in (128, 256):
+        for values in ("ints", "normal"):
+            w = W.gemm_workload(name, 304, 264, K, ab_dtype="bf16", values=values)
+            desc = _parity(oracle, w, {"LC_TUNE_GEMM_TILE": tile})
+            assert desc.count("direct-to-LDS") == 2 and "k_tiles=%d " % (K // 64) in desc, desc
 
 
 def test_gemm_f16_and_element_loads(oracle):
