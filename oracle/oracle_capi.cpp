@@ -230,6 +230,13 @@ int oracle_slayout_right_inverse(const oracle::SLayout* a, Layout** out) {
   *out = new Layout(r);
   return oracle::OK;
 }
+int oracle_slayout_xor_right_inverse(const oracle::SLayout* a, oracle::SLayout** out) {
+  oracle::SLayout r;
+  oracle::Status st = oracle::xor_right_inverse(*a, &r);
+  if (st != oracle::OK) return st;
+  *out = new oracle::SLayout(r);
+  return oracle::OK;
+}
 
 // ---- GEMM (Sec. 2.6.2) ----
 int oracle_gemm_check(const Layout* a, const Layout* b, const Layout* c, int64_t* M, int64_t* N, int64_t* K, int64_t* L) {

@@ -94,6 +94,7 @@ def lib():
         L.oracle_slayout_composition.argtypes = [P, P, PP]
         L.oracle_slayout_coalesce.argtypes = [P, PP]
         L.oracle_slayout_right_inverse.argtypes = [P, PP]
+        L.oracle_slayout_xor_right_inverse.argtypes = [P, PP]
         L.oracle_copy.argtypes = [P, P, P, P, ctypes.c_int]
         L.oracle_copy_range.argtypes = [P, P, P, P, ctypes.c_int, i64, i64]
         L.oracle_gemm_check.argtypes = [P, P, P, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -251,6 +252,14 @@ def slayout_right_inverse(a):
     h = ctypes.c_void_p()
     _check(lib().oracle_slayout_right_inverse(a._h, ctypes.byref(h)), "right_inverse(%s)" % a)
     return Layout(_handle=h)
+
+
+def slayout_xor_right_inverse(a):
+    """Table rinv, last row: R = (2,...,2):(f_x0, f_x1, ...) with A(R(k)) = k; raises when A is not additive over XOR."""
+    a = _as_slayout(a)
+    h = ctypes.c_void_p()
+    _check(lib().oracle_slayout_xor_right_inverse(a._h, ctypes.byref(h)), "xor_right_inverse(%s)" % a)
+    return SLayout(_handle=h)
 
 
 def _tuple_text(c):

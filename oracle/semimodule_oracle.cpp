@@ -261,4 +261,45 @@ Status right_inverse(const SLayout& A, Layout* R) {
   return OK;
 }
 
+Status xor_right_inverse(const SLayout& A, SLayout* R) {
+  if (kind_of(A) != Elem::XOR) return ERR_INVALID_ARG;
+  const int64_t n = size(A.shape);
+  if (n > (int64_t(1) << 24)) return ERR_INVALID_ARG;   // the definition is applied by enumeration
+  std::vector<int64_t> x;   // x[b]: smallest integral coordinate whose offset is 2^b
+  for (int b = 0; b < 62; ++b) {
+    int64_t found = -1;
+    for (int64_t i = 0; i < n && found < 0; ++i)
+      if (eval(A, i)[0] == (int64_t(1) << b)) found = i;
+    if (found < 0) break;
+    x.push_back(found);
+  }
+  // the longest prefix of them for which the defining property holds, coordinate by coordinate
+  for (size_t j = x.size();; --j) {
+    SLayout out;
+    std::vector<HTuple> leaves_;
+    if (j == 0) {
+      out.shape = HTuple::Int(1);
+      out.stride.push_back(Elem{});
+    } else {
+      for (size_t b = 0; b < j; ++b) {
+        leaves_.push_back(HTuple::Int(2));
+        Elem e;
+        e.kind = Elem::XOR;
+        e.a = x[b];
+        out.stride.push_back(e);
+      }
+      out.shape = j == 1 ? leaves_[0] : HTuple::Tup(leaves_);
+    }
+    bool holds = true;
+    for (int64_t k = 0; k < (int64_t(1) << j) && holds; ++k) {
+      const int64_t c = eval(out, k)[0];
+      holds = c >= 0 && c < n && eval(A, c)[0] == k;
+    }
+    if (holds) {
+      *R = out;
+      return OK;
+    }
+  }
+}
+
 }  // namespace oracle

@@ -39,5 +39,12 @@ SLayout coalesce(const SLayout& A);
 // Right-inverse of a coordinate layout (Table rinv, rows with e_i strides): an integer layout on the
 // largest box of coordinates starting at 0, axis by axis, with L(R(c)) = c.
 Status right_inverse(const SLayout& A, Layout* R);
+// Right-inverse of a layout with XOR strides (Table rinv, last row: "possible to define"; this reading).  Offsets add by XOR,
+// so the inverse is sought among layouts that add by XOR too: R = (2,...,2):(f_x0, f_x1, ...) over the bits of k, where x_b is the
+// SMALLEST integral coordinate of A with A(x_b) = 2^b, for b = 0, 1, ... up to the first power of two A does not reach.
+// R(k) is then the XOR of the x_b of k's set bits.  Of these modes the longest prefix is kept for which R(k) is an integral
+// coordinate of A and A(R(k)) = k for every k < |R| (XOR of coordinates need not be additive under A: an extent that is no
+// power of two, a stride whose multiples inside a mode meet a carry); nothing left: 1:0.
+Status xor_right_inverse(const SLayout& A, SLayout* R);
 
 }  // namespace oracle
