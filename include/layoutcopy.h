@@ -191,6 +191,12 @@ lc_status_t lc_slayout_eval(const lc_slayout_t* layout, int64_t integral_coord, 
 lc_status_t lc_slayout_composition(const lc_slayout_t* a, const lc_layout_t* b, lc_slayout_t** out);
 lc_status_t lc_slayout_coalesce(const lc_slayout_t* a, lc_slayout_t** out);
 lc_status_t lc_slayout_right_inverse(const lc_slayout_t* a, lc_layout_t** out);
+/* lc_slayout_xor_right_inverse: layouts with XOR strides (Table rinv, last row, which only says that one can be defined; this
+ * reading): *out = (2,...,2):(f_x0, f_x1, ...), x_b the smallest integral coordinate of a whose offset is 2^b, up to the first power
+ * of two a does not reach (nothing: 1:0); then a(out(k)) = k for every k < size(out).  Host work only.  a must be additive over XOR
+ * of integral coordinates -- extents powers of two, no carry among a stride's multiples inside its mode -- else LC_ERR_INVALID_ARG;
+ * the caller destroys *out. */
+lc_status_t lc_slayout_xor_right_inverse(const lc_slayout_t* a, lc_slayout_t** out);
 
 /* ---------------------------------------------------------------------------------------------
  * COPY (Sec. 2.6.1): dst(i) = src(i) for i in [0, size(dst)), executed on the GPU.

@@ -76,6 +76,7 @@ def lib():
     L.lc_slayout_composition.argtypes = [P, P, PP]
     L.lc_slayout_coalesce.argtypes = [P, PP]
     L.lc_slayout_right_inverse.argtypes = [P, PP]
+    L.lc_slayout_xor_right_inverse.argtypes = [P, PP]
     L.lc_layout_min_offset.argtypes = [P]
     L.lc_layout_min_offset.restype = i64
     L.lc_max_common_vector.argtypes = [P, P, ctypes.POINTER(i64)]
@@ -258,6 +259,13 @@ def lc_slayout_right_inverse(a):
     h = ctypes.c_void_p()
     _check(lib().lc_slayout_right_inverse(a._h, ctypes.byref(h)), "lc_slayout_right_inverse(%s)" % a)
     return Layout(_handle=h)
+
+
+def lc_slayout_xor_right_inverse(a):
+    a = _as_slayout(a)
+    h = ctypes.c_void_p()
+    _check(lib().lc_slayout_xor_right_inverse(a._h, ctypes.byref(h)), "lc_slayout_xor_right_inverse(%s)" % a)
+    return SLayout(_handle=h)
 
 
 def lc_complement(a, cotarget=0):

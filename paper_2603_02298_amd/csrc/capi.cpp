@@ -382,5 +382,17 @@ lc_status_t lc_slayout_right_inverse(const lc_slayout_t* a, lc_layout_t** out) {
     return LC_ERR_INVALID_ARG;
   }
 }
+lc_status_t lc_slayout_xor_right_inverse(const lc_slayout_t* a, lc_slayout_t** out) {
+  if (!a || !out) return LC_ERR_INVALID_ARG;
+  try {
+    lc::SemiLayout r;
+    lc_status_t st = lc::xor_right_inverse(a->L, &r);
+    if (st != LC_OK) return st;
+    *out = new lc_slayout{r};
+    return LC_OK;
+  } catch (...) {
+    return LC_ERR_INVALID_ARG;
+  }
+}
 
 }  // extern "C"

@@ -242,4 +242,83 @@ lc_status_t right_inverse(const SemiLayout& a, Layout* out) {
   return LC_OK;
 }
 
+lc_status_t xor_right_inverse(const SemiLayout& a, SemiLayout* out) {
+  if (a.kind() != SemiStride::Xor) return LC_ERR_INVALID_ARG;
+  // column t of the matrix: what bit t of the integral coordinate adds (by XOR) to the offset
+  std::vector<uint64_t> col;
+  for (size_t k = 0; k < a.extent.size(); ++k) {
+    const int64_t e = a.extent[k];
+    if (e < 1 || (e & (e - 1)) != 0) return LC_ERR_INVALID_ARG;
+    int bits = 0;
+    while ((int64_t(1) << bits) < e) ++bits;
+    const uint64_t d = (uint64_t)a.stride[k].a;
+    if (a.stride[k].a < 0 || (bits > 0 && d >= (uint64_t(1) << (62 - bits)))) return LC_ERR_INVALID_ARG;
+    // c * d for c < 2^bits equals the XOR of d << u over the bits u of c exactly when those shifted copies share no bit
+    uint64_t seen = 0;
+    for (int u = 0; u < bits; ++u) {
+      if (seen & (d << u)) return LC_ERR_INVALID_ARG;
+      seen |= d << u;
+      col.push_back(d << u);
+    }
+  }
+  const int n = (int)col.size();
+  if (n > 62) return LC_ERR_INVALID_ARG;
+  // elimination: a basis of the image, each vector with the coordinate that produces it, and the coordinates that produce 0
+  struct Row { uint64_t image, coord; };
+  std::vector<Row> basis;          // distinct leading bits of `image`
+  std::vector<uint64_t> kernel;    // coordinates A sends to 0, reduced to distinct leading bits below
+  auto reduce = [&](Row r) {
+    for (const Row& b : basis) {
+      const uint64_t lead = uint64_t(1) << (63 - __builtin_clzll(b.image));
+      if (r.image & lead) { r.image ^= b.image; r.coord ^= b.coord; }
+    }
+    return r;
+  };
+  for (int t = 0; t < n; ++t) {
+    Row r = reduce(Row{col[(size_t)t], uint64_t(1) << t});
+    if (r.image == 0) { kernel.push_back(r.coord); continue; }
+    basis.push_back(r);
+    std::sort(basis.begin(), basis.end(), [](const Row& x, const Row& y) { return x.image > y.image; });
+  }
+  // kernel vectors with distinct leading bits, highest first: subtracting them greedily gives the smallest member of a coset
+  std::vector<uint64_t> kred;
+  for (uint64_t v : kernel) {
+    for (uint64_t w : kred) {
+      const uint64_t lead = uint64_t(1) << (63 - __builtin_clzll(w));
+      if (v & lead) v ^= w;
+    }
+    if (v) {
+      kred.push_back(v);
+      std::sort(kred.begin(), kred.end(), [](uint64_t x, uint64_t y) { return x > y; });
+    }
+  }
+  // full reduction of kred so that a vector's leading bit appears in no other vector
+  for (size_t i = 0; i < kred.size(); ++i) {
+    const uint64_t lead = uint64_t(1) << (63 - __builtin_clzll(kred[i]));
+    for (size_t j = 0; j < kred.size(); ++j)
+      if (j != i && (kred[j] & lead)) kred[j] ^= kred[i];
+  }
+  std::sort(kred.begin(), kred.end(), [](uint64_t x, uint64_t y) { return x > y; });
+  SemiLayout r;
+  for (int b = 0; b < 62; ++b) {
+    Row want = reduce(Row{uint64_t(1) << b, 0});
+    if (want.image != 0) break;          // 2^b is not in the image
+    uint64_t x = want.coord;            // A(x) = 2^b
+    for (uint64_t v : kred) {
+      const uint64_t lead = uint64_t(1) << (63 - __builtin_clzll(v));
+      if (x & lead) x ^= v;
+    }
+    r.extent.push_back(2);
+    SemiStride st;
+    st.kind = SemiStride::Xor;
+    st.a = (int64_t)x;
+    r.stride.push_back(st);
+  }
+  if (r.extent.empty()) { r.extent.push_back(1); r.stride.push_back(SemiStride{}); }
+  if (r.extent.size() == 1) r.profile = {0};
+  else { r.profile.assign(r.extent.size() + 1, 0); r.profile[0] = (int32_t)r.extent.size(); }
+  *out = r;
+  return LC_OK;
+}
+
 }  // namespace lc

@@ -33,6 +33,12 @@ lc_status_t parse(const char* text, SemiLayout* out);
 lc_status_t composition(const SemiLayout& a, const Layout& b, SemiLayout* out);   // Sec. 3.3, "Reductive case: Coordinate"
 SemiLayout coalesce(const SemiLayout& a);                                        // Sec. 3.2 in the semimodule
 lc_status_t right_inverse(const SemiLayout& a, Layout* out);                      // Table rinv, rows with e_i strides
+// Table rinv, last row: a layout with XOR strides whose function is additive over XOR of integral coordinates (extents
+// powers of two, no carry among a stride's multiples inside its mode) is a matrix over F2 from the coordinate's bits to the
+// offset's bits.  R = (2,...,2):(f_x0, f_x1, ...) with x_b the smallest integral coordinate that A sends to 2^b, for
+// b = 0, 1, ... up to the first power of two outside A's image; A(R(k)) = k for every k < |R|.  By elimination over F2;
+// layouts that are not additive are refused (LC_ERR_INVALID_ARG).
+lc_status_t xor_right_inverse(const SemiLayout& a, SemiLayout* out);
 
 }  // namespace lc
 

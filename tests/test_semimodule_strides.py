@@ -294,3 +294,125 @@ def test_errors():
     with pytest.raises(lc.LayoutCopyError) as e:
         lc.lc_slayout_composition("(8,8):(e0,e1)", "(4,3):(3,1)")     # stride 3 does not divide into the modes of (8,8)
     assert e.value.status_name in ("STRIDE_DIVISIBILITY", "SHAPE_DIVISIBILITY")
+
+
+# ---------------------------------------------------------------------------------------------
+# Right-inverse of layouts with XOR strides (Table rinv, last row: "possible to define"; the reading taken here:
+# R = (2,...,2):(f_x0, f_x1, ...), x_b the smallest integral coordinate whose offset is 2^b, A(R(k)) = k on all of R).
+# The printed FORM is this build's choice (parity unpinned); the defining property, the size and the special cases are pinned.
+# ---------------------------------------------------------------------------------------------
+def _brute_xor_right_inverse_size(A):
+    """Largest j with a function r on [0, 2^j) that is a XOR layout over the bits of k and inverts A: found independently
+    of either implementation by trying, for growing j, whether the smallest preimages of 2^0 .. 2^(j-1) combine."""
+    img = [A(i) for i in range(A.size)]
+    first = {}
+    for i, v in enumerate(img):
+        first.setdefault(v, i)
+    xs = []
+    while (1 << len(xs)) in first:
+        xs.append(first[1 << len(xs)])
+    for j in range(len(xs), -1, -1):
+        ok = True
+        for k in range(1 << j):
+            c = 0
+            for b in range(j):
+                if (k >> b) & 1:
+                    c ^= xs[b]
+            if c >= A.size or img[c] != k:
+                ok = False
+                break
+        if ok:
+            return j, xs[:j]
+    return 0, []
+
+
+def test_xor_right_inverse_oracle_pins(oracle):
+    # the swizzle of Table TVLayoutExamples' Swizzled row is its own inverse (XOR-ing bit 3.. into bit 0.. twice is the identity)
+    r = oracle.slayout_xor_right_inverse("(8,8):(f1,f9)")
+    assert str(r) == "(2,2,2,2,2,2):(f1,f2,f4,f9,f18,f36)"
+    assert all(oracle.SLayout("(8,8):(f1,f9)")(r(k)) == k for k in range(64)) and all(r(k) == oracle.SLayout("(8,8):(f1,f9)")(k) for k in range(64))
+    # Table rinv's own XOR example, (4,(4,3)):(f1,(f5,f16)): offsets 0..31 are inverted; 32 is reached (coordinate 32) but
+    # 16 xor 32 = 48 is no coordinate of a 48-element layout
+    A = oracle.SLayout("(4,(4,3)):(f1,(f5,f16))")
+    r = oracle.slayout_xor_right_inverse(A)
+    assert r.size == 32 and all(A(r(k)) == k for k in range(32))
+    # strides that are plain powers of two: XOR is addition, the inverse is the ordinary right-inverse of the integer layout
+    for text, ints in (("(4,4):(f1,f4)", "(4,4):(1,4)"), ("(8,2,4):(f8,f1,f2)", "(8,2,4):(8,1,2)"), ("(4,2):(f2,f1)", "(4,2):(2,1)")):
+        r, ri = oracle.slayout_xor_right_inverse(text), oracle.right_inverse(ints)
+        assert r.size == ri.size and all(r(k) == ri(k) for k in range(r.size)), (text, str(r), str(ri))
+    # nothing to invert: 1 is not in the image; a carry inside a mode (3 * f3 = f9, not f3 xor f6) ends the inverse early
+    assert str(oracle.slayout_xor_right_inverse("(4,4):(f3,f12)")) == "1:0"
+    A = oracle.SLayout("(4,4):(f1,f3)")
+    r = oracle.slayout_xor_right_inverse(A)
+    assert r.size == 8 and all(A(r(k)) == k for k in range(8))
+    # brute force: random XOR layouts, additive or not; the size is the largest that works, the modes are the smallest preimages
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        rank = int(rng.integers(1, 4))
+        ext = [int(rng.choice([2, 3, 4, 8])) for _ in range(rank)]
+        strides = [int(rng.integers(0, 40)) for _ in range(rank)]
+        text = "(%s):(%s)" % (",".join(map(str, ext)), ",".join("f%d" % d if d else "0" for d in strides))
+        if all(d == 0 for d in strides):
+            continue
+        A = oracle.SLayout(text)
+        j, xs = _brute_xor_right_inverse_size(A)
+        r = oracle.slayout_xor_right_inverse(A)
+        assert r.size == (1 << j), (text, str(r), j)
+        assert all(A(r(k)) == k for k in range(r.size)), text
+        if j:
+            assert str(r) == ("(%s):(%s)" % (",".join(["2"] * j), ",".join("f%d" % x for x in xs)) if j > 1 else "2:f%d" % xs[0]), (text, str(r), xs)
+
+
+def test_xor_right_inverse_library_against_oracle(oracle):
+    # the library eliminates over F2 (layouts that are additive over XOR of coordinates); the oracle applies the definition
+    cases = ["(8,8):(f1,f9)", "(4,4):(f1,f5)", "(4,4):(f1,f4)", "(8,2,4):(f8,f1,f2)", "(4,2):(f2,f1)", "(4,4):(f3,f12)",
+             "(2,2,2,2,2,2,2,2,2,2,2):(f1,f2,f4,f8,f16,f32,f65,f130,f260,f512,f1024)",     # the LDS slot layout of workload 2's tiles
+             "(2,2,2,2):(f1,f1,f2,f4)",                                                  # not injective: the smallest preimage is taken
+             "(4,4,4):(f1,f1,f4)", "(2,4,2):(f6,f1,f4)", "(16,4):(f3,f48)"]
+    rng = np.random.default_rng(6)
+    for _ in range(200):
+        rank = int(rng.integers(1, 5))
+        ext = [int(rng.choice([2, 4, 8])) for _ in range(rank)]
+        text = "(%s):(%s)" % (",".join(map(str, ext)), ",".join("f%d" % int(rng.integers(1, 64)) for _ in range(rank)))
+        cases.append(text)
+    for _ in range(200):   # strides of one or two bits far enough apart that a mode's multiples meet no carry: always additive
+        rank = int(rng.integers(1, 5))
+        ext = [int(rng.choice([2, 4, 8])) for _ in range(rank)]
+        ds = []
+        for e in ext:
+            lo = int(rng.integers(0, 6))
+            d = 1 << lo
+            if rng.integers(0, 2):
+                d |= 1 << (lo + e.bit_length() - 1 + int(rng.integers(0, 3)))
+            ds.append(d)
+        cases.append("(%s):(%s)" % (",".join(map(str, ext)), ",".join("f%d" % d for d in ds)))
+    checked = 0
+    for text in cases:
+        want = oracle.slayout_xor_right_inverse(text)
+        try:
+            got = lc.lc_slayout_xor_right_inverse(text)
+        except lc.LayoutCopyError as e:
+            # refused: some stride's multiples carry inside its mode (the oracle's inverse then stops where additivity does)
+            assert e.status_name == "INVALID_ARG", text
+            A = oracle.SLayout(text)
+            ext = [int(x) for x in text.split(":")[0].strip("()").split(",")]
+            ds = [int(x[1:]) for x in text.split(":")[1].strip("()").split(",")]
+            assert any(any(c * d != _xor_multiples(c, d) for c in range(e_)) for e_, d in zip(ext, ds)), text
+            continue
+        assert str(got) == str(want), (text, str(got), str(want))
+        A = lc.SLayout(text)
+        assert all(A(got(k)) == k for k in range(got.size)), text
+        checked += 1
+    assert checked > 200
+    for bad in ("(3,4):(f1,f4)", "(4,4):(f1,f3)", "(4,4):(1,4)", "(4,4):(e0,e1)"):
+        with pytest.raises(lc.LayoutCopyError):
+            lc.lc_slayout_xor_right_inverse(bad)
+
+
+def _xor_multiples(c, d):
+    r, u = 0, 0
+    while c >> u:
+        if (c >> u) & 1:
+            r ^= d << u
+        u += 1
+    return r
