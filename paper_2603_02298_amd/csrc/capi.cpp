@@ -274,7 +274,7 @@ lc_status_t lc_copy(const void* src, const lc_layout_t* src_layout, void* dst, c
     for (int64_t v : {(int64_t)tune.micro_per_thread, (int64_t)tune.rest_order, (int64_t)tune.wgs_per_cu, (int64_t)tune.unroll,
                       (int64_t)tune.swizzle_shift, (int64_t)tune.nontemporal, (int64_t)tune.blocked, tune.max_items, (int64_t)tune.force_class,
                       (int64_t)tune.max_vec_bytes, (int64_t)tune.tile_queue, (int64_t)tune.queue_rounds, (int64_t)tune.queue_counters,
-                      (int64_t)tune.leftover_lead, (int64_t)tune.grid, (int64_t)tune.early_loads, (int64_t)tune.gather})
+                      (int64_t)tune.leftover_lead, (int64_t)tune.grid, (int64_t)tune.early_loads, (int64_t)tune.gather, (int64_t)tune.direct_queue})
       key += "," + std::to_string(v);
     for (int64_t v : tune.tile) key += ";" + std::to_string(v);
     std::shared_ptr<const lc_plan_t> plan = copy_plans().find(key);

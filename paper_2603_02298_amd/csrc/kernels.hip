@@ -93,6 +93,25 @@ __global__ __launch_bounds__(kBlock) void last_writer_move_kernel(GenericParams 
   }
 }
 
+// Tile queues: blocks of counters in device memory that belongs to the library's code object: nothing is allocated.
+// A block is kQueueLines lines of 128 bytes with one counter at the start of each, so that no two counters share a cache
+// line: line 0 counts the workgroups that are done, lines 1.. count the tiles handed out (a launch spreads its requests
+// over up to kQueueLines - 1 of them, workgroup w asking counter w mod n).  Launches on one stream run one after the
+// other, so a stream keeps one block for good; the host hands out kTileQueues blocks and launches on further streams, or
+// under graph capture, use the fixed order.
+constexpr int kTileQueues = 64;
+constexpr int kQueueLines = 16;
+constexpr int kQueueLineWords = 32;   // 128 bytes
+constexpr int kQueueBlockWords = kQueueLines * kQueueLineWords;
+__device__ __attribute__((aligned(256))) unsigned int g_tile_queues[kTileQueues * kQueueBlockWords];
+__device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
+  if (atomicAdd(&queue[0], 1u) == gridDim.x - 1u) {   // the last workgroup out: nobody asks any more
+#pragma unroll
+    for (int c = 0; c < kQueueLines; ++c) queue[c * kQueueLineWords] = 0u;
+    __threadfence();
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Direct: one W-byte access per item and side; lanes are consecutive along the destination order.
 // U items are in flight per lane; an optional looped mode re-uses a loaded value when its source
@@ -149,6 +168,85 @@ __device__ __forceinline__ void direct_body(const typename Word<W>::type* __rest
   }
 }
 
+// The same work handed out on request: the items are cut into chunks of chunk_items consecutive items (about 32 KiB of
+// destination), wavefront w starts on chunk w and asks a counter for every further one -- lane 0 asks, one chunk ahead, and
+// the answer reaches the other lanes by v_readfirstlane: no barrier, no LDS.  In a grid-stride loop over gigabytes the
+// workgroups drift apart and what is in flight at any moment spreads over memory; chunks taken in the order of asking keep
+// it one compact window (measured on MI355X, plain copy of 2 x 2 GiB: 72-75 -> 76-77 % of the HBM peak; at 2 x 1 GiB and below
+// the fixed order is faster, so the planner asks for chunks from 2 GiB per side on).  Counter c of n_counters hands out the chunks waves + c, waves + c + n_counters, ...; queue[0] counts
+// the wavefronts that are done and the last one puts the counters back to zero (see the tile queues above).
+template <int W, int U, int NT, bool LINEAR, class Offsets>
+__device__ __forceinline__ void direct_body_on_request(const typename Word<W>::type* __restrict__ src, typename Word<W>::type* __restrict__ dst,
+                                                       uint32_t n_items, uint32_t loop_extent, int64_t loop_sa, int64_t loop_sb,
+                                                       unsigned int* queue, uint32_t chunk_items, uint32_t n_counters,
+                                                       int64_t lin_sa, int64_t lin_sb, Offsets offsets) {
+  typedef typename Word<W>::type T;
+  const uint32_t lane = threadIdx.x & 63u, wave = (blockIdx.x * kBlock + threadIdx.x) >> 6, waves = gridDim.x * (kBlock / 64u);
+  const uint32_t n_chunks = (n_items + chunk_items - 1u) / chunk_items, c = wave % n_counters;
+  unsigned int* counter = queue + (1u + c) * kQueueLineWords;
+  uint32_t chunk = wave;
+  while (chunk < n_chunks) {
+    uint32_t asked = 0;
+    if (lane == 0) asked = atomicAdd(counter, 1u);
+    const uint32_t first = chunk * chunk_items;
+    if (LINEAR && loop_extent == 1 && n_items - first >= chunk_items) {
+      // one joint mode: the offsets are item * stride, so a lane steps two pointers through the chunk
+      const T* sp = src + (int64_t)(first + lane) * lin_sa;
+      T* dp = dst + (int64_t)(first + lane) * lin_sb;
+      const int64_t s64 = 64 * lin_sa, d64 = 64 * lin_sb;
+      for (uint32_t t = 0; t < chunk_items; t += 64u * U, sp += U * s64, dp += U * d64) {
+        T v[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) v[j] = gload<NT>(sp + j * s64);
+#pragma unroll
+        for (int j = 0; j < U; ++j) gstore<NT>(dp + j * d64, v[j]);
+      }
+    } else if (n_items - first >= chunk_items) {
+      // a whole chunk (chunk_items is a multiple of 64 U): no lane is ever idle, so nothing here is predicated and the U
+      // loads of a trip go out together
+      for (uint32_t base = first + lane; base < first + chunk_items; base += 64u * U) {
+        int64_t so[U], dof[U];
+        T v[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) offsets(base + (uint32_t)j * 64u, &so[j], &dof[j]);
+        if (loop_extent == 1) {
+#pragma unroll
+          for (int j = 0; j < U; ++j) v[j] = gload<NT>(src + so[j]);
+#pragma unroll
+          for (int j = 0; j < U; ++j) gstore<NT>(dst + dof[j], v[j]);
+        } else {
+          for (uint32_t r = 0; r < loop_extent; ++r) {
+            if (r == 0 || loop_sa != 0) {
+#pragma unroll
+              for (int j = 0; j < U; ++j) v[j] = gload<NT>(src + so[j] + (int64_t)r * loop_sa);
+            }
+#pragma unroll
+            for (int j = 0; j < U; ++j) gstore<NT>(dst + dof[j] + (int64_t)r * loop_sb, v[j]);
+          }
+        }
+      }
+    } else {
+      // the last, short chunk: item by item
+      for (uint32_t it = first + lane; it < n_items; it += 64u) {
+        int64_t so, dof;
+        offsets(it, &so, &dof);
+        T v = gload<NT>(src + so);
+        for (uint32_t r = 0; r < loop_extent; ++r) {
+          if (r != 0 && loop_sa != 0) v = gload<NT>(src + so + (int64_t)r * loop_sa);
+          gstore<NT>(dst + dof + (int64_t)r * loop_sb, v);
+        }
+      }
+    }
+    asked = (uint32_t)__builtin_amdgcn_readfirstlane((int)asked);
+    chunk = waves + c + asked * n_counters;
+  }
+  if (lane == 0 && atomicAdd(&queue[0], 1u) == waves - 1u) {   // the last wavefront out: nobody asks any more
+#pragma unroll
+    for (int k = 0; k < kQueueLines; ++k) queue[k * kQueueLineWords] = 0u;
+    __threadfence();
+  }
+}
+
 // The leading scalar arguments (fourteen dwords, preloaded into scalar registers where the hardware does it) describe a
 // copy over ONE joint mode completely (a plain copy, a strided gather or scatter, a broadcast): with h_ctl's bit 0 set the
 // kernel never reads the argument block and its first loads wait for no memory.  h_ctl: bit 0 valid, bit 1 blocked,
@@ -156,7 +254,19 @@ __device__ __forceinline__ void direct_body(const typename Word<W>::type* __rest
 template <int W, int U, int NT>
 __global__ __launch_bounds__(kBlock) void direct_kernel(const typename Word<W>::type* __restrict__ src, typename Word<W>::type* __restrict__ dst,
                                                        uint32_t h_ctl, uint32_t h_items, int64_t h_sa, int64_t h_sb, int64_t h_loop_sa,
-                                                       int64_t h_loop_sb, DirectParams P) {
+                                                       int64_t h_loop_sb, DirectParams P, unsigned int* queue, uint32_t chunk_items,
+                                                       uint32_t n_counters) {
+  if (queue != nullptr) {   // long copies: chunks on request
+    if (h_ctl & 1u) {
+      direct_body_on_request<W, U, NT, true>(src, dst, h_items, h_ctl >> 2, h_loop_sa, h_loop_sb, queue, chunk_items, n_counters, h_sa, h_sb,
+                                             [&](uint32_t item, int64_t* so, int64_t* dof) { *so = (int64_t)item * h_sa; *dof = (int64_t)item * h_sb; });
+      return;
+    }
+    touch_kernel_arguments<(int)sizeof(DirectParams) + 64>();
+    direct_body_on_request<W, U, NT, false>(src, dst, P.n_items, P.loop_extent, P.loop_sa, P.loop_sb, queue, chunk_items, n_counters, 0, 0,
+                                            [&](uint32_t item, int64_t* so, int64_t* dof) { direct_offsets(P, item, so, dof); });
+    return;
+  }
   if (h_ctl & 1u) {
     direct_body<W, U, NT>(src, dst, h_items, (h_ctl & 2u) != 0, h_ctl >> 2, h_loop_sa, h_loop_sb,
                           [&](uint32_t item, int64_t* so, int64_t* dof) { *so = (int64_t)item * h_sa; *dof = (int64_t)item * h_sb; });
@@ -269,25 +379,6 @@ __device__ __forceinline__ void micro_transpose(const uint32_t (&r)[V][V * ES / 
         uint32_t lo = r[2 * j][ip / 2], hi = r[2 * j + 1][ip / 2];
         o[ip][j] = (ip % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
       }
-  }
-}
-
-// Tile queues: blocks of counters in device memory that belongs to the library's code object: nothing is allocated.
-// A block is kQueueLines lines of 128 bytes with one counter at the start of each, so that no two counters share a cache
-// line: line 0 counts the workgroups that are done, lines 1.. count the tiles handed out (a launch spreads its requests
-// over up to kQueueLines - 1 of them, workgroup w asking counter w mod n).  Launches on one stream run one after the
-// other, so a stream keeps one block for good; the host hands out kTileQueues blocks and launches on further streams, or
-// under graph capture, use the fixed order.
-constexpr int kTileQueues = 64;
-constexpr int kQueueLines = 16;
-constexpr int kQueueLineWords = 32;   // 128 bytes
-constexpr int kQueueBlockWords = kQueueLines * kQueueLineWords;
-__device__ __attribute__((aligned(256))) unsigned int g_tile_queues[kTileQueues * kQueueBlockWords];
-__device__ __forceinline__ void leave_tile_queue(unsigned int* queue) {
-  if (atomicAdd(&queue[0], 1u) == gridDim.x - 1u) {   // the last workgroup out: nobody asks any more
-#pragma unroll
-    for (int c = 0; c < kQueueLines; ++c) queue[c * kQueueLineWords] = 0u;
-    __threadfence();
   }
 }
 
@@ -630,7 +721,7 @@ static void launch_generic(const lc_plan& plan, const void* src, void* dst, unsi
 }
 
 template <int W, int U>
-static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s, unsigned int* queue) {
   typedef typename Word<W>::type T;
   const T* sp = static_cast<const T*>(src);
   T* dp = static_cast<T*>(dst);
@@ -640,11 +731,12 @@ static void launch_direct_u(const lc_plan& plan, const void* src, void* dst, uns
   if (plan.early_loads && P.n_modes == 1 && P.loop_extent < (1u << 30)) ctl = 1u | (P.blocked ? 2u : 0u) | (P.loop_extent << 2);
   const uint32_t items = P.n_items;
   const int64_t sa = P.sa[0], sb = P.sb[0], lsa = P.loop_sa, lsb = P.loop_sb;
+  const uint32_t chunk = (uint32_t)((std::max(1, plan.direct_queue_items) + 64 * U - 1) / (64 * U) * (64 * U)), counters = (uint32_t)std::max(1, std::min(plan.queue_counters, kQueueLines - 1));
   switch (plan.nontemporal) {
-    case 0: hipLaunchKernelGGL((direct_kernel<W, U, 0>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
-    case 1: hipLaunchKernelGGL((direct_kernel<W, U, 1>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
-    case 2: hipLaunchKernelGGL((direct_kernel<W, U, 2>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
-    default: hipLaunchKernelGGL((direct_kernel<W, U, 3>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P); break;
+    case 0: hipLaunchKernelGGL((direct_kernel<W, U, 0>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P, queue, chunk, counters); break;
+    case 1: hipLaunchKernelGGL((direct_kernel<W, U, 1>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P, queue, chunk, counters); break;
+    case 2: hipLaunchKernelGGL((direct_kernel<W, U, 2>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P, queue, chunk, counters); break;
+    default: hipLaunchKernelGGL((direct_kernel<W, U, 3>), dim3(grid), dim3(kBlock), 0, s, sp, dp, ctl, items, sa, sb, lsa, lsb, P, queue, chunk, counters); break;
   }
 }
 template <int ES, int GS>
@@ -667,12 +759,12 @@ static bool launch_gather(const lc_plan& plan, const void* src, void* dst, unsig
   return false;
 }
 template <int W>
-static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s) {
+static void launch_direct(const lc_plan& plan, const void* src, void* dst, unsigned grid, hipStream_t s, unsigned int* queue) {
   switch (plan.unroll) {
-    case 1: launch_direct_u<W, 1>(plan, src, dst, grid, s); break;
-    case 2: launch_direct_u<W, 2>(plan, src, dst, grid, s); break;
-    case 8: launch_direct_u<W, 8>(plan, src, dst, grid, s); break;
-    default: launch_direct_u<W, 4>(plan, src, dst, grid, s); break;
+    case 1: launch_direct_u<W, 1>(plan, src, dst, grid, s, queue); break;
+    case 2: launch_direct_u<W, 2>(plan, src, dst, grid, s, queue); break;
+    case 8: launch_direct_u<W, 8>(plan, src, dst, grid, s, queue); break;
+    default: launch_direct_u<W, 4>(plan, src, dst, grid, s, queue); break;
   }
 }
 
@@ -910,6 +1002,12 @@ static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst,
   } else if (plan.cls == KernelClass::Direct) {
     uint64_t want = ((uint64_t)plan.direct.n_items + (uint64_t)kBlock * plan.unroll - 1) / ((uint64_t)kBlock * plan.unroll);
     unsigned grid = (unsigned)std::max<uint64_t>(1, std::min<uint64_t>(want, plan.grid_override > 0 ? (uint64_t)plan.grid_override : (uint64_t)cus * plan.wgs_per_cu));
+    // long copies take their chunks on request, through the stream's block of counters (none to be had: the fixed order)
+    unsigned int* dq = nullptr;
+    if (plan.direct_queue_items > 0 && plan.gather_stride == 0) {
+      pre.status = tile_queue_of_stream(s, &dq, &pre.call);
+      if (hip_failed(pre.status, pre.call)) return LC_ERR_HIP;
+    }
     for (int64_t j = 0; j < plan.n_launches; ++j) {
       const void* sj = static_cast<const unsigned char*>(src) + j * plan.launch_src_step * plan.elem_bytes;
       void* dj = static_cast<unsigned char*>(dst) + j * plan.launch_dst_step * plan.elem_bytes;
@@ -924,11 +1022,11 @@ static lc_status_t execute_with(const lc_plan& plan, const void* src, void* dst,
         continue;
       }
       switch (plan.width_bytes) {
-        case 1: launch_direct<1>(plan, sj, dj, grid, s); break;
-        case 2: launch_direct<2>(plan, sj, dj, grid, s); break;
-        case 4: launch_direct<4>(plan, sj, dj, grid, s); break;
-        case 8: launch_direct<8>(plan, sj, dj, grid, s); break;
-        case 16: launch_direct<16>(plan, sj, dj, grid, s); break;
+        case 1: launch_direct<1>(plan, sj, dj, grid, s, dq); break;
+        case 2: launch_direct<2>(plan, sj, dj, grid, s, dq); break;
+        case 4: launch_direct<4>(plan, sj, dj, grid, s, dq); break;
+        case 8: launch_direct<8>(plan, sj, dj, grid, s, dq); break;
+        case 16: launch_direct<16>(plan, sj, dj, grid, s, dq); break;
         default: return LC_ERR_UNSUPPORTED_DTYPE;
       }
     }

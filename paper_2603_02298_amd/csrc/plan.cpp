@@ -29,6 +29,7 @@ Tuning tuning_from_env() {
   t.grid = env_int("LC_TUNE_GRID", t.grid);
   t.early_loads = env_int("LC_TUNE_EARLY_LOADS", t.early_loads);
   t.gather = env_int("LC_TUNE_GATHER", t.gather);
+  t.direct_queue = env_int("LC_TUNE_DIRECT_QUEUE", t.direct_queue);
   t.max_items = env_int("LC_TUNE_MAX_ITEMS", (int)t.max_items);
   if (const char* v = std::getenv("LC_TUNE_TILE")) {
     for (const char* p = v; *p;) {
@@ -1037,6 +1038,21 @@ lc_status_t make_plan(const Layout& src, const Layout& dst, int es, unsigned src
   int dflt_unroll = W >= 16 ? 2 : (W >= 4 ? 4 : 8), dflt_wgs = W >= 8 ? 3 : 4;   // 3 x 256 CUs: a grid that is not a power of two
   plan->unroll = (tune.unroll == 1 || tune.unroll == 2 || tune.unroll == 4 || tune.unroll == 8) ? tune.unroll : dflt_unroll;
   plan->wgs_per_cu = tune.wgs_per_cu > 0 ? tune.wgs_per_cu : dflt_wgs;
+  // Contiguous copies of 2 GiB and more per side: the grid-stride order lets workgroups drift apart, chunks of 32 KiB handed
+  // out to the wavefronts on request keep what is in flight together (measured on MI355X, plain copy, fixed order -> chunks:
+  // 2 x 4 GiB 72 -> 77 % of the HBM peak, 2 x 2 GiB 72-75 -> 76-77 %; 2 x 1 GiB 72-78 (by where the buffers lie) -> 74-75 %,
+  // 2 x 512 MiB 76 -> 70 %, the stride-3 gather of 256 MiB 82 -> 70 %: those stay with the fixed order).  Two workgroups per
+  // CU and eight counters measured best.
+  {
+    const int64_t dst_bytes = items * W * (int64_t)P.loop_extent;
+    const bool contiguous = P.n_modes == 1 && P.loop_extent == 1 && std::abs(P.sa[0]) == 1 && std::abs(P.sb[0]) == 1;
+    const int kib = tune.direct_queue >= 0 ? tune.direct_queue : (dst_bytes >= (2ll << 30) && contiguous && plan->gather_stride == 0 ? 32 : 0);
+    plan->direct_queue_items = kib > 0 ? (int)std::max<int64_t>(64 * plan->unroll, (int64_t)kib * 1024 / W) : 0;
+    if (plan->direct_queue_items > 0) {
+      if (tune.wgs_per_cu <= 0) plan->wgs_per_cu = 2;
+      plan->queue_counters = tune.queue_counters >= 1 ? tune.queue_counters : 8;
+    }
+  }
   if (tune.nontemporal < 0 && ((int64_t)W * (q >= 0 ? J[(size_t)q].extent / VEC : 1)) % 128 == 0) plan->nontemporal |= 2;
   plan->src_align = (unsigned)(VEC * es);
   plan->dst_align = (unsigned)(VEC * es);
@@ -1093,6 +1109,7 @@ std::string describe(const lc_plan& plan) {
     s += " launches=" + std::to_string(plan.n_launches);
     s += " unroll=" + std::to_string(plan.unroll);
     if (plan.gather_stride) s += " gather_stride=" + std::to_string(plan.gather_stride);
+    if (plan.direct_queue_items) s += " chunk_items=" + std::to_string(plan.direct_queue_items) + " queue_counters=" + std::to_string(plan.queue_counters);
     s += " early_loads=" + std::to_string(!plan.gather_stride && plan.early_loads && plan.direct.n_modes == 1 && plan.direct.loop_extent < (1u << 30) ? 1 : 0);
   }
   if (plan.cls == KernelClass::LastWriter) s += " workspace_bytes=" + std::to_string(plan.workspace_bytes);

@@ -34,6 +34,7 @@ struct Tuning {
   int queue_counters = -1;     // transpose: counters the requests are spread over (1..15)
   int grid = -1;               // workgroups of the launch (overrides CUs * wgs_per_cu)
   int leftover_lead = -1;      // transpose, fixed order: the tiles left after the last whole round go to this many leading workgroups
+  int direct_queue = -1;       // direct: KiB of destination per chunk handed out on request; 0 = grid-stride order
   int gather = -1;             // direct: 1 = a small source stride along the destination-contiguous mode is read in whole 16-byte words (gather_kernel)
   int early_loads = -1;        // transpose: 0 = the first loads wait for the whole argument block (no TransposeHead)
 };
@@ -62,6 +63,7 @@ struct lc_plan {
   int width_bytes = 0;                     // bytes per access (element width x vector length)
   lc::DirectParams direct{};
   int unroll = 4;
+  int direct_queue_items = 0;              // > 0: items per chunk; wavefronts take chunks on request (long copies)
   int gather_stride = 0;                   // > 0: the destination-contiguous mode is read with this stride; 16-byte words on both sides (gather_kernel)
   int64_t n_launches = 1;                  // slices along the outermost mode, one launch each
   int64_t launch_src_step = 0, launch_dst_step = 0;   // elements between consecutive slices

@@ -77,6 +77,33 @@ def test_full_size(oracle, name):
     assert torch.equal(dst.view(ref.shape), ref)
 
 
+def test_long_plain_copy_hands_chunks_out_on_request(oracle):
+    """A contiguous copy of 2 GiB per side (and a ragged tail): the size from which the planner hands the items out to
+    the wavefronts in chunks by itself.  Every element against the oracle's loop, two calls in a row."""
+    dev = torch.device("cuda:0")
+    n = (1 << 29) + 4 * 777
+    layout = "%d:1" % n
+    plan = lc.Plan(layout, layout, "f32")
+    desc = plan.describe()
+    print(desc, flush=True)
+    assert "class=direct" in desc and "chunk_items=2048" in desc, desc
+    g = torch.Generator(device=dev)
+    g.manual_seed(W.SEED_BASE + 9)
+    src = torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), device=dev, generator=g, dtype=torch.int32)
+    src_host = src.cpu().numpy().view(np.uint32)
+    want = np.full(n, 0x5A5A5A5A, dtype=np.uint32)
+    threads = oracle.host_threads(16)
+    oracle.copy_parallel(src_host, layout, want, layout, threads)
+    print("oracle walked %d integral coordinates on %d host threads" % (n, threads), flush=True)
+    for rep in range(2):
+        dst = torch.full((n,), 0x5A5A5A5A, dtype=torch.int32, device=dev)
+        lc.copy_tensor(src, layout, dst, layout, "f32")
+        torch.cuda.synchronize()
+        got = dst.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, want), "call %d differs from the oracle at offsets %s" % (rep, np.flatnonzero(got != want)[:8])
+        del dst, got
+
+
 def test_head_permute_through_word_tiles(oracle):
     """(B,S,H,D) -> (B,H,S,D) with 128-byte heads, 2^26 bf16 elements: the common vector is 8 words
     long, so the planner re-orders 16-byte words through LDS tiles instead of reading 128-byte pieces."""

@@ -239,6 +239,52 @@ def test_tile_queue(oracle, monkeypatch):
             assert "tile_queue=%d" % grab in desc, desc
 
 
+def test_direct_class_chunks_on_request(oracle, monkeypatch):
+    # the direct class with its items handed out to the wavefronts in chunks (counters of the stream's block, put back to zero
+    # by the last wavefront): forced on at sizes the oracle walks in full.  Plain copies, a strided gather, a broadcast
+    # (looped mode), several joint modes, every element width; chunks of 1, 4 and 32 KiB, 1, 8 and 15 counters, grids from
+    # one workgroup to more wavefronts than chunks; each case twice in a row (the second launch finds the counters at zero)
+    cases = [("%d:1" % n, "%d:1" % n, dt) for n in (1 << 20, (1 << 20) + 77, 5000) for dt in ("f32", "bf16", "b8", "b64")]
+    cases += [("%d:3" % (1 << 18), "%d:1" % (1 << 18), "f32"), ("(%d,16):(1,0)" % (1 << 14), "(%d,16):(1,%d)" % (1 << 14, 1 << 14), "f32"),
+              ("(256,240):(1,256)", "(256,240):(1,300)", "bf16"), ("(30,7,111):(1,30,210)", "(30,7,111):(777,111,1)", "f32")]
+    for kib, counters, grid in ((1, 8, 0), (4, 1, 7), (32, 15, 0), (1, 3, 1), (4, 8, 2000)):
+        monkeypatch.setenv("LC_TUNE_DIRECT_QUEUE", str(kib))
+        monkeypatch.setenv("LC_TUNE_QUEUE_COUNTERS", str(counters))
+        monkeypatch.setenv("LC_TUNE_FORCE_CLASS", "1")
+        if grid:
+            monkeypatch.setenv("LC_TUNE_GRID", str(grid))
+        for s_, d_, dt in cases:
+            for rep in range(2):
+                desc = _parity(oracle, s_, d_, dt, seed=31 + rep, tag="chunks %d KiB, %d counters, grid %d" % (kib, counters, grid))
+            assert "class=direct" in desc and "chunk_items=" in desc, desc
+        if grid:
+            monkeypatch.delenv("LC_TUNE_GRID")
+    # sliced into launches as well: every launch takes the counters afresh
+    monkeypatch.setenv("LC_TUNE_DIRECT_QUEUE", "1")
+    monkeypatch.setenv("LC_TUNE_MAX_ITEMS", "1000")
+    desc = _parity(oracle, "%d:3" % (1 << 14), "%d:1" % (1 << 14), "f32", seed=33, tag="chunks, sliced")
+    assert "chunk_items=" in desc and "launches=1 " not in desc, desc
+
+
+def test_direct_class_chunks_on_several_streams(oracle, monkeypatch):
+    monkeypatch.setenv("LC_TUNE_DIRECT_QUEUE", "4")
+    n = (1 << 22) + 40
+    src_layout = dst_layout = "%d:1" % n
+    dev = torch.device("cuda:0")
+    plan = lc.Plan(src_layout, dst_layout, "f32")
+    assert "chunk_items=" in plan.describe()
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    srcs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (n,), dtype=torch.int32, device=dev) for _ in streams]
+    dsts = [torch.zeros(n, dtype=torch.int32, device=dev) for _ in streams]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for st, a, d in zip(streams, srcs, dsts):
+            plan.execute(a.data_ptr(), d.data_ptr(), st.cuda_stream)
+    torch.cuda.synchronize()
+    for a, d in zip(srcs, dsts):
+        assert torch.equal(a, d)
+
+
 def test_tile_queue_after_whole_rounds_and_over_several_counters(oracle, monkeypatch):
     # the queue taking over after two (or, capped, all) whole rounds of the grid, requests spread over 8 and 15 counters;
     # and, in the fixed order, the tiles left after the last whole round going to the leading workgroups only
