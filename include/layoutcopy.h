@@ -220,12 +220,13 @@ lc_status_t lc_plan_create(const lc_layout_t* src, const lc_layout_t* dst, lc_dt
 lc_status_t lc_plan_describe(const lc_plan_t* plan, char* buf, size_t cap, size_t* needed);
 /* Enqueue the copy on `hip_stream`.  Asynchronous; allocates nothing, copies nothing, synchronises nothing (it may be
  * recorded into a HIP graph).  Errors: MISALIGNED, HIP.
- * Long transposing copies hand their tiles out through a pair of counters in device memory of the library's own code
- * object, one pair per stream (the library's launches on a stream run in stream order, which is what keeps a pair to one
- * kernel at a time); launches on more than 64 streams of a device, launches under graph capture, launches on the
- * per-thread default stream handle (hipStreamPerThread: one handle value, a different stream in every host thread) and
- * launches on a stream of another device than the current one use a fixed tile order instead.  A stream that is destroyed with such a copy still queued, and whose handle value the runtime then
- * gives to a new stream, would share its pair with it: synchronise before destroying the stream. */
+ * Long transposing copies hand their tiles, and contiguous copies of 2 GiB or more their chunks, out through a block of
+ * counters in device memory of the library's own code object, one block per stream (the library's launches on a stream
+ * run in stream order, which is what keeps a block to one kernel at a time); launches on more than 64 streams of a
+ * device, launches under graph capture, launches on the per-thread default stream handle (hipStreamPerThread: one handle
+ * value, a different stream in every host thread) and launches on a stream of another device than the current one use a
+ * fixed order instead.  A stream that is destroyed with such a copy still queued, and whose handle value the runtime then
+ * gives to a new stream, would share its block with it: synchronise before destroying the stream. */
 lc_status_t lc_plan_execute(const lc_plan_t* plan, const void* src, void* dst, void* hip_stream);
 /* Scatter with repeated destination offsets (Table copy, Sec. 2.6.1): the loop runs i upwards, so an offset that several
  * integral coordinates reach keeps the value of the largest of them.  A destination that aliases in another way than
