@@ -54,7 +54,7 @@ def test_copy_plan_in_a_graph(oracle, src_layout, dst_layout, dtype, monkeypatch
         assert (dst_t.cpu().numpy() == want).all(), (rep, plan.describe())
 
 
-@pytest.mark.parametrize("name,mnk,env_direct", [("tn", (264, 136, 128), True), ("nt", (136, 264, 128), True), ("gett", (192, 100, 72), False)])
+@pytest.mark.parametrize("name,mnk,env_direct", [("tn", (264, 136, 128), True), ("nt", (136, 264, 128), True), ("gett", (192, 100, 72), True), ("gett", (192, 100, 76), False)])   # a short last k tile on the direct path; staged loads
 def test_gemm_plan_in_a_graph(oracle, name, mnk, env_direct):
     w = W.gemm_workload(name, *mnk, ab_dtype="bf16", values="ints")
     plan = lc.GemmPlan(w.a_layout, w.b_layout, w.c_layout, "bf16")
