@@ -203,6 +203,15 @@ Status composition(const SLayout& A, const Layout& B, SLayout* R) {
     if (e.a == 0) e = Elem();
     out.stride.push_back(e);
   }
+  if (kind_of(A) == Elem::XOR) {
+    // With XOR strides the modes found above describe A o B only while, inside one leaf of A, the modes of B add up
+    // without a carry: (c0 a0 + c1 a1) d and (c0 a0 d) xor (c1 a1 d) differ as soon as two terms meet in a bit.  Composition
+    // is functional composition (Sec. 3.3), so the definition decides: R(c) = A(B(c)) on every coordinate of B, or no result.
+    const int64_t n = size(B);
+    if (n > (int64_t(1) << 24)) return ERR_INVALID_ARG;             // too large to enumerate here
+    for (int64_t c = 0; c < n; ++c)
+      if (eval(out, c) != eval(A, eval(B, c))) return ERR_NOT_SEGREGATED;
+  }
   *R = out;
   return OK;
 }

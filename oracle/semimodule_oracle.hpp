@@ -31,6 +31,8 @@ std::vector<int64_t> eval(const SLayout& L, int64_t i);
 // A o B for an integer layout B (Sec. 3.3; Table TVLayoutExamples rows Swizzled and Coordinate).
 // Admissibility depends on the shape of A and on B only; each mode of the result lies in one leaf of
 // A and takes that leaf's stride scaled by its step inside the leaf ("Reductive case: Coordinate").
+// With XOR strides that construction is A o B only while the modes of B that walk one leaf of A never meet in a bit;
+// the result is compared with A(B(c)) on every coordinate of B and refused (ERR_NOT_SEGREGATED) when it differs.
 Status composition(const SLayout& A, const Layout& B, SLayout* R);
 // Sec. 3.2 for semimodule strides: unit modes go; neighbours merge when the second stride is the first
 // scaled by the first extent AND the merged mode is the same function (always for e_i, never for f_d,

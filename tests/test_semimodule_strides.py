@@ -416,3 +416,96 @@ def _xor_multiples(c, d):
             r ^= d << u
         u += 1
     return r
+
+
+# ---------------------------------------------------------------------------------------------
+# Composition with XOR strides.  The construction of Sec. 3.3 (each mode of the result walks one leaf of A and takes that
+# leaf's stride scaled by its step) is functional composition only while the modes that walk one leaf add up without a
+# carry; the oracle compares its result with A(B(c)) and refuses otherwise.  Pinned here to hand-checked cases and to a
+# closed form of "a carry can happen" that is derived independently: mode j of the result contributes c_j * m_j with
+# m_j = step_j * d_k, and two modes in one leaf can carry iff the OR of their possible contributions share a bit.
+# ---------------------------------------------------------------------------------------------
+XOR_COMPOSITION_SIDES = ["oracle"]
+
+
+def _xor_sides(oracle, side):
+    return (oracle.slayout_composition, oracle.OracleError) if side == "oracle" else (lc.lc_slayout_composition, lc.LayoutCopyError)
+
+
+@pytest.mark.parametrize("side", XOR_COMPOSITION_SIDES)
+def test_xor_composition_hand_cases(oracle, side):
+    compose, error = _xor_sides(oracle, side)
+    # A = 4:f5, B = (2,2):(1,2): contributions {0,5} and {0,10} share no bit: R = (2,2):(f5,f10), R(1,1) = 15 = A(3)
+    R = compose("4:f5", "(2,2):(1,2)")
+    assert str(R) == "(2,2):(f5,f10)" and R(3) == 15 and oracle.SLayout("4:f5")(3) == 15
+    # A = 8:f3, B = (2,2):(1,2): {0,3} and {0,6} meet in bit 1: A(B(1,1)) = A(3) = 9 but f3 xor f6 = 5: no layout result
+    with pytest.raises(error) as e:
+        compose("8:f3", "(2,2):(1,2)")
+    assert e.value.status_name == "NOT_SEGREGATED"
+    # a single mode of B per leaf never carries, whatever the stride
+    assert str(compose("(8,8):(f3,f24)", "(4,4):(2,8)")) == "(4,4):(f6,f24)"
+
+
+def _random_xor_layout(rng):
+    n = int(rng.integers(1, 4))
+    ext = [int(rng.choice([2, 4, 8, 3, 6])) for _ in range(n)]
+    st = [int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16, 17, 24])) for _ in range(n)]
+    return "(%s):(%s)" % (",".join(map(str, ext)), ",".join("f%d" % d for d in st)) if n > 1 else "%d:f%d" % (ext[0], st[0])
+
+
+@pytest.mark.parametrize("side", XOR_COMPOSITION_SIDES)
+def test_xor_composition_is_exact_or_refused(oracle, side):
+    compose, error = _xor_sides(oracle, side)
+    rng = np.random.default_rng(235)
+    composed = refused = 0
+    for _ in range(3000):
+        A, B = _random_xor_layout(rng), _random_int_layout(rng)
+        Ao, Bo = oracle.SLayout(A), oracle.Layout(B)
+        # the closed form, from the integer composition of the proxy layouts alone: P has A's shape and place values
+        # with a gap of 2 after each leaf, so a mode of P o B with stride t walks leaf k = the last leaf whose place <= t
+        ext = [int(x) for x in A.split(":")[0].strip("()").split(",")]
+        ds = [int(x[1:]) for x in A.split(":")[1].strip("()").split(",")]
+        place, run = [], 1
+        for e_ in ext:
+            place.append(run)
+            run *= 2 * e_
+        P = "(%s):(%s)" % (",".join(map(str, ext)), ",".join(map(str, place))) if len(ext) > 1 else "%d:%d" % (ext[0], place[0])
+        try:
+            PB = oracle.composition(P, B)
+        except oracle.OracleError as err:
+            with pytest.raises(error) as e2:
+                compose(A, B)
+            assert e2.value.status_name == err.status_name, (A, B)
+            continue
+        import re
+        shp, strd = [[int(x) for x in re.findall(r"\d+", part)] for part in str(PB).split(":")]
+        masks = {}
+        carry = False
+        for s_, t in zip(shp, strd):
+            if s_ == 1 or t == 0:
+                continue
+            k = max(i for i in range(len(place)) if place[i] <= t)
+            if t % place[k]:
+                carry = None          # not a walk inside one leaf: refused for another reason
+                break
+            m = (t // place[k]) * ds[k]
+            mask = 0
+            for c in range(s_):
+                mask |= c * m
+            for other in masks.setdefault(k, []):
+                carry = carry or bool(other & mask)
+            masks[k].append(mask)
+        if carry is None:
+            continue
+        if carry:
+            with pytest.raises(error) as e2:
+                compose(A, B)
+            assert e2.value.status_name == "NOT_SEGREGATED", (A, B)
+            refused += 1
+            continue
+        R = compose(A, B)
+        assert str(R) == str(oracle.slayout_composition(A, B)), (A, B)
+        for c in range(Bo.size):
+            assert R(c) == Ao(Bo(c)), (A, B, c)
+        composed += 1
+    assert composed > 300 and refused > 100, (composed, refused)
