@@ -175,8 +175,9 @@ lc_status_t lc_max_common_vector(const lc_layout_t* a, const lc_layout_t* b, int
  * values to out (cap = room in out); the extended domain applies as for lc_layout_eval.
  * lc_slayout_composition: A o B for an integer layout B (Sec. 3.3 "Reductive case: Coordinate",
  * Table TVLayoutExamples rows Swizzled and Coordinate); errors as lc_composition.  With XOR strides the
- * result equals A(B(c)) only while the modes of B that fall into one mode of A do not meet in a bit
- * (true for the paper's example); the paper asks for "special care" there and so does this call.
+ * modes of B that walk one mode of A are added as integers before A scales them, which is their XOR only while no two
+ * of them can set the same bit (true for the paper's example): otherwise no layout with XOR strides equals A(B(c)) and
+ * the call answers NOT_SEGREGATED; TOO_LARGE when a mode is too long to decide that (more than 2^24 positions).
  * lc_slayout_coalesce: Sec. 3.2 in the semimodule (XOR modes never merge).
  * lc_slayout_right_inverse: coordinate layouts only (Table rinv, rows with e_i strides): the integer
  * layout R on the largest box of coordinates starting at 0 with A(R(c)) = c; INVALID_ARG otherwise.

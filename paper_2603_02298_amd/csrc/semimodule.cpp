@@ -176,6 +176,11 @@ lc_status_t composition(const SemiLayout& a, const Layout& b, SemiLayout* out) {
   if (st != LC_OK) return st;
   SemiLayout r;
   r.profile = pb.profile;
+  // XOR strides: the bits that the modes walking leaf k can set so far.  A mode contributes c * (step * d_k) for c below its
+  // extent; inside one leaf those contributions are added as integers before A scales them, and that equals their XOR
+  // exactly when no two modes can set the same bit.  Otherwise no layout with XOR strides is A o B: refused.
+  const bool is_xor = a.kind() == SemiStride::Xor;
+  std::vector<uint64_t> bits_of_leaf(a.extent.size(), 0);
   for (const Mode& m : pb.leaves) {
     r.extent.push_back(m.extent);
     SemiStride s;
@@ -186,6 +191,13 @@ lc_status_t composition(const SemiLayout& a, const Layout& b, SemiLayout* out) {
       s = a.stride[k];
       s.a *= m.stride / lo[k];
       if (s.a == 0) s = SemiStride{};
+      if (is_xor && s.a != 0) {
+        if (s.a < 0 || m.extent > (int64_t(1) << 24) || (long double)s.a * (long double)(m.extent - 1) > 4.0e18L) return LC_ERR_TOO_LARGE;
+        uint64_t mine = 0;
+        for (int64_t c = 1; c < m.extent; ++c) mine |= (uint64_t)c * (uint64_t)s.a;
+        if (mine & bits_of_leaf[k]) return LC_ERR_NOT_SEGREGATED;
+        bits_of_leaf[k] |= mine;
+      }
     }
     r.stride.push_back(s);
   }

@@ -425,7 +425,7 @@ def _xor_multiples(c, d):
 # closed form of "a carry can happen" that is derived independently: mode j of the result contributes c_j * m_j with
 # m_j = step_j * d_k, and two modes in one leaf can carry iff the OR of their possible contributions share a bit.
 # ---------------------------------------------------------------------------------------------
-XOR_COMPOSITION_SIDES = ["oracle"]
+XOR_COMPOSITION_SIDES = ["oracle", "library"]
 
 
 def _xor_sides(oracle, side):
