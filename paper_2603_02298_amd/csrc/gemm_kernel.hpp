@@ -458,23 +458,46 @@ __global__ __launch_bounds__(kBlock, (WMB <= 2 ? 2 : 1)) void gemm_kernel(GemmPa
     const uint32_t n = n0 + wn * (WNB * 32u) + 32u * (uint32_t)j + mfma_c_col(lane);
     const bool n_in = n < P.N;
     const uint32_t noff = gemm_mode_eval(P.c_n, n_in ? n : 0u);
-    static_for<WMB>([&](auto i) {
-      static_for<4>([&](auto g) {
-        const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
-        if (P.c_vec) {
-          if (n_in && m < P.M) {
-            f32x4* p = reinterpret_cast<f32x4*>(C + gemm_mode_eval(P.c_m, m) + noff);
-            f32x4 c = *p;
-            static_for<4>([&](auto v) { c[(int)v] += acc[i][j][4 * g + v]; });
-            *p = c;
-          }
-        } else {
-          static_for<4>([&](auto v) {
-            if (n_in && m + (uint32_t)v < P.M) C[gemm_mode_eval(P.c_m, m + (uint32_t)v) + noff] += acc[i][j][4 * g + v];
-          });
-        }
+    if (P.c_vec) {
+      // All 4 WMB vectors of this fragment column are loaded before the first is stored.  Written as one read-modify-write
+      // after the other, every load waits behind the store before it (they may alias as far as the compiler knows) and a
+      // lane pays 16 WMB memory round trips per tile instead of 4: measured 0.905 -> 0.873 ms on 8192^3.  Loading column
+      // j + 1 before column j is stored (two columns of registers) measured slower again (0.885 ms).
+      f32x4 cv[WMB][4];
+      static_for<WMB>([&](auto i) {
+        static_for<4>([&](auto g) {
+          const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
+          if (n_in && m < P.M) cv[i][g] = *reinterpret_cast<const f32x4*>(C + gemm_mode_eval(P.c_m, m) + noff);
+        });
       });
-    });
+      static_for<WMB>([&](auto i) {
+        static_for<4>([&](auto g) {
+          const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
+          if (n_in && m < P.M) {
+            f32x4 c = cv[i][g];
+            static_for<4>([&](auto v) { c[(int)v] += acc[i][j][4 * g + v]; });
+            *reinterpret_cast<f32x4*>(C + gemm_mode_eval(P.c_m, m) + noff) = c;
+          }
+        });
+      });
+    } else {
+      // element by element, for the same reason a fragment (16 elements per lane) at a time
+      static_for<WMB>([&](auto i) {
+        float cs[4][4];
+        static_for<4>([&](auto g) {
+          const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
+          static_for<4>([&](auto v) {
+            if (n_in && m + (uint32_t)v < P.M) cs[g][v] = C[gemm_mode_eval(P.c_m, m + (uint32_t)v) + noff];
+          });
+        });
+        static_for<4>([&](auto g) {
+          const uint32_t m = m0 + wm * (WMB * 32u) + 32u * (uint32_t)i + mfma_c_row(lane, 4u * (uint32_t)g);
+          static_for<4>([&](auto v) {
+            if (n_in && m + (uint32_t)v < P.M) C[gemm_mode_eval(P.c_m, m + (uint32_t)v) + noff] = cs[g][v] + acc[i][j][4 * g + v];
+          });
+        });
+      });
+    }
   });
 }
 
