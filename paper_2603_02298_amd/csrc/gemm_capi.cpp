@@ -63,7 +63,7 @@ lc_status_t lc_gemm(const void* a, const lc_layout_t* a_layout, const void* b, c
     std::string key = a_layout->L.str() + "|" + b_layout->L.str() + "|" + c_layout->L.str() + "|" + std::to_string((int)ab_dtype) + "|" +
                       std::to_string(pointer_alignment(a)) + "|" + std::to_string(pointer_alignment(b)) + "|" + std::to_string(pointer_alignment(c));
     for (const char* knob : {"LC_TUNE_GEMM_LOAD", "LC_TUNE_GEMM_DIRECT", "LC_TUNE_GEMM_CVEC", "LC_TUNE_GEMM_TILE", "LC_TUNE_GEMM_GROUP_M",
-                             "LC_TUNE_GEMM_EXCHANGE"}) {
+                             "LC_TUNE_GEMM_EXCHANGE", "LC_TUNE_GEMM_KTAIL"}) {
       const char* v = std::getenv(knob);
       key += std::string(",") + (v ? v : "");
     }
