@@ -10,6 +10,7 @@
 // A second universe takes every stride in 0..Dmax for rank <= 3, extents <= 4.
 //
 // usage: bruteforce [--rank R] [--extent E] [--pair-rank r] [--pair-extent e] [--random N] [--seed S] [--product-budget C]
+//                   [--phases unary,pairs,random] [--pair-slice k/n]   (a long run can be cut into parts whose tallies add up)
 // Exit status 0 iff no post-condition failed.
 #include <algorithm>
 #include <atomic>
@@ -442,6 +443,8 @@ int main(int argc, char** argv) {
   int R = 3, E = 4, pr = 2, pe = 4, Dmax = 6;
   long nrandom = 20000;
   uint64_t seed = 2603022980ull;
+  bool do_unary = true, do_pairs = true, do_random = true;
+  long slice_k = 0, slice_n = 1;   // the pair phase walks the k-th of n slices of the left operands
   for (int i = 1; i + 1 < argc; i += 2) {
     if (!strcmp(argv[i], "--rank")) R = atoi(argv[i + 1]);
     else if (!strcmp(argv[i], "--extent")) E = atoi(argv[i + 1]);
@@ -451,6 +454,8 @@ int main(int argc, char** argv) {
     else if (!strcmp(argv[i], "--random")) nrandom = atol(argv[i + 1]);
     else if (!strcmp(argv[i], "--seed")) seed = strtoull(argv[i + 1], nullptr, 10);
     else if (!strcmp(argv[i], "--product-budget")) g_product_budget = atoll(argv[i + 1]);
+    else if (!strcmp(argv[i], "--phases")) { do_unary = strstr(argv[i + 1], "unary"); do_pairs = strstr(argv[i + 1], "pairs"); do_random = strstr(argv[i + 1], "random"); }
+    else if (!strcmp(argv[i], "--pair-slice")) { if (sscanf(argv[i + 1], "%ld/%ld", &slice_k, &slice_n) != 2 || slice_n < 1 || slice_k < 0 || slice_k >= slice_n) { fprintf(stderr, "bad --pair-slice\n"); return 2; } }
     else { fprintf(stderr, "unknown option %s\n", argv[i]); return 2; }
   }
   rng_state = seed;
@@ -469,7 +474,7 @@ int main(int argc, char** argv) {
   fflush(stdout);
 
 #pragma omp parallel for schedule(dynamic, 64)
-  for (long k = 0; k < (long)uni.size(); ++k) {
+  for (long k = 0; k < (do_unary ? (long)uni.size() : 0); ++k) {
     const Flat& f = uni[(size_t)k];
     unsigned ncuts = 1u << (f.first.size() - 1);
     for (unsigned cuts = 0; cuts < ncuts; ++cuts) check_unary(regroup(f.first, f.second, cuts));
@@ -486,14 +491,16 @@ int main(int argc, char** argv) {
   printf("pair universe: %zu layouts -> %zu ordered pairs, plus %ld random pairs from the unary universe\n",
          pl.size(), pl.size() * pl.size(), nrandom);
   fflush(stdout);
+  const long a_begin = do_pairs ? (long)pl.size() * slice_k / slice_n : 0, a_end = do_pairs ? (long)pl.size() * (slice_k + 1) / slice_n : 0;
 #pragma omp parallel for schedule(dynamic, 4)
-  for (long a = 0; a < (long)pl.size(); ++a)
+  for (long a = a_begin; a < a_end; ++a)
     for (size_t b = 0; b < pl.size(); ++b) {
       check_pair(pl[(size_t)a], pl[b]);
       check_tiler(pl[(size_t)a], pl[b]);
     }
 
   std::vector<std::pair<Layout, Layout>> rnd;
+  if (!do_random) nrandom = 0;
   for (long k = 0; k < nrandom; ++k) {
     const Flat& fa = uni[rng() % uni.size()];
     const Flat& fb = uni[rng() % uni.size()];

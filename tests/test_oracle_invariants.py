@@ -58,7 +58,7 @@ def test_rank4_extent8_universe_tally_is_committed():
 
 
 @pytest.mark.slow
-@pytest.mark.skipif(os.environ.get("RUN_SLOW_UNIVERSE") != "1", reason="about an hour on 8 cores: set RUN_SLOW_UNIVERSE=1")
+@pytest.mark.skipif(os.environ.get("RUN_SLOW_UNIVERSE") != "1", reason="about three hours on 8 cores: set RUN_SLOW_UNIVERSE=1")
 def test_rank4_extent8_universe_rerun():
     """Runs the universe again and compares its tally with the committed one."""
     import importlib.util
