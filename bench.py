@@ -67,7 +67,8 @@ def time_workload(torch, lc, w, dev, steps, warmup, stream):
     """Times one workload: ms per step through lc_copy by host clock, ms per launch by HIP events on the launch
     stream, the plan's text, the number of rotating buffer pairs, ms per launch inside a HIP graph (short kernels
     only), the source bits of buffer 0 on the host (for the oracle's baseline) and ms per launch when one buffer pair
-    is used over and over (workloads whose footprint the last-level cache holds)."""
+    is used over and over (workloads whose footprint the last-level cache holds), and the median and minimum of the
+    per-launch times of one more pass with an event after every launch."""
     srcs, dsts = make_buffers(torch, w, dev, 4 * CACHE_BYTES)
     sl, dl = lc.Layout(w.src_layout), lc.Layout(w.dst_layout)
     n = len(srcs)
@@ -85,12 +86,13 @@ def time_workload(torch, lc, w, dev, steps, warmup, stream):
     ms_kernel = plan.time(sp, dp, warmup=min(warmup, 3), iters=steps, stream=stream)
     # footprints that fit the last-level cache: the same launches on ONE buffer pair (warm), beside the rotating (cold) figure
     ms_warm = plan.time(sp[:1], dp[:1], warmup=min(warmup, 3), iters=steps, stream=stream) if n > 1 else None
+    each = sorted(plan.time_each(sp, dp, warmup=min(warmup, 3), iters=steps, stream=stream))
     desc = plan.describe()
     graph_ms = time_in_graph(torch, plan, sp, dp, steps) if ms_kernel < 0.05 else None
     src_host = srcs[0].cpu().numpy()
     del srcs, dsts
     torch.cuda.empty_cache()
-    return ms_step, ms_kernel, desc, n, graph_ms, src_host, ms_warm
+    return ms_step, ms_kernel, desc, n, graph_ms, src_host, ms_warm, (each[len(each) // 2], each[0])
 
 
 def time_in_graph(torch, plan, sp, dp, steps):
@@ -299,7 +301,7 @@ def main():
 
     def record(name, headline):
         w = W.workload(name)
-        ms_step, ms_kernel, desc, n_pairs, graph_ms, src_host, ms_warm = time_workload(torch, lc, w, dev, args.steps, args.warmup, stream)
+        ms_step, ms_kernel, desc, n_pairs, graph_ms, src_host, ms_warm, (ms_median, ms_min) = time_workload(torch, lc, w, dev, args.steps, args.warmup, stream)
         sec = ms_kernel * 1e-3
         achieved = w.dram_minimum_bytes / sec / 1e9
         rec = {
@@ -314,6 +316,9 @@ def main():
                          "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_table.get(w.name),
                          "traffic_source": traffic_note, "kernel_ms": round(ms_kernel, 5),
                          "kernel_ms_one_buffer_pair_cache_warm": None if ms_warm is None else round(ms_warm, 5),
+                         # a second pass over the same launches with an event between every two (adds about a microsecond
+                         # per launch to kernels of a few microseconds): the median and the fastest of the --steps launches
+                         "kernel_ms_median_event_per_launch": round(ms_median, 5), "kernel_ms_min_event_per_launch": round(ms_min, 5),
                          "bytes_priced": "dram_minimum_bytes",
                          "achieved_algorithmic": round(w.algorithmic_bytes / sec / 1e9, 2),
                          "frac_algorithmic": round(w.algorithmic_bytes / sec / 1e9 / HBM_PEAK_GBS, 4)},

@@ -272,6 +272,12 @@ int64_t lc_plan_algorithmic_bytes(const lc_plan_t* plan);
  * device pointers used round-robin, so that successive executions touch different memory. */
 lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers,
                          int warmup, int iters, void* hip_stream, float* ms_per_iter);
+/* The same executions with a HIP event between every two of them: ms_each (host array of `iters` floats, iters <= 4096)
+ * receives, per execution, the time between the events around it: a median and a minimum beside lc_plan_time's mean.
+ * An event between two short kernels delays the second by about a microsecond, so for kernels of a few microseconds
+ * these figures lie above lc_plan_time's.  Errors: INVALID_ARG, HIP, and those of lc_plan_execute. */
+lc_status_t lc_plan_time_each(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers,
+                              int warmup, int iters, void* hip_stream, float* ms_each);
 
 /* ---------------------------------------------------------------------------------------------
  * GEMM (Sec. 2.6.2): C(m,n) += A(m,k) * B(n,k) for every m < M, n < N, k < K, executed on the GPU's

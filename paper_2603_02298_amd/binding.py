@@ -95,6 +95,7 @@ def lib():
     L.lc_plan_algorithmic_bytes.argtypes = [P]
     L.lc_plan_algorithmic_bytes.restype = i64
     L.lc_plan_time.argtypes = [P, PP, PP, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
+    L.lc_plan_time_each.argtypes = [P, PP, PP, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, ctypes.POINTER(ctypes.c_float)]
     L.lc_debug_replay_on_host.argtypes = [P, P, i64, P, i64, ctypes.POINTER(i64)]
     L.lc_debug_replay_on_host_at.argtypes = [P, P, i64, i64, P, i64, i64, ctypes.POINTER(i64)]
     u = ctypes.c_uint
@@ -343,6 +344,15 @@ class Plan:
         ms = ctypes.c_float()
         _check(lib().lc_plan_time(self._h, a, b, n, warmup, iters, stream, ctypes.byref(ms)), "lc_plan_time")
         return ms.value
+
+    def time_each(self, src_ptrs, dst_ptrs, warmup, iters, stream=0):
+        """Milliseconds of each of `iters` executions (an event between every two of them)."""
+        n = len(src_ptrs)
+        a = (ctypes.c_void_p * n)(*src_ptrs)
+        b = (ctypes.c_void_p * n)(*dst_ptrs)
+        ms = (ctypes.c_float * iters)()
+        _check(lib().lc_plan_time_each(self._h, a, b, n, warmup, iters, stream, ms), "lc_plan_time_each")
+        return list(ms)
 
     def debug_replay_on_host(self, src, dst, src_origin=0, dst_origin=0):
         """Test instrumentation: walk the plan's index arithmetic over numpy arrays on the host

@@ -299,6 +299,12 @@ lc_status_t lc_plan_time(const lc_plan_t* plan, const void* const* srcs, void* c
   return lc::time_plan(*plan, srcs, dsts, n_buffers, warmup, iters, hip_stream, ms_per_iter);
 }
 
+lc_status_t lc_plan_time_each(const lc_plan_t* plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup, int iters,
+                              void* hip_stream, float* ms_each) {
+  if (!plan) return LC_ERR_INVALID_ARG;
+  return lc::time_plan_each(*plan, srcs, dsts, n_buffers, warmup, iters, hip_stream, ms_each);
+}
+
 // Checking device for tests: replays the plan's index arithmetic on HOST buffers (see plan.hpp).
 // Not declared in the public header; never used to execute a copy.
 lc_status_t lc_debug_replay_on_host(const lc_plan_t* plan, const void* src_host, int64_t src_elems, void* dst_host,

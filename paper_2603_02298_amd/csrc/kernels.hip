@@ -1084,4 +1084,29 @@ lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const*
   return st;
 }
 
+// The same launches with an event between every two of them: ms_each[i] is the time from the event before execution i
+// to the event after it (the kernel and whatever gap the stream leaves before the next event).
+lc_status_t time_plan_each(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
+                           int iters, void* stream, float* ms_each) {
+  if (!srcs || !dsts || n_buffers < 1 || iters < 1 || iters > 4096 || warmup < 0 || !ms_each) return LC_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<hipEvent_t> ev((size_t)iters + 1, nullptr);
+  lc_status_t st = LC_OK;
+  for (hipEvent_t& e : ev)
+    if (st == LC_OK && hip_failed(hipEventCreate(&e), "hipEventCreate")) { e = nullptr; st = LC_ERR_HIP; }
+  int b = 0;
+  for (int i = 0; i < warmup && st == LC_OK; ++i, b = (b + 1) % n_buffers) st = execute_plan(plan, srcs[b], dsts[b], stream);
+  if (st == LC_OK && hip_failed(hipEventRecord(ev[0], s), "hipEventRecord")) st = LC_ERR_HIP;
+  for (int i = 0; i < iters && st == LC_OK; ++i, b = (b + 1) % n_buffers) {
+    st = execute_plan(plan, srcs[b], dsts[b], stream);
+    if (st == LC_OK && hip_failed(hipEventRecord(ev[(size_t)i + 1], s), "hipEventRecord")) st = LC_ERR_HIP;
+  }
+  if (st == LC_OK && hip_failed(hipEventSynchronize(ev[(size_t)iters]), "hipEventSynchronize")) st = LC_ERR_HIP;
+  for (int i = 0; i < iters && st == LC_OK; ++i)
+    if (hip_failed(hipEventElapsedTime(&ms_each[i], ev[(size_t)i], ev[(size_t)i + 1]), "hipEventElapsedTime")) st = LC_ERR_HIP;
+  for (hipEvent_t e : ev)
+    if (e) (void)hipEventDestroy(e);
+  return st;
+}
+
 }  // namespace lc

@@ -132,5 +132,7 @@ lc_status_t execute_plan_static(const lc_plan& plan, const void* src, void* dst,
 lc_status_t execute_plan_workspace(const lc_plan& plan, const void* src, void* dst, void* workspace, size_t workspace_bytes, void* stream);
 lc_status_t time_plan(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
                       int iters, void* stream, float* ms_per_iter);
+lc_status_t time_plan_each(const lc_plan& plan, const void* const* srcs, void* const* dsts, int n_buffers, int warmup,
+                           int iters, void* stream, float* ms_each);
 
 }  // namespace lc

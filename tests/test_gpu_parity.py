@@ -239,6 +239,26 @@ def test_tile_queue(oracle, monkeypatch):
             assert "tile_queue=%d" % grab in desc, desc
 
 
+def test_plan_time_each_reports_every_launch(oracle):
+    # per-launch timing: as many figures as launches, all positive, their mean close to the batch mean of lc_plan_time
+    w = W.workload("c5", 64)
+    dev = torch.device("cuda:0")
+    src = torch.from_numpy(W.source_bits(w).view(np.int32)).to(dev)
+    dsts = [torch.zeros(w.dst_elems, dtype=torch.int32, device=dev) for _ in range(2)]
+    plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
+    sp, dp = [src.data_ptr()] * 2, [d.data_ptr() for d in dsts]
+    each = plan.time_each(sp, dp, 2, 12)
+    mean = plan.time(sp, dp, 2, 12)
+    assert len(each) == 12 and min(each) > 0
+    assert 0.5 * mean < sum(each) / len(each) < 3.0 * mean + 0.01, (each, mean)
+    want = np.zeros(w.dst_elems, np.uint32)
+    oracle.copy(W.source_bits(w).view(np.uint32), oracle.Layout(w.src_layout), want, oracle.Layout(w.dst_layout))
+    for d in dsts:
+        assert (d.cpu().numpy().view(np.uint32) == want).all()
+    with pytest.raises(lc.LayoutCopyError):
+        plan.time_each(sp, dp, 0, 0)
+
+
 def test_direct_class_chunks_on_request(oracle, monkeypatch):
     # the direct class with its items handed out to the wavefronts in chunks (counters of the stream's block, put back to zero
     # by the last wavefront): forced on at sizes the oracle walks in full.  Plain copies, a strided gather, a broadcast
