@@ -6,7 +6,7 @@ call of a workload plans on the host (validate, coalesce, refine, sort, vector w
 that plan in the library's plan cache, so a timed step is plan look-up + launch + kernel.  Buffers rotate so that a
 step never finds its data in the last-level cache.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c1|c2|c3|c4a|c4b|copy|gemm_tn|gemm_nt|calibrate] [--no-all]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c1|c2|c3|c4a|c4b|copy|gemm_tn|gemm_nt|calibrate] [--no-all] [--no-extra-passes]
 
 Prints ONE JSON line.  The headline (`value`, `config`, `roofline`, `cpu_baseline`) is the largest single-GPU
 configuration, workload 5 (NCHW -> NHWC, 2^30 fp32 elements, 8 GiB moved); `workloads` carries the same record for
@@ -63,7 +63,7 @@ def make_buffers(torch, w, dev, rotate_bytes):
     return srcs, dsts
 
 
-def time_workload(torch, lc, w, dev, steps, warmup, stream):
+def time_workload(torch, lc, w, dev, steps, warmup, stream, extra_passes=True):
     """Times one workload: ms per step through lc_copy by host clock, ms per launch by HIP events on the launch
     stream, the plan's text, the number of rotating buffer pairs, ms per launch inside a HIP graph (short kernels
     only), the source bits of buffer 0 on the host (for the oracle's baseline) and ms per launch when one buffer pair
@@ -85,10 +85,10 @@ def time_workload(torch, lc, w, dev, steps, warmup, stream):
     plan = lc.Plan(w.src_layout, w.dst_layout, w.dtype)
     ms_kernel = plan.time(sp, dp, warmup=min(warmup, 3), iters=steps, stream=stream)
     # footprints that fit the last-level cache: the same launches on ONE buffer pair (warm), beside the rotating (cold) figure
-    ms_warm = plan.time(sp[:1], dp[:1], warmup=min(warmup, 3), iters=steps, stream=stream) if n > 1 else None
-    each = sorted(plan.time_each(sp, dp, warmup=min(warmup, 3), iters=steps, stream=stream))
+    ms_warm = plan.time(sp[:1], dp[:1], warmup=min(warmup, 3), iters=steps, stream=stream) if (n > 1 and extra_passes) else None
+    each = sorted(plan.time_each(sp, dp, warmup=min(warmup, 3), iters=steps, stream=stream)) if extra_passes else [float("nan")]
     desc = plan.describe()
-    graph_ms = time_in_graph(torch, plan, sp, dp, steps) if ms_kernel < 0.05 else None
+    graph_ms = time_in_graph(torch, plan, sp, dp, steps) if (ms_kernel < 0.05 and extra_passes) else None
     src_host = srcs[0].cpu().numpy()
     del srcs, dsts
     torch.cuda.empty_cache()
@@ -247,6 +247,9 @@ def main():
     ap.add_argument("--workload", default="c5")
     ap.add_argument("--no-all", action="store_true", help="time the headline workload only (no `workloads` map, no GEMM)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-passes", action="store_true",
+                    help="only the warm-up, the timed steps and the event-timed launches on rotating buffers (no cache-warm pass, no "
+                         "per-launch pass, no graph replay): what the kernel traces under profiles/ are taken with")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; the path has no multi-GPU part (how it would shard is described in the design notes)", file=sys.stderr)
@@ -301,7 +304,7 @@ def main():
 
     def record(name, headline):
         w = W.workload(name)
-        ms_step, ms_kernel, desc, n_pairs, graph_ms, src_host, ms_warm, (ms_median, ms_min) = time_workload(torch, lc, w, dev, args.steps, args.warmup, stream)
+        ms_step, ms_kernel, desc, n_pairs, graph_ms, src_host, ms_warm, (ms_median, ms_min) = time_workload(torch, lc, w, dev, args.steps, args.warmup, stream, not args.no_extra_passes)
         sec = ms_kernel * 1e-3
         achieved = w.dram_minimum_bytes / sec / 1e9
         rec = {
@@ -318,7 +321,8 @@ def main():
                          "kernel_ms_one_buffer_pair_cache_warm": None if ms_warm is None else round(ms_warm, 5),
                          # a second pass over the same launches with an event between every two (adds about a microsecond
                          # per launch to kernels of a few microseconds): the median and the fastest of the --steps launches
-                         "kernel_ms_median_event_per_launch": round(ms_median, 5), "kernel_ms_min_event_per_launch": round(ms_min, 5),
+                         "kernel_ms_median_event_per_launch": None if ms_median != ms_median else round(ms_median, 5),
+                         "kernel_ms_min_event_per_launch": None if ms_min != ms_min else round(ms_min, 5),
                          "bytes_priced": "dram_minimum_bytes",
                          "achieved_algorithmic": round(w.algorithmic_bytes / sec / 1e9, 2),
                          "frac_algorithmic": round(w.algorithmic_bytes / sec / 1e9 / HBM_PEAK_GBS, 4)},
